@@ -1,0 +1,328 @@
+"""CPU oracle for the Agile-Quant W4A8 / W4A4 linear layer and its log2-softmax path.
+
+TEST INFRASTRUCTURE ONLY.  This module is the slow, plain definition that the
+GPU library is checked against.  Only the tests, the smoke check and the
+`cpu_baseline` leg of the benchmark may import it; the product path never does.
+It shares no code with the HIP kernels and imports nothing from the package.
+
+Every function states the passage of the paper (arxiv 2312.05693) it follows.
+Floating point is done in float64, where every product below is exact, and is
+rounded once at the end; integer work is done in int64 and asserted to fit the
+int32 accumulator the method uses.
+
+Readings taken where the paper is silent (each is repeated at its function):
+  * activation scale is a power of two, s = 2^e, one per tensor (layer-wise);
+  * round-to-nearest with ties to even;
+  * zp == 0 selects the signed grid of Eq.1, zp > 0 the unsigned grid of Eq.2;
+  * weights: symmetric round-to-nearest per output channel stands in for GPTQ;
+  * Eq.3 is applied to softmax probabilities with max|X| taken as 1.0;
+  * token importance is the attention paid to the first token, summed over heads.
+NaN inputs are outside every quantizer's domain: the oracle raises on them.
+"""
+from __future__ import annotations
+
+import numpy as np
+
+# --------------------------------------------------------------------------
+# Eq.1  integer grids
+# --------------------------------------------------------------------------
+
+def grid_bounds(bits: int, zp: int = 0) -> tuple[int, int]:
+    """Section 4.1, Eq.1: the signed grid {-2^(b-1) .. 2^(b-1)-1} (taken when
+    zp == 0) or the unsigned grid {0 .. 2^b-1} (taken when zp > 0)."""
+    if bits < 2 or bits > 8:
+        raise ValueError("bits must be in 2..8")
+    if zp == 0:
+        return -(1 << (bits - 1)), (1 << (bits - 1)) - 1
+    if zp < 0 or zp > (1 << bits) - 1:
+        raise ValueError("zp outside the unsigned grid")
+    return 0, (1 << bits) - 1
+
+
+def _as_f64(x) -> np.ndarray:
+    x = np.asarray(x)
+    if x.dtype != np.float16:
+        raise TypeError("activations are fp16")
+    x64 = x.astype(np.float64)          # exact
+    if np.isnan(x64).any():
+        raise ValueError("NaN is outside the quantizer's domain")
+    return x64
+
+
+# --------------------------------------------------------------------------
+# Eq.2  uniform quantizer with s = 2^e
+# --------------------------------------------------------------------------
+
+def quantize_act(x, bits: int, e: int, zp: int = 0) -> np.ndarray:
+    """Section 4.1, Eq.2: q = CLIP(round(x / s) + zp, lo, hi) with s = 2^e.
+
+    x / 2^e is exact in float64; `np.rint` rounds ties to even; +-Inf land on
+    the clip bounds.  Returns int32 codes on the grid of `grid_bounds`."""
+    lo, hi = grid_bounds(bits, zp)
+    r = np.ldexp(_as_f64(x), -int(e))               # exact scaling by 2^-e
+    t = np.rint(r)                                   # ties to even
+    q = np.clip(t + float(zp), float(lo), float(hi))
+    return q.astype(np.int32)
+
+
+def dequantize_act(q, e: int, zp: int = 0) -> np.ndarray:
+    """Inverse map of Eq.2: x_hat = (q - zp) * 2^e (exact in float64)."""
+    return np.ldexp((np.asarray(q, dtype=np.int64) - int(zp)).astype(np.float64), int(e))
+
+
+def calibrate_act_exp(x, bits: int) -> int:
+    """Layer-wise power-of-two scale (Section 4.4, one scale for all channels):
+    the smallest integer e with max|x| <= qmax * 2^e, qmax = 2^(b-1)-1.
+    An all-zero tensor gives e = 0.  Non-finite entries count as magnitude 2^16
+    (above every finite fp16), so the result is always defined."""
+    x = np.asarray(x)
+    if x.dtype != np.float16:
+        raise TypeError("activations are fp16")
+    a = np.abs(x.astype(np.float64))
+    a = np.where(np.isfinite(a), a, 65536.0)
+    amax = float(a.max()) if a.size else 0.0
+    if amax == 0.0:
+        return 0
+    qmax = (1 << (bits - 1)) - 1
+    e = -64
+    while amax > qmax * (2.0 ** e):                  # predicate, never a log
+        e += 1
+    return e
+
+
+# --------------------------------------------------------------------------
+# 4-bit storage: two codes per byte
+# --------------------------------------------------------------------------
+
+def pack_nibbles(q) -> np.ndarray:
+    """Two 4-bit codes per byte along the last axis: the low nibble holds the
+    even index, the high nibble the odd one; signed codes are stored in two's
+    complement (Section 4.4 packs two adjacent 4-bit values into one byte)."""
+    q = np.asarray(q, dtype=np.int64)
+    if q.shape[-1] % 2:
+        raise ValueError("last axis must be even")
+    if q.min(initial=0) < -8 or q.max(initial=0) > 15:
+        raise ValueError("code does not fit four bits")
+    u = (q & 0xF).astype(np.uint8)
+    return (u[..., 0::2] | (u[..., 1::2] << 4)).astype(np.uint8)
+
+
+def unpack_nibbles(b, signed: bool = True) -> np.ndarray:
+    """Inverse of `pack_nibbles`; returns int32 codes."""
+    b = np.asarray(b, dtype=np.uint8)
+    lo = (b & 0xF).astype(np.int32)
+    hi = (b >> 4).astype(np.int32)
+    out = np.empty(b.shape[:-1] + (b.shape[-1] * 2,), dtype=np.int32)
+    out[..., 0::2] = lo
+    out[..., 1::2] = hi
+    if signed:
+        out = np.where(out >= 8, out - 16, out)
+    return out
+
+
+# --------------------------------------------------------------------------
+# weights: per-output-channel symmetric 4-bit (stand-in for GPTQ, Section 5.1)
+# --------------------------------------------------------------------------
+
+def quantize_weight_rtn(w) -> tuple[np.ndarray, np.ndarray]:
+    """Per-output-channel weight parameters (Section 4.4: engines take per-channel
+    scales for weights).  sw[n] = fp16(max_k |W[n,k]| / 7), 1 where the row is
+    zero; Wq = CLIP(round(W / sw), -8, 7) with ties to even.  W is [N, K]."""
+    w = np.asarray(w, dtype=np.float64)
+    amax = np.abs(w).max(axis=1)
+    sw = (amax / 7.0).astype(np.float16)
+    sw = np.where(sw == 0, np.float16(1.0), sw).astype(np.float16)
+    q = np.rint(w / sw.astype(np.float64)[:, None])
+    q = np.clip(q, -8, 7).astype(np.int8)
+    return q, sw
+
+
+# --------------------------------------------------------------------------
+# integer contraction and dequantisation
+# --------------------------------------------------------------------------
+
+INT32_MAX = (1 << 31) - 1
+
+
+def gemm_int(q, zp: int, wq) -> np.ndarray:
+    """acc[m,n] = sum_k (q[m,k] - zp) * Wq[n,k]: the product of the quantized
+    activation with the 4-bit weight matrix, accumulated in integers
+    (Section 4.4: layer-wise activation, per-channel weight).  int64 here,
+    asserted to fit the 32-bit accumulator."""
+    a = np.asarray(q, dtype=np.int64) - int(zp)
+    b = np.asarray(wq, dtype=np.int64)
+    if a.shape[-1] != b.shape[-1]:
+        raise ValueError("K mismatch")
+    acc = a @ b.T
+    if acc.size and max(int(acc.max()), -int(acc.min())) > INT32_MAX:
+        raise OverflowError("accumulator leaves int32")
+    return acc
+
+
+def dequant_out(acc, e: int, sw) -> np.ndarray:
+    """y[m,n] = fp16( acc[m,n] * 2^e * sw[n] ): the layer-wise activation scale
+    times the per-channel weight scale (Section 4.4).  The product is exact in
+    float64 (32 + 11 significant bits) and is rounded once, to fp16."""
+    sw = np.asarray(sw)
+    if sw.dtype != np.float16:
+        raise TypeError("weight scales are fp16")
+    g = np.ldexp(sw.astype(np.float64), int(e))              # exact
+    y = np.asarray(acc, dtype=np.int64).astype(np.float64) * g[None, :]
+    with np.errstate(over="ignore"):
+        return y.astype(np.float16)
+
+
+def linear_w4(x, bits: int, e: int, zp: int, wq, sw):
+    """The whole linear layer: Eq.2 on the activation, integer product with the
+    4-bit weights, per-channel dequantisation.  Returns (acc int64, y fp16)."""
+    q = quantize_act(x, bits, e, zp)
+    acc = gemm_int(q, zp, wq)
+    return acc, dequant_out(acc, e, sw)
+
+
+# --------------------------------------------------------------------------
+# Eq.3  log2 quantizer on softmax probabilities, and the product with V
+# --------------------------------------------------------------------------
+
+def log2_quant(p, qmax: int) -> np.ndarray:
+    """Section 4.1, Eq.3 with max|X| = 1: c = CLIP(round(-log2 p), 0, qmax).
+    p = 0 gives +Inf before the clip, hence qmax.  -log2 p is never half-way
+    between integers for a rational p, so the tie rule cannot matter; float64's
+    log2 error is many orders below the distance of any fp16 value from a
+    half-way point.  p must lie in [0, 1]."""
+    p64 = _as_f64(p)
+    if p64.size and (p64.min() < 0.0 or p64.max() > 1.0):
+        raise ValueError("probabilities must lie in [0, 1]")
+    with np.errstate(divide="ignore"):
+        t = np.rint(-np.log2(p64))
+    return np.clip(t, 0.0, float(qmax)).astype(np.int32)
+
+
+def attn_v_rows(p_rows, n_valid, vq_h, qmax: int) -> np.ndarray:
+    """Rows of the product of Eq.3's codes with one head's value matrix:
+    A[r,d] = sum_{j < n_valid[r]} 2^(qmax - c[r,j]) * vq_h[j,d], c = Eq.3 of
+    p_rows[r,j].  p_rows fp16 [R,S], vq_h int8 [S,D], n_valid int [R].  int64,
+    asserted to fit int32."""
+    p_rows = np.asarray(p_rows)
+    R, S = p_rows.shape
+    c = log2_quant(p_rows, qmax).astype(np.int64)
+    wgt = np.left_shift(np.int64(1), qmax - c)                # 2^(qmax-c)
+    keep = np.arange(S)[None, :] < np.asarray(n_valid, dtype=np.int64)[:, None]
+    wgt = np.where(keep, wgt, 0)
+    A = wgt @ np.asarray(vq_h, dtype=np.int64)
+    if A.size and max(int(A.max()), -int(A.min())) > INT32_MAX:
+        raise OverflowError("accumulator leaves int32")
+    return A
+
+
+def attn_v_log2(p, vq, e_v: int, qmax: int, causal: bool = True):
+    """Softmax output quantized by Eq.3 and multiplied with the int8 value matrix
+    (Section 5.1: log2 quantization for the softmax activation; Section 3.3:
+    the attention-times-V product).
+
+    p  : fp16 [H, S, S], row i = query i.  With `causal`, entries j > i are
+         neither quantized nor multiplied.
+    vq : int8 [H, S, D] on the grid of Eq.2 with scale 2^e_v.
+    Returns (A, O):  A[h,i,d] = sum_j 2^(qmax - c[h,i,j]) * vq[h,j,d]  (int64,
+    asserted < 2^31), and O[i, h*D + d] = fp16( A * 2^(e_v - qmax) )."""
+    p = np.asarray(p)
+    vq = np.asarray(vq)
+    H, S, S2 = p.shape
+    if S != S2 or vq.shape[:2] != (H, S):
+        raise ValueError("shape mismatch")
+    D = vq.shape[2]
+    n_valid = np.arange(1, S + 1) if causal else np.full(S, S)
+    A = np.stack([attn_v_rows(p[h], n_valid, vq[h], qmax) for h in range(H)])
+    O = np.ldexp(A.astype(np.float64), int(e_v) - int(qmax))  # exact
+    with np.errstate(over="ignore"):
+        O = O.astype(np.float16)
+    return A, np.ascontiguousarray(O.transpose(1, 0, 2).reshape(S, H * D))
+
+
+def log2_codes_packed(p, qmax: int, causal: bool = True) -> np.ndarray:
+    """The 4-bit codes of Eq.3, two per byte (low nibble = even j).  With
+    `causal`, entries j > i carry code qmax (they stand for probability 0)."""
+    p = np.asarray(p)
+    c = log2_quant(p, qmax)
+    if causal:
+        S = p.shape[-1]
+        c = np.where(np.tril(np.ones((S, S), dtype=bool))[None], c, qmax)
+    return pack_nibbles(c)
+
+
+# --------------------------------------------------------------------------
+# token importance and pruning (Section 4.3, Eq.4; Section 5.2, Eq.9)
+# --------------------------------------------------------------------------
+
+def start_token_score(p) -> np.ndarray:
+    """Importance of token i = its attention to the first (start) token
+    (Section 4.3), summed over heads on the unquantized map.  Returned as the
+    exact integer sum_h p[h,i,0] * 2^24 (every fp16 value times 2^24 is an
+    integer), so the ranking has no rounding in it."""
+    col = np.ldexp(_as_f64(np.asarray(p)[:, :, 0]), 24)
+    t = col.sum(axis=0)
+    assert np.all(t == np.floor(t))
+    return t.astype(np.int64)
+
+
+def progressive_ratio(beta: float, m: int) -> float:
+    """Section 5.2, Eq.9: gamma = 1 - (1 - beta)^(1/m)."""
+    return 1.0 - (1.0 - beta) ** (1.0 / m)
+
+
+def n_keep(S: int, gamma: float) -> int:
+    """Tokens that survive one pruning stage of ratio gamma: S - floor(S*gamma)."""
+    return S - int(np.floor(S * gamma))
+
+
+def prune_select(score, keep: int) -> np.ndarray:
+    """Section 4.3, Eq.4: indices of the `keep` most important tokens; equal
+    scores go to the lower index; the survivors stay in their original order."""
+    score = np.asarray(score, dtype=np.int64)
+    S = score.shape[0]
+    if keep < 0 or keep > S:
+        raise ValueError("keep outside 0..S")
+    order = sorted(range(S), key=lambda i: (-int(score[i]), i))
+    return np.array(sorted(order[:keep]), dtype=np.int32)
+
+
+def prune_tokens(score, keep: int, x):
+    """Eq.4: X^P = F^P(X), the rows of x at `prune_select`'s indices."""
+    idx = prune_select(score, keep)
+    return idx, np.asarray(x)[idx]
+
+
+# --------------------------------------------------------------------------
+# the same integer contraction in plain C (for sizes numpy's int64 is slow at)
+# --------------------------------------------------------------------------
+
+def gemm_int_c(q, wq, threads: int = 1) -> np.ndarray:
+    """`gemm_int` with zp = 0 through the plain-C loops of agq_oracle_gemm.c
+    (loop order m, n, k; 64-bit running sum checked against int32).  Needs
+    oracle/build.py to have been run.  Returns int32 [M, N]."""
+    import ctypes
+    import os
+    lib = ctypes.CDLL(os.path.join(os.path.dirname(os.path.abspath(__file__)), "libagq_oracle.so"))
+    q = np.ascontiguousarray(q, dtype=np.int8)
+    wq = np.ascontiguousarray(wq, dtype=np.int8)
+    M, K = q.shape
+    N, K2 = wq.shape
+    if K != K2:
+        raise ValueError("K mismatch")
+    acc = np.empty((M, N), dtype=np.int32)
+    fn = lib.agq_oracle_gemm_i8
+    fn.restype = ctypes.c_int
+    fn.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int64, ctypes.c_int64,
+                   ctypes.c_int64, ctypes.c_void_p, ctypes.c_int]
+    bad = fn(q.ctypes.data, wq.ctypes.data, M, N, K, acc.ctypes.data, int(threads))
+    if bad:
+        raise OverflowError("accumulator leaves int32")
+    return acc
+
+
+def c_max_threads() -> int:
+    import ctypes
+    import os
+    lib = ctypes.CDLL(os.path.join(os.path.dirname(os.path.abspath(__file__)), "libagq_oracle.so"))
+    lib.agq_oracle_max_threads.restype = ctypes.c_int
+    return int(lib.agq_oracle_max_threads())
