@@ -1,0 +1,142 @@
+/* agq - the W4A8 / W4A4 quantized linear layer of Agile-Quant (arxiv 2312.05693)
+ * and its log2-quantized softmax x V path, as HIP kernels for gfx950 (MI355X).
+ *
+ * C ABI.  Conventions that hold for every call unless a comment says otherwise:
+ *   - every tensor pointer is a DEVICE pointer owned by the caller; the library
+ *     allocates nothing and keeps no state between calls;
+ *   - tensors are row-major, leading dimensions are in elements;
+ *   - work is enqueued asynchronously on `stream` (a hipStream_t passed as
+ *     void*, NULL = the default stream); the caller synchronises;
+ *   - the return value is an agq_status: 0 on success, negative on error.
+ *     Argument errors (AGQ_EINVAL, AGQ_ESIZE) are found on the host before any
+ *     HIP call is made; AGQ_EHIP reports a failed launch.  Nothing is printed,
+ *     thrown or aborted;
+ *   - fp16 inputs must not hold NaN (a NaN yields an unspecified code inside
+ *     the grid); +-Inf saturate.
+ */
+#ifndef AGQ_H
+#define AGQ_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum agq_status {
+    AGQ_OK = 0,
+    AGQ_EINVAL = -1, /* bad argument (null pointer, size, granularity, range) */
+    AGQ_ESIZE = -2,  /* workspace too small                                    */
+    AGQ_EHIP = -3    /* the HIP runtime refused a launch                       */
+};
+
+/* what `x` of the GEMM calls holds */
+enum agq_x_kind {
+    AGQ_X_F16 = 0, /* fp16 [M,K]; Eq.2 is applied inside the call            */
+    AGQ_X_Q = 1    /* codes written by agq_quantize_act with the same
+                      bits / e / zp: int8 [M,K] (8 bit) or nibbles [M,K/2]   */
+};
+
+/* range of the activation exponent e (scale s = 2^e) accepted everywhere */
+#define AGQ_E_MIN (-40)
+#define AGQ_E_MAX 40
+
+const char *agq_status_string(int status);
+int agq_version(void);
+
+/* Layer-wise power-of-two activation scale (Section 4.4: all channels share one
+ * set of quantization parameters; the scale is read as a power of two).
+ * Writes to *e_dev (device int32) the smallest e with max|x| <= qmax * 2^e,
+ * qmax = 2^(bits-1)-1; 0 for an all-zero tensor; +-Inf/NaN count as 2^16.
+ * x_f16: fp16 [M,K], ldx >= K.  bits in {4,8}.  M*K may be 0 (e = 0).        */
+int agq_calibrate_act_exp(const void *x_f16, int64_t M, int64_t K, int64_t ldx,
+                          int bits, int32_t *e_dev, void *stream);
+
+/* Uniform quantizer, Section 4.1 Eq.2, with s = 2^e and round-half-to-even:
+ *   q = CLIP(round(x / 2^e) + zp, lo, hi)
+ * zp == 0 selects the signed grid of Eq.1, [-2^(b-1), 2^(b-1)-1]; zp > 0 the
+ * unsigned grid [0, 2^b-1] of Eq.2 as printed.  bits in {4,8}.
+ * x_f16 : fp16 [M,K], ldx >= K, ldx % 8 == 0, 16-byte aligned; K % 8 == 0.
+ * xq_out: bits=8: one byte per code, [M,K] contiguous (int8, or uint8 if zp>0);
+ *         bits=4: two codes per byte, [M,K/2] contiguous, low nibble = even k,
+ *         signed codes in two's complement.
+ * M == 0 is a no-op.                                                          */
+int agq_quantize_act(const void *x_f16, int64_t M, int64_t K, int64_t ldx,
+                     int bits, int e, int zp, void *xq_out, void *stream);
+
+/* 4-bit weight storage (Section 4.4 stores two 4-bit weights per byte).  The
+ * order of nibbles inside `packed` is private to the library: it is laid out
+ * for 64-lane coalesced loads and the int8 MFMA operand order.  Only
+ * agq_unpack_w4(agq_pack_w4(W)) == W is contractual.
+ * wq     : int8 [N,K], K contiguous, values in [-8,7]; K % 128 == 0, N >= 1.
+ *          Values outside [-8,7] are saturated and counted into *bad_count_dev
+ *          (device int32, may be NULL; the caller zeroes it and reads it after
+ *          synchronising).
+ * packed : agq_pack_w4_bytes(N,K) bytes, 16-byte aligned (0 = invalid N,K).   */
+size_t agq_pack_w4_bytes(int64_t N, int64_t K);
+int agq_pack_w4(const int8_t *wq, int64_t N, int64_t K, void *packed,
+                int32_t *bad_count_dev, void *stream);
+int agq_unpack_w4(const void *packed, int64_t N, int64_t K, int8_t *wq_out,
+                  void *stream);
+
+/* The quantized linear layer (Sections 4.2 and 4.4): the activation on the
+ * b-bit grid of Eq.2 with the layer-wise scale 2^e, times the 4-bit weights,
+ * accumulated in int32, dequantized per output channel:
+ *   acc[m,n] = sum_k q[m,k] * Wq[n,k]              (int32, exact)
+ *   y[m,n]   = fp16( float(acc[m,n]) * (2^e * sw[n]) )
+ * agq_gemm_w4a8 uses b = 8, agq_gemm_w4a4 b = 4 (codes widened to int8 for the
+ * MFMA; CDNA4 has no 4-bit matrix instruction).
+ * x        : see agq_x_kind.  fp16: ldx % 8 == 0; codes: ldx in code units,
+ *            ldx % 16 == 0 (8 bit) or ldx % 32 == 0 (4 bit); 16-byte aligned.
+ * zp       : must be 0 (signed grid); other values return AGQ_EINVAL.
+ * w_packed : output of agq_pack_w4 for [N,K].   w_scale_f16: fp16 [N].
+ * y_f16    : fp16 [M,N], ldy >= N.   acc_out: optional int32 [M,N] contiguous
+ *            copy of the accumulators (NULL to skip).
+ * workspace: agq_gemm_workspace_bytes(M,N,K) bytes, 16-byte aligned, may be
+ *            NULL when that is 0.  Holds the quantized activation when M is
+ *            large enough for the tiled kernel; contents are scratch.
+ * K % 128 == 0, K <= 65536 (keeps every partial sum inside int32), M >= 0.    */
+size_t agq_gemm_workspace_bytes(int64_t M, int64_t N, int64_t K);
+int agq_gemm_w4a8(const void *x, int x_kind, int64_t M, int64_t K, int64_t ldx,
+                  int e, int zp, const void *w_packed, const void *w_scale_f16,
+                  int64_t N, void *y_f16, int64_t ldy, int32_t *acc_out,
+                  void *workspace, size_t workspace_bytes, void *stream);
+int agq_gemm_w4a4(const void *x, int x_kind, int64_t M, int64_t K, int64_t ldx,
+                  int e, int zp, const void *w_packed, const void *w_scale_f16,
+                  int64_t N, void *y_f16, int64_t ldy, int32_t *acc_out,
+                  void *workspace, size_t workspace_bytes, void *stream);
+
+/* Log2 quantizer on softmax probabilities (Section 4.1 Eq.3 with max|X| = 1,
+ * used for the softmax output per Section 5.1) fused with the product with the
+ * int8 value matrix, plus the token importance of Section 4.3 (attention paid
+ * to the first token):
+ *   c[h,i,j]  = CLIP(round(-log2 p[h,i,j]), 0, qmax)            (p = 0 -> qmax)
+ *   o[i,h*D+d]= fp16( 2^(e_v-qmax) * sum_j 2^(qmax-c[h,i,j]) * v_q[h,j,d] )
+ *   score[i]  = sum_h p[h,i,0] * 2^24                           (exact integer)
+ * p_f16   : fp16 [H,S,S] in [0,1], row i = query i; causal != 0 reads j <= i only.
+ * qmax    : 15 (all four bits carry magnitude) or 7 (Eq.3's 2^(b-1)-1, b = 4).
+ * v_q     : int8 [H,S,D], scale 2^e_v;  D % 16 == 0, D <= 256;  S % 8 == 0.
+ * o_f16   : fp16 [S, H*D].   codes_out: optional [H,S,S/2] bytes, two codes per
+ *           byte, low nibble = even j, entries above the diagonal carry qmax.
+ * score_out: optional int32 [S]; needs H <= 127.
+ * Precondition: rows are softmax outputs (sum <= ~1), which keeps the integer
+ * sum below 2^24; arbitrary inputs may lose low bits.                         */
+int agq_log2_quant_softmax(const void *p_f16, int64_t H, int64_t S, int64_t D,
+                           int causal, int qmax, const int8_t *v_q, int e_v,
+                           void *o_f16, void *codes_out, int32_t *score_out,
+                           void *stream);
+
+/* Token pruning, Section 4.3 Eq.4: keep the n_keep tokens with the largest
+ * score (equal scores: lower index first), in their original order.
+ * score  : int32 [S], S <= 16384.   x_f16: fp16 [S,d] contiguous, d % 8 == 0.
+ * idx_out: int32 [n_keep] ascending.  x_out_f16: fp16 [n_keep,d].
+ * 0 <= n_keep <= S.                                                           */
+int agq_prune_tokens(const int32_t *score, int64_t S, int64_t n_keep,
+                     const void *x_f16, int64_t d, int32_t *idx_out,
+                     void *x_out_f16, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* AGQ_H */

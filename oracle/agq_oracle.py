@@ -201,18 +201,22 @@ def log2_quant(p, qmax: int) -> np.ndarray:
 def attn_v_rows(p_rows, n_valid, vq_h, qmax: int) -> np.ndarray:
     """Rows of the product of Eq.3's codes with one head's value matrix:
     A[r,d] = sum_{j < n_valid[r]} 2^(qmax - c[r,j]) * vq_h[j,d], c = Eq.3 of
-    p_rows[r,j].  p_rows fp16 [R,S], vq_h int8 [S,D], n_valid int [R].  int64,
+    p_rows[r,j].  p_rows fp16 [R,S], vq_h int8 [S,D], n_valid int [R].
+    The matrix product runs in float64, where it is exact: every term is an
+    integer below 2^23 and a row has at most 2^30 of them.  Returned as int64,
     asserted to fit int32."""
     p_rows = np.asarray(p_rows)
     R, S = p_rows.shape
-    c = log2_quant(p_rows, qmax).astype(np.int64)
-    wgt = np.left_shift(np.int64(1), qmax - c)                # 2^(qmax-c)
+    if S >= (1 << 30):
+        raise ValueError("row too long for an exact float64 sum")
+    c = log2_quant(p_rows, qmax)
+    wgt = np.ldexp(1.0, qmax - c)                             # 2^(qmax-c), exact
     keep = np.arange(S)[None, :] < np.asarray(n_valid, dtype=np.int64)[:, None]
-    wgt = np.where(keep, wgt, 0)
-    A = wgt @ np.asarray(vq_h, dtype=np.int64)
-    if A.size and max(int(A.max()), -int(A.min())) > INT32_MAX:
+    wgt = np.where(keep, wgt, 0.0)
+    A = wgt @ np.asarray(vq_h, dtype=np.float64)
+    if A.size and float(np.abs(A).max()) > INT32_MAX:
         raise OverflowError("accumulator leaves int32")
-    return A
+    return A.astype(np.int64)
 
 
 def attn_v_log2(p, vq, e_v: int, qmax: int, causal: bool = True):

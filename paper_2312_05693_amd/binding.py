@@ -1,0 +1,160 @@
+"""ctypes binding of libagq.so with the names of include/agq.h.
+
+Argument marshalling only: every step of the path runs in the HIP kernels.
+PyTorch is used for device memory and the current stream, nothing else.  There
+is no CPU fallback: if the library has not been built, loading raises."""
+from __future__ import annotations
+
+import ctypes
+import os
+
+import torch
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(HERE, "libagq.so")
+
+AGQ_OK, AGQ_EINVAL, AGQ_ESIZE, AGQ_EHIP = 0, -1, -2, -3
+AGQ_X_F16, AGQ_X_Q = 0, 1
+
+_i64, _int, _vp, _sz = ctypes.c_int64, ctypes.c_int, ctypes.c_void_p, ctypes.c_size_t
+_GEMM_ARGS = [_vp, _int, _i64, _i64, _i64, _int, _int, _vp, _vp, _i64, _vp, _i64, _vp, _vp, _sz, _vp]
+SIGNATURES = {
+    "agq_status_string": (ctypes.c_char_p, [_int]),
+    "agq_version": (_int, []),
+    "agq_calibrate_act_exp": (_int, [_vp, _i64, _i64, _i64, _int, _vp, _vp]),
+    "agq_quantize_act": (_int, [_vp, _i64, _i64, _i64, _int, _int, _int, _vp, _vp]),
+    "agq_pack_w4_bytes": (_sz, [_i64, _i64]),
+    "agq_pack_w4": (_int, [_vp, _i64, _i64, _vp, _vp, _vp]),
+    "agq_unpack_w4": (_int, [_vp, _i64, _i64, _vp, _vp]),
+    "agq_gemm_workspace_bytes": (_sz, [_i64, _i64, _i64]),
+    "agq_gemm_w4a8": (_int, _GEMM_ARGS),
+    "agq_gemm_w4a4": (_int, _GEMM_ARGS),
+    "agq_log2_quant_softmax": (_int, [_vp, _i64, _i64, _i64, _int, _int, _vp, _int, _vp, _vp, _vp, _vp]),
+    "agq_prune_tokens": (_int, [_vp, _i64, _i64, _vp, _i64, _vp, _vp, _vp]),
+}
+
+_lib = None
+
+
+class AgqError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__("%s: %s (%d)" % (where, lib().agq_status_string(status).decode(), status))
+
+
+def lib() -> ctypes.CDLL:
+    """The loaded C-ABI library; raises if it has not been built."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError("libagq.so is missing: run paper_2312_05693_amd/build.py (no CPU fallback exists)")
+        handle = ctypes.CDLL(LIB_PATH)
+        for name, (res, args) in SIGNATURES.items():
+            fn = getattr(handle, name)
+            fn.restype, fn.argtypes = res, args
+        _lib = handle
+    return _lib
+
+
+def _ptr(t):
+    return None if t is None else t.data_ptr()
+
+
+def _stream():
+    return torch.cuda.current_stream().cuda_stream
+
+
+def _ok(status: int, where: str):
+    if status != AGQ_OK:
+        raise AgqError(status, where)
+
+
+def version() -> int:
+    return lib().agq_version()
+
+
+def calibrate_act_exp(x: torch.Tensor, bits: int, e_dev: torch.Tensor | None = None) -> torch.Tensor:
+    """Device int32 tensor holding e (read it with .item() after the call)."""
+    M, K = x.shape
+    if e_dev is None:
+        e_dev = torch.empty(1, dtype=torch.int32, device=x.device)
+    _ok(lib().agq_calibrate_act_exp(_ptr(x), M, K, x.stride(0), bits, _ptr(e_dev), _stream()), "agq_calibrate_act_exp")
+    return e_dev
+
+
+def quantize_act(x: torch.Tensor, bits: int, e: int, zp: int = 0, out: torch.Tensor | None = None) -> torch.Tensor:
+    M, K = x.shape
+    if out is None:
+        cols = K if bits == 8 else K // 2
+        out = torch.empty((M, cols), dtype=torch.uint8 if (zp or bits == 4) else torch.int8, device=x.device)
+    _ok(lib().agq_quantize_act(_ptr(x), M, K, x.stride(0), bits, e, zp, _ptr(out), _stream()), "agq_quantize_act")
+    return out
+
+
+def pack_w4_bytes(N: int, K: int) -> int:
+    return lib().agq_pack_w4_bytes(N, K)
+
+
+def pack_w4(wq: torch.Tensor, packed: torch.Tensor | None = None, bad_count: torch.Tensor | None = None):
+    N, K = wq.shape
+    if packed is None:
+        packed = torch.empty(pack_w4_bytes(N, K), dtype=torch.uint8, device=wq.device)
+    _ok(lib().agq_pack_w4(_ptr(wq), N, K, _ptr(packed), _ptr(bad_count), _stream()), "agq_pack_w4")
+    return packed
+
+
+def unpack_w4(packed: torch.Tensor, N: int, K: int) -> torch.Tensor:
+    out = torch.empty((N, K), dtype=torch.int8, device=packed.device)
+    _ok(lib().agq_unpack_w4(_ptr(packed), N, K, _ptr(out), _stream()), "agq_unpack_w4")
+    return out
+
+
+def gemm_workspace_bytes(M: int, N: int, K: int) -> int:
+    return lib().agq_gemm_workspace_bytes(M, N, K)
+
+
+def _gemm(fn_name, x, x_kind, M, K, ldx, e, zp, w_packed, w_scale, N, y, acc_out, workspace):
+    if y is None:
+        y = torch.empty((M, N), dtype=torch.float16, device=w_packed.device)
+    need = gemm_workspace_bytes(M, N, K)
+    if workspace is None and need:
+        workspace = torch.empty(need, dtype=torch.uint8, device=w_packed.device)
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    fn = getattr(lib(), fn_name)
+    _ok(fn(_ptr(x), x_kind, M, K, ldx, e, zp, _ptr(w_packed), _ptr(w_scale), N, _ptr(y), y.stride(0) if M else N,
+           _ptr(acc_out), _ptr(workspace), ws_bytes, _stream()), fn_name)
+    return y
+
+
+def gemm_w4a8(x, e, w_packed, w_scale, N, K, x_kind=AGQ_X_F16, y=None, acc_out=None, workspace=None, zp=0):
+    """x: fp16 [M,K] (AGQ_X_F16) or int8 codes [M,K] (AGQ_X_Q)."""
+    M = x.shape[0]
+    return _gemm("agq_gemm_w4a8", x, x_kind, M, K, x.stride(0) if M else K, e, zp, w_packed, w_scale, N, y, acc_out,
+                 workspace)
+
+
+def gemm_w4a4(x, e, w_packed, w_scale, N, K, x_kind=AGQ_X_F16, y=None, acc_out=None, workspace=None, zp=0):
+    """x: fp16 [M,K] (AGQ_X_F16) or nibble codes [M,K/2] bytes (AGQ_X_Q)."""
+    M = x.shape[0]
+    ldx = (x.stride(0) if M else K) * (2 if x_kind == AGQ_X_Q else 1)
+    return _gemm("agq_gemm_w4a4", x, x_kind, M, K, ldx, e, zp, w_packed, w_scale, N, y, acc_out, workspace)
+
+
+def log2_quant_softmax(p, v_q, e_v, qmax=15, causal=True, want_codes=False, want_score=True):
+    """p fp16 [H,S,S], v_q int8 [H,S,D] -> (o fp16 [S,H*D], codes or None, score or None)."""
+    H, S, _ = p.shape
+    D = v_q.shape[2]
+    o = torch.empty((S, H * D), dtype=torch.float16, device=p.device)
+    codes = torch.empty((H, S, S // 2), dtype=torch.uint8, device=p.device) if want_codes else None
+    score = torch.empty(S, dtype=torch.int32, device=p.device) if want_score else None
+    _ok(lib().agq_log2_quant_softmax(_ptr(p), H, S, D, int(causal), qmax, _ptr(v_q), e_v, _ptr(o), _ptr(codes),
+                                     _ptr(score), _stream()), "agq_log2_quant_softmax")
+    return o, codes, score
+
+
+def prune_tokens(score, n_keep, x):
+    S, d = x.shape
+    idx = torch.empty(n_keep, dtype=torch.int32, device=x.device)
+    out = torch.empty((n_keep, d), dtype=torch.float16, device=x.device)
+    _ok(lib().agq_prune_tokens(_ptr(score), S, n_keep, _ptr(x), d, _ptr(idx), _ptr(out), _stream()), "agq_prune_tokens")
+    return idx, out

@@ -1,0 +1,147 @@
+// The C ABI of include/agq.h: argument checks on the host (before any HIP
+// call), then dispatch to the kernel launchers.
+#include "../../include/agq.h"
+#include "agq_internal.h"
+
+#define AGQ_VERSION 1
+
+namespace {
+
+inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; }
+inline bool bits_ok(int bits) { return bits == 4 || bits == 8; }
+inline bool e_ok(int e) { return e >= AGQ_E_MIN && e <= AGQ_E_MAX; }
+inline int hip_status(int err) { return err == 0 ? AGQ_OK : AGQ_EHIP; }
+constexpr int64_t kMaxDim = (int64_t)1 << 30;
+
+int gemm_w4(int bits, const void *x, int x_kind, int64_t M, int64_t K, int64_t ldx, int e, int zp,
+            const void *w_packed, const void *sw, int64_t N, void *y, int64_t ldy, int32_t *acc_out,
+            void *workspace, size_t workspace_bytes, void *stream) {
+    if (M < 0 || M > kMaxDim || N < 1 || N > kMaxDim || K < 128 || K > 65536 || (K % 128) != 0) return AGQ_EINVAL;
+    if (x_kind != AGQ_X_F16 && x_kind != AGQ_X_Q) return AGQ_EINVAL;
+    if (!e_ok(e) || zp != 0) return AGQ_EINVAL;
+    if (ldx < K || ldy < N) return AGQ_EINVAL;
+    if (x_kind == AGQ_X_F16 && (ldx % 8) != 0) return AGQ_EINVAL;
+    if (x_kind == AGQ_X_Q && (ldx % (bits == 8 ? 16 : 32)) != 0) return AGQ_EINVAL;
+    if (M == 0) return AGQ_OK;
+    if (!x || !w_packed || !sw || !y) return AGQ_EINVAL;
+    if (!aligned16(x) || !aligned16(w_packed)) return AGQ_EINVAL;
+    const size_t need = agq_gemm_workspace_bytes(M, N, K);
+    if (need > 0) {
+        if (!workspace || !aligned16(workspace)) return AGQ_EINVAL;
+        if (workspace_bytes < need) return AGQ_ESIZE;
+    }
+    if (M <= AGQ_DECODE_MAX_M)
+        return hip_status(agq_launch_gemm_decode(x, x_kind, bits, M, K, ldx, e, w_packed, sw, N, y, ldy, acc_out, stream));
+
+    const int8_t *xq = static_cast<const int8_t *>(x);
+    int64_t ldq = ldx;
+    if (x_kind == AGQ_X_F16) {
+        int err = agq_launch_quantize(x, M, K, ldx, bits, e, 0, workspace, K, 8, stream);
+        if (err) return AGQ_EHIP;
+        xq = static_cast<const int8_t *>(workspace);
+        ldq = K;
+    } else if (bits == 4) {
+        int err = agq_launch_widen4(x, M, K, ldx, workspace, K, stream);
+        if (err) return AGQ_EHIP;
+        xq = static_cast<const int8_t *>(workspace);
+        ldq = K;
+    }
+    return hip_status(agq_launch_gemm_tiled(xq, ldq, M, K, e, w_packed, sw, N, y, ldy, acc_out, stream));
+}
+
+}  // namespace
+
+extern "C" {
+
+const char *agq_status_string(int status) {
+    switch (status) {
+        case AGQ_OK: return "ok";
+        case AGQ_EINVAL: return "invalid argument";
+        case AGQ_ESIZE: return "workspace too small";
+        case AGQ_EHIP: return "HIP launch failed";
+        default: return "unknown status";
+    }
+}
+
+int agq_version(void) { return AGQ_VERSION; }
+
+int agq_calibrate_act_exp(const void *x_f16, int64_t M, int64_t K, int64_t ldx, int bits, int32_t *e_dev,
+                          void *stream) {
+    if (M < 0 || K < 0 || M > kMaxDim || K > kMaxDim || !bits_ok(bits) || !e_dev) return AGQ_EINVAL;
+    if ((K % 8) != 0 || ldx < K || (ldx % 8) != 0) return AGQ_EINVAL;
+    if (M * K > 0 && (!x_f16 || !aligned16(x_f16))) return AGQ_EINVAL;
+    return hip_status(agq_launch_calibrate(x_f16, M, K, ldx, bits, e_dev, stream));
+}
+
+int agq_quantize_act(const void *x_f16, int64_t M, int64_t K, int64_t ldx, int bits, int e, int zp, void *xq_out,
+                     void *stream) {
+    if (M < 0 || K < 0 || M > kMaxDim || K > kMaxDim || !bits_ok(bits) || !e_ok(e)) return AGQ_EINVAL;
+    if (zp < 0 || zp > (1 << bits) - 1) return AGQ_EINVAL;
+    if ((K % 8) != 0 || ldx < K || (ldx % 8) != 0) return AGQ_EINVAL;
+    if (M * K == 0) return AGQ_OK;
+    if (!x_f16 || !xq_out || !aligned16(x_f16) || !aligned16(xq_out)) return AGQ_EINVAL;
+    const int64_t ld_out = bits == 8 ? K : K / 2;
+    return hip_status(agq_launch_quantize(x_f16, M, K, ldx, bits, e, zp, xq_out, ld_out, bits, stream));
+}
+
+size_t agq_pack_w4_bytes(int64_t N, int64_t K) {
+    if (N < 1 || N > kMaxDim || K < 128 || K > 65536 || (K % 128) != 0) return 0;
+    return (size_t)agq_n_tiles_padded(N) * (size_t)agq_k_tiles(K) * 1024;
+}
+
+int agq_pack_w4(const int8_t *wq, int64_t N, int64_t K, void *packed, int32_t *bad_count_dev, void *stream) {
+    if (agq_pack_w4_bytes(N, K) == 0 || !wq || !packed) return AGQ_EINVAL;
+    if (!aligned16(wq) || !aligned16(packed)) return AGQ_EINVAL;
+    return hip_status(agq_launch_pack(wq, N, K, packed, bad_count_dev, stream));
+}
+
+int agq_unpack_w4(const void *packed, int64_t N, int64_t K, int8_t *wq_out, void *stream) {
+    if (agq_pack_w4_bytes(N, K) == 0 || !wq_out || !packed) return AGQ_EINVAL;
+    if (!aligned16(wq_out) || !aligned16(packed)) return AGQ_EINVAL;
+    return hip_status(agq_launch_unpack(packed, N, K, wq_out, stream));
+}
+
+size_t agq_gemm_workspace_bytes(int64_t M, int64_t N, int64_t K) {
+    (void)N;
+    if (M <= AGQ_DECODE_MAX_M || K < 1) return 0;
+    return ((size_t)M * (size_t)K + 255) & ~(size_t)255;
+}
+
+int agq_gemm_w4a8(const void *x, int x_kind, int64_t M, int64_t K, int64_t ldx, int e, int zp, const void *w_packed,
+                  const void *w_scale_f16, int64_t N, void *y_f16, int64_t ldy, int32_t *acc_out, void *workspace,
+                  size_t workspace_bytes, void *stream) {
+    return gemm_w4(8, x, x_kind, M, K, ldx, e, zp, w_packed, w_scale_f16, N, y_f16, ldy, acc_out, workspace,
+                   workspace_bytes, stream);
+}
+
+int agq_gemm_w4a4(const void *x, int x_kind, int64_t M, int64_t K, int64_t ldx, int e, int zp, const void *w_packed,
+                  const void *w_scale_f16, int64_t N, void *y_f16, int64_t ldy, int32_t *acc_out, void *workspace,
+                  size_t workspace_bytes, void *stream) {
+    return gemm_w4(4, x, x_kind, M, K, ldx, e, zp, w_packed, w_scale_f16, N, y_f16, ldy, acc_out, workspace,
+                   workspace_bytes, stream);
+}
+
+int agq_log2_quant_softmax(const void *p_f16, int64_t H, int64_t S, int64_t D, int causal, int qmax,
+                           const int8_t *v_q, int e_v, void *o_f16, void *codes_out, int32_t *score_out,
+                           void *stream) {
+    if (H < 1 || H > 65535 || S < 8 || S > kMaxDim || (S % 8) != 0 || D < 16 || D > 256 || (D % 16) != 0)
+        return AGQ_EINVAL;
+    if (qmax != 15 && qmax != 7) return AGQ_EINVAL;
+    if (!e_ok(e_v) || !p_f16 || !v_q || !o_f16) return AGQ_EINVAL;
+    if (score_out && H > 127) return AGQ_EINVAL;
+    if (!aligned16(p_f16) || !aligned16(v_q) || !aligned16(o_f16)) return AGQ_EINVAL;
+    if (codes_out && !aligned16(codes_out)) return AGQ_EINVAL;
+    return hip_status(agq_launch_log2_attn(p_f16, H, S, D, causal != 0, qmax, v_q, e_v, o_f16, codes_out, score_out,
+                                           stream));
+}
+
+int agq_prune_tokens(const int32_t *score, int64_t S, int64_t n_keep, const void *x_f16, int64_t d,
+                     int32_t *idx_out, void *x_out_f16, void *stream) {
+    if (S < 1 || S > 16384 || n_keep < 0 || n_keep > S || d < 8 || d > kMaxDim || (d % 8) != 0) return AGQ_EINVAL;
+    if (!score || !x_f16) return AGQ_EINVAL;
+    if (n_keep == 0) return AGQ_OK;
+    if (!idx_out || !x_out_f16 || !aligned16(x_f16) || !aligned16(x_out_f16)) return AGQ_EINVAL;
+    return hip_status(agq_launch_prune(score, S, n_keep, x_f16, d, idx_out, x_out_f16, stream));
+}
+
+}  // extern "C"

@@ -1,0 +1,28 @@
+// Host-side launcher prototypes; every launcher returns hipError_t as int.
+#pragma once
+#include <stddef.h>
+#include <stdint.h>
+
+// geometry of the packed weight blob (see agq_pack.hip)
+static inline int64_t agq_n_tiles_padded(int64_t N) { return ((N + 255) / 256) * 16; }  // 16-row tiles, padded to 256 rows
+static inline int64_t agq_k_tiles(int64_t K) { return K / 128; }
+
+// tokens up to which the weight-streaming kernel is used
+#define AGQ_DECODE_MAX_M 16
+
+int agq_launch_calibrate(const void *x, int64_t M, int64_t K, int64_t ldx, int bits, int32_t *e_dev, void *stream);
+int agq_launch_quantize(const void *x, int64_t M, int64_t K, int64_t ldx, int bits, int e, int zp,
+                        void *out, int64_t ld_out_bytes, int out_bits, void *stream);
+int agq_launch_widen4(const void *xq4, int64_t M, int64_t K, int64_t ldx, void *out, int64_t ld_out_bytes, void *stream);
+int agq_launch_pack(const int8_t *wq, int64_t N, int64_t K, void *packed, int32_t *bad, void *stream);
+int agq_launch_unpack(const void *packed, int64_t N, int64_t K, int8_t *wq, void *stream);
+int agq_launch_gemm_decode(const void *x, int x_kind, int bits, int64_t M, int64_t K, int64_t ldx, int e,
+                           const void *w_packed, const void *sw, int64_t N, void *y, int64_t ldy,
+                           int32_t *acc_out, void *stream);
+int agq_launch_gemm_tiled(const int8_t *xq, int64_t ldq, int64_t M, int64_t K, int e,
+                          const void *w_packed, const void *sw, int64_t N, void *y, int64_t ldy,
+                          int32_t *acc_out, void *stream);
+int agq_launch_log2_attn(const void *p, int64_t H, int64_t S, int64_t D, int causal, int qmax,
+                         const int8_t *vq, int e_v, void *o, void *codes, int32_t *score, void *stream);
+int agq_launch_prune(const int32_t *score, int64_t S, int64_t n_keep, const void *x, int64_t d,
+                     int32_t *idx, void *x_out, void *stream);

@@ -1,0 +1,110 @@
+"""Host-side checks of the C ABI that need no GPU: the library loads, exports
+every symbol include/agq.h declares, sizes are right, and every argument error
+is reported as a status before any HIP call is made."""
+from __future__ import annotations
+
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    from paper_2312_05693_amd import build
+    build.build(force=False)
+    from paper_2312_05693_amd import binding
+    return binding.lib()
+
+
+def test_exports_every_declared_symbol(lib):
+    from paper_2312_05693_amd import binding
+    header = open(os.path.join(ROOT, "include", "agq.h")).read()
+    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+    declared = set(re.findall(r"\b(agq_[a-z0-9_]+)\s*\(", header))
+    assert {"agq_quantize_act", "agq_pack_w4", "agq_gemm_w4a8", "agq_gemm_w4a4", "agq_log2_quant_softmax"} <= declared
+    for name in declared:
+        assert hasattr(lib, name), name
+    assert declared == set(binding.SIGNATURES)
+    assert lib.agq_version() >= 1
+    assert lib.agq_status_string(0) == b"ok"
+    assert lib.agq_status_string(-1) == b"invalid argument"
+
+
+def test_sizes(lib):
+    assert lib.agq_pack_w4_bytes(768, 768) == 768 * 768 // 2
+    assert lib.agq_pack_w4_bytes(4096, 4096) == 8388608
+    assert lib.agq_pack_w4_bytes(11008, 4096) == 22544384
+    assert lib.agq_pack_w4_bytes(4096, 11008) == 22544384
+    assert lib.agq_pack_w4_bytes(13824, 5120) == 35389440
+    assert lib.agq_pack_w4_bytes(100, 128) == 256 * 128 // 2          # rows padded to 256
+    assert lib.agq_pack_w4_bytes(16, 100) == 0                        # K must be a multiple of 128
+    assert lib.agq_pack_w4_bytes(0, 128) == 0
+    assert lib.agq_gemm_workspace_bytes(16, 4096, 4096) == 0
+    assert lib.agq_gemm_workspace_bytes(2048, 4096, 4096) == 2048 * 4096
+
+
+def test_argument_errors_need_no_gpu(lib):
+    EINVAL, ESIZE = -1, -2
+    p = ctypes.c_void_p(4096)       # plausible, aligned, never dereferenced: every call below fails validation
+    odd = ctypes.c_void_p(4100)
+    g = lib.agq_gemm_w4a8
+    ok_args = dict(x=p, kind=0, M=4, K=256, ldx=256, e=0, zp=0, w=p, sw=p, N=64, y=p, ldy=64, acc=None, ws=None, wsb=0, st=None)
+
+    def call(fn=g, **kw):
+        a = dict(ok_args, **kw)
+        return fn(a["x"], a["kind"], a["M"], a["K"], a["ldx"], a["e"], a["zp"], a["w"], a["sw"], a["N"], a["y"],
+                  a["ldy"], a["acc"], a["ws"], a["wsb"], a["st"])
+
+    assert call(x=None) == EINVAL
+    assert call(w=None) == EINVAL
+    assert call(sw=None) == EINVAL
+    assert call(y=None) == EINVAL
+    assert call(x=odd) == EINVAL
+    assert call(K=200) == EINVAL and call(K=0) == EINVAL and call(K=131072) == EINVAL
+    assert call(N=0) == EINVAL and call(M=-1) == EINVAL
+    assert call(ldx=128) == EINVAL and call(ldx=260) == EINVAL and call(ldy=32) == EINVAL
+    assert call(e=41) == EINVAL and call(e=-41) == EINVAL
+    assert call(zp=128) == EINVAL                    # asymmetric product is not built
+    assert call(kind=7) == EINVAL
+    assert call(kind=1, ldx=264) == EINVAL           # int8 codes need ldx % 16 == 0
+    assert call(fn=lib.agq_gemm_w4a4, kind=1, ldx=272) == EINVAL
+    assert call(M=64, ws=None) == EINVAL             # tiled kernel needs the workspace
+    assert call(M=64, ws=p, wsb=100) == ESIZE
+    assert call(M=0, x=None, y=None) == 0            # empty batch is a no-op
+
+    q = lib.agq_quantize_act
+    assert q(p, 4, 64, 64, 5, 0, 0, p, None) == EINVAL          # bits
+    assert q(p, 4, 60, 64, 8, 0, 0, p, None) == EINVAL          # K % 8
+    assert q(p, 4, 64, 32, 8, 0, 0, p, None) == EINVAL          # ldx < K
+    assert q(p, 4, 64, 64, 8, 0, 256, p, None) == EINVAL        # zp outside the grid
+    assert q(p, 4, 64, 64, 4, 0, 16, p, None) == EINVAL
+    assert q(None, 4, 64, 64, 8, 0, 0, p, None) == EINVAL
+    assert q(p, 0, 64, 64, 8, 0, 0, p, None) == 0               # no rows
+    assert lib.agq_calibrate_act_exp(p, 4, 64, 64, 8, None, None) == EINVAL
+    assert lib.agq_calibrate_act_exp(p, 4, 64, 64, 3, p, None) == EINVAL
+    assert lib.agq_pack_w4(p, 16, 100, p, None, None) == EINVAL
+    assert lib.agq_pack_w4(None, 16, 128, p, None, None) == EINVAL
+    assert lib.agq_unpack_w4(p, 16, 128, None, None) == EINVAL
+    a = lib.agq_log2_quant_softmax
+    assert a(p, 2, 64, 64, 1, 9, p, 0, p, None, None, None) == EINVAL     # qmax
+    assert a(p, 2, 60, 64, 1, 15, p, 0, p, None, None, None) == EINVAL    # S % 8
+    assert a(p, 2, 64, 72, 1, 15, p, 0, p, None, None, None) == EINVAL    # D % 16
+    assert a(p, 200, 64, 64, 1, 15, p, 0, p, None, p, None) == EINVAL     # score needs H <= 127
+    assert a(None, 2, 64, 64, 1, 15, p, 0, p, None, None, None) == EINVAL
+    pr = lib.agq_prune_tokens
+    assert pr(p, 64, 65, p, 64, p, p, None) == EINVAL
+    assert pr(p, 64, 8, p, 60, p, p, None) == EINVAL
+    assert pr(p, 20000, 8, p, 64, p, p, None) == EINVAL
+    assert pr(p, 64, 0, p, 64, None, None, None) == 0
+
+
+def test_binding_refuses_missing_library(monkeypatch):
+    from paper_2312_05693_amd import binding
+    monkeypatch.setattr(binding, "_lib", None)
+    monkeypatch.setattr(binding, "LIB_PATH", "/nonexistent/libagq.so")
+    with pytest.raises(RuntimeError):
+        binding.lib()

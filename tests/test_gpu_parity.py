@@ -1,0 +1,392 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU oracle on
+the same seeded inputs.  Integer results (codes, packed bytes, accumulators,
+indices) must be bit-exact; fp16 outputs must agree within 1e-3 relative (plus
+one fp16 subnormal step absolute), the tolerance of the benchmark spec - the
+kernel's float(acc) * g is rounded to fp32 and then to fp16, the oracle rounds
+the exact product once, so they differ by at most one fp16 ulp, rarely."""
+from __future__ import annotations
+
+import numpy as np
+import pytest
+
+torch = pytest.importorskip("torch")
+pytestmark = pytest.mark.gpu
+
+from paper_2312_05693_amd import synth  # noqa: E402
+
+REL_TOL = 1e-3
+ABS_TOL = 2.0 ** -24
+
+
+@pytest.fixture(scope="module")
+def agq():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    from paper_2312_05693_amd import binding
+    binding.lib()          # must load: there is no fallback
+    return binding
+
+
+def dev(a):
+    return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+
+def host(t):
+    torch.cuda.synchronize()
+    return t.cpu().numpy()
+
+
+def assert_f16_close(got, want, what=""):
+    got = np.asarray(got, dtype=np.float16)
+    want = np.asarray(want, dtype=np.float16)
+    assert got.shape == want.shape, what
+    g64, w64 = got.astype(np.float64), want.astype(np.float64)
+    fin = np.isfinite(w64)
+    assert np.array_equal(np.isfinite(g64), fin), what
+    assert np.array_equal(g64[~fin], w64[~fin]), what
+    err = np.abs(g64[fin] - w64[fin])
+    bound = REL_TOL * np.abs(w64[fin]) + ABS_TOL
+    assert np.all(err <= bound), "%s: max excess %g" % (what, float((err - bound).max()))
+    # and the disagreements are single-ulp, rare double-rounding cases
+    diff = got.view(np.int16).astype(np.int32)[fin] - want.view(np.int16).astype(np.int32)[fin]
+    assert np.abs(diff).max(initial=0) <= 1, what
+    assert (diff != 0).mean() <= 2e-3 if diff.size > 2000 else True, what
+
+
+def make_case(M, K, N, seed, n_out=4):
+    x = synth.make_activation(M, K, n_out, seed)
+    wq, sw = synth.make_weight_q4(N, K, seed)
+    return x, wq, sw
+
+
+# ------------------------------------------------------------------ pack / unpack
+
+def test_pack_roundtrip(agq, oracle):
+    rng = np.random.default_rng(0)
+    # every nibble value at every position of one 16 x 128 chunk, and ragged N
+    for N, K in ((16, 128), (40, 256), (256, 384), (300, 128)):
+        wq = rng.integers(-8, 8, size=(N, K)).astype(np.int8)
+        if N == 16:
+            wq = ((np.arange(N * K).reshape(N, K) * 7 + np.arange(N)[:, None]) % 16 - 8).astype(np.int8)
+        packed = agq.pack_w4(dev(wq))
+        assert packed.numel() == agq.pack_w4_bytes(N, K)
+        assert np.array_equal(host(agq.unpack_w4(packed, N, K)), wq)
+        # a 4-bit blob holds exactly the multiset of nibbles of W (plus zero padding)
+        nib = host(packed)
+        counts = np.bincount(np.concatenate([nib & 0xF, nib >> 4]), minlength=16)
+        want = np.bincount((wq.astype(np.int64) & 0xF).ravel(), minlength=16)
+        want[0] += nib.size * 2 - wq.size
+        assert np.array_equal(counts, want)
+    # out-of-range values are saturated and counted
+    wq = rng.integers(-8, 8, size=(16, 128)).astype(np.int8)
+    wq[3, 5], wq[9, 100], wq[0, 0] = 9, -100, 127
+    bad = torch.zeros(1, dtype=torch.int32, device="cuda")
+    packed = agq.pack_w4(dev(wq), bad_count=bad)
+    assert int(host(bad)[0]) == 3
+    assert np.array_equal(host(agq.unpack_w4(packed, 16, 128)), np.clip(wq, -8, 7))
+
+
+# ------------------------------------------------------------------ Eq.2
+
+def test_quantize_all_fp16_patterns(agq, oracle):
+    allh = np.arange(0x10000, dtype=np.uint16).view(np.float16)
+    x = allh[np.isfinite(allh.astype(np.float32)) | np.isinf(allh.astype(np.float32))]
+    x = x[~np.isnan(x.astype(np.float32))]
+    x = np.concatenate([x, np.zeros((-x.size) % 64, np.float16)]).reshape(-1, 64)
+    xd = dev(x)
+    for bits in (8, 4):
+        for e in (-8, -3, -1, 0, 1, 2, 7):
+            for zp in (0, 1 << (bits - 1), 3):
+                want = oracle.quantize_act(x, bits, e, zp)
+                got = host(agq.quantize_act(xd, bits, e, zp))
+                if bits == 8:
+                    got = got.astype(np.int32) if zp == 0 else got.view(np.uint8).astype(np.int32)
+                    assert np.array_equal(got, want), (bits, e, zp)
+                else:
+                    assert np.array_equal(got.view(np.uint8), oracle.pack_nibbles(want)), (bits, e, zp)
+
+
+def test_quantize_strided_and_edges(agq, oracle):
+    x = synth.make_activation(37, 200, 3, 4)            # K % 8 == 0, ragged rows
+    big = torch.zeros((37, 256), dtype=torch.float16, device="cuda")
+    big[:, :200] = dev(x)
+    view = big[:, :200]
+    got = host(agq.quantize_act(view, 8, -2, 0))
+    assert np.array_equal(got.astype(np.int32), oracle.quantize_act(x, 8, -2, 0))
+    empty = torch.zeros((0, 64), dtype=torch.float16, device="cuda")
+    assert agq.quantize_act(empty, 8, 0).shape == (0, 64)
+
+
+def test_calibrate(agq, oracle):
+    cases = [synth.make_activation(128, 768, 4, 0), synth.make_activation(1, 4096, 4, 1),
+             synth.make_activation(300, 1024, 11, 2), np.zeros((4, 64), np.float16),
+             (synth.make_activation(8, 64, 0, 3).astype(np.float32) * 1e-4).astype(np.float16),
+             np.full((2, 8), 127.0, np.float16), np.full((2, 8), 127.5, np.float16),
+             np.array([[np.inf] + [0] * 7], np.float16), np.full((1, 8), 6e-8, np.float16)]
+    for x in cases:
+        for bits in (8, 4):
+            e = int(host(agq.calibrate_act_exp(dev(x), bits))[0])
+            assert e == oracle.calibrate_act_exp(x, bits), (x.shape, bits)
+
+
+# ------------------------------------------------------------------ the linear layer
+
+def run_linear(agq, oracle, x, wq, sw, bits, x_kind="f16", e=None, check_y=True):
+    M, K = x.shape
+    N = wq.shape[0]
+    if e is None:
+        e = oracle.calibrate_act_exp(x, bits) if M else 0
+    acc_want, y_want = oracle.linear_w4(x, bits, e, 0, wq, sw)
+    packed = agq.pack_w4(dev(wq))
+    acc = torch.full((M, N), -12345, dtype=torch.int32, device="cuda")
+    fn = agq.gemm_w4a8 if bits == 8 else agq.gemm_w4a4
+    if x_kind == "f16":
+        xin, kind = dev(x), agq.AGQ_X_F16
+    else:
+        xin, kind = agq.quantize_act(dev(x), bits, e, 0), agq.AGQ_X_Q
+    y = fn(xin, e, packed, dev(sw), N, K, x_kind=kind, acc_out=acc)
+    assert np.array_equal(host(acc).astype(np.int64), acc_want), "accumulators differ"
+    if check_y:
+        assert_f16_close(host(y), y_want, "y")
+    return e
+
+
+@pytest.mark.parametrize("M", [1, 2, 3, 4, 5, 8, 13, 16])
+@pytest.mark.parametrize("K,N", [(128, 16), (256, 40), (768, 768), (1408, 272), (4096, 64)])
+def test_decode_small(agq, oracle, M, K, N):
+    x, wq, sw = make_case(M, K, N, seed=100 + M + K + N)
+    run_linear(agq, oracle, x, wq, sw, 8)
+
+
+@pytest.mark.parametrize("bits,x_kind", [(8, "q"), (4, "f16"), (4, "q")])
+@pytest.mark.parametrize("M,K,N", [(1, 256, 48), (7, 1024, 100), (16, 768, 256)])
+def test_decode_variants(agq, oracle, bits, x_kind, M, K, N):
+    x, wq, sw = make_case(M, K, N, seed=7 * M + K + N + bits)
+    run_linear(agq, oracle, x, wq, sw, bits, x_kind)
+
+
+@pytest.mark.parametrize("M", [17, 64, 128, 129, 200, 333])
+@pytest.mark.parametrize("K,N", [(128, 16), (384, 272), (768, 768), (1024, 500)])
+def test_tiled_small(agq, oracle, M, K, N):
+    x, wq, sw = make_case(M, K, N, seed=200 + M + K + N)
+    run_linear(agq, oracle, x, wq, sw, 8)
+
+
+@pytest.mark.parametrize("bits,x_kind", [(8, "q"), (4, "f16"), (4, "q")])
+def test_tiled_variants(agq, oracle, bits, x_kind):
+    x, wq, sw = make_case(150, 512, 300, seed=31 + bits)
+    run_linear(agq, oracle, x, wq, sw, bits, x_kind)
+
+
+def test_extreme_operands_hit_the_bound(agq, oracle):
+    # all codes at -128 and all weights at -8: acc = 128 * 8 * K exactly, the
+    # largest value the accumulator can take (times 16 inside the kernel)
+    for M in (3, 40):
+        K, N = 13824, 32
+        x = np.full((M, K), -128.0, np.float16)
+        wq = np.full((N, K), -8, np.int8)
+        sw = np.full(N, 2.0 ** -10, np.float16)
+        run_linear(agq, oracle, x, wq, sw, 8, e=0)
+
+
+def test_clipping_and_small_exponent(agq, oracle):
+    # an exponent that is too small for the data: codes saturate on both sides
+    x, wq, sw = make_case(9, 256, 64, seed=5)
+    run_linear(agq, oracle, x, wq, sw, 8, e=-4)
+    run_linear(agq, oracle, x, wq, sw, 4, e=-2)
+    x, wq, sw = make_case(70, 256, 64, seed=6)
+    run_linear(agq, oracle, x, wq, sw, 8, e=-4)
+
+
+def test_empty_batch(agq):
+    wq, sw = synth.make_weight_q4(16, 128, 1)
+    packed = agq.pack_w4(dev(wq))
+    x = torch.zeros((0, 128), dtype=torch.float16, device="cuda")
+    y = agq.gemm_w4a8(x, 0, packed, dev(sw), 16, 128)
+    assert y.shape == (0, 16)
+
+
+def test_deterministic_repeat(agq, oracle):
+    x, wq, sw = make_case(16, 4096, 4096, seed=9)
+    e = oracle.calibrate_act_exp(x, 8)
+    packed, xd, swd = agq.pack_w4(dev(wq)), dev(x), dev(sw)
+    first = host(agq.gemm_w4a8(xd, e, packed, swd, 4096, 4096)).copy()
+    for _ in range(20):
+        assert np.array_equal(host(agq.gemm_w4a8(xd, e, packed, swd, 4096, 4096)).view(np.uint16), first.view(np.uint16))
+
+
+# ------------------------------------------------------------------ the paper-shaped configurations
+
+def test_config0_opt125m_w4a8(agq, oracle):
+    # single W4A8 linear: X fp16 [128,768] with 4 outlier channels, W [768,768], seed 0
+    x, wq, sw = make_case(128, 768, 768, seed=0, n_out=4)
+    e = run_linear(agq, oracle, x, wq, sw, 8)
+    assert e in (-2, -1, 0)
+
+
+def sampled_linear(agq, oracle, M, K, N, bits, seed, n_out, rows):
+    """Full-size GEMM on the GPU in the benchmark's launch configuration; the
+    oracle computes whole sampled rows (its C loops), compared bit for bit."""
+    x, wq, sw = make_case(M, K, N, seed=seed, n_out=n_out)
+    e = oracle.calibrate_act_exp(x, bits)
+    packed = agq.pack_w4(dev(wq))
+    acc = torch.empty((M, N), dtype=torch.int32, device="cuda")
+    fn = agq.gemm_w4a8 if bits == 8 else agq.gemm_w4a4
+    y = fn(dev(x), e, packed, dev(sw), N, K, acc_out=acc)
+    acc_h, y_h = host(acc), host(y)
+    rows = sorted(set(min(r, M - 1) for r in rows))
+    q = oracle.quantize_act(x[rows], bits, e, 0).astype(np.int8)
+    want = oracle.gemm_int_c(q, wq, threads=oracle.c_max_threads())
+    assert np.array_equal(acc_h[rows], want)
+    assert_f16_close(y_h[rows], oracle.dequant_out(want, e, sw), "y")
+    # property that holds at any size: column sums of acc equal (sum of codes) @ Wq^T
+    qall = oracle.quantize_act(x, bits, e, 0).astype(np.int64)
+    colsum = qall.sum(axis=0) @ wq.T.astype(np.int64)
+    assert np.array_equal(acc_h.astype(np.int64).sum(axis=0), colsum)
+
+
+@pytest.mark.parametrize("M", [1, 4, 16])
+@pytest.mark.parametrize("K,N", [(4096, 4096), (4096, 11008), (11008, 4096)])
+def test_config1_llama7b_decode(agq, oracle, M, K, N):
+    sampled_linear(agq, oracle, M, K, N, 8, seed=1, n_out=4, rows=range(M))
+
+
+@pytest.mark.parametrize("K,N", [(4096, 4096), (4096, 11008), (11008, 4096)])
+def test_config2_llama7b_prefill_w4a8(agq, oracle, K, N):
+    rows = [0, 1, 15, 16, 127, 128, 1000, 1023, 1024, 2047] + list(range(500, 520))
+    sampled_linear(agq, oracle, 2048, K, N, 8, seed=2, n_out=synth.n_outlier_channels(K), rows=rows)
+
+
+@pytest.mark.parametrize("K,N", [(4096, 4096), (4096, 11008), (11008, 4096)])
+def test_config3_llama7b_prefill_w4a4(agq, oracle, K, N):
+    rows = [0, 63, 64, 1500, 2047] + list(range(700, 716))
+    sampled_linear(agq, oracle, 2048, K, N, 4, seed=3, n_out=synth.n_outlier_channels(K), rows=rows)
+
+
+# ------------------------------------------------------------------ Eq.3 path, pruning
+
+@pytest.mark.parametrize("H,S,D,qmax,causal", [(2, 64, 16, 15, True), (3, 128, 64, 15, True), (2, 192, 128, 7, True),
+                                                (1, 72, 32, 15, True), (2, 64, 128, 15, False), (1, 200, 48, 7, False)])
+def test_log2_attn_small(agq, oracle, H, S, D, qmax, causal):
+    p, v = synth.make_attention(H, S, D, seed=H + S + D)
+    if not causal:      # make the upper triangle meaningful too
+        p2, _ = synth.make_attention(H, S, D, seed=99)
+        p = (0.5 * p.astype(np.float32) + 0.5 * p2.astype(np.float32).transpose(0, 2, 1)).astype(np.float16)
+        p = np.minimum(p, np.float16(1.0))
+    e_v = oracle.calibrate_act_exp(v.reshape(H * S, D), 8)
+    vq = oracle.quantize_act(v.reshape(H * S, D), 8, e_v, 0).astype(np.int8).reshape(H, S, D)
+    A, O = oracle.attn_v_log2(p, vq, e_v, qmax, causal)
+    o, codes, score = agq.log2_quant_softmax(dev(p), dev(vq), e_v, qmax=qmax, causal=causal, want_codes=True)
+    assert np.array_equal(host(o).view(np.uint16), O.view(np.uint16))       # exact integers, one rounding
+    assert np.array_equal(host(codes), oracle.log2_codes_packed(p, qmax, causal))
+    assert np.array_equal(host(score).astype(np.int64), oracle.start_token_score(p))
+
+
+def test_log2_codes_all_fp16_probabilities(agq, oracle):
+    # every fp16 in [0,1] once, through the kernel's code output (non-causal rows)
+    vals = np.arange(0x3C00 + 1, dtype=np.uint16).view(np.float16)
+    S = 128
+    n = (vals.size + S - 1) // S
+    flat = np.concatenate([vals, np.zeros(n * S - vals.size, np.float16)])
+    H = (n + S - 1) // S
+    p = np.zeros((H, S, S), np.float16)
+    p.reshape(-1)[: flat.size] = flat
+    vq = np.zeros((H, S, 16), np.int8)
+    for qmax in (15, 7):
+        _, codes, _ = agq.log2_quant_softmax(dev(p), dev(vq), 0, qmax=qmax, causal=False, want_codes=True,
+                                             want_score=False)
+        assert np.array_equal(host(codes), oracle.log2_codes_packed(p, qmax, causal=False))
+
+
+@pytest.mark.parametrize("S,keep,d", [(64, 32, 64), (100, 1, 8), (257, 200, 40), (2048, 1024, 5120), (7, 7, 16)])
+def test_prune(agq, oracle, S, keep, d):
+    rng = np.random.default_rng(S + keep)
+    score = rng.integers(0, max(S // 3, 2), size=S).astype(np.int32)      # many ties
+    x = rng.standard_normal((S, d)).astype(np.float16)
+    idx, out = agq.prune_tokens(dev(score), keep, dev(x))
+    want_idx, want_x = oracle.prune_tokens(score, keep, x)
+    assert np.array_equal(host(idx), want_idx)
+    assert np.array_equal(host(out).view(np.uint16), want_x.view(np.uint16))
+
+
+def test_config4_attention_block_reduced(agq, oracle):
+    """Config 4 at a size the oracle finishes: heads x head_dim as LLaMA-13B
+    scaled down (H=4, D=128, S=256), top 50 % of tokens, then two W4A8
+    projections on the survivors."""
+    H, D, S = 4, 128, 256
+    hid, ffn = H * D, 1408
+    p, v = synth.make_attention(H, S, D, seed=4)
+    e_v = oracle.calibrate_act_exp(v.reshape(H * S, D), 8)
+    vq = oracle.quantize_act(v.reshape(H * S, D), 8, e_v, 0).astype(np.int8).reshape(H, S, D)
+    gamma = oracle.progressive_ratio(0.5, 1)
+    keep = oracle.n_keep(S, gamma)
+    # oracle chain
+    _, O = oracle.attn_v_log2(p, vq, e_v, 15, True)
+    t = oracle.start_token_score(p)
+    idx_w, xp = oracle.prune_tokens(t, keep, O)
+    w1, s1 = synth.make_weight_q4(hid, hid, 41)
+    w2, s2 = synth.make_weight_q4(ffn, hid, 42)
+    e1 = oracle.calibrate_act_exp(xp, 8)
+    _, y1 = oracle.linear_w4(xp, 8, e1, 0, w1, s1)
+    # GPU chain through the C ABI
+    o, _, score = agq.log2_quant_softmax(dev(p), dev(vq), e_v, qmax=15, causal=True)
+    idx, xg = agq.prune_tokens(score, keep, o)
+    assert np.array_equal(host(idx), idx_w)
+    assert np.array_equal(host(xg).view(np.uint16), xp.view(np.uint16))
+    eg = int(host(agq.calibrate_act_exp(xg, 8))[0])
+    assert eg == e1
+    acc1 = torch.empty((keep, hid), dtype=torch.int32, device="cuda")
+    yg1 = agq.gemm_w4a8(xg, eg, agq.pack_w4(dev(w1)), dev(s1), hid, hid, acc_out=acc1)
+    assert_f16_close(host(yg1), y1, "y1")
+    # second projection: fed with the oracle's y1 on both sides so that a legal
+    # 1-ulp difference in y1 cannot change a code of the next layer
+    e2 = oracle.calibrate_act_exp(y1, 8)
+    acc2_w, y2 = oracle.linear_w4(y1, 8, e2, 0, w2, s2)
+    acc2 = torch.empty((keep, ffn), dtype=torch.int32, device="cuda")
+    yg2 = agq.gemm_w4a8(dev(y1), e2, agq.pack_w4(dev(w2)), dev(s2), ffn, hid, acc_out=acc2)
+    assert np.array_equal(host(acc2).astype(np.int64), acc2_w)
+    assert_f16_close(host(yg2), y2, "y2")
+
+
+def test_config4_attention_block_full(agq, oracle):
+    """Config 4 at full size: 40 heads x 128, 2048 tokens, 4-bit log2 codes times
+    int8 V, keep the top half of the tokens by start-token attention, then W4A8
+    5120->5120 and 5120->13824 on the survivors.  The oracle does the attention
+    product with an exact float64 matmul and the projections with its C loops
+    on sampled rows."""
+    H, D, S = synth.LLAMA13B_ATTN["H"], synth.LLAMA13B_ATTN["D"], synth.LLAMA13B_ATTN["S"]
+    p, v = synth.make_attention(H, S, D, seed=4)
+    e_v = oracle.calibrate_act_exp(v.reshape(H * S, D), 8)
+    vq = oracle.quantize_act(v.reshape(H * S, D), 8, e_v, 0).astype(np.int8).reshape(H, S, D)
+    keep = oracle.n_keep(S, oracle.progressive_ratio(0.5, 1))
+    assert keep == 1024
+    _, O = oracle.attn_v_log2(p, vq, e_v, 15, True)
+    t = oracle.start_token_score(p)
+    idx_w, xp = oracle.prune_tokens(t, keep, O)
+
+    o, _, score = agq.log2_quant_softmax(dev(p), dev(vq), e_v, qmax=15, causal=True)
+    assert np.array_equal(host(score).astype(np.int64), t)
+    assert np.array_equal(host(o).view(np.uint16), O.view(np.uint16))
+    idx, xg = agq.prune_tokens(score, keep, o)
+    assert np.array_equal(host(idx), idx_w)
+    assert np.array_equal(host(xg).view(np.uint16), xp.view(np.uint16))
+
+    rows = [0, 1, 17, 511, 512, 1000, 1023] + list(range(300, 309))
+    x_in = xp
+    for k, (name, K, N) in enumerate(synth.LLAMA13B_TAIL):
+        wq, sw = synth.make_weight_q4(N, K, 40 + k)
+        e = oracle.calibrate_act_exp(x_in, 8)
+        assert int(host(agq.calibrate_act_exp(dev(x_in), 8))[0]) == e
+        acc = torch.empty((keep, N), dtype=torch.int32, device="cuda")
+        y = agq.gemm_w4a8(dev(x_in), e, agq.pack_w4(dev(wq)), dev(sw), N, K, acc_out=acc)
+        q = oracle.quantize_act(x_in, 8, e, 0).astype(np.int8)
+        if k == 0:   # whole first projection through the C loops: its output feeds the next one
+            want = oracle.gemm_int_c(q, wq, threads=oracle.c_max_threads())
+            assert np.array_equal(host(acc), want)
+            y_w = oracle.dequant_out(want, e, sw)
+            assert_f16_close(host(y), y_w, name)
+            x_in = y_w
+        else:
+            want = oracle.gemm_int_c(q[rows], wq, threads=oracle.c_max_threads())
+            assert np.array_equal(host(acc)[rows], want)
+            assert_f16_close(host(y)[rows], oracle.dequant_out(want, e, sw), name)
