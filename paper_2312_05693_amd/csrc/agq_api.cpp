@@ -33,20 +33,10 @@ int gemm_w4(int bits, const void *x, int x_kind, int64_t M, int64_t K, int64_t l
     if (M <= AGQ_DECODE_MAX_M)
         return hip_status(agq_launch_gemm_decode(x, x_kind, bits, M, K, ldx, e, w_packed, sw, N, y, ldy, acc_out, stream));
 
-    const int8_t *xq = static_cast<const int8_t *>(x);
-    int64_t ldq = ldx;
-    if (x_kind == AGQ_X_F16) {
-        int err = agq_launch_quantize(x, M, K, ldx, bits, e, 0, workspace, K, 8, stream);
-        if (err) return AGQ_EHIP;
-        xq = static_cast<const int8_t *>(workspace);
-        ldq = K;
-    } else if (bits == 4) {
-        int err = agq_launch_widen4(x, M, K, ldx, workspace, K, stream);
-        if (err) return AGQ_EHIP;
-        xq = static_cast<const int8_t *>(workspace);
-        ldq = K;
-    }
-    return hip_status(agq_launch_gemm_tiled(xq, ldq, M, K, e, w_packed, sw, N, y, ldy, acc_out, stream));
+    // many tokens: lay the codes out in MFMA operand order (quantizing on the way
+    // when x is fp16), then run the tiled kernel on that private copy
+    if (agq_launch_prepack_act(x, x_kind, bits, M, K, ldx, e, workspace, stream)) return AGQ_EHIP;
+    return hip_status(agq_launch_gemm_tiled(workspace, M, K, e, w_packed, sw, N, y, ldy, acc_out, stream));
 }
 
 }  // namespace
@@ -104,7 +94,7 @@ int agq_unpack_w4(const void *packed, int64_t N, int64_t K, int8_t *wq_out, void
 size_t agq_gemm_workspace_bytes(int64_t M, int64_t N, int64_t K) {
     (void)N;
     if (M <= AGQ_DECODE_MAX_M || K < 1) return 0;
-    return ((size_t)M * (size_t)K + 255) & ~(size_t)255;
+    return (size_t)((M + 127) / 128) * 128 * (size_t)K;   // int8 codes, tokens padded to the 128-row tile
 }
 
 int agq_gemm_w4a8(const void *x, int x_kind, int64_t M, int64_t K, int64_t ldx, int e, int zp, const void *w_packed,

@@ -13,13 +13,14 @@ static inline int64_t agq_k_tiles(int64_t K) { return K / 128; }
 int agq_launch_calibrate(const void *x, int64_t M, int64_t K, int64_t ldx, int bits, int32_t *e_dev, void *stream);
 int agq_launch_quantize(const void *x, int64_t M, int64_t K, int64_t ldx, int bits, int e, int zp,
                         void *out, int64_t ld_out_bytes, int out_bits, void *stream);
-int agq_launch_widen4(const void *xq4, int64_t M, int64_t K, int64_t ldx, void *out, int64_t ld_out_bytes, void *stream);
+int agq_launch_prepack_act(const void *x, int x_kind, int bits, int64_t M, int64_t K, int64_t ldx, int e, void *out,
+                           void *stream);
 int agq_launch_pack(const int8_t *wq, int64_t N, int64_t K, void *packed, int32_t *bad, void *stream);
 int agq_launch_unpack(const void *packed, int64_t N, int64_t K, int8_t *wq, void *stream);
 int agq_launch_gemm_decode(const void *x, int x_kind, int bits, int64_t M, int64_t K, int64_t ldx, int e,
                            const void *w_packed, const void *sw, int64_t N, void *y, int64_t ldy,
                            int32_t *acc_out, void *stream);
-int agq_launch_gemm_tiled(const int8_t *xq, int64_t ldq, int64_t M, int64_t K, int e,
+int agq_launch_gemm_tiled(const void *x_tiles, int64_t M, int64_t K, int e,
                           const void *w_packed, const void *sw, int64_t N, void *y, int64_t ldy,
                           int32_t *acc_out, void *stream);
 int agq_launch_log2_attn(const void *p, int64_t H, int64_t S, int64_t D, int causal, int qmax,

@@ -71,32 +71,61 @@ __global__ __launch_bounds__(kThreads) void quantize_kernel(const __half *__rest
     }
 }
 
-// nibble codes [M,K/2] -> int8 [M,K]; one lane = 16 codes
-__global__ __launch_bounds__(kThreads) void widen4_kernel(const uint8_t *__restrict__ in, int64_t M, int64_t K16,
-                                                           int64_t ld_in_bytes, uint8_t *__restrict__ out,
-                                                           int64_t ld_out_bytes) {
-    const int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x;
-    if (i >= M * K16) return;
-    const int64_t r = i / K16, c = i - r * K16;
-    const uint2 v = *reinterpret_cast<const uint2 *>(in + r * ld_in_bytes + c * 8);
-    const uint32_t w[2] = {v.x, v.y};
-    uint32_t o[4];
+// ------------------------------------------------------------------ activation tiles for the MFMA kernel
+//
+// The tiled GEMM reads its activation codes from a private int8 copy laid out in
+// MFMA operand order, so that its global-to-LDS copies are contiguous 1 KiB runs
+// and its fragment reads are linear.  For every 128-token tile and every K step
+// of 128 there is one 16 KiB stage [i (4)][t (4)][lane (64)][16 bytes]: i = which
+// 32-token tile, t = which k-block of 32, lane = 32 (k-half of 16) + token % 32,
+// the 16 bytes = 16 consecutive k.  One workgroup produces the 4 KiB of one
+// (32-token tile, K step): coalesced row-major loads, Eq.2 (or a plain copy /
+// nibble widening for pre-quantized input), a transpose through LDS, and a
+// linear 16-byte-per-lane store.  Rows past M are written as zeros.
+enum { PRE_F16 = 0, PRE_I8 = 1, PRE_I4 = 2 };
+
+template <int MODE>
+__global__ __launch_bounds__(kThreads) void prepack_act_kernel(const void *__restrict__ x, int64_t M, int64_t KT,
+                                                                int64_t ldx, AgqQuant q, uint4 *__restrict__ out) {
+    __shared__ uint4 tile[256];                       // 4 KiB in operand order
+    const int tid = threadIdx.x;
+    const int64_t kt = blockIdx.x, mt = blockIdx.y;  // K step, 32-token tile
+    const int r = tid >> 3, c = tid & 7;              // token row in the tile, 16-wide k segment
+    const int64_t m = mt * 32 + r;
+    uint4 codes = make_uint4(0, 0, 0, 0);
+    if (m < M) {
+        const int64_t k0 = kt * 128 + c * 16;
+        if (MODE == PRE_F16) {
+            const __half *xp = reinterpret_cast<const __half *>(x) + m * ldx + k0;
+            const uint2 lo = agq_quant8(*reinterpret_cast<const uint4 *>(xp), q);
+            const uint2 hi = agq_quant8(*reinterpret_cast<const uint4 *>(xp + 8), q);
+            codes = make_uint4(lo.x, lo.y, hi.x, hi.y);
+        } else if (MODE == PRE_I8) {
+            codes = *reinterpret_cast<const uint4 *>(reinterpret_cast<const int8_t *>(x) + m * ldx + k0);
+        } else {
+            const uint2 v = *reinterpret_cast<const uint2 *>(reinterpret_cast<const uint8_t *>(x) + m * (ldx >> 1) + (k0 >> 1));
+            const uint32_t w[2] = {v.x, v.y};
+            uint32_t o[4];
 #pragma unroll
-    for (int j = 0; j < 2; ++j) {
+            for (int j = 0; j < 2; ++j)
 #pragma unroll
-        for (int h = 0; h < 2; ++h) {
-            const uint32_t two = (w[j] >> (16 * h)) & 0xFFFFu;  // four codes
-            uint32_t r4 = 0;
+                for (int h = 0; h < 2; ++h) {
+                    const uint32_t four = (w[j] >> (16 * h)) & 0xFFFFu;
+                    uint32_t r4 = 0;
 #pragma unroll
-            for (int t = 0; t < 4; ++t) {
-                const int code = (int)((two >> (4 * t)) & 0xF);
-                const int s = (code ^ 8) - 8;  // sign-extend
-                r4 |= (uint32_t)(s & 0xFF) << (8 * t);
-            }
-            o[2 * j + h] = r4;
+                    for (int t = 0; t < 4; ++t) {
+                        const int code = (int)((four >> (4 * t)) & 0xF);
+                        r4 |= (uint32_t)(((code ^ 8) - 8) & 0xFF) << (8 * t);
+                    }
+                    o[2 * j + h] = r4;
+                }
+            codes = make_uint4(o[0], o[1], o[2], o[3]);
         }
     }
-    *reinterpret_cast<uint4 *>(out + r * ld_out_bytes + c * 16) = make_uint4(o[0], o[1], o[2], o[3]);
+    tile[(c >> 1) * 64 + (c & 1) * 32 + r] = codes;   // k-block c >> 1, lane 32 (c & 1) + r
+    __syncthreads();
+    // stage of (128-token tile mt >> 2, step kt); this workgroup owns chunks 4 (mt & 3) .. + 3
+    out[(((mt >> 2) * KT + kt) * 16 + (mt & 3) * 4) * 64 + tid] = tile[tid];
 }
 
 // ------------------------------------------------------------------ weight blob
@@ -200,13 +229,18 @@ int agq_launch_quantize(const void *x, int64_t M, int64_t K, int64_t ldx, int bi
     return (int)hipGetLastError();
 }
 
-int agq_launch_widen4(const void *xq4, int64_t M, int64_t K, int64_t ldx, void *out, int64_t ld_out_bytes,
-                      void *stream) {
-    const int64_t total = M * (K / 16);
-    if (total == 0) return 0;
-    widen4_kernel<<<(unsigned)blocks_for(total), kThreads, 0, (hipStream_t)stream>>>((const uint8_t *)xq4, M, K / 16,
-                                                                                     ldx / 2, (uint8_t *)out,
-                                                                                     ld_out_bytes);
+int agq_launch_prepack_act(const void *x, int x_kind, int bits, int64_t M, int64_t K, int64_t ldx, int e, void *out,
+                           void *stream) {
+    const AgqQuant q = agq_make_quant(bits, e, 0);
+    const int64_t KT = K / 128;
+    const dim3 grid((unsigned)KT, (unsigned)(((M + 127) / 128) * 4));
+    hipStream_t st = (hipStream_t)stream;
+    if (x_kind == 0)
+        prepack_act_kernel<PRE_F16><<<grid, kThreads, 0, st>>>(x, M, KT, ldx, q, (uint4 *)out);
+    else if (bits == 8)
+        prepack_act_kernel<PRE_I8><<<grid, kThreads, 0, st>>>(x, M, KT, ldx, q, (uint4 *)out);
+    else
+        prepack_act_kernel<PRE_I4><<<grid, kThreads, 0, st>>>(x, M, KT, ldx, q, (uint4 *)out);
     return (int)hipGetLastError();
 }
 
