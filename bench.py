@@ -3,8 +3,10 @@
 
 A step = one decode pass over all 224 projections of a LLaMA-7B-shaped model
 (32 blocks x q/k/v/o/gate/up/down), run once for each token count M in
-{1, 4, 16}: 672 agq_gemm_w4a8 calls with the activation quantizer fused as
-prologue and the per-channel dequantisation as epilogue.  All 224 packed 4-bit
+{1, 4, 16}, with the activation quantizer fused as prologue and the per-channel
+dequantisation as epilogue.  Projections that read the same activation (q/k/v,
+gate/up) go through agq_gemm_w4a8_multi, i.e. one kernel launch: 4 launches per
+block, 384 per step.  All 224 packed 4-bit
 weight matrices are distinct buffers (3.24 GB, far beyond the 256 MB Infinity
 Cache), resident in HBM before the timed region.  The metric is the algorithmic
 bytes of those calls (4-bit weights + fp16 scales + fp16 activation in and out)
@@ -48,6 +50,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-prefill", action="store_true")
+    ap.add_argument("--per-projection", action="store_true", help="seven single calls per block instead of four")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (the path has no collective); use --gpus 1", file=sys.stderr)
@@ -83,17 +86,45 @@ def main():
             x = torch.from_numpy(synth.make_activation(M, K, 4, seed=1)).to(dev)
             xs[(M, K)] = x
             es[(M, K)] = int(agq.calibrate_act_exp(x, 8).item())
-        for N in (4096, 11008):
-            ys[(M, N)] = torch.empty((M, N), dtype=torch.float16, device=dev)
     torch.cuda.synchronize()
+
+    # One decode pass over a block: q, k and v read the same activation and run as
+    # one agq_gemm_w4a8_multi call (one kernel launch), then o, then gate and up
+    # as one call, then down: four launches for seven projections, each with its
+    # own weights, scales and output.  --per-projection issues seven single calls.
+    for M in DECODE_M:
+        for name in ("q", "k", "v", "o", "down"):
+            ys[(M, name)] = torch.empty((M, 4096), dtype=torch.float16, device=dev)
+        for name in ("gate", "up"):
+            ys[(M, name)] = torch.empty((M, 11008), dtype=torch.float16, device=dev)
+    NAMES = ("q", "k", "v", "o", "gate", "up", "down")
+
+    def single(M, layer, idx):
+        K, N, packed, sw = layer[idx]
+        agq.gemm_w4a8(xs[(M, K)], es[(M, K)], packed, sw, N, K, y=ys[(M, NAMES[idx])])
+
+    def multi(M, layer, idxs):
+        K = layer[idxs[0]][0]
+        projs = [(layer[i][2], layer[i][3], layer[i][1], ys[(M, NAMES[i])], None) for i in idxs]
+        agq.gemm_w4a8_multi(xs[(M, K)], es[(M, K)], projs, K)
+
+    def decode_pass(M):
+        for layer in layers:
+            if args.per_projection:
+                for idx in range(7):
+                    single(M, layer, idx)
+            else:
+                multi(M, layer, (0, 1, 2))
+                single(M, layer, 3)
+                multi(M, layer, (4, 5))
+                single(M, layer, 6)
 
     def decode_step():
         for M in DECODE_M:
-            for layer in layers:
-                for (K, N, packed, sw) in layer:
-                    agq.gemm_w4a8(xs[(M, K)], es[(M, K)], packed, sw, N, K, y=ys[(M, N)])
+            decode_pass(M)
 
-    launches_per_step = len(DECODE_M) * len(layers) * len(synth.LLAMA7B_PROJ)
+    launches_per_pass = len(layers) * (7 if args.per_projection else 4)
+    launches_per_step = len(DECODE_M) * launches_per_pass
     bytes_per_step = sum(algorithmic_bytes(M, K, N) for M in DECODE_M for layer in layers for (K, N, _, _) in layer)
 
     def timed(fn, warmup, steps):
@@ -124,9 +155,7 @@ def main():
     per_m = {}
     for M in DECODE_M:
         def one():
-            for layer in layers:
-                for (K, N, packed, sw) in layer:
-                    agq.gemm_w4a8(xs[(M, K)], es[(M, K)], packed, sw, N, K, y=ys[(M, N)])
+            decode_pass(M)
         reps = max(3, args.steps // 3)
         ms = timed(one, 1, reps) / reps
         by = sum(algorithmic_bytes(M, K, N) for layer in layers for (K, N, _, _) in layer)
@@ -155,7 +184,8 @@ def main():
                      "kernel": "gemm_decode_kernel", "avg_launch_us": round(avg_launch_us, 3),
                      "algorithmic_bytes_per_launch": int(bytes_per_step / launches_per_step)},
         "decode_by_M": per_m,
-        "launch": "one HIP graph per step (672 kernel nodes), replayed",
+        "launch": "one HIP graph per step, replayed; per block: qkv (one multi call), o, gate+up (one multi call), down"
+                  if not args.per_projection else "one HIP graph per step, replayed; seven single calls per block",
     }
 
     # ---- prefill: one block's seven shapes at M = 2048, W4A8 and W4A4 (int8 MFMA bound)

@@ -89,6 +89,7 @@ int agq_unpack_w4(const void *packed, int64_t N, int64_t K, int8_t *wq_out,
  * MFMA; CDNA4 has no 4-bit matrix instruction).
  * x        : see agq_x_kind.  fp16: ldx % 8 == 0; codes: ldx in code units,
  *            ldx % 16 == 0 (8 bit) or ldx % 32 == 0 (4 bit); 16-byte aligned.
+ *            w_packed, w_scale_f16 and y_f16 are 16-byte aligned too.
  * zp       : must be 0 (signed grid); other values return AGQ_EINVAL.
  * w_packed : output of agq_pack_w4 for [N,K].   w_scale_f16: fp16 [N].
  * y_f16    : fp16 [M,N], ldy >= N.   acc_out: optional int32 [M,N] contiguous
@@ -106,6 +107,31 @@ int agq_gemm_w4a4(const void *x, int x_kind, int64_t M, int64_t K, int64_t ldx,
                   int e, int zp, const void *w_packed, const void *w_scale_f16,
                   int64_t N, void *y_f16, int64_t ldy, int32_t *acc_out,
                   void *workspace, size_t workspace_bytes, void *stream);
+
+/* Several projections of the same activation in one call (q/k/v, gate/up of a
+ * transformer block; Section 4.2's pipeline quantizes such an activation once).
+ * Same computation as `count` calls of agq_gemm_w4a8 / agq_gemm_w4a4 with the
+ * same x, M, K, e: Eq.2 (or the layout pre-pass) runs once, and for M <= 16 all
+ * projections run as one kernel launch, which is what a launch-bound decode
+ * step needs.  projs: HOST array of `count` descriptors (1 <= count <=
+ * AGQ_MAX_PROJ), read before the call returns.  workspace:
+ * agq_gemm_workspace_bytes(M, N, K) for any N.  Other arguments and errors as
+ * for the single calls.                                                       */
+#define AGQ_MAX_PROJ 4
+typedef struct agq_proj {
+    const void *w_packed;    /* agq_pack_w4 output for [N,K]            */
+    const void *w_scale_f16; /* fp16 [N]                                */
+    int64_t N;
+    void *y_f16;             /* fp16 [M,N]                              */
+    int64_t ldy;
+    int32_t *acc_out;        /* optional int32 [M,N] contiguous, or NULL */
+} agq_proj;
+int agq_gemm_w4a8_multi(const void *x, int x_kind, int64_t M, int64_t K, int64_t ldx,
+                        int e, int zp, const agq_proj *projs, int count,
+                        void *workspace, size_t workspace_bytes, void *stream);
+int agq_gemm_w4a4_multi(const void *x, int x_kind, int64_t M, int64_t K, int64_t ldx,
+                        int e, int zp, const agq_proj *projs, int count,
+                        void *workspace, size_t workspace_bytes, void *stream);
 
 /* Log2 quantizer on softmax probabilities (Section 4.1 Eq.3 with max|X| = 1,
  * used for the softmax output per Section 5.1) fused with the product with the

@@ -29,9 +29,20 @@ SIGNATURES = {
     "agq_gemm_workspace_bytes": (_sz, [_i64, _i64, _i64]),
     "agq_gemm_w4a8": (_int, _GEMM_ARGS),
     "agq_gemm_w4a4": (_int, _GEMM_ARGS),
+    "agq_gemm_w4a8_multi": (_int, [_vp, _int, _i64, _i64, _i64, _int, _int, _vp, _int, _vp, _sz, _vp]),
+    "agq_gemm_w4a4_multi": (_int, [_vp, _int, _i64, _i64, _i64, _int, _int, _vp, _int, _vp, _sz, _vp]),
     "agq_log2_quant_softmax": (_int, [_vp, _i64, _i64, _i64, _int, _int, _vp, _int, _vp, _vp, _vp, _vp]),
     "agq_prune_tokens": (_int, [_vp, _i64, _i64, _vp, _i64, _vp, _vp, _vp]),
 }
+
+AGQ_MAX_PROJ = 4
+
+
+class AgqProj(ctypes.Structure):
+    """struct agq_proj of include/agq.h"""
+    _fields_ = [("w_packed", _vp), ("w_scale_f16", _vp), ("N", _i64), ("y_f16", _vp), ("ldy", _i64),
+                ("acc_out", _vp)]
+
 
 _lib = None
 
@@ -138,6 +149,37 @@ def gemm_w4a4(x, e, w_packed, w_scale, N, K, x_kind=AGQ_X_F16, y=None, acc_out=N
     M = x.shape[0]
     ldx = (x.stride(0) if M else K) * (2 if x_kind == AGQ_X_Q else 1)
     return _gemm("agq_gemm_w4a4", x, x_kind, M, K, ldx, e, zp, w_packed, w_scale, N, y, acc_out, workspace)
+
+
+def _gemm_multi(fn_name, x, x_kind, M, K, ldx, e, zp, projs, workspace):
+    """projs: list of (w_packed, w_scale, N, y or None, acc_out or None); returns the list of y."""
+    dev = projs[0][0].device
+    ys, arr = [], (AgqProj * len(projs))()
+    for i, (packed, scale, N, y, acc) in enumerate(projs):
+        if y is None:
+            y = torch.empty((M, N), dtype=torch.float16, device=dev)
+        ys.append(y)
+        arr[i] = AgqProj(_ptr(packed), _ptr(scale), N, _ptr(y), y.stride(0) if M else N, _ptr(acc))
+    need = gemm_workspace_bytes(M, projs[0][2], K)
+    if workspace is None and need:
+        workspace = torch.empty(need, dtype=torch.uint8, device=dev)
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    fn = getattr(lib(), fn_name)
+    _ok(fn(_ptr(x), x_kind, M, K, ldx, e, zp, ctypes.cast(arr, _vp), len(projs), _ptr(workspace), ws_bytes,
+           _stream()), fn_name)
+    return ys
+
+
+def gemm_w4a8_multi(x, e, projs, K, x_kind=AGQ_X_F16, workspace=None, zp=0):
+    """Several projections of one activation: projs = [(w_packed, w_scale, N, y|None, acc_out|None), ...]."""
+    M = x.shape[0]
+    return _gemm_multi("agq_gemm_w4a8_multi", x, x_kind, M, K, x.stride(0) if M else K, e, zp, projs, workspace)
+
+
+def gemm_w4a4_multi(x, e, projs, K, x_kind=AGQ_X_F16, workspace=None, zp=0):
+    M = x.shape[0]
+    ldx = (x.stride(0) if M else K) * (2 if x_kind == AGQ_X_Q else 1)
+    return _gemm_multi("agq_gemm_w4a4_multi", x, x_kind, M, K, ldx, e, zp, projs, workspace)
 
 
 def log2_quant_softmax(p, v_q, e_v, qmax=15, causal=True, want_codes=False, want_score=True):

@@ -13,30 +13,51 @@ inline bool e_ok(int e) { return e >= AGQ_E_MIN && e <= AGQ_E_MAX; }
 inline int hip_status(int err) { return err == 0 ? AGQ_OK : AGQ_EHIP; }
 constexpr int64_t kMaxDim = (int64_t)1 << 30;
 
-int gemm_w4(int bits, const void *x, int x_kind, int64_t M, int64_t K, int64_t ldx, int e, int zp,
-            const void *w_packed, const void *sw, int64_t N, void *y, int64_t ldy, int32_t *acc_out,
-            void *workspace, size_t workspace_bytes, void *stream) {
-    if (M < 0 || M > kMaxDim || N < 1 || N > kMaxDim || K < 128 || K > 65536 || (K % 128) != 0) return AGQ_EINVAL;
+int gemm_w4_multi(int bits, const void *x, int x_kind, int64_t M, int64_t K, int64_t ldx, int e, int zp,
+                  const agq_proj *projs, int count, void *workspace, size_t workspace_bytes, void *stream) {
+    if (M < 0 || M > kMaxDim || K < 128 || K > 65536 || (K % 128) != 0) return AGQ_EINVAL;
     if (x_kind != AGQ_X_F16 && x_kind != AGQ_X_Q) return AGQ_EINVAL;
-    if (!e_ok(e) || zp != 0) return AGQ_EINVAL;
-    if (ldx < K || ldy < N) return AGQ_EINVAL;
+    if (!e_ok(e) || zp != 0 || ldx < K) return AGQ_EINVAL;
     if (x_kind == AGQ_X_F16 && (ldx % 8) != 0) return AGQ_EINVAL;
     if (x_kind == AGQ_X_Q && (ldx % (bits == 8 ? 16 : 32)) != 0) return AGQ_EINVAL;
+    if (!projs || count < 1 || count > AGQ_MAX_PROJ) return AGQ_EINVAL;
+    int64_t tiles = 0;
+    for (int p = 0; p < count; ++p) {
+        if (projs[p].N < 1 || projs[p].N > kMaxDim || projs[p].ldy < projs[p].N) return AGQ_EINVAL;
+        tiles += (projs[p].N + 15) / 16;
+    }
+    if (tiles > kMaxDim) return AGQ_EINVAL;
     if (M == 0) return AGQ_OK;
-    if (!x || !w_packed || !sw || !y) return AGQ_EINVAL;
-    if (!aligned16(x) || !aligned16(w_packed)) return AGQ_EINVAL;
-    const size_t need = agq_gemm_workspace_bytes(M, N, K);
+    if (!x || !aligned16(x)) return AGQ_EINVAL;
+    for (int p = 0; p < count; ++p) {
+        if (!projs[p].w_packed || !projs[p].w_scale_f16 || !projs[p].y_f16) return AGQ_EINVAL;
+        if (!aligned16(projs[p].w_packed) || !aligned16(projs[p].w_scale_f16) || !aligned16(projs[p].y_f16))
+            return AGQ_EINVAL;
+    }
+    const size_t need = agq_gemm_workspace_bytes(M, projs[0].N, K);
     if (need > 0) {
         if (!workspace || !aligned16(workspace)) return AGQ_EINVAL;
         if (workspace_bytes < need) return AGQ_ESIZE;
     }
     if (M <= AGQ_DECODE_MAX_M)
-        return hip_status(agq_launch_gemm_decode(x, x_kind, bits, M, K, ldx, e, w_packed, sw, N, y, ldy, acc_out, stream));
+        return hip_status(agq_launch_gemm_decode(x, x_kind, bits, M, K, ldx, e, projs, count, stream));
 
-    // many tokens: lay the codes out in MFMA operand order (quantizing on the way
-    // when x is fp16), then run the tiled kernel on that private copy
+    // many tokens: lay the codes out in MFMA operand order once (quantizing on the
+    // way when x is fp16), then run the tiled kernel per projection on that copy
     if (agq_launch_prepack_act(x, x_kind, bits, M, K, ldx, e, workspace, stream)) return AGQ_EHIP;
-    return hip_status(agq_launch_gemm_tiled(workspace, M, K, e, w_packed, sw, N, y, ldy, acc_out, stream));
+    for (int p = 0; p < count; ++p) {
+        if (agq_launch_gemm_tiled(workspace, M, K, e, projs[p].w_packed, projs[p].w_scale_f16, projs[p].N,
+                                  projs[p].y_f16, projs[p].ldy, projs[p].acc_out, stream))
+            return AGQ_EHIP;
+    }
+    return AGQ_OK;
+}
+
+int gemm_w4(int bits, const void *x, int x_kind, int64_t M, int64_t K, int64_t ldx, int e, int zp,
+            const void *w_packed, const void *sw, int64_t N, void *y, int64_t ldy, int32_t *acc_out,
+            void *workspace, size_t workspace_bytes, void *stream) {
+    const agq_proj one = {w_packed, sw, N, y, ldy, acc_out};
+    return gemm_w4_multi(bits, x, x_kind, M, K, ldx, e, zp, &one, 1, workspace, workspace_bytes, stream);
 }
 
 }  // namespace
@@ -109,6 +130,16 @@ int agq_gemm_w4a4(const void *x, int x_kind, int64_t M, int64_t K, int64_t ldx, 
                   size_t workspace_bytes, void *stream) {
     return gemm_w4(4, x, x_kind, M, K, ldx, e, zp, w_packed, w_scale_f16, N, y_f16, ldy, acc_out, workspace,
                    workspace_bytes, stream);
+}
+
+int agq_gemm_w4a8_multi(const void *x, int x_kind, int64_t M, int64_t K, int64_t ldx, int e, int zp,
+                        const agq_proj *projs, int count, void *workspace, size_t workspace_bytes, void *stream) {
+    return gemm_w4_multi(8, x, x_kind, M, K, ldx, e, zp, projs, count, workspace, workspace_bytes, stream);
+}
+
+int agq_gemm_w4a4_multi(const void *x, int x_kind, int64_t M, int64_t K, int64_t ldx, int e, int zp,
+                        const agq_proj *projs, int count, void *workspace, size_t workspace_bytes, void *stream) {
+    return gemm_w4_multi(4, x, x_kind, M, K, ldx, e, zp, projs, count, workspace, workspace_bytes, stream);
 }
 
 int agq_log2_quant_softmax(const void *p_f16, int64_t H, int64_t S, int64_t D, int causal, int qmax,

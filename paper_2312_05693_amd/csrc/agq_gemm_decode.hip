@@ -15,6 +15,7 @@
 // written, and never reach a stored result, because an MFMA output row depends
 // on the matching operand row only.  A single LDS reduction joins the
 // wavefronts before the fused per-channel dequantisation.
+#include "../../include/agq.h"
 #include "agq_device.h"
 #include "agq_internal.h"
 
@@ -22,17 +23,24 @@ AgqQuant agq_make_quant(int bits, int e, int zp);
 
 namespace {
 
+// Up to kMaxProj projections that read the same activation (q/k/v, gate/up) run
+// as one launch: workgroup b serves 16-channel tile b - tile_start[p] of the
+// projection p whose tile range contains b.
+constexpr int kMaxProj = AGQ_MAX_PROJ;
+
 struct DecodeArgs {
     const void *x;
     int64_t ldx;      // elements (fp16 / int8) or codes (nibbles)
-    int M, N, KT;
+    int M, KT, count;
     AgqQuant q;
-    const uint4 *blob;
-    const __half *sw;
-    __half *y;
-    int64_t ldy;
-    int32_t *acc_out;
     float scale_e;    // 2^e
+    int tile_start[kMaxProj + 1];
+    int N[kMaxProj];
+    const uint4 *blob[kMaxProj];
+    const __half *sw[kMaxProj];
+    __half *y[kMaxProj];
+    int64_t ldy[kMaxProj];
+    int32_t *acc_out[kMaxProj];
 };
 
 enum { XK_F16 = 0, XK_I8 = 1, XK_I4 = 2 };
@@ -61,9 +69,13 @@ __global__ __launch_bounds__(KPW == 8 ? 1024 : 512, KPW == 8 ? 4 : (MP == 1 ? 6 
     const int lane = threadIdx.x & 63;
     const int wave = threadIdx.x >> 6;
     const int nwaves = blockDim.x >> 6;
-    const int nt = blockIdx.x;
+    int pj = 0;   // which projection this workgroup serves (uniform)
+    while (pj + 1 < a.count && (int)blockIdx.x >= a.tile_start[pj + 1]) ++pj;
+    const int nt = blockIdx.x - a.tile_start[pj];
     const int KT = a.KT;
-    const agq_u4 *wptr = reinterpret_cast<const agq_u4 *>(a.blob) + ((int64_t)nt * KT) * 64 + lane;
+    const int pN = a.N[pj];
+    const __half *psw = a.sw[pj];
+    const agq_u4 *wptr = reinterpret_cast<const agq_u4 *>(a.blob[pj]) + ((int64_t)nt * KT) * 64 + lane;
 
     agq_v4i acc0 = {0, 0, 0, 0}, acc1 = {0, 0, 0, 0};
     agq_u4 *stage = reinterpret_cast<agq_u4 *>(smem) + wave * 128;   // 2 KiB per wavefront
@@ -125,8 +137,8 @@ __global__ __launch_bounds__(KPW == 8 ? 1024 : 512, KPW == 8 ? 4 : (MP == 1 ? 6 
 #pragma unroll
         for (int i = 0; i < KPW; ++i) w[i] = wptr[(int64_t)min(kb + i, KT - 1) * 64];
         if (kb == wave * KPW && threadIdx.x < 256) {
-            const int n = min(nt * 16 + (lane & 15), a.N - 1);
-            sw_bits = reinterpret_cast<const uint16_t *>(a.sw)[n];
+            const int n = min(nt * 16 + (lane & 15), pN - 1);
+            sw_bits = reinterpret_cast<const uint16_t *>(psw)[n];
         }
         asm volatile("" ::: "memory");
 
@@ -180,13 +192,13 @@ __global__ __launch_bounds__(KPW == 8 ? 1024 : 512, KPW == 8 ? 4 : (MP == 1 ? 6 
         const int l = o & 63, r = o >> 6;
         const int m = 4 * (l >> 4) + r;
         const int n = nt * 16 + (l & 15);
-        if (m < a.M && n < a.N) {
+        if (m < a.M && n < pN) {
             int sum = 0;
             for (int w = 0; w < nwaves; ++w) sum += red[(w * 4 + r) * 64 + l];
             const int v = sum >> shift;   // exact: every term carries the factor
-            if (a.acc_out) a.acc_out[(int64_t)m * a.N + n] = v;
-            const uint32_t sb = blockDim.x >= 256 ? sw_bits : (uint32_t) reinterpret_cast<const uint16_t *>(a.sw)[n];
-            a.y[(int64_t)m * a.ldy + n] = agq_dequant(v, a.scale_e * __half2float(__ushort_as_half((unsigned short)sb)));
+            if (a.acc_out[pj]) a.acc_out[pj][(int64_t)m * pN + n] = v;
+            const uint32_t sb = blockDim.x >= 256 ? sw_bits : (uint32_t) reinterpret_cast<const uint16_t *>(psw)[n];
+            a.y[pj][(int64_t)m * a.ldy[pj] + n] = agq_dequant(v, a.scale_e * __half2float(__ushort_as_half((unsigned short)sb)));
         }
     }
 }
@@ -205,28 +217,36 @@ int launch_xk(const DecodeArgs &a, int kpw, unsigned grid, int waves, size_t lds
 }  // namespace
 
 int agq_launch_gemm_decode(const void *x, int x_kind, int bits, int64_t M, int64_t K, int64_t ldx, int e,
-                           const void *w_packed, const void *sw, int64_t N, void *y, int64_t ldy, int32_t *acc_out,
-                           void *stream) {
+                           const agq_proj *projs, int count, void *stream) {
     DecodeArgs a;
     a.x = x;
     a.ldx = ldx;
     a.M = (int)M;
-    a.N = (int)N;
     a.KT = (int)agq_k_tiles(K);
+    a.count = count;
     a.q = agq_make_quant(bits, e, 0);
-    a.blob = (const uint4 *)w_packed;
-    a.sw = (const __half *)sw;
-    a.y = (__half *)y;
-    a.ldy = ldy;
-    a.acc_out = acc_out;
     a.scale_e = ldexpf(1.0f, e);
+    int tiles = 0;
+    for (int p = 0; p < kMaxProj; ++p) {
+        const agq_proj &pr = projs[p < count ? p : count - 1];
+        a.tile_start[p] = tiles;
+        if (p < count) tiles += (int)((pr.N + 15) / 16);
+        a.N[p] = (int)pr.N;
+        a.blob[p] = (const uint4 *)pr.w_packed;
+        a.sw[p] = (const __half *)pr.w_scale_f16;
+        a.y[p] = (__half *)pr.y_f16;
+        a.ldy[p] = pr.ldy;
+        a.acc_out[p] = pr.acc_out;
+    }
+    a.tile_start[kMaxProj] = tiles;
+    for (int p = count; p <= kMaxProj; ++p) a.tile_start[p] = tiles;
     // chunks per wavefront: the smallest of 1, 2, 4, 8 that needs at most 8
     // wavefronts (16 for the largest); very long K loops inside the kernel
     int kpw = 1;
     while (kpw < 8 && (a.KT + kpw - 1) / kpw > 8) kpw *= 2;
     int waves = (a.KT + kpw - 1) / kpw;
     if (waves > 16) waves = 16;
-    const unsigned grid = (unsigned)((N + 15) / 16);
+    const unsigned grid = (unsigned)tiles;
     const size_t lds = (size_t)waves * 2048;   // staging; reused as waves * 1 KiB of partial sums
     hipStream_t st = (hipStream_t)stream;
     if (x_kind == 0) {

@@ -17,9 +17,9 @@ int agq_launch_prepack_act(const void *x, int x_kind, int bits, int64_t M, int64
                            void *stream);
 int agq_launch_pack(const int8_t *wq, int64_t N, int64_t K, void *packed, int32_t *bad, void *stream);
 int agq_launch_unpack(const void *packed, int64_t N, int64_t K, int8_t *wq, void *stream);
+struct agq_proj;
 int agq_launch_gemm_decode(const void *x, int x_kind, int bits, int64_t M, int64_t K, int64_t ldx, int e,
-                           const void *w_packed, const void *sw, int64_t N, void *y, int64_t ldy,
-                           int32_t *acc_out, void *stream);
+                           const struct agq_proj *projs, int count, void *stream);
 int agq_launch_gemm_tiled(const void *x_tiles, int64_t M, int64_t K, int e,
                           const void *w_packed, const void *sw, int64_t N, void *y, int64_t ldy,
                           int32_t *acc_out, void *stream);

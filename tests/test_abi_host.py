@@ -76,6 +76,20 @@ def test_argument_errors_need_no_gpu(lib):
     assert call(M=64, ws=p, wsb=100) == ESIZE
     assert call(M=0, x=None, y=None) == 0            # empty batch is a no-op
 
+    from paper_2312_05693_amd.binding import AgqProj
+    m = lib.agq_gemm_w4a8_multi
+    good = (AgqProj * 2)(AgqProj(4096, 4096, 64, 4096, 64, None), AgqProj(4096, 4096, 32, 4096, 32, None))
+    gp = ctypes.cast(good, ctypes.c_void_p)
+    assert m(p, 0, 4, 256, 256, 0, 0, gp, 0, None, 0, None) == EINVAL          # count
+    assert m(p, 0, 4, 256, 256, 0, 0, gp, 5, None, 0, None) == EINVAL
+    assert m(p, 0, 4, 256, 256, 0, 0, None, 2, None, 0, None) == EINVAL        # no descriptors
+    assert m(None, 0, 4, 256, 256, 0, 0, gp, 2, None, 0, None) == EINVAL
+    bad = (AgqProj * 2)(AgqProj(4096, 4096, 64, 4096, 64, None), AgqProj(4096, None, 32, 4096, 32, None))
+    assert m(p, 0, 4, 256, 256, 0, 0, ctypes.cast(bad, ctypes.c_void_p), 2, None, 0, None) == EINVAL
+    bad = (AgqProj * 1)(AgqProj(4096, 4096, 64, 4096, 32, None))               # ldy < N
+    assert m(p, 0, 4, 256, 256, 0, 0, ctypes.cast(bad, ctypes.c_void_p), 1, None, 0, None) == EINVAL
+    assert m(p, 0, 0, 256, 256, 0, 0, gp, 2, None, 0, None) == 0               # no tokens
+
     q = lib.agq_quantize_act
     assert q(p, 4, 64, 64, 5, 0, 0, p, None) == EINVAL          # bits
     assert q(p, 4, 60, 64, 8, 0, 0, p, None) == EINVAL          # K % 8

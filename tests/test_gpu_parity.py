@@ -178,6 +178,32 @@ def test_tiled_variants(agq, oracle, bits, x_kind):
     run_linear(agq, oracle, x, wq, sw, bits, x_kind)
 
 
+@pytest.mark.parametrize("M,bits", [(1, 8), (4, 8), (16, 8), (3, 4), (40, 8), (150, 4)])
+def test_multi_projection_equals_single_calls(agq, oracle, M, bits):
+    # q/k/v-style: several weight matrices on one activation, one call
+    K = 512
+    Ns = [64, 272, 100, 16]
+    x = synth.make_activation(M, K, 3, seed=50 + M)
+    e = oracle.calibrate_act_exp(x, bits)
+    projs, wants, accs = [], [], []
+    for i, N in enumerate(Ns):
+        wq, sw = synth.make_weight_q4(N, K, seed=60 + i)
+        acc = torch.full((M, N), -7, dtype=torch.int32, device="cuda")
+        projs.append((agq.pack_w4(dev(wq)), dev(sw), N, None, acc))
+        accs.append(acc)
+        wants.append(oracle.linear_w4(x, bits, e, 0, wq, sw))
+    fn = agq.gemm_w4a8_multi if bits == 8 else agq.gemm_w4a4_multi
+    ys = fn(dev(x), e, projs, K)
+    for (acc_w, y_w), acc, y in zip(wants, accs, ys):
+        assert np.array_equal(host(acc).astype(np.int64), acc_w)
+        assert_f16_close(host(y), y_w, "multi")
+    # three projections, pre-quantized codes as input
+    xq = agq.quantize_act(dev(x), bits, e, 0)
+    ys = fn(xq, e, projs[:3], K, x_kind=agq.AGQ_X_Q)
+    for (acc_w, y_w), y in zip(wants, ys):
+        assert_f16_close(host(y), y_w, "multi q")
+
+
 def test_extreme_operands_hit_the_bound(agq, oracle):
     # all codes at -128 and all weights at -8: acc = 128 * 8 * K exactly, the
     # largest value the accumulator can take (times 16 inside the kernel)
