@@ -192,35 +192,48 @@ def main():
     if not args.no_prefill:
         prefill = {}
         for name, fn, bits in (("w4a8", agq.gemm_w4a8, 8), ("w4a4", agq.gemm_w4a4, 4)):
-            shapes = []
-            tot_ms, tot_ops = 0.0, 0.0
-            for (pname, K, N), (_, _, packed, sw) in zip(synth.LLAMA7B_PROJ, layers[0]):
-                x = torch.from_numpy(synth.make_activation(PREFILL_M, K, synth.n_outlier_channels(K), seed=2)).to(dev)
-                e = int(agq.calibrate_act_exp(x, bits).item())
-                y = torch.empty((PREFILL_M, N), dtype=torch.float16, device=dev)
-                ws = torch.empty(agq.gemm_workspace_bytes(PREFILL_M, N, K), dtype=torch.uint8, device=dev)
+            mfn = agq.gemm_w4a8_multi if bits == 8 else agq.gemm_w4a4_multi
+            L = layers[0]
+            xk = {K: torch.from_numpy(synth.make_activation(PREFILL_M, K, synth.n_outlier_channels(K), seed=2)).to(dev)
+                  for K in (4096, 11008)}
+            ek = {K: int(agq.calibrate_act_exp(xk[K], bits).item()) for K in xk}
+            yk = [torch.empty((PREFILL_M, N), dtype=torch.float16, device=dev) for (_, _, N) in synth.LLAMA7B_PROJ]
+            ws = torch.empty(agq.gemm_workspace_bytes(PREFILL_M, 4096, 11008), dtype=torch.uint8, device=dev)
+
+            def block():
+                # q/k/v share one quantize pre-pass, gate/up another: 4 pre-passes, 7 GEMMs
+                mfn(xk[4096], ek[4096], [(L[i][2], L[i][3], L[i][1], yk[i], None) for i in (0, 1, 2)], 4096, workspace=ws)
+                fn(xk[4096], ek[4096], L[3][2], L[3][3], 4096, 4096, y=yk[3], workspace=ws)
+                mfn(xk[4096], ek[4096], [(L[i][2], L[i][3], L[i][1], yk[i], None) for i in (4, 5)], 4096, workspace=ws)
+                fn(xk[11008], ek[11008], L[6][2], L[6][3], 4096, 11008, y=yk[6], workspace=ws)
+
+            def time_it(f, reps=20):
                 for _ in range(3):
-                    fn(x, e, packed, sw, N, K, y=y, workspace=ws)
+                    f()
                 torch.cuda.synchronize()
                 a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-                reps = 20
                 a.record()
                 for _ in range(reps):
-                    fn(x, e, packed, sw, N, K, y=y, workspace=ws)
+                    f()
                 b.record()
                 torch.cuda.synchronize()
-                ms = a.elapsed_time(b) / reps
-                ops = 2.0 * PREFILL_M * N * K
-                tot_ms += ms
-                tot_ops += ops
+                return a.elapsed_time(b) / reps
+
+            tot_ms = time_it(block)
+            tot_ops = sum(2.0 * PREFILL_M * N * K for (_, K, N) in synth.LLAMA7B_PROJ)
+            shapes = []
+            for i in (0, 4, 6):       # one of each shape, single call with fp16 input (pre-pass included)
+                pname, K, N = synth.LLAMA7B_PROJ[i]
+                ms = time_it(lambda: fn(xk[K], ek[K], L[i][2], L[i][3], N, K, y=yk[i], workspace=ws))
                 shapes.append({"proj": pname, "K": K, "N": N, "us": round(ms * 1e3, 2),
-                               "TOP/s": round(ops / (ms * 1e-3) / 1e12, 1)})
+                               "TOP/s": round(2.0 * PREFILL_M * N * K / (ms * 1e-3) / 1e12, 1)})
             tops = tot_ops / (tot_ms * 1e-3) / 1e12
             prefill[name] = {"M": PREFILL_M, "ms_per_block": round(tot_ms, 4), "TOP/s": round(tops, 1),
                              "roofline": {"bound": "mfma", "achieved": round(tops, 1), "peak": INT8_PEAK_TOPS,
                                           "unit": "TOP/s", "frac": round(tops / INT8_PEAK_TOPS, 4), "traffic": None,
-                                          "note": "fp16 input: time includes the activation-quantize pass"},
-                             "shapes": shapes}
+                                          "kernel": "gemm_tiled_kernel",
+                                          "note": "fp16 input: time includes the 4 quantize/layout pre-passes of a block"},
+                             "single_calls": shapes}
         result["prefill"] = prefill
 
     # ---- CPU baseline: the oracle as it stands, on a bounded sample of the decode workload
@@ -233,7 +246,7 @@ def main():
         cpu_x = {(M, K): synth.make_activation(M, K, 4, seed=1) for M in DECODE_M for K in (4096, 11008)}
         t_start = time.perf_counter()
         done_bytes, passes = 0, 0
-        while time.perf_counter() - t_start < 10.0 and passes < synth.LLAMA7B_LAYERS:
+        while time.perf_counter() - t_start < 12.0 and passes < 400:
             for M in DECODE_M:
                 for (K, N, wq, sw) in cpu_layer:
                     x = cpu_x[(M, K)]
