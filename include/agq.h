@@ -155,7 +155,7 @@ int agq_log2_quant_softmax(const void *p_f16, int64_t H, int64_t S, int64_t D,
 
 /* Token pruning, Section 4.3 Eq.4: keep the n_keep tokens with the largest
  * score (equal scores: lower index first), in their original order.
- * score  : int32 [S], S <= 16384.   x_f16: fp16 [S,d] contiguous, d % 8 == 0.
+ * score  : int32 [S], S <= 8192.   x_f16: fp16 [S,d] contiguous, d % 8 == 0.
  * idx_out: int32 [n_keep] ascending.  x_out_f16: fp16 [n_keep,d].
  * 0 <= n_keep <= S.                                                           */
 int agq_prune_tokens(const int32_t *score, int64_t S, int64_t n_keep,

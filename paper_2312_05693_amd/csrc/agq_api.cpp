@@ -158,7 +158,7 @@ int agq_log2_quant_softmax(const void *p_f16, int64_t H, int64_t S, int64_t D, i
 
 int agq_prune_tokens(const int32_t *score, int64_t S, int64_t n_keep, const void *x_f16, int64_t d,
                      int32_t *idx_out, void *x_out_f16, void *stream) {
-    if (S < 1 || S > 16384 || n_keep < 0 || n_keep > S || d < 8 || d > kMaxDim || (d % 8) != 0) return AGQ_EINVAL;
+    if (S < 1 || S > 8192 || n_keep < 0 || n_keep > S || d < 8 || d > kMaxDim || (d % 8) != 0) return AGQ_EINVAL;
     if (!score || !x_f16) return AGQ_EINVAL;
     if (n_keep == 0) return AGQ_OK;
     if (!idx_out || !x_out_f16 || !aligned16(x_f16) || !aligned16(x_out_f16)) return AGQ_EINVAL;

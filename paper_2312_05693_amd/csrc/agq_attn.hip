@@ -164,42 +164,104 @@ __global__ __launch_bounds__(256) void log2_attn_kernel(const AttnArgs a) {
 // ------------------------------------------------------------------ pruning
 
 constexpr int kSelThreads = 1024;
+constexpr int kSelMaxS = 8192;
+constexpr int kSelPer = kSelMaxS / kSelThreads;   // tokens per thread, kept in registers
 
-// keep[i] = fewer than n_keep tokens beat token i (higher score, or equal score
-// and lower index); survivors are written in ascending order
+// Survivors of Eq.4: the n_keep tokens with the largest score, equal scores to
+// the lower index, written in ascending order.  One workgroup, no sort:
+//   1. radix select (four 8-bit digits, LDS histograms) finds the score T of the
+//      n_keep-th largest token and how many tokens with exactly that score
+//      still fit (`need`);
+//   2. a token survives if its score is above T, or equals T and fewer than
+//      `need` equal-scored tokens precede it;
+//   3. wavefront-shuffle prefix sums give the tie ordinals and output positions.
+// Thread t owns the contiguous tokens [t * per, t * per + per).
 __global__ __launch_bounds__(kSelThreads) void prune_select_kernel(const int32_t *__restrict__ score, int S, int n_keep,
                                                                     int32_t *__restrict__ idx_out) {
-    extern __shared__ int sc[];          // S scores, then kSelThreads scan cells
-    int *cnt = sc + S;
-    for (int i = threadIdx.x; i < S; i += kSelThreads) sc[i] = score[i];
-    __syncthreads();
+    __shared__ int hist[256];
+    __shared__ int wave_tot[kSelThreads / 64];
+    __shared__ unsigned sel_prefix;
+    __shared__ int sel_k;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int per = (S + kSelThreads - 1) / kSelThreads;
-    const int lo = threadIdx.x * per, hi = min(lo + per, S);
-    unsigned long long keepmask = 0;     // per <= 16 for S <= 16384
-    int mine = 0;
-    for (int i = lo; i < hi; ++i) {
-        const int si = sc[i];
-        int rank = 0;
-        for (int j = 0; j < S; ++j) {
-            const int sj = sc[j];
-            rank += (sj > si) || (sj == si && j < i);
+    const int lo = threadIdx.x * per;
+    unsigned key[kSelPer];     // order-preserving unsigned image of the signed score
+#pragma unroll
+    for (int e = 0; e < kSelPer; ++e)
+        key[e] = (e < per && lo + e < S) ? ((unsigned)score[lo + e] ^ 0x80000000u) : 0u;
+    auto live = [&](int e) { return e < per && lo + e < S; };
+
+    unsigned prefix = 0, himask = 0;
+    int k = n_keep;            // the k-th largest among the tokens matching `prefix`
+    for (int shift = 24; shift >= 0; shift -= 8) {
+        if (threadIdx.x < 256) hist[threadIdx.x] = 0;
+        __syncthreads();
+#pragma unroll
+        for (int e = 0; e < kSelPer; ++e)
+            if (live(e) && (key[e] & himask) == prefix) atomicAdd(&hist[(key[e] >> shift) & 255], 1);
+        __syncthreads();
+        if (wave == 0) {
+            // lane l owns digits 4l .. 4l+3; suffix sums from the top digit down
+            const int c0 = hist[4 * lane], c1 = hist[4 * lane + 1], c2 = hist[4 * lane + 2], c3 = hist[4 * lane + 3];
+            const int mine4 = c0 + c1 + c2 + c3;
+            int above = mine4;                       // inclusive suffix sum over lanes >= l
+#pragma unroll
+            for (int off = 1; off < 64; off <<= 1) {
+                const int v = __shfl_down(above, off);
+                if (lane + off < 64) above += v;
+            }
+            const int higher = above - mine4;        // tokens in digits owned by higher lanes
+            if (higher < k && k <= above) {          // the k-th largest falls into this lane's digits
+                int rem = k - higher, d = 3;
+                const int c[4] = {c0, c1, c2, c3};
+                while (rem > c[d]) {
+                    rem -= c[d];
+                    --d;
+                }
+                sel_prefix = prefix | ((unsigned)(4 * lane + d) << shift);
+                sel_k = rem;
+            }
         }
-        if (rank < n_keep) {
-            keepmask |= 1ull << (i - lo);
+        __syncthreads();
+        prefix = sel_prefix;
+        k = sel_k;
+        himask |= 0xFFu << shift;
+    }
+    // prefix = image of T; k = number of tokens with score T that survive
+    int ties = 0;
+#pragma unroll
+    for (int e = 0; e < kSelPer; ++e) ties += live(e) && key[e] == prefix;
+    auto excl_scan = [&](int v) {                    // exclusive prefix over the workgroup
+        int incl = v;
+#pragma unroll
+        for (int off = 1; off < 64; off <<= 1) {
+            const int u = __shfl_up(incl, off);
+            if (lane >= off) incl += u;
+        }
+        __syncthreads();                             // wave_tot is reused between the two scans
+        if (lane == 63) wave_tot[wave] = incl;
+        __syncthreads();
+        int base = 0;
+        for (int w = 0; w < wave; ++w) base += wave_tot[w];
+        return base + incl - v;
+    };
+    int tie_ord = excl_scan(ties);
+    unsigned keepmask = 0;
+    int mine = 0;
+#pragma unroll
+    for (int e = 0; e < kSelPer; ++e) {
+        if (!live(e)) continue;
+        bool keep = key[e] > prefix;
+        if (key[e] == prefix) keep = tie_ord++ < k;
+        if (keep) {
+            keepmask |= 1u << e;
             ++mine;
         }
     }
-    cnt[threadIdx.x] = mine;
-    __syncthreads();
-    for (int off = 1; off < kSelThreads; off <<= 1) {
-        const int v = threadIdx.x >= off ? cnt[threadIdx.x - off] : 0;
-        __syncthreads();
-        cnt[threadIdx.x] += v;
-        __syncthreads();
-    }
-    int pos = cnt[threadIdx.x] - mine;
-    for (int i = lo; i < hi; ++i)
-        if (keepmask >> (i - lo) & 1) idx_out[pos++] = i;
+    int pos = excl_scan(mine);
+#pragma unroll
+    for (int e = 0; e < kSelPer; ++e)
+        if (keepmask >> e & 1) idx_out[pos++] = lo + e;
 }
 
 __global__ __launch_bounds__(256) void gather_rows_kernel(const uint4 *__restrict__ x, const int32_t *__restrict__ idx,
@@ -232,11 +294,7 @@ int agq_launch_log2_attn(const void *p, int64_t H, int64_t S, int64_t D, int cau
 int agq_launch_prune(const int32_t *score, int64_t S, int64_t n_keep, const void *x, int64_t d, int32_t *idx,
                      void *x_out, void *stream) {
     hipStream_t st = (hipStream_t)stream;
-    const size_t lds = ((size_t)S + kSelThreads) * sizeof(int);
-    hipError_t err = hipFuncSetAttribute((const void *)prune_select_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                         (int)lds);
-    if (err != hipSuccess) return (int)err;
-    prune_select_kernel<<<1, kSelThreads, lds, st>>>(score, (int)S, (int)n_keep, idx);
+    prune_select_kernel<<<1, kSelThreads, 0, st>>>(score, (int)S, (int)n_keep, idx);
     gather_rows_kernel<<<(unsigned)n_keep, 256, 0, st>>>((const uint4 *)x, idx, d / 8, (uint4 *)x_out);
     return (int)hipGetLastError();
 }

@@ -112,7 +112,7 @@ def test_argument_errors_need_no_gpu(lib):
     pr = lib.agq_prune_tokens
     assert pr(p, 64, 65, p, 64, p, p, None) == EINVAL
     assert pr(p, 64, 8, p, 60, p, p, None) == EINVAL
-    assert pr(p, 20000, 8, p, 64, p, p, None) == EINVAL
+    assert pr(p, 8193, 8, p, 64, p, p, None) == EINVAL
     assert pr(p, 64, 0, p, 64, None, None, None) == 0
 
 
