@@ -142,16 +142,23 @@ int agq_gemm_w4a4_multi(const void *x, int x_kind, int64_t M, int64_t K, int64_t
  *   score[i]  = sum_h p[h,i,0] * 2^24                           (exact integer)
  * p_f16   : fp16 [H,S,S] in [0,1], row i = query i; causal != 0 reads j <= i only.
  * qmax    : 15 (all four bits carry magnitude) or 7 (Eq.3's 2^(b-1)-1, b = 4).
- * v_q     : int8 [H,S,D], scale 2^e_v;  D % 16 == 0, D <= 256;  S % 8 == 0.
+ * v_q     : int8 [H,S,D], scale 2^e_v;  D % 16 == 0, D <= 256;  S % 8 == 0,
+ *           S <= 32768.
  * o_f16   : fp16 [S, H*D].   codes_out: optional [H,S,S/2] bytes, two codes per
  *           byte, low nibble = even j, entries above the diagonal carry qmax.
  * score_out: optional int32 [S]; needs H <= 127.
- * Precondition: rows are softmax outputs (sum <= ~1), which keeps the integer
- * sum below 2^24; arbitrary inputs may lose low bits.                         */
+ * workspace: agq_log2_quant_softmax_workspace_bytes(H,S,D) bytes (0 = invalid
+ *           sizes), 16-byte aligned; holds V transposed into the order the
+ *           matrix cores read it, written by a pre-pass of this call;
+ *           contents are scratch.  Too small a workspace returns AGQ_ESIZE.
+ * Precondition: rows are softmax outputs (values in [0,1], sum <= ~1), which
+ * keeps the integer sum below 2^24; a value above 1 gives an unspecified
+ * result, and arbitrary inputs may lose low bits.                            */
+size_t agq_log2_quant_softmax_workspace_bytes(int64_t H, int64_t S, int64_t D);
 int agq_log2_quant_softmax(const void *p_f16, int64_t H, int64_t S, int64_t D,
                            int causal, int qmax, const int8_t *v_q, int e_v,
                            void *o_f16, void *codes_out, int32_t *score_out,
-                           void *stream);
+                           void *workspace, size_t workspace_bytes, void *stream);
 
 /* Token pruning, Section 4.3 Eq.4: keep the n_keep tokens with the largest
  * score (equal scores: lower index first), in their original order.

@@ -15,19 +15,25 @@
 #include "agq_device.h"
 #include "agq_internal.h"
 
+#include <type_traits>
+
 typedef _Float16 agq_v8h __attribute__((ext_vector_type(8)));
-typedef float agq_v4f __attribute__((ext_vector_type(4)));
+typedef _Float16 agq_v2h __attribute__((ext_vector_type(2)));
+typedef unsigned short agq_v2us __attribute__((ext_vector_type(2)));
+typedef float agq_v16f __attribute__((ext_vector_type(16)));
+typedef uint32_t agq_u4 __attribute__((ext_vector_type(4)));
 
 namespace {
 
-constexpr int kQRows = 64;      // query rows per workgroup (16 per wavefront)
-constexpr int kKeys = 64;       // keys per step
-constexpr int kVPad = kKeys + 8;  // row stride of the transposed V tile in halves (144 B: conflict-free 16-byte reads)
+constexpr int kQRows = 128;     // query rows per workgroup (32 per wavefront)
+constexpr int kKeys = 64;       // keys per tile: four MFMA steps of 16
+constexpr int kVRow = 144;      // bytes per channel row of the V tile in LDS: 64 keys in fp16 + 16 of padding
 constexpr int kMaxD = 256;
 
 struct AttnArgs {
     const uint16_t *p;   // fp16 bits [H,S,S]
     const int8_t *v;     // [H,S,D]
+    const uint8_t *vt;   // byte images of V written by vt_prepack_kernel
     __half *o;           // [S, H*D]
     uint8_t *codes;      // [H,S,S/2] or null
     int32_t *score;      // [S] or null
@@ -36,128 +42,310 @@ struct AttnArgs {
     float out_scale;     // 2^(e_v - qmax)
 };
 
-// Eq.3 code of one fp16 bit pattern in [0, 1]
-__device__ __forceinline__ int log2_code(uint32_t h, int qmax) {
-    int c = 15 - (int)((h + 599u) >> 10);
-    if (h < 1024u) c = h >= 725u ? 14 : 15;
-    return max(min(c, qmax), 0);
+// Two probabilities (packed fp16) -> two weights 2^(qmax - c) as packed fp16 bit
+// patterns.  Scaling by 2^10 first makes every non-zero input a normal number, so
+// one formula covers subnormals: with e = (bits(1024 p) + 599) >> 10 the code is
+// c = min(25 - e, qmax) and the weight's exponent field 15 + max(e - (25 - qmax), 0).
+// kmin = (25 - qmax) << 10 and kadd = (qmax - 10) << 10, both replicated per half
+// (kadd in wrap-around arithmetic: no half ever borrows from the other).
+__device__ __forceinline__ uint32_t log2_weight2(uint32_t p2, uint32_t kmin, uint32_t kadd) {
+    const agq_v2h x = __builtin_bit_cast(agq_v2h, p2) * agq_v2h{(_Float16)1024.0f, (_Float16)1024.0f};
+    uint32_t u = (__builtin_bit_cast(uint32_t, x) + 0x02570257u) & 0xFC00FC00u;
+    agq_v2us e = __builtin_bit_cast(agq_v2us, u);
+    e = __builtin_elementwise_min(__builtin_elementwise_max(e, __builtin_bit_cast(agq_v2us, kmin)),
+                                  agq_v2us{25u << 10, 25u << 10});
+    return __builtin_bit_cast(uint32_t, e) + kadd;
 }
 
-__global__ __launch_bounds__(256) void log2_attn_kernel(const AttnArgs a) {
-    __shared__ __align__(16) _Float16 vt[kMaxD * kVPad];   // V tile, transposed: [d][key]
+constexpr int kImgRow = 64;     // bytes per channel row of a V image in memory: 64 keys, one byte each
+
+// Byte offset of the 16-byte piece (eight keys in fp16) `chunk` of row `slot`
+// inside the LDS tile; rows are padded to 144 bytes so that sixteen lanes
+// reading the same chunk of consecutive rows hit sixteen different bank groups.
+__device__ __forceinline__ int vt_offset(int slot, int chunk) { return slot * kVRow + (chunk << 4); }
+
+// Bytes of one V image in memory: D rows of 64, rounded up to whole 4 KiB so that
+// 256 threads copy it in 16-byte pieces without a bounds test.
+__host__ __device__ constexpr int vt_image_bytes(int D) { return (D * kImgRow + 4095) & ~4095; }
+
+// int8 V [H,S,D] -> per (head, 64-key tile) an image of D rows x 64 bytes:
+// [row of d][key], bytes v + 128, rows in the order the multiply kernel reads
+// (channel d in row (d & 3) * D/4 + (d >> 2)).  Thread unit = (eight keys kg,
+// four channels 4 c .. 4 c + 3): eight dword loads and a byte transpose by
+// v_perm.  The image is built in LDS and written out linearly.
+__global__ __launch_bounds__(256) void vt_prepack_kernel(const int8_t *__restrict__ v, int S, int D,
+                                                         uint8_t *__restrict__ vt) {
+    __shared__ __align__(16) uint8_t imgbuf[vt_image_bytes(kMaxD)];
+    const int DQ = D >> 2, img = vt_image_bytes(D);
+    const int tile = blockIdx.x, h = blockIdx.y, ntile = gridDim.x;
+    const int8_t *vh = v + (int64_t)h * S * D;
+    for (int unit = threadIdx.x; unit < 8 * DQ; unit += 256) {
+        const int c = unit % DQ, kg = unit / DQ;
+        uint32_t x[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            const int key = min(tile * kKeys + 8 * kg + i, S - 1);   // keys past S get weight 0 downstream
+            x[i] = *reinterpret_cast<const uint32_t *>(vh + (int64_t)key * D + 4 * c) ^ 0x80808080u;
+        }
+#pragma unroll
+        for (int bb = 0; bb < 4; ++bb) {
+            const uint32_t sel = 0x0C0C0000u | (uint32_t)bb | ((uint32_t)(4 + bb) << 8);   // byte bb of two words
+            uint2 out;
+            out.x = __builtin_amdgcn_perm(__builtin_amdgcn_perm(x[3], x[2], sel), __builtin_amdgcn_perm(x[1], x[0], sel),
+                                          0x05040100u);
+            out.y = __builtin_amdgcn_perm(__builtin_amdgcn_perm(x[7], x[6], sel), __builtin_amdgcn_perm(x[5], x[4], sel),
+                                          0x05040100u);
+            *reinterpret_cast<uint2 *>(imgbuf + (bb * DQ + c) * kImgRow + 8 * kg) = out;
+        }
+    }
+    __syncthreads();
+    uint8_t *dst = vt + ((int64_t)h * ntile + tile) * img;
+    for (int off = threadIdx.x * 16; off < img; off += 256 * 16)
+        *reinterpret_cast<agq_u4 *>(dst + off) = *reinterpret_cast<const agq_u4 *>(imgbuf + off);
+}
+
+// One workgroup = 128 query rows of one head; wavefront w owns rows 32 w .. 32 w + 31
+// as the A operand of the 32x32x16 fp16 MFMA (lane: row l & 31, eight keys of
+// k-group l >> 5).  Inside a 64-key tile the keys are dealt to the MFMA steps so
+// that a lane's four steps cover 32 consecutive keys (64 contiguous bytes of its
+// row): step t of k-group g uses keys 32 g + 8 t .. + 7, for both operands.
+// V arrives as the byte images of vt_prepack_kernel: per tile a thread copies
+// 16 bytes per 4 KiB of image, widening each byte u = v + 128 to fp16 on the way
+// (0x6400 | u is 1024 + u; minus 1152) into the LDS tile [row of d][key].
+// The MFMA reads walk consecutive rows, and a lane ends up with four
+// consecutive channels of its query rows.
+// P runs two tiles ahead in registers, V one tile ahead; V loads are issued
+// before the P loads so that waiting for V leaves the P loads in flight.
+template <int CB, bool CODES>
+__global__ __launch_bounds__(256, CB == 1 ? 3 : 1) void log2_attn_kernel(const AttnArgs a) {
+    constexpr int NBUF = CB == 1 ? 2 : 1;
+    __shared__ __align__(16) uint8_t vt[NBUF][CB * 128 * kVRow];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int h = blockIdx.y;
-    const int q0 = blockIdx.x * kQRows;
-    const int S = a.S, D = a.D;
-    const int ntile = D >> 4;
+    const int S = a.S, D = a.D, H = a.H, DQ = D >> 2;
+    const int nb = (S + kQRows - 1) / kQRows;
 
-    const int row = q0 + wave * 16 + (lane & 15);       // query row of this lane's P fragment
-    const int rowc = min(row, S - 1);
-    const int g = lane >> 4;
-    const uint16_t *prow = a.p + ((int64_t)h * S + rowc) * S;
-    const int8_t *vh = a.v + (int64_t)h * S * D;
-    const int last_key = a.causal ? min(q0 + kQRows, S) : S;   // keys needed by this workgroup
-    const int row_limit = a.causal ? row : S - 1;               // last key this row may use
-
-    agq_v4f acc[kMaxD / 16];
-#pragma unroll
-    for (int j = 0; j < kMaxD / 16; ++j) acc[j] = agq_v4f{0.f, 0.f, 0.f, 0.f};
-
-    for (int k0 = 0; k0 < last_key; k0 += kKeys) {
-        __syncthreads();   // previous tile fully consumed
-        // V tile: 16 channels of one key per lane, int8 -> fp16, scattered transposed
-        for (int idx = threadIdx.x; idx < kKeys * (D >> 4); idx += blockDim.x) {
-            const int key = idx / (D >> 4), dq = idx - key * (D >> 4);
-            uint4 raw = make_uint4(0, 0, 0, 0);
-            if (k0 + key < S) raw = *reinterpret_cast<const uint4 *>(vh + (int64_t)(k0 + key) * D + dq * 16);
-            const uint32_t w[4] = {raw.x, raw.y, raw.z, raw.w};
-#pragma unroll
-            for (int b = 0; b < 16; ++b) {
-                const int val = (int)(int8_t)(w[b >> 2] >> (8 * (b & 3)));
-                vt[(dq * 16 + b) * kVPad + key] = (_Float16)val;
-            }
+    // workgroup -> (head, row block): all row blocks of a head on one XCD when the
+    // heads divide evenly (its V stays in that L2), longest causal blocks first
+    int h, b;
+    {
+        const int wg = blockIdx.x;
+        if ((H & 7) == 0) {
+            const int hpx = H >> 3, j = wg >> 3;
+            h = (wg & 7) * hpx + j % hpx;
+            b = j / hpx;
+        } else {
+            h = wg % H;
+            b = wg / H;
         }
-        __syncthreads();
+        if (a.causal) b = nb - 1 - b;
+    }
+    const int q0 = b * kQRows;
+    const int r0 = q0 + wave * 32;                        // first row of this wavefront
+    const int row = r0 + (lane & 31);
+    const int g = lane >> 5;
+    const int last_key = a.causal ? min(q0 + kQRows, S) : S;
+    const int nt = (last_key + kKeys - 1) / kKeys;
+    const int lim = a.causal ? row : S - 1;               // last key this row uses
+    const int wave_lim = a.causal ? r0 : S - 1;           // a tile reaching past this needs the mask
+    const int wave_last = a.causal ? r0 + 31 : S - 1;     // tiles starting past this are dead for the wavefront
 
-        // P fragment: 16 consecutive keys of one row per lane, two MFMA steps of 8
-        uint4 praw[2];
-        const int kbase = k0 + g * 16;
-#pragma unroll
-        for (int t = 0; t < 2; ++t) {
-            praw[t] = make_uint4(0, 0, 0, 0);
-            if (kbase + t * 8 < S) praw[t] = *reinterpret_cast<const uint4 *>(prow + kbase + t * 8);
-        }
-        agq_v8h pf[2];
-        uint32_t codes[4];
-#pragma unroll
-        for (int t = 0; t < 2; ++t) {
-            const uint32_t w[4] = {praw[t].x, praw[t].y, praw[t].z, praw[t].w};
-            uint32_t cw = 0;
-#pragma unroll
-            for (int i = 0; i < 8; ++i) {
-                const uint32_t hb = (w[i >> 1] >> (16 * (i & 1))) & 0xFFFFu;
-                const int key = kbase + t * 8 + i;
-                const int c = log2_code(hb, a.qmax);
-                const bool live = key <= row_limit && key < S;
-                // 2^(qmax - c) as fp16: exponent field 15 + qmax - c; dead entries are 0
-                const uint16_t bits = live ? (uint16_t)((15 + a.qmax - c) << 10) : (uint16_t)0;
-                pf[t][i] = __builtin_bit_cast(_Float16, bits);
-                cw |= (uint32_t)(live ? c : a.qmax) << (4 * i);
-            }
-            codes[t] = cw;
-        }
-        if (a.codes && row < S && kbase < S) {
-            uint8_t *dst = a.codes + ((int64_t)h * S + row) * (S >> 1) + (kbase >> 1);
-            *reinterpret_cast<uint32_t *>(dst) = codes[0];
-            if (kbase + 8 < S) *reinterpret_cast<uint32_t *>(dst + 4) = codes[1];
-        }
+    const uint32_t kmin = ((uint32_t)(25 - a.qmax) << 10) * 0x00010001u;
+    const uint32_t kadd = (uint32_t)((a.qmax - 10) * 1024) * 0x00010001u;
+    const uint32_t ctop = ((uint32_t)(15 + a.qmax) << 10) * 0x00010001u;
+    const uint32_t cdead = ((uint32_t)a.qmax << 10) * 0x00010001u;
 
+    // Addresses are a uniform base plus a 32-bit per-lane byte offset (one head of
+    // P is below 4 GiB: S <= 32768).
+    const uint8_t *phead = reinterpret_cast<const uint8_t *>(a.p + (int64_t)h * S * S);
+    const uint32_t prow_off = (uint32_t)min(row, S - 1) * (uint32_t)S * 2u;
+    const int img = vt_image_bytes(D);
+    const uint8_t *vimg = a.vt + (int64_t)h * ((S + kKeys - 1) / kKeys) * img;
+
+    // V image of a tile: thread i-th piece = bytes [16 (tid + 256 i), + 16) = 16 keys of one row
+    agq_u4 vr[2 * CB];
+    const uint32_t voff = threadIdx.x * 16u;
+    auto load_v = [&](int t) {
+        const uint8_t *src = vimg + (int64_t)min(t, nt - 1) * img;
 #pragma unroll
-        for (int t = 0; t < 2; ++t) {
+        for (int i = 0; i < 2 * CB; ++i)
+            vr[i] = *reinterpret_cast<const agq_u4 *>(src + (voff + (i * 4096 < img ? i * 4096u : 0u)));
+    };
+    auto store_v = [&](uint8_t *buf) {
+        const agq_v2h bias = {(_Float16)1152.0f, (_Float16)1152.0f};
 #pragma unroll
-            for (int j = 0; j < kMaxD / 16; ++j) {
-                if (j < ntile) {
-                    const agq_v8h vf = *reinterpret_cast<const agq_v8h *>(&vt[(j * 16 + (lane & 15)) * kVPad + g * 16 + t * 8]);
-                    acc[j] = __builtin_amdgcn_mfma_f32_16x16x32_f16(vf, pf[t], acc[j], 0, 0, 0);
+        for (int i = 0; i < 2 * CB; ++i) {
+            const int piece = (int)threadIdx.x + 256 * i;
+            const int slot = piece >> 2, chunk = (piece & 3) * 2;
+            agq_u4 lo, hi;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                // bytes (u0 u1 u2 u3) -> halves 0x64u0 0x64u1 | 0x64u2 0x64u3
+                const uint32_t w = vr[i][j];
+                const uint32_t e0 = __builtin_amdgcn_perm(0x64646464u, w, 0x04010400u);
+                const uint32_t e1 = __builtin_amdgcn_perm(0x64646464u, w, 0x04030402u);
+                const uint32_t h0 = __builtin_bit_cast(uint32_t, __builtin_bit_cast(agq_v2h, e0) - bias);
+                const uint32_t h1 = __builtin_bit_cast(uint32_t, __builtin_bit_cast(agq_v2h, e1) - bias);
+                if (j < 2) {
+                    lo[2 * j] = h0;
+                    lo[2 * j + 1] = h1;
+                } else {
+                    hi[2 * (j - 2)] = h0;
+                    hi[2 * (j - 2) + 1] = h1;
                 }
             }
+            if (piece * 16 < D * kImgRow) {
+                uint8_t *dst = buf + vt_offset(slot, chunk);
+                *reinterpret_cast<agq_u4 *>(dst) = lo;
+                *reinterpret_cast<agq_u4 *>(dst + 16) = hi;
+            }
         }
+    };
+    // four 16-byte pieces of this lane's row: keys k0 + 32 g + 8 t .. + 7
+    auto load_p = [&](agq_u4 (&dst)[4], int t) {
+        int tt = min(t, nt - 1);
+        if (tt * kKeys > wave_last) tt = 0;               // dead tile: re-read a line that is already cached
+#pragma unroll
+        for (int st = 0; st < 4; ++st) {
+            const uint32_t kc = (uint32_t)min(tt * kKeys + 32 * g + 8 * st, S - 8);
+            dst[st] = *reinterpret_cast<const agq_u4 *>(phead + (prow_off + kc * 2u));
+        }
+    };
+
+    agq_v16f acc[4][CB];
+#pragma unroll
+    for (int n = 0; n < 4; ++n)
+#pragma unroll
+        for (int cb = 0; cb < CB; ++cb)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[n][cb][r] = 0.f;
+
+    __shared__ int ssum[kQRows];
+    if (a.score && threadIdx.x < kQRows) ssum[threadIdx.x] = 0;   // made visible by the main loop's barriers
+
+    int bslot[CB];                                          // LDS row of this lane's B operand, n = 0
+#pragma unroll
+    for (int cb = 0; cb < CB; ++cb) bslot[cb] = min(cb * 32 + (lane & 31), DQ - 1);
+
+    // MASKED: the tile reaches past the last key of some row (diagonal tiles of the
+    // causal case, the ragged last tile); dead keys get weight 0 and code qmax.
+    auto multiply = [&](const agq_u4 (&pc)[4], int k0, const uint8_t *buf, auto masked_tag) {
+        constexpr bool MASKED = decltype(masked_tag)::value;
+#pragma unroll
+        for (int st = 0; st < 4; ++st) {
+            const int kc = k0 + 32 * g + 8 * st;
+            const int nl = lim - kc + 1;                   // live keys of this piece (may be <= 0 or >= 8)
+            uint32_t wv[4];
+            uint32_t cw = 0;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                uint32_t u = log2_weight2(pc[st][j], kmin, kadd);
+                uint32_t m = 0xFFFFFFFFu;
+                if (MASKED) {
+                    const int lv = nl - 2 * j;
+                    m = lv >= 2 ? 0xFFFFFFFFu : (lv == 1 ? 0x0000FFFFu : 0u);
+                    u &= m;
+                }
+                if (CODES) {
+                    uint32_t c10 = ctop - u;               // code << 10 per half (dead: above qmax, fixed below)
+                    if (MASKED) c10 = (c10 & m) | (cdead & ~m);
+                    cw |= (((c10 >> 10) | (c10 >> 22)) & 0xFFu) << (8 * j);
+                }
+                wv[j] = u;
+            }
+            if (CODES) {
+                if (row < S && kc < S)
+                    *reinterpret_cast<uint32_t *>(a.codes + ((int64_t)h * S + row) * (S >> 1) + (kc >> 1)) = cw;
+            }
+            const agq_u4 wq = {wv[0], wv[1], wv[2], wv[3]};
+            const agq_v8h af = __builtin_bit_cast(agq_v8h, wq);
+#pragma unroll
+            for (int n = 0; n < 4; ++n)
+#pragma unroll
+                for (int cb = 0; cb < CB; ++cb) {
+                    const int slot = n * DQ + bslot[cb];
+                    const agq_v8h bf = *reinterpret_cast<const agq_v8h *>(buf + vt_offset(slot, 4 * g + st));
+                    acc[n][cb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(af, bf, acc[n][cb], 0, 0, 0);
+                }
+        }
+    };
+    auto compute = [&](const agq_u4 (&pc)[4], int t, const uint8_t *buf) {
+        const int k0 = t * kKeys;
+        if (k0 > wave_last) return;
+        if (k0 + kKeys - 1 > wave_lim) multiply(pc, k0, buf, std::true_type{});
+        else multiply(pc, k0, buf, std::false_type{});
+    };
+
+    // tile t: V(t) registers -> LDS, issue V(t+1) then P(t+2), barrier, multiply
+    auto tile = [&](const agq_u4 (&pc)[4], agq_u4 (&pfar)[4], int t, bool more_v, bool more_p) {
+        uint8_t *buf = vt[NBUF == 2 ? (t & 1) : 0];
+        if (NBUF == 1) __syncthreads();                     // everyone is done reading the only buffer
+        store_v(buf);
+        if (more_v) load_v(t + 1);
+        if (more_p) load_p(pfar, t + 2);
+        __syncthreads();
+        compute(pc, t, buf);
+    };
+
+    // The steady-state loop always runs three whole tiles, so every path around
+    // its back edge has consumed the same register sets; the last one or two
+    // tiles follow outside it.
+    agq_u4 p0[4], p1[4], p2[4];
+    load_v(0);
+    load_p(p0, 0);
+    load_p(p1, 1);
+    int t = 0;
+    for (; t + 3 <= nt; t += 3) {
+        tile(p0, p2, t, true, true);
+        tile(p1, p0, t + 1, true, true);
+        tile(p2, p1, t + 2, true, true);
+    }
+    if (t < nt) {
+        const bool two = t + 2 == nt;                       // uniform over the workgroup
+        tile(p0, p2, t, true, false);
+        if (two) tile(p1, p0, t + 1, false, false);
     }
 
-    // entries of the code map to the right of the last tile this workgroup visited
-    if (a.codes && a.causal && row < S) {
+    // code map right of the last tile this wavefront multiplied: all qmax
+    if (CODES && a.causal && row < S) {
         const uint32_t fill = 0x11111111u * (uint32_t)a.qmax;
         uint8_t *dst = a.codes + ((int64_t)h * S + row) * (S >> 1);
-        const int start = ((last_key + kKeys - 1) / kKeys) * kKeys;
-        for (int k = start + g * 8; k < S; k += 32) *reinterpret_cast<uint32_t *>(dst + (k >> 1)) = fill;
+        const int done = min(nt, wave_last / kKeys + 1);
+        for (int k = done * kKeys + g * 8; k < S; k += 16) *reinterpret_cast<uint32_t *>(dst + (k >> 1)) = fill;
     }
 
-    // lane holds four consecutive channels (4 g + r) of query row (lane & 15)
-    if (row < S) {
+    // accumulator register 4 q + r holds query row 8 q + 4 g + r of the wavefront,
+    // channel 4 c + n in tile n: four consecutive channels per lane and row
 #pragma unroll
-        for (int j = 0; j < kMaxD / 16; ++j) {
-            if (j < ntile) {
+    for (int cb = 0; cb < CB; ++cb) {
+        const int c = cb * 32 + (lane & 31);
+#pragma unroll
+        for (int q = 0; q < 4; ++q)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                const int orow = r0 + 8 * q + 4 * g + r;
                 __half hv[4];
 #pragma unroll
-                for (int r = 0; r < 4; ++r) hv[r] = __float2half_rn(acc[j][r] * a.out_scale);
-                *reinterpret_cast<uint2 *>(a.o + (int64_t)row * ((int64_t)a.H * D) + (int64_t)h * D + j * 16 + g * 4) =
-                    *reinterpret_cast<const uint2 *>(hv);
+                for (int n = 0; n < 4; ++n) hv[n] = __float2half_rn(acc[n][cb][4 * q + r] * a.out_scale);
+                if (orow < S && c < DQ)
+                    *reinterpret_cast<uint2 *>(a.o + (int64_t)orow * ((int64_t)H * D) + (int64_t)h * D + 4 * c) =
+                        *reinterpret_cast<const uint2 *>(hv);
             }
-        }
     }
 
-    // importance of a token = attention it pays to the first token, summed over
-    // heads as exact integers p * 2^24 (Section 4.3)
-    if (a.score && h == 0 && threadIdx.x < kQRows) {
-        const int i = q0 + threadIdx.x;
-        if (i < S) {
-            int sum = 0;
-            for (int hh = 0; hh < a.H; ++hh) {
-                const uint16_t hb = a.p[((int64_t)hh * S + i) * S];
-                sum += (int)(__half2float(__ushort_as_half(hb)) * 16777216.0f);
-            }
-            a.score[i] = sum;
-        }
+    // Importance of a token = attention it pays to the first token, summed over
+    // heads as exact integers p * 2^24 (Section 4.3).  The 128 rows of a row block
+    // are dealt to the H workgroups that share it; each loads its rows' first
+    // column from every head (one value per thread) and sums them in LDS.
+    if (a.score) {
+        const int rows_per = (kQRows + H - 1) / H;
+        const int j = threadIdx.x / H, hh = threadIdx.x - j * H;
+        const int i = q0 + h * rows_per + j;
+        if (j < rows_per && h * rows_per + j < kQRows && i < S)
+            atomicAdd(&ssum[j], (int)(__half2float(__ushort_as_half(a.p[((int64_t)hh * S + i) * S])) * 16777216.0f));
+        __syncthreads();
+        const int io = q0 + h * rows_per + (int)threadIdx.x;
+        if ((int)threadIdx.x < rows_per && h * rows_per + (int)threadIdx.x < kQRows && io < S)
+            a.score[io] = ssum[threadIdx.x];
     }
 }
 
@@ -273,10 +461,11 @@ __global__ __launch_bounds__(256) void gather_rows_kernel(const uint4 *__restric
 }  // namespace
 
 int agq_launch_log2_attn(const void *p, int64_t H, int64_t S, int64_t D, int causal, int qmax, const int8_t *vq,
-                         int e_v, void *o, void *codes, int32_t *score, void *stream) {
+                         int e_v, void *o, void *codes, int32_t *score, void *workspace, void *stream) {
     AttnArgs a;
     a.p = (const uint16_t *)p;
     a.v = vq;
+    a.vt = (const uint8_t *)workspace;
     a.o = (__half *)o;
     a.codes = (uint8_t *)codes;
     a.score = score;
@@ -286,8 +475,17 @@ int agq_launch_log2_attn(const void *p, int64_t H, int64_t S, int64_t D, int cau
     a.causal = causal;
     a.qmax = qmax;
     a.out_scale = ldexpf(1.0f, e_v - qmax);
-    dim3 grid((unsigned)((S + kQRows - 1) / kQRows), (unsigned)H);
-    log2_attn_kernel<<<grid, 256, 0, (hipStream_t)stream>>>(a);
+    hipStream_t st = (hipStream_t)stream;
+    vt_prepack_kernel<<<dim3((unsigned)((S + kKeys - 1) / kKeys), (unsigned)H), 256, 0, st>>>(vq, (int)S, (int)D,
+                                                                                            (uint8_t *)workspace);
+    const unsigned grid = (unsigned)(((S + kQRows - 1) / kQRows) * H);
+    if (D <= 128) {
+        if (codes) log2_attn_kernel<1, true><<<grid, 256, 0, st>>>(a);
+        else log2_attn_kernel<1, false><<<grid, 256, 0, st>>>(a);
+    } else {
+        if (codes) log2_attn_kernel<2, true><<<grid, 256, 0, st>>>(a);
+        else log2_attn_kernel<2, false><<<grid, 256, 0, st>>>(a);
+    }
     return (int)hipGetLastError();
 }
 

@@ -308,6 +308,25 @@ def test_log2_attn_small(agq, oracle, H, S, D, qmax, causal):
     assert np.array_equal(host(score).astype(np.int64), oracle.start_token_score(p))
 
 
+@pytest.mark.parametrize("H,S,D,qmax,causal", [(8, 264, 128, 15, True), (16, 136, 64, 7, True), (2, 328, 256, 15, True),
+                                                (1, 8, 16, 15, True), (3, 200, 240, 7, False), (8, 392, 128, 15, False)])
+def test_log2_attn_shapes_without_codes(agq, oracle, H, S, D, qmax, causal):
+    """The variant that skips the code map, over: several row blocks with a ragged
+    last one, head counts that do and do not spread evenly over the chip's eight
+    partitions, head dims above 128 (two column blocks) and the smallest S."""
+    p, v = synth.make_attention(H, S, D, seed=7 * H + S + D)
+    e_v = oracle.calibrate_act_exp(v.reshape(H * S, D), 8)
+    vq = oracle.quantize_act(v.reshape(H * S, D), 8, e_v, 0).astype(np.int8).reshape(H, S, D)
+    _, O = oracle.attn_v_log2(p, vq, e_v, qmax, causal)
+    o, _, score = agq.log2_quant_softmax(dev(p), dev(vq), e_v, qmax=qmax, causal=causal, want_codes=False)
+    assert np.array_equal(host(o).view(np.uint16), O.view(np.uint16))
+    assert np.array_equal(host(score).astype(np.int64), oracle.start_token_score(p))
+    o2, codes, _ = agq.log2_quant_softmax(dev(p), dev(vq), e_v, qmax=qmax, causal=causal, want_codes=True,
+                                          want_score=False)
+    assert np.array_equal(host(o2).view(np.uint16), O.view(np.uint16))
+    assert np.array_equal(host(codes), oracle.log2_codes_packed(p, qmax, causal))
+
+
 def test_log2_codes_all_fp16_probabilities(agq, oracle):
     # every fp16 in [0,1] once, through the kernel's code output (non-causal rows)
     vals = np.arange(0x3C00 + 1, dtype=np.uint16).view(np.float16)
@@ -328,6 +347,33 @@ def test_log2_codes_all_fp16_probabilities(agq, oracle):
 def test_prune(agq, oracle, S, keep, d):
     rng = np.random.default_rng(S + keep)
     score = rng.integers(0, max(S // 3, 2), size=S).astype(np.int32)      # many ties
+    x = rng.standard_normal((S, d)).astype(np.float16)
+    idx, out = agq.prune_tokens(dev(score), keep, dev(x))
+    want_idx, want_x = oracle.prune_tokens(score, keep, x)
+    assert np.array_equal(host(idx), want_idx)
+    assert np.array_equal(host(out).view(np.uint16), want_x.view(np.uint16))
+
+
+@pytest.mark.parametrize("kind", ["equal", "signed", "extremes", "max_size", "keep_none"])
+def test_prune_degenerate(agq, oracle, kind):
+    """Score patterns that stress the threshold search: one value everywhere
+    (index order alone decides), both signs, the int32 limits, the largest S the
+    call takes, and n_keep = 0."""
+    rng = np.random.default_rng(11)
+    S, keep, d = 1000, 333, 16
+    if kind == "equal":
+        score = np.full(S, 5, np.int32)
+    elif kind == "signed":
+        score = rng.integers(-50, 50, size=S).astype(np.int32)
+    elif kind == "extremes":
+        score = rng.choice(np.array([-2**31, -1, 0, 1, 2**31 - 1], np.int64), size=S).astype(np.int32)
+    elif kind == "max_size":
+        S, keep = 8192, 4097
+        score = rng.integers(-2**31, 2**31, size=S).astype(np.int32)
+        score[::7] = score[0]
+    else:
+        keep = 0
+        score = rng.integers(0, 9, size=S).astype(np.int32)
     x = rng.standard_normal((S, d)).astype(np.float16)
     idx, out = agq.prune_tokens(dev(score), keep, dev(x))
     want_idx, want_x = oracle.prune_tokens(score, keep, x)
