@@ -124,27 +124,24 @@ __global__ __launch_bounds__(256, CB == 1 ? 3 : 1) void log2_attn_kernel(const A
     const int S = a.S, D = a.D, H = a.H, DQ = D >> 2;
     const int nb = (S + kQRows - 1) / kQRows;
 
-    // workgroup -> (head, row block): all row blocks of a head on one XCD when the
-    // heads divide evenly (its V stays in that L2), longest causal blocks first
-    int h, b;
-    {
-        const int wg = blockIdx.x;
-        if ((H & 7) == 0) {
-            const int hpx = H >> 3, j = wg >> 3;
-            h = (wg & 7) * hpx + j % hpx;
-            b = j / hpx;
-        } else {
-            h = wg % H;
-            b = wg / H;
-        }
-        if (a.causal) b = nb - 1 - b;
-    }
+    // workgroup -> (head, row block), longest causal blocks first
+    const int h = blockIdx.x % H;
+    const int b = a.causal ? nb - 1 - (int)blockIdx.x / H : (int)blockIdx.x / H;
     const int q0 = b * kQRows;
     const int r0 = q0 + wave * 32;                        // first row of this wavefront
     const int row = r0 + (lane & 31);
     const int g = lane >> 5;
     const int last_key = a.causal ? min(q0 + kQRows, S) : S;
     const int nt = (last_key + kKeys - 1) / kKeys;
+    // Step t of this workgroup handles tile (t + rot) mod nt.  Workgroups that run
+    // side by side would otherwise all read the same column window of their rows
+    // at the same time; with a row pitch that is a power of two those addresses
+    // fall on few memory channels.
+    const int rot = (int)((blockIdx.x * 11u) % (unsigned)nt);
+    auto tile_of = [&](int t) {
+        int kt = min(t, nt - 1) + rot;
+        return kt >= nt ? kt - nt : kt;
+    };
     const int lim = a.causal ? row : S - 1;               // last key this row uses
     const int wave_lim = a.causal ? r0 : S - 1;           // a tile reaching past this needs the mask
     const int wave_last = a.causal ? r0 + 31 : S - 1;     // tiles starting past this are dead for the wavefront
@@ -165,7 +162,7 @@ __global__ __launch_bounds__(256, CB == 1 ? 3 : 1) void log2_attn_kernel(const A
     agq_u4 vr[2 * CB];
     const uint32_t voff = threadIdx.x * 16u;
     auto load_v = [&](int t) {
-        const uint8_t *src = vimg + (int64_t)min(t, nt - 1) * img;
+        const uint8_t *src = vimg + (int64_t)tile_of(t) * img;
 #pragma unroll
         for (int i = 0; i < 2 * CB; ++i)
             vr[i] = *reinterpret_cast<const agq_u4 *>(src + (voff + (i * 4096 < img ? i * 4096u : 0u)));
@@ -202,7 +199,7 @@ __global__ __launch_bounds__(256, CB == 1 ? 3 : 1) void log2_attn_kernel(const A
     };
     // four 16-byte pieces of this lane's row: keys k0 + 32 g + 8 t .. + 7
     auto load_p = [&](agq_u4 (&dst)[4], int t) {
-        int tt = min(t, nt - 1);
+        int tt = tile_of(t);
         if (tt * kKeys > wave_last) tt = 0;               // dead tile: re-read a line that is already cached
 #pragma unroll
         for (int st = 0; st < 4; ++st) {
@@ -269,7 +266,7 @@ __global__ __launch_bounds__(256, CB == 1 ? 3 : 1) void log2_attn_kernel(const A
         }
     };
     auto compute = [&](const agq_u4 (&pc)[4], int t, const uint8_t *buf) {
-        const int k0 = t * kKeys;
+        const int k0 = tile_of(t) * kKeys;
         if (k0 > wave_last) return;
         if (k0 + kKeys - 1 > wave_lim) multiply(pc, k0, buf, std::true_type{});
         else multiply(pc, k0, buf, std::false_type{});
