@@ -19,6 +19,9 @@ struct AgqQuant {
     float lo;     // MAGIC + lower grid bound - zp
     float hi;     // MAGIC + upper grid bound - zp
     int zp;
+    // the same in packed fp16 pairs for the signed grid (zp = 0): 2^-e, lower and
+    // upper bound; h_scale2 == 0 when 2^-e is not a normal fp16 number
+    uint32_t h_scale2, h_lo2, h_hi2;
 };
 #define AGQ_MAGIC 12582912.0f  // 1.5 * 2^23
 
@@ -33,6 +36,25 @@ __device__ __forceinline__ uint32_t agq_pack4(uint32_t b0, uint32_t b1, uint32_t
     uint32_t p01 = __builtin_amdgcn_perm(b1, b0, 0x0c0c0400u);
     uint32_t p23 = __builtin_amdgcn_perm(b3, b2, 0x0c0c0400u);
     return __builtin_amdgcn_perm(p23, p01, 0x05040100u);
+}
+
+// Eq.2 on the signed grid in packed fp16, eight values (four words) -> eight codes
+// in two words, k ascending.  x * 2^-e is exact in fp16 unless it underflows, and
+// then it rounds to code 0 either way; clamping to the (integer) grid bounds
+// before rounding gives the same code as clamping after; adding 1536 = 1.5 * 2^10
+// rounds half-to-even to an integer k and leaves k's two's complement in the low
+// byte of the bit pattern 0x6600 + k.  Requires q.h_scale2 != 0.
+typedef _Float16 agq_h2v __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ uint32_t agq_quant2h(uint32_t two, const AgqQuant &q) {
+    agq_h2v v = __builtin_bit_cast(agq_h2v, two) * __builtin_bit_cast(agq_h2v, q.h_scale2);
+    v = __builtin_elementwise_min(__builtin_elementwise_max(v, __builtin_bit_cast(agq_h2v, q.h_lo2)),
+                                  __builtin_bit_cast(agq_h2v, q.h_hi2));
+    v = v + agq_h2v{(_Float16)1536.0f, (_Float16)1536.0f};
+    return __builtin_bit_cast(uint32_t, v);
+}
+__device__ __forceinline__ uint2 agq_quant8h(uint32_t h0, uint32_t h1, uint32_t h2, uint32_t h3, const AgqQuant &q) {
+    const uint32_t t0 = agq_quant2h(h0, q), t1 = agq_quant2h(h1, q), t2 = agq_quant2h(h2, q), t3 = agq_quant2h(h3, q);
+    return make_uint2(__builtin_amdgcn_perm(t1, t0, 0x06040200u), __builtin_amdgcn_perm(t3, t2, 0x06040200u));
 }
 
 // eight fp16 (one 16-byte load) -> eight codes in two words, k ascending.

@@ -28,20 +28,35 @@ namespace {
 // projection p whose tile range contains b.
 constexpr int kMaxProj = AGQ_MAX_PROJ;
 
+// Everything about one projection sits together so that a workgroup fetches it
+// with one round of scalar loads once it knows which projection it serves.
+struct DecodeProj {
+    const uint4 *blob;
+    const __half *sw;
+    __half *y;
+    int32_t *acc_out;
+    int64_t ldy;
+    int N, pad;
+};
+
 struct DecodeArgs {
     const void *x;
     int64_t ldx;      // elements (fp16 / int8) or codes (nibbles)
     int M, KT, count;
     AgqQuant q;
     float scale_e;    // 2^e
-    int tile_start[kMaxProj + 1];
-    int N[kMaxProj];
-    const uint4 *blob[kMaxProj];
-    const __half *sw[kMaxProj];
-    __half *y[kMaxProj];
-    int64_t ldy[kMaxProj];
-    int32_t *acc_out[kMaxProj];
+    int tile_start[kMaxProj + 1];   // entries from `count` on hold the total
+    DecodeProj proj[kMaxProj];
 };
+
+// Which projection a tile belongs to, and its index inside it, without a loop of
+// dependent loads: the three inner boundaries are compared at once.
+__device__ __forceinline__ int find_proj(const DecodeArgs &a, int tile, int &nt) {
+    const int t1 = a.tile_start[1], t2 = a.tile_start[2], t3 = a.tile_start[3];
+    const int pj = (tile >= t1) + (tile >= t2) + (tile >= t3);
+    nt = tile - (pj == 0 ? 0 : (pj == 1 ? t1 : (pj == 2 ? t2 : t3)));
+    return pj;
+}
 
 enum { XK_F16 = 0, XK_I8 = 1, XK_I4 = 2 };
 
@@ -50,6 +65,11 @@ typedef unsigned int agq_u2 __attribute__((ext_vector_type(2)));
 
 // eight fp16 -> eight int8 codes (signed grid), k ascending
 __device__ __forceinline__ agq_u2 quant8v(const agq_u4 &h, const AgqQuant &q) {
+    if (q.h_scale2 != 0) {       // uniform: the packed fp16 quantizer covers every usual exponent
+        const uint32_t h0 = h[0], h1 = h[1], h2 = h[2], h3 = h[3];
+        const uint2 c = agq_quant8h(h0, h1, h2, h3, q);
+        return agq_u2{c.x, c.y};
+    }
     uint32_t c[8];
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
@@ -64,23 +84,37 @@ __device__ __forceinline__ agq_u2 quant8v(const agq_u4 &h, const AgqQuant &q) {
 // XK: what x holds; KPW: weight chunks per wavefront and pass over K;
 // MP: passes of four token rows the Eq.2 prologue makes (M <= 4 MP).
 template <int XK, int KPW, int MP>
-__global__ __launch_bounds__(KPW == 8 ? 1024 : 512, KPW == 8 ? 4 : (MP == 1 ? 6 : 5)) void gemm_decode_kernel(const DecodeArgs a) {
+__global__ __launch_bounds__(KPW == 8 ? 1024 : 512, KPW == 8 ? 4 : (MP == 1 ? 6 : (MP == 2 ? 5 : 4))) void gemm_decode_kernel(const DecodeArgs a) {
     extern __shared__ __align__(16) unsigned char smem[];
     const int lane = threadIdx.x & 63;
-    const int wave = threadIdx.x >> 6;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int nwaves = blockDim.x >> 6;
-    int pj = 0;   // which projection this workgroup serves (uniform)
-    while (pj + 1 < a.count && (int)blockIdx.x >= a.tile_start[pj + 1]) ++pj;
-    const int nt = blockIdx.x - a.tile_start[pj];
+    // all scalar arguments are requested in the first round of loads; only the
+    // projection record depends on one of them
     const int KT = a.KT;
-    const int pN = a.N[pj];
-    const __half *psw = a.sw[pj];
-    const agq_u4 *wptr = reinterpret_cast<const agq_u4 *>(a.blob[pj]) + ((int64_t)nt * KT) * 64 + lane;
+    const int t1 = a.tile_start[1], t2 = a.tile_start[2], t3 = a.tile_start[3];
+    asm volatile("" ::"s"(a.x), "s"(a.ldx), "s"(a.M), "s"(KT), "s"(t1), "s"(t2), "s"(t3), "s"(a.q.scale), "s"(a.q.lo),
+                 "s"(a.q.hi), "s"(a.q.h_scale2), "s"(a.q.h_lo2), "s"(a.q.h_hi2), "s"(a.scale_e));
+    int nt;
+    const int pj = find_proj(a, blockIdx.x, nt);   // which projection this workgroup serves (uniform)
+    const DecodeProj pr = a.proj[pj];
+    const int pN = pr.N;
+    const __half *psw = pr.sw;
+    const agq_u4 *wptr = reinterpret_cast<const agq_u4 *>(pr.blob) + ((int64_t)nt * KT) * 64 + lane;
 
     agq_v4i acc0 = {0, 0, 0, 0}, acc1 = {0, 0, 0, 0};
-    agq_u4 *stage = reinterpret_cast<agq_u4 *>(smem) + wave * 128;   // 2 KiB per wavefront
+    // Staging of the quantized activation: one region per chunk of a batch, in MFMA
+    // operand order [k-half s][k-group g][row m] x 16 bytes with only the R = 4 MP
+    // rows the prologue writes (operand rows beyond R alias lower rows; they never
+    // reach a stored result).  A batch is HB chunks: all of them are written, then
+    // all operands are read back, so the LDS round trip is paid once per batch.
+    constexpr int R = 4 * MP;
+    constexpr int HB = XK != XK_F16 ? KPW : (8 / MP < KPW ? 8 / MP : KPW);
+    constexpr int kRegion = 8 * R;                                     // 16-byte pieces per chunk
+    agq_u4 *stage = reinterpret_cast<agq_u4 *>(smem) + wave * (HB * kRegion);
     const int arow = min(lane & 15, a.M - 1);   // operand row of this lane, clamped into the tensor
     const int ag = lane >> 4;
+    const int srow = (lane & 15) & (R - 1);     // staged row this lane's operand comes from
     uint32_t sw_bits = 0;                       // raw fp16 scale of this thread's output channel
 
     for (int kb = wave * KPW; kb < KT; kb += nwaves * KPW) {
@@ -90,10 +124,9 @@ __global__ __launch_bounds__(KPW == 8 ? 1024 : 512, KPW == 8 ? 4 : (MP == 1 ? 6 
         // Chunk indices are clamped into the tensors: a chunk past the end is
         // loaded again and its weights are zeroed.  With many token rows the
         // activation is fetched HB chunks at a time to bound the registers.
-        constexpr int HB = XK != XK_F16 ? KPW : (8 / MP < KPW ? 8 / MP : KPW);
         const int c16 = lane & 15, rr = lane >> 4;
         agq_u4 xv[XK == XK_F16 ? HB : 1][XK == XK_F16 ? MP : 1];
-        agq_v4i fa0[XK == XK_F16 ? 1 : KPW], fa1[XK == XK_F16 ? 1 : KPW];
+        agq_v4i fa0[XK == XK_F16 ? HB : KPW], fa1[XK == XK_F16 ? HB : KPW];
         auto load_x = [&](int i0) {
 #pragma unroll
             for (int i = 0; i < HB; ++i) {
@@ -143,38 +176,43 @@ __global__ __launch_bounds__(KPW == 8 ? 1024 : 512, KPW == 8 ? 4 : (MP == 1 ? 6 
         asm volatile("" ::: "memory");
 
 #pragma unroll
-        for (int i = 0; i < KPW; ++i) {
-            const bool valid = kb + i < KT;            // wave-uniform
-            agq_v4i a0, a1;
+        for (int b0 = 0; b0 < KPW; b0 += HB) {
             if (XK == XK_F16) {
-                if (i > 0 && i % HB == 0) load_x(i);
-                // Eq.2 on the M x 128 slice of this chunk: lane = 8 consecutive k of one
+                if (b0 > 0) load_x(b0);
+                // Eq.2 on the M x 128 slice of each chunk: lane = 8 consecutive k of one
                 // row, four rows per pass; rows were clamped for the load and are
                 // masked for the LDS store
                 const int s = c16 >> 3, g = (c16 & 7) >> 1, hf = c16 & 1;
 #pragma unroll
-                for (int it = 0; it < MP; ++it) {
-                    const int m = it * 4 + rr;
-                    const agq_u2 codes = quant8v(xv[i % HB][it], a.q);
-                    if (m < a.M) reinterpret_cast<agq_u2 *>(stage + s * 64 + g * 16 + m)[hf] = codes;
-                }
+                for (int i = 0; i < HB; ++i)
+#pragma unroll
+                    for (int it = 0; it < MP; ++it) {
+                        const int m = it * 4 + rr;
+                        const agq_u2 codes = quant8v(xv[i][it], a.q);
+                        if (m < a.M) reinterpret_cast<agq_u2 *>(stage + i * kRegion + (s * 4 + g) * R + m)[hf] = codes;
+                    }
                 // the same wavefront wrote and now reads: LDS keeps program order per wave
                 __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
                 __builtin_amdgcn_wave_barrier();
                 __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-                a0 = __builtin_bit_cast(agq_v4i, stage[lane]);
-                a1 = __builtin_bit_cast(agq_v4i, stage[64 + lane]);
+#pragma unroll
+                for (int i = 0; i < HB; ++i) {
+                    fa0[i] = __builtin_bit_cast(agq_v4i, stage[i * kRegion + ag * R + srow]);
+                    fa1[i] = __builtin_bit_cast(agq_v4i, stage[i * kRegion + (4 + ag) * R + srow]);
+                }
                 __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
                 __builtin_amdgcn_wave_barrier();
-            } else {
-                a0 = fa0[i];
-                a1 = fa1[i];
             }
-            const agq_u4 wv = valid ? w[i] : agq_u4{0u, 0u, 0u, 0u};
-            const agq_v4i b0 = __builtin_bit_cast(agq_v4i, (wv << 4) & 0xF0F0F0F0u);
-            const agq_v4i b1 = __builtin_bit_cast(agq_v4i, wv & 0xF0F0F0F0u);
-            acc0 = __builtin_amdgcn_mfma_i32_16x16x64_i8(a0, b0, acc0, 0, 0, 0);
-            acc1 = __builtin_amdgcn_mfma_i32_16x16x64_i8(a1, b1, acc1, 0, 0, 0);
+#pragma unroll
+            for (int i = 0; i < HB; ++i) {
+                const bool valid = kb + b0 + i < KT;            // wave-uniform
+                const agq_v4i a0 = fa0[XK == XK_F16 ? i : b0 + i], a1 = fa1[XK == XK_F16 ? i : b0 + i];
+                const agq_u4 wv = valid ? w[b0 + i] : agq_u4{0u, 0u, 0u, 0u};
+                const agq_v4i b0v = __builtin_bit_cast(agq_v4i, (wv << 4) & 0xF0F0F0F0u);
+                const agq_v4i b1v = __builtin_bit_cast(agq_v4i, wv & 0xF0F0F0F0u);
+                acc0 = __builtin_amdgcn_mfma_i32_16x16x64_i8(a0, b0v, acc0, 0, 0, 0);
+                acc1 = __builtin_amdgcn_mfma_i32_16x16x64_i8(a1, b1v, acc1, 0, 0, 0);
+            }
         }
     }
 
@@ -196,10 +234,175 @@ __global__ __launch_bounds__(KPW == 8 ? 1024 : 512, KPW == 8 ? 4 : (MP == 1 ? 6 
             int sum = 0;
             for (int w = 0; w < nwaves; ++w) sum += red[(w * 4 + r) * 64 + l];
             const int v = sum >> shift;   // exact: every term carries the factor
-            if (a.acc_out[pj]) a.acc_out[pj][(int64_t)m * pN + n] = v;
+            if (pr.acc_out) pr.acc_out[(int64_t)m * pN + n] = v;
             const uint32_t sb = blockDim.x >= 256 ? sw_bits : (uint32_t) reinterpret_cast<const uint16_t *>(psw)[n];
-            a.y[pj][(int64_t)m * a.ldy[pj] + n] = agq_dequant(v, a.scale_e * __half2float(__ushort_as_half((unsigned short)sb)));
+            pr.y[(int64_t)m * pr.ldy + n] = agq_dequant(v, a.scale_e * __half2float(__ushort_as_half((unsigned short)sb)));
         }
+    }
+}
+
+// Variant for 5..16 token rows of fp16 input.  With that many rows the activation
+// is no longer small: every workgroup that covers the whole K reads all of it
+// from L2 (M x K x 2 bytes, times the number of workgroups: several times the
+// weight bytes) and quantizes all of it.  So here few, large workgroups each do
+// it ONCE, into LDS (MFMA operand order, 2 KiB per 128-column chunk: K <= 8192),
+// and then walk over many channel tiles: the wavefronts form `nstreams` groups
+// of `wpt`, each group streaming its own sequence of tiles with K split over
+// its wavefronts.  All activation loads are issued up front, ahead of the first
+// tiles' weight chunks; the next tile's chunks are requested before the current
+// tile is multiplied, so the weight stream never drains.
+constexpr int kSharedMaxKT = 64;     // 64 chunks x 2 KiB = 128 KiB of LDS for the activation
+
+template <int KPW, int MP>
+__global__ __launch_bounds__(1024) void gemm_decode_shared_kernel(const DecodeArgs a, int total_tiles, int wpt) {
+    extern __shared__ __align__(16) unsigned char smem[];
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int nwaves = blockDim.x >> 6;
+    const int nstreams = nwaves / wpt;
+    const int stream = wave / wpt, ws = wave - stream * wpt;           // tile stream, wavefront inside it
+    const int KT = a.KT;
+    // all scalar arguments are requested in the first round of loads
+    asm volatile("" ::"s"(a.x), "s"(a.ldx), "s"(a.M), "s"(KT), "s"(a.tile_start[1]), "s"(a.tile_start[2]),
+                 "s"(a.tile_start[3]), "s"(a.q.h_scale2), "s"(a.q.h_lo2), "s"(a.q.h_hi2), "s"(a.scale_e));
+    agq_u4 *xq = reinterpret_cast<agq_u4 *>(smem);                    // [KT][128] 16-byte operand pieces
+    int *red = reinterpret_cast<int *>(smem + (size_t)KT * 2048) + stream * wpt * 256;   // [wpt][4][64] per stream
+
+    const int kb = ws * KPW;                                           // this wavefront's chunks, every tile
+    auto tile_ptr = [&](int tile, DecodeProj &pr, int &nt) {
+        pr = a.proj[find_proj(a, min(tile, total_tiles - 1), nt)];
+        return reinterpret_cast<const agq_u4 *>(pr.blob) + ((int64_t)nt * KT) * 64 + lane;
+    };
+
+    // ---- Eq.2 on the whole activation.  Unit = (chunk, pass of four rows): lane =
+    // eight consecutive k of one row.  Units are dealt round-robin to wavefronts.
+    constexpr int XB = KPW == 8 ? 4 : 8;   // activation loads in flight per lane, bounded by the 128 registers
+    const int units = KT * MP;
+    const int c16 = lane & 15, rr = lane >> 4;
+    const int s = c16 >> 3, g = (c16 & 7) >> 1, hf = c16 & 1;
+    // Every workgroup reads the same activation; each starts at a different unit so
+    // that they do not all queue at the same L2 channel at the same time.
+    const int rot = (int)((blockIdx.x * 37u) % (unsigned)units);
+    auto unit_of = [&](int u) {
+        u += rot;
+        return u >= units ? u - units : u;
+    };
+    const int tile_step = (int)gridDim.x * nstreams;
+    int tile = (int)blockIdx.x * nstreams + stream;
+    DecodeProj pr;
+    int nt;
+    const agq_u4 *wptr = tile_ptr(tile, pr, nt);
+    agq_u4 w[KPW];
+    for (int u0 = wave; u0 < units; u0 += nwaves * XB) {
+        agq_u4 xv[XB];
+#pragma unroll
+        for (int i = 0; i < XB; ++i) {
+            const int u = unit_of(min(u0 + i * nwaves, units - 1));
+            const int kc = u / MP, it = u - kc * MP;
+            const __half *xh = reinterpret_cast<const __half *>(a.x) + (int64_t)kc * 128 + c16 * 8;
+            xv[i] = *reinterpret_cast<const agq_u4 *>(xh + (int64_t)min(it * 4 + rr, a.M - 1) * a.ldx);
+        }
+        if (u0 == wave) {
+            asm volatile("" ::: "memory");   // activation requests first: loads return in order
+#pragma unroll
+            for (int i = 0; i < KPW; ++i) w[i] = wptr[(int64_t)min(kb + i, KT - 1) * 64];
+            asm volatile("" ::: "memory");
+        }
+#pragma unroll
+        for (int i = 0; i < XB; ++i) {
+            const int u = unit_of(min(u0 + i * nwaves, units - 1));
+            const int kc = u / MP, it = u - kc * MP;
+            const int m = it * 4 + rr;
+            const agq_u2 codes = quant8v(xv[i], a.q);
+            if (u0 + i * nwaves < units && m < a.M)
+                reinterpret_cast<agq_u2 *>(xq + (int64_t)kc * 128 + s * 64 + g * 16 + m)[hf] = codes;
+        }
+    }
+    if (units <= wave) {   // a wavefront without a unit still has to request its first chunks
+#pragma unroll
+        for (int i = 0; i < KPW; ++i) w[i] = wptr[(int64_t)min(kb + i, KT - 1) * 64];
+    }
+    __syncthreads();
+
+    // every stream runs the same number of rounds (the barriers are workgroup-wide);
+    // a round past the end of the tiles is computed on the last tile and not stored
+    const int rounds = (total_tiles + tile_step - 1) / tile_step;
+    for (int round = 0; round < rounds; ++round, tile += tile_step) {
+        const bool live = tile < total_tiles;
+        // request the next tile's chunks and scale before multiplying this one
+        DecodeProj prn = pr;
+        int ntn = nt;
+        agq_u4 wn[KPW];
+        const int pN = pr.N;
+        uint32_t sw_bits = 0;
+        if (ws < 4) sw_bits = reinterpret_cast<const uint16_t *>(pr.sw)[min(nt * 16 + (lane & 15), pN - 1)];
+        if (round + 1 < rounds) {
+            const agq_u4 *wnext = tile_ptr(tile + tile_step, prn, ntn);
+#pragma unroll
+            for (int i = 0; i < KPW; ++i) wn[i] = wnext[(int64_t)min(kb + i, KT - 1) * 64];
+        }
+        agq_v4i acc0 = {0, 0, 0, 0}, acc1 = {0, 0, 0, 0};
+#pragma unroll
+        for (int i = 0; i < KPW; ++i) {
+            const int kc = min(kb + i, KT - 1);
+            const agq_v4i a0 = __builtin_bit_cast(agq_v4i, xq[kc * 128 + lane]);
+            const agq_v4i a1 = __builtin_bit_cast(agq_v4i, xq[kc * 128 + 64 + lane]);
+            const agq_u4 wv = kb + i < KT ? w[i] : agq_u4{0u, 0u, 0u, 0u};
+            const agq_v4i b0 = __builtin_bit_cast(agq_v4i, (wv << 4) & 0xF0F0F0F0u);
+            const agq_v4i b1 = __builtin_bit_cast(agq_v4i, wv & 0xF0F0F0F0u);
+            acc0 = __builtin_amdgcn_mfma_i32_16x16x64_i8(a0, b0, acc0, 0, 0, 0);
+            acc1 = __builtin_amdgcn_mfma_i32_16x16x64_i8(a1, b1, acc1, 0, 0, 0);
+        }
+        const agq_v4i acc = acc0 + acc1;
+#pragma unroll
+        for (int r = 0; r < 4; ++r) red[(ws * 4 + r) * 64 + lane] = acc[r];
+        __syncthreads();
+        if (ws < 4 && live) {
+            const int r = ws;
+            const int m = 4 * (lane >> 4) + r;
+            const int n = nt * 16 + (lane & 15);
+            if (m < a.M && n < pN) {
+                int sum = 0;
+                for (int wv = 0; wv < wpt; ++wv) sum += red[(wv * 4 + r) * 64 + lane];
+                const int v = sum >> AGQ_W_SHIFT;   // exact: every term carries the factor
+                if (pr.acc_out) pr.acc_out[(int64_t)m * pN + n] = v;
+                pr.y[(int64_t)m * pr.ldy + n] =
+                    agq_dequant(v, a.scale_e * __half2float(__ushort_as_half((unsigned short)sw_bits)));
+            }
+        }
+        __syncthreads();   // partial sums consumed before the next tile overwrites them
+        if (round + 1 < rounds) {
+#pragma unroll
+            for (int i = 0; i < KPW; ++i) w[i] = wn[i];
+        }
+        pr = prn;
+        nt = ntn;
+    }
+}
+
+// More than 48 KiB of dynamic LDS needs the limit of the kernel raised, once per
+// process and kernel (the first call does it; it is a host-side setting, not a
+// stream operation).
+template <int KPW, int MP>
+int launch_shared_kpw(const DecodeArgs &a, int tiles, unsigned grid, int wpt, int nstreams, size_t lds, hipStream_t st) {
+    static bool raised = false;
+    if (!raised) {
+        hipError_t err = hipFuncSetAttribute(reinterpret_cast<const void *>(gemm_decode_shared_kernel<KPW, MP>),
+                                             hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024 - 512);
+        if (err != hipSuccess) return (int)err;
+        raised = true;
+    }
+    gemm_decode_shared_kernel<KPW, MP><<<grid, wpt * nstreams * 64, lds, st>>>(a, tiles, wpt);
+    return (int)hipGetLastError();
+}
+
+template <int MP>
+int launch_shared(const DecodeArgs &a, int kpw, int tiles, unsigned grid, int wpt, int nstreams, size_t lds, hipStream_t st) {
+    switch (kpw) {
+        case 1: return launch_shared_kpw<1, MP>(a, tiles, grid, wpt, nstreams, lds, st);
+        case 2: return launch_shared_kpw<2, MP>(a, tiles, grid, wpt, nstreams, lds, st);
+        case 4: return launch_shared_kpw<4, MP>(a, tiles, grid, wpt, nstreams, lds, st);
+        default: return launch_shared_kpw<8, MP>(a, tiles, grid, wpt, nstreams, lds, st);
     }
 }
 
@@ -231,12 +434,13 @@ int agq_launch_gemm_decode(const void *x, int x_kind, int bits, int64_t M, int64
         const agq_proj &pr = projs[p < count ? p : count - 1];
         a.tile_start[p] = tiles;
         if (p < count) tiles += (int)((pr.N + 15) / 16);
-        a.N[p] = (int)pr.N;
-        a.blob[p] = (const uint4 *)pr.w_packed;
-        a.sw[p] = (const __half *)pr.w_scale_f16;
-        a.y[p] = (__half *)pr.y_f16;
-        a.ldy[p] = pr.ldy;
-        a.acc_out[p] = pr.acc_out;
+        a.proj[p].N = (int)pr.N;
+        a.proj[p].pad = 0;
+        a.proj[p].blob = (const uint4 *)pr.w_packed;
+        a.proj[p].sw = (const __half *)pr.w_scale_f16;
+        a.proj[p].y = (__half *)pr.y_f16;
+        a.proj[p].ldy = pr.ldy;
+        a.proj[p].acc_out = pr.acc_out;
     }
     a.tile_start[kMaxProj] = tiles;
     for (int p = count; p <= kMaxProj; ++p) a.tile_start[p] = tiles;
@@ -247,8 +451,25 @@ int agq_launch_gemm_decode(const void *x, int x_kind, int bits, int64_t M, int64
     int waves = (a.KT + kpw - 1) / kpw;
     if (waves > 16) waves = 16;
     const unsigned grid = (unsigned)tiles;
-    const size_t lds = (size_t)waves * 2048;   // staging; reused as waves * 1 KiB of partial sums
+    // staging: per wavefront HB chunks x (8 x 4 MP) 16-byte pieces (see the kernel);
+    // reused as waves x 1 KiB of partial sums
+    const int mp = M <= 4 ? 1 : (M <= 8 ? 2 : 4);
+    const int hb = x_kind != 0 ? kpw : (8 / mp < kpw ? 8 / mp : kpw);
+    size_t per_wave = x_kind != 0 ? 0 : (size_t)hb * 8 * 4 * mp * 16;
+    if (per_wave < 1024) per_wave = 1024;
+    const size_t lds = (size_t)waves * per_wave;
     hipStream_t st = (hipStream_t)stream;
+    if (x_kind == 0 && M > 4 && a.KT <= kSharedMaxKT && a.KT <= waves * kpw && waves >= 4) {
+        // one tile stream per workgroup, one workgroup per CU: measured faster than
+        // fewer, larger workgroups with several streams
+        const int nstreams = 1;
+        int g = (tiles + nstreams - 1) / nstreams;
+        const int cap = 256 / nstreams;
+        if (g > cap) g = cap;
+        const size_t lds_shared = (size_t)a.KT * 2048 + (size_t)waves * nstreams * 1024;
+        if (M <= 8) return launch_shared<2>(a, kpw, tiles, (unsigned)g, waves, nstreams, lds_shared, st);
+        return launch_shared<4>(a, kpw, tiles, (unsigned)g, waves, nstreams, lds_shared, st);
+    }
     if (x_kind == 0) {
         if (M <= 4) return launch_xk<XK_F16, 1>(a, kpw, grid, waves, lds, st);
         if (M <= 8) return launch_xk<XK_F16, 2>(a, kpw, grid, waves, lds, st);

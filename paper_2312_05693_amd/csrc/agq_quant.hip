@@ -198,6 +198,12 @@ AgqQuant agq_make_quant(int bits, int e, int zp) {
     q.lo = AGQ_MAGIC + (float)(lo - zp);
     q.hi = AGQ_MAGIC + (float)(hi - zp);
     q.zp = zp;
+    // fp16 images: 2^-e has exponent field 15 - e, a normal number for 1 <= 15 - e <= 30
+    auto pair = [](uint32_t h) { return h | (h << 16); };
+    const int field = 15 - e;
+    q.h_scale2 = (field >= 1 && field <= 30) ? pair((uint32_t)field << 10) : 0u;
+    q.h_lo2 = pair(bits == 8 ? 0xD800u : 0xC800u);   // -128, -8
+    q.h_hi2 = pair(bits == 8 ? 0x57F0u : 0x4700u);   //  127,  7
     return q;
 }
 

@@ -204,6 +204,47 @@ def test_multi_projection_equals_single_calls(agq, oracle, M, bits):
         assert_f16_close(host(y), y_w, "multi q")
 
 
+@pytest.mark.parametrize("M,K,Ns", [(9, 8192, [4100]), (16, 1024, [4096, 4096, 1000]), (5, 4096, [11008, 11008])])
+def test_decode_many_tiles_per_workgroup(agq, oracle, M, K, Ns):
+    """5..16 rows with more channel tiles than compute units: the workgroups that
+    keep the quantized activation on chip walk over several tiles, also across
+    the projections of one call and into a ragged last tile."""
+    x = synth.make_activation(M, K, 4, seed=70 + M)
+    e = oracle.calibrate_act_exp(x, 8)
+    projs, wants = [], []
+    for i, N in enumerate(Ns):
+        wq, sw = synth.make_weight_q4(N, K, seed=80 + i)
+        acc = torch.full((M, N), -7, dtype=torch.int32, device="cuda")
+        projs.append((agq.pack_w4(dev(wq)), dev(sw), N, None, acc))
+        wants.append(oracle.linear_w4(x, 8, e, 0, wq, sw))
+    ys = agq.gemm_w4a8_multi(dev(x), e, projs, K)
+    for (acc_w, y_w), pr, y in zip(wants, projs, ys):
+        assert np.array_equal(host(pr[4]).astype(np.int64), acc_w)
+        assert_f16_close(host(y), y_w, "many tiles")
+
+
+@pytest.mark.parametrize("bits", [8, 4])
+@pytest.mark.parametrize("e", [-16, -15, -14, -3, 0, 5, 14, 15])
+@pytest.mark.parametrize("M", [4, 16])
+def test_decode_prologue_every_fp16_value(agq, oracle, M, e, bits):
+    """The Eq.2 prologue of the few-token kernels over every finite fp16 bit
+    pattern (ties, subnormals, both infinities) at exponents on both sides of
+    the range its half-precision arithmetic covers: a single wrong code shows in
+    the exact accumulators."""
+    pat = np.arange(65536, dtype=np.uint32).astype(np.uint16)
+    vals = pat.view(np.float16)
+    vals = vals[~np.isnan(vals)]
+    K = 128 * ((vals.size + M * 128 - 1) // (M * 128))
+    x = np.zeros(M * K, np.float16)
+    x[: vals.size] = vals
+    x = x.reshape(M, K)
+    rng = np.random.default_rng(e + 100)
+    wq = rng.integers(-8, 8, size=(32, K)).astype(np.int8)
+    wq[wq == 0] = 1                      # every code reaches every accumulator of its row
+    sw = np.full(32, 2.0 ** -12, np.float16)
+    run_linear(agq, oracle, x, wq, sw, bits, e=e, check_y=False)
+
+
 def test_extreme_operands_hit_the_bound(agq, oracle):
     # all codes at -128 and all weights at -8: acc = 128 * 8 * K exactly, the
     # largest value the accumulator can take (times 16 inside the kernel)
