@@ -149,48 +149,46 @@ __global__ __launch_bounds__(kThreads) void gemm_tiled_kernel(const TiledArgs a)
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0;
 
-    agq_u4 xa[2], bset[4];   // fragments of the current step: activation k-block 0, packed weights
+    // Fragments of a whole step live in registers: eight activation fragments
+    // (index i * 4 + t: 32-token tile i, k-block t) and four packed weight pieces.
+    // Two such sets alternate: while one is multiplied, the other is filled from
+    // the next step's LDS stage, so no MFMA ever waits for an LDS read it issued
+    // a few instructions earlier.
+    agq_u4 xa0[8], b0[4], xa1[8], b1[4];
 
     // One K step, software-pipelined by hand.  A wavefront issues in order and an
     // MFMA blocks the next MFMA while the matrix core is busy, but LDS reads,
     // copies and bit operations slip in between: every pair of MFMAs is followed
-    // by the LDS read of a fragment needed one k-block later, and the four copies
-    // of the step three ahead are spread over the step.  The last k-block
-    // prefetches the first fragments of the next stage.
-    auto step = [&](int kt, const unsigned char *cur, const unsigned char *nxt, unsigned char *fill) {
-        const agq_u4 *sc = reinterpret_cast<const agq_u4 *>(cur) + lane;
+    // by LDS reads for the next step (twelve per step), and the four copies of the
+    // step three ahead are spread over the step.
+    auto step = [&](int kt, const unsigned char *nxt, unsigned char *fill, const agq_u4 (&xc)[8], const agq_u4 (&bc)[4],
+                    agq_u4 (&xn)[8], agq_u4 (&bn)[4]) {
         const agq_u4 *sn = reinterpret_cast<const agq_u4 *>(nxt) + lane;
-        agq_u4 xn[2], bn[4];
 #pragma unroll
         for (int t = 0; t < 4; ++t) {
             agq_v4i wb[2];
 #pragma unroll
             for (int j = 0; j < 2; ++j) {
-                const agq_u4 p = bset[j * 2 + (t & 1)];
+                const agq_u4 p = bc[j * 2 + (t & 1)];
                 const agq_u4 w = t < 2 ? ((p << 4) & 0xF0F0F0F0u) : (p & 0xF0F0F0F0u);
                 wb[j] = __builtin_bit_cast(agq_v4i, w);
             }
             __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
             for (int i = 0; i < 2; ++i) {
-                const agq_v4i x = __builtin_bit_cast(agq_v4i, xa[i]);
+                const agq_v4i x = __builtin_bit_cast(agq_v4i, xc[i * 4 + t]);
                 acc[i][0] = __builtin_amdgcn_mfma_i32_32x32x32_i8(wb[0], x, acc[i][0], 0, 0, 0);
                 acc[i][1] = __builtin_amdgcn_mfma_i32_32x32x32_i8(wb[1], x, acc[i][1], 0, 0, 0);
                 __builtin_amdgcn_sched_barrier(0);
                 const int mi = wm * 2 + i;   // 32-token tile of the stage
-                xn[i] = t < 3 ? sc[(mi * 4 + t + 1) * 64] : sn[(mi * 4) * 64];
-                if (t == 3) {
-                    bn[2 * i] = sn[(kAChunks + wn * 4 + 2 * i) * 64];
-                    bn[2 * i + 1] = sn[(kAChunks + wn * 4 + 2 * i + 1) * 64];
+                xn[i * 4 + t] = sn[(mi * 4 + t) * 64];
+                if (i == 1) {
+                    bn[t] = sn[(kAChunks + wn * 4 + t) * 64];
+                    copy_piece(t, kt + 3, fill);
                 }
-                if (i == 1) copy_piece(t, kt + 3, fill);
                 __builtin_amdgcn_sched_barrier(0);
             }
-#pragma unroll
-            for (int i = 0; i < 2; ++i) xa[i] = xn[i];
         }
-#pragma unroll
-        for (int j = 0; j < 4; ++j) bset[j] = bn[j];
     };
 
 #pragma unroll
@@ -204,26 +202,28 @@ __global__ __launch_bounds__(kThreads) void gemm_tiled_kernel(const TiledArgs a)
     {
         const agq_u4 *s0 = reinterpret_cast<const agq_u4 *>(stage0) + lane;
 #pragma unroll
-        for (int i = 0; i < 2; ++i) xa[i] = s0[((wm * 2 + i) * 4) * 64];
+        for (int i = 0; i < 2; ++i)
 #pragma unroll
-        for (int j = 0; j < 4; ++j) bset[j] = s0[(kAChunks + wn * 4 + j) * 64];
+            for (int t = 0; t < 4; ++t) xa0[i * 4 + t] = s0[((wm * 2 + i) * 4 + t) * 64];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) b0[j] = s0[(kAChunks + wn * 4 + j) * 64];
     }
     // Every step kt: wait until this wavefront's copies of step kt+1 have landed
     // (loads return in order, each step issues four, so only the four of step
     // kt+2 may still fly), meet the others (everybody's copies of step kt+1 are
     // in LDS, and everybody has left step kt-1, whose LDS stage is refilled next),
     // then multiply step kt while copying step kt+3.
-#define AGQ_STEP(KT_, CUR, NXT, FILL)                                        \
+#define AGQ_STEP(KT_, NXT, FILL, XC, BC, XN, BN)                             \
     if ((KT_) < KT) {                                                        \
         asm volatile("s_waitcnt vmcnt(4)" ::: "memory");                     \
         __syncthreads();                                                     \
-        step((KT_), CUR, NXT, FILL);                                         \
+        step((KT_), NXT, FILL, XC, BC, XN, BN);                              \
     }
     for (int kt = 0; kt < KT; kt += 4) {      // stage of step kt is kt % 4
-        AGQ_STEP(kt, stage0, stage1, stage3)
-        AGQ_STEP(kt + 1, stage1, stage2, stage0)
-        AGQ_STEP(kt + 2, stage2, stage3, stage1)
-        AGQ_STEP(kt + 3, stage3, stage0, stage2)
+        AGQ_STEP(kt, stage1, stage3, xa0, b0, xa1, b1)
+        AGQ_STEP(kt + 1, stage2, stage0, xa1, b1, xa0, b0)
+        AGQ_STEP(kt + 2, stage3, stage1, xa0, b0, xa1, b1)
+        AGQ_STEP(kt + 3, stage0, stage2, xa1, b1, xa0, b0)
     }
 #undef AGQ_STEP
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // drain the trailing reloads
