@@ -1,17 +1,18 @@
 // Tiled int8-MFMA kernel of the quantized linear layer for many tokens (the
 // prefill regime, bound by the matrix cores).
 //
-// Workgroup tile 128 (tokens) x 256 (output channels), K step 128, eight
-// wavefronts as 2 (tokens) x 4 (channels): each owns 64 x 64 as 2 x 2 MFMA tiles
+// Workgroup tile 128 (tokens) x 128 (output channels), K step 128, four
+// wavefronts as 2 (tokens) x 2 (channels): each owns 64 x 64 as 2 x 2 MFMA tiles
 // of 32 x 32 (v_mfma_i32_32x32x32_i8, 64 accumulator registers per lane).  Two
-// wavefronts share a SIMD, so the matrix core has work while one of them waits
-// on LDS or on the copy queue; the 32 x 32 x 32 form is used because back-to-back
+// workgroups share a CU, one wavefront of each per SIMD: a workgroup barrier (one
+// per K step), a prologue or an epilogue stalls only one of the two wavefronts
+// that feed a matrix core.  The 32 x 32 x 32 form is used because back-to-back
 // 16 x 16 x 64 MFMAs of one wavefront keep the matrix core only 55 % busy.
 //
 //   activation codes: int8, already laid out in MFMA operand order by the
 //     pre-pass (16 KiB per 128-token tile and K step, see agq_quant.hip), copied
 //     HBM/L2 -> LDS by direct global-to-LDS loads (no registers in between,
-//     contiguous 1 KiB per instruction), four stages deep.  A fragment read is
+//     contiguous 1 KiB per instruction), three stages deep.  A fragment read is
 //     one conflict-free ds_read_b128 at lane * 16.
 //   weights: the packed 4-bit blob is copied the same way (16 bytes per lane,
 //     512-byte contiguous runs); a wavefront reads its 64 channels back once per
@@ -22,7 +23,8 @@
 //   No load in the main loop returns to registers, so the only waits on vector
 //   memory are the ones written here: loads return in order, every step issues
 //   four per wavefront, and a step waits until at most the four of the step two
-//   ahead are still in flight (copies start three steps ahead).
+//   ahead are still in flight (copies start three steps ahead; the fragments of the
+//   step being multiplied are already in registers, so three stages suffice).
 //
 // The weight fragment is the MFMA's first operand and the activation the second:
 // a lane then holds four consecutive output channels of one token.  The
@@ -36,13 +38,15 @@ typedef int agq_v16i __attribute__((ext_vector_type(16)));
 
 namespace {
 
-constexpr int BM = 128, BN = 256, BK = 128;
-constexpr int kThreads = 512;
+constexpr int BM = 128, BN = 128, BK = 128;
+constexpr int kThreads = 256;
 constexpr int kBand = 4;                  // token tiles per band of the tile walk
 constexpr int kAChunks = (BM / 32) * 4;   // 16 chunks of 1 KiB per stage
-constexpr int kBChunks = BN / 16;         // 16 chunks of 1 KiB per stage
+constexpr int kBChunks = BN / 16;         // 8 chunks of 1 KiB per stage
 constexpr int kABytes = kAChunks * 1024;
-constexpr int kStageBytes = (kAChunks + kBChunks) * 1024;   // 32 KiB
+constexpr int kStageBytes = (kAChunks + kBChunks) * 1024;   // 24 KiB
+constexpr int kStages = 3;
+constexpr int kCopies = (kAChunks + kBChunks) * 64 / kThreads;   // 6 copies per wavefront and step
 constexpr int kOutStride = 144;           // bytes per row of a wavefront's 64 x 64 fp16 output tile in LDS
 
 struct TiledArgs {
@@ -69,14 +73,13 @@ __device__ __forceinline__ void lds_dma16(const void *gsrc, uint32_t lds_addr) {
                  : "memory", "m0");
 }
 
-__global__ __launch_bounds__(kThreads) void gemm_tiled_kernel(const TiledArgs a) {
-    // Four pipeline stages of 32 KiB; the epilogue reuses the first 72 KiB.
-    __shared__ __align__(16) unsigned char lds[4 * kStageBytes];
-    unsigned char *const stage0 = lds, *const stage1 = lds + kStageBytes;
-    unsigned char *const stage2 = lds + 2 * kStageBytes, *const stage3 = lds + 3 * kStageBytes;
+__global__ __launch_bounds__(kThreads, 2) void gemm_tiled_kernel(const TiledArgs a) {
+    // Three pipeline stages of 24 KiB; the epilogue reuses the first 36 KiB.
+    __shared__ __align__(16) unsigned char lds[kStages * kStageBytes];
+    unsigned char *const stage0 = lds, *const stage1 = lds + kStageBytes, *const stage2 = lds + 2 * kStageBytes;
     const int lane = threadIdx.x & 63;
     const int wave = threadIdx.x >> 6;
-    const int wm = wave >> 2, wn = wave & 3;
+    const int wm = wave >> 1, wn = wave & 1;
 
     // XCD-aware tile order.  Consecutive workgroup ids land on different XCDs
     // (round-robin over 8), each with its own L2, so first give every XCD a
@@ -93,13 +96,13 @@ __global__ __launch_bounds__(kThreads) void gemm_tiled_kernel(const TiledArgs a)
     const int m0 = tm * BM, n0 = tn * BN;
     const int KT = a.KT;
 
-    // Copies of this wavefront per step: activation chunks 2 wave, 2 wave + 1 of
+    // Copies of this wavefront per step: activation chunks 4 wave .. 4 wave + 3 of
     // the 16 KiB stage, and weight chunks 2 wave, 2 wave + 1.  Weight chunk c
     // serves channel group c >> 2 (64 channels), 32-channel tile (c >> 1) & 1,
     // k-blocks t = c & 1 (low nibbles) and t + 2 (high nibbles): channel l & 31
     // of the tile lives in the blob's 16-row chunk (l & 31) >> 4 at blob lane
     // (2 t + (l >> 5)) * 16 + (l & 15).
-    const agq_u4 *asrc = a.xt + ((int64_t)tm * KT * 16 + wave * 2) * 64 + lane;
+    const agq_u4 *asrc = a.xt + ((int64_t)tm * KT * 16 + wave * 4) * 64 + lane;
     const agq_u4 *bsrc[2];
 #pragma unroll
     for (int p = 0; p < 2; ++p) {
@@ -109,15 +112,17 @@ __global__ __launch_bounds__(kThreads) void gemm_tiled_kernel(const TiledArgs a)
     }
     // LDS byte address (wave-uniform, kept in a scalar register) of this
     // wavefront's first activation chunk in stage 0
-    const uint32_t lds_w = __builtin_amdgcn_readfirstlane(
-        (uint32_t)(uintptr_t)(const __attribute__((address_space(3))) unsigned char *)lds + (uint32_t)wave * 2048u);
+    const uint32_t lds_base = __builtin_amdgcn_readfirstlane(
+        (uint32_t)(uintptr_t)(const __attribute__((address_space(3))) unsigned char *)lds);
+    const uint32_t wave_u = __builtin_amdgcn_readfirstlane((uint32_t)wave);
     auto copy_piece = [&](int p, int kt, unsigned char *st) {
-        const int k = min(kt, KT - 1);      // past the end: reload the last step (harmless, keeps counts uniform)
-        const uint32_t dst = lds_w + (uint32_t)(st - lds);
-        if (p < 2)
-            lds_dma16(asrc + ((int64_t)k * 16 + p) * 64, dst + p * 1024);
+        if (kt >= KT) return;               // nothing to fetch past the last step (uniform)
+        const int k = kt;
+        const uint32_t dst = lds_base + (uint32_t)(st - lds);
+        if (p < 4)
+            lds_dma16(asrc + ((int64_t)k * 16 + p) * 64, dst + (wave_u * 4 + p) * 1024);
         else
-            lds_dma16(bsrc[p - 2] + (int64_t)k * 64, dst + kABytes + (p - 2) * 1024);
+            lds_dma16(bsrc[p - 4] + (int64_t)k * 64, dst + kABytes + (wave_u * 2 + (p - 4)) * 1024);
     };
 
     // per-channel scales of this lane's output columns, fetched early
@@ -129,14 +134,13 @@ __global__ __launch_bounds__(kThreads) void gemm_tiled_kernel(const TiledArgs a)
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
             const int n = ncol + j * 32 + q * 8;
-            swp[j][q] = make_uint2(0, 0);
-            if (n + 3 < a.N) {
-                const uint16_t *sp = reinterpret_cast<const uint16_t *>(a.sw) + n;   // 8-byte aligned: n % 4 == 0
-                swp[j][q] = *reinterpret_cast<const uint2 *>(sp);
+            // channels past N are never stored: clamp their addresses into the array
+            const uint16_t *sp = reinterpret_cast<const uint16_t *>(a.sw);
+            if ((a.N & 3) == 0) {
+                swp[j][q] = *reinterpret_cast<const uint2 *>(sp + min(n, a.N - 4));   // 8-byte aligned: n % 4 == 0
             } else {
-                uint32_t h[4] = {0, 0, 0, 0};
-                for (int r = 0; r < 4; ++r)
-                    if (n + r < a.N) h[r] = reinterpret_cast<const uint16_t *>(a.sw)[n + r];
+                uint32_t h[4];
+                for (int r = 0; r < 4; ++r) h[r] = sp[min(n + r, a.N - 1)];
                 swp[j][q] = make_uint2(h[0] | (h[1] << 16), h[2] | (h[3] << 16));
             }
         }
@@ -159,7 +163,7 @@ __global__ __launch_bounds__(kThreads) void gemm_tiled_kernel(const TiledArgs a)
     // One K step, software-pipelined by hand.  A wavefront issues in order and an
     // MFMA blocks the next MFMA while the matrix core is busy, but LDS reads,
     // copies and bit operations slip in between: every pair of MFMAs is followed
-    // by LDS reads for the next step (twelve per step), and the four copies of the
+    // by LDS reads for the next step (twelve per step), and the six copies of the
     // step three ahead are spread over the step.
     auto step = [&](int kt, const unsigned char *nxt, unsigned char *fill, const agq_u4 (&xc)[8], const agq_u4 (&bc)[4],
                     agq_u4 (&xn)[8], agq_u4 (&bn)[4]) {
@@ -182,22 +186,23 @@ __global__ __launch_bounds__(kThreads) void gemm_tiled_kernel(const TiledArgs a)
                 __builtin_amdgcn_sched_barrier(0);
                 const int mi = wm * 2 + i;   // 32-token tile of the stage
                 xn[i * 4 + t] = sn[(mi * 4 + t) * 64];
-                if (i == 1) {
-                    bn[t] = sn[(kAChunks + wn * 4 + t) * 64];
-                    copy_piece(t, kt + 3, fill);
-                }
+                if (i == 1) bn[t] = sn[(kAChunks + wn * 4 + t) * 64];
+                if (2 * t + i < kCopies) copy_piece(2 * t + i, kt + 3, fill);
                 __builtin_amdgcn_sched_barrier(0);
             }
         }
     };
 
 #pragma unroll
-    for (int p = 0; p < 4; ++p) copy_piece(p, 0, stage0);
+    for (int p = 0; p < kCopies; ++p) copy_piece(p, 0, stage0);
 #pragma unroll
-    for (int p = 0; p < 4; ++p) copy_piece(p, 1, stage1);
+    for (int p = 0; p < kCopies; ++p) copy_piece(p, 1, stage1);
 #pragma unroll
-    for (int p = 0; p < 4; ++p) copy_piece(p, 2, stage2);
-    asm volatile("s_waitcnt vmcnt(8)" ::: "memory");   // step 0 has landed
+    for (int p = 0; p < kCopies; ++p) copy_piece(p, 2, stage2);
+    if (KT >= 3)
+        asm volatile("s_waitcnt vmcnt(12)" ::: "memory");   // step 0 has landed
+    else
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
     {
         const agq_u4 *s0 = reinterpret_cast<const agq_u4 *>(stage0) + lane;
@@ -209,24 +214,28 @@ __global__ __launch_bounds__(kThreads) void gemm_tiled_kernel(const TiledArgs a)
         for (int j = 0; j < 4; ++j) b0[j] = s0[(kAChunks + wn * 4 + j) * 64];
     }
     // Every step kt: wait until this wavefront's copies of step kt+1 have landed
-    // (loads return in order, each step issues four, so only the four of step
-    // kt+2 may still fly), meet the others (everybody's copies of step kt+1 are
-    // in LDS, and everybody has left step kt-1, whose LDS stage is refilled next),
-    // then multiply step kt while copying step kt+3.
+    // (loads return in order, each step issues six, so only the six of step
+    // kt+2, if there is one, may still fly), meet the others (everybody's copies of step kt+1 are
+    // in LDS, and everybody has read step kt's fragments out of the stage that is
+    // refilled next), then multiply step kt while copying step kt+3.
 #define AGQ_STEP(KT_, NXT, FILL, XC, BC, XN, BN)                             \
     if ((KT_) < KT) {                                                        \
-        asm volatile("s_waitcnt vmcnt(4)" ::: "memory");                     \
+        if ((KT_) + 2 < KT)                                                  \
+            asm volatile("s_waitcnt vmcnt(6)" ::: "memory");                 \
+        else                                                                 \
+            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");                 \
         __syncthreads();                                                     \
         step((KT_), NXT, FILL, XC, BC, XN, BN);                              \
     }
-    for (int kt = 0; kt < KT; kt += 4) {      // stage of step kt is kt % 4
-        AGQ_STEP(kt, stage1, stage3, xa0, b0, xa1, b1)
-        AGQ_STEP(kt + 1, stage2, stage0, xa1, b1, xa0, b0)
-        AGQ_STEP(kt + 2, stage3, stage1, xa0, b0, xa1, b1)
-        AGQ_STEP(kt + 3, stage0, stage2, xa1, b1, xa0, b0)
+    for (int kt = 0; kt < KT; kt += 6) {      // stage of step kt is kt % 3, register set kt % 2
+        AGQ_STEP(kt, stage1, stage0, xa0, b0, xa1, b1)
+        AGQ_STEP(kt + 1, stage2, stage1, xa1, b1, xa0, b0)
+        AGQ_STEP(kt + 2, stage0, stage2, xa0, b0, xa1, b1)
+        AGQ_STEP(kt + 3, stage1, stage0, xa1, b1, xa0, b0)
+        AGQ_STEP(kt + 4, stage2, stage1, xa0, b0, xa1, b1)
+        AGQ_STEP(kt + 5, stage0, stage2, xa1, b1, xa0, b0)
     }
 #undef AGQ_STEP
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // drain the trailing reloads
     __syncthreads();                                   // every wavefront is done with the stages
 
     // Fused epilogue.  Drop the factor 16 of the widened weights, dequantize with
@@ -245,7 +254,7 @@ __global__ __launch_bounds__(kThreads) void gemm_tiled_kernel(const TiledArgs a)
                     if (m < a.M && n < a.N) a.acc_out[(int64_t)m * a.N + n] = acc[i][j][r] >> AGQ_W_SHIFT;
                 }
     }
-    unsigned char *obuf = lds + wave * (64 * kOutStride);   // 9 KiB per wavefront, 72 KiB in all
+    unsigned char *obuf = lds + wave * (64 * kOutStride);   // 9 KiB per wavefront, 36 KiB in all
 #pragma unroll
     for (int i = 0; i < 2; ++i)
 #pragma unroll
