@@ -50,6 +50,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-prefill", action="store_true")
+    ap.add_argument("--no-attention", action="store_true")
     ap.add_argument("--per-projection", action="store_true", help="seven single calls per block instead of four")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -181,7 +182,8 @@ def main():
                    "algorithmic_bytes_per_step": int(bytes_per_step)},
         "roofline": {"bound": "hbm", "achieved": round(gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": round(gbs / HBM_PEAK_GBS, 4), "traffic": MEASURED_TRAFFIC_BYTES_PER_LAUNCH,
-                     "kernel": "gemm_decode_kernel", "avg_launch_us": round(avg_launch_us, 3),
+                     "kernel": "gemm_decode_kernel (M <= 4, K > 8192) and gemm_decode_shared_kernel (5..16 rows): "
+                               "every launch of a step", "avg_launch_us": round(avg_launch_us, 3),
                      "algorithmic_bytes_per_launch": int(bytes_per_step / launches_per_step)},
         "decode_by_M": per_m,
         "launch": "one HIP graph per step, replayed; per block: qkv (one multi call), o, gate+up (one multi call), down"
@@ -235,6 +237,55 @@ def main():
                                           "note": "fp16 input: time includes the 4 quantize/layout pre-passes of a block"},
                              "single_calls": shapes}
         result["prefill"] = prefill
+
+    # ---- attention side path at LLaMA-13B size: log2-quantized softmax x V with the start-token score,
+    #      then Eq.4 pruning to half the tokens (HBM bound: the probabilities are read once)
+    if not args.no_attention:
+        H, S, D = 40, 2048, 128
+        g2 = torch.Generator(device=dev)
+        g2.manual_seed(4)
+        qh = torch.randn(H, S, D, generator=g2, device=dev)
+        kh = torch.randn(H, S, D, generator=g2, device=dev)
+        logits = qh @ kh.transpose(1, 2) / D ** 0.5
+        logits[:, :, 0] += 4.0                                           # the start-token stripe of Section 4.3
+        causal = torch.tril(torch.ones(S, S, dtype=torch.bool, device=dev))
+        p0 = torch.softmax(logits.masked_fill(~causal, float("-inf")), dim=-1).to(torch.float16).contiguous()
+        del qh, kh, logits, causal
+        probs = [p0, p0.clone(), p0.clone()]                              # 1 GB in rotation: no cache reuse between calls
+        vq = torch.randint(-127, 128, (H, S, D), generator=g2, device=dev, dtype=torch.int8)
+        ws_a = torch.empty(agq.log2_quant_softmax_workspace_bytes(H, S, D), dtype=torch.uint8, device=dev)
+        turn = [0]
+
+        def attn():
+            turn[0] += 1
+            return agq.log2_quant_softmax(probs[turn[0] % 3], vq, -5, workspace=ws_a)
+
+        def time_plain(f, reps=12):
+            for _ in range(3):
+                f()
+            torch.cuda.synchronize()
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a.record()
+            for _ in range(reps):
+                f()
+            b.record()
+            torch.cuda.synchronize()
+            return a.elapsed_time(b) / reps
+
+        us_attn = time_plain(attn) * 1e3
+        o_a, _, score_a = attn()
+        us_prune = time_plain(lambda: agq.prune_tokens(score_a, S // 2, o_a)) * 1e3
+        by_attn = H * S * (S + 1) // 2 * 2 + H * S * D + S * H * D * 2       # causal half of P, V, O
+        by_prune = 4 * S + 2 * (S // 2) * H * D * 2
+        result["attention"] = {
+            "workload": "llama13b attention block: H=40, S=2048, D=128, causal, qmax=15, prune to 1024 tokens",
+            "log2_softmax_v": {"us": round(us_attn, 1), "GB/s": round(by_attn / us_attn / 1e3, 1),
+                               "roofline": {"bound": "hbm", "achieved": round(by_attn / us_attn / 1e3, 1),
+                                            "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                                            "frac": round(by_attn / us_attn / 1e3 / HBM_PEAK_GBS, 4), "traffic": None,
+                                            "kernel": "vt_prepack_kernel + log2_attn_kernel"}},
+            "prune_tokens": {"us": round(us_prune, 1), "GB/s": round(by_prune / us_prune / 1e3, 1)}}
+        del probs, p0
 
     # ---- CPU baseline: the oracle as it stands, on a bounded sample of the decode workload
     if not args.no_cpu_baseline:

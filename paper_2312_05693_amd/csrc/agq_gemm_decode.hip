@@ -241,7 +241,7 @@ __global__ __launch_bounds__(KPW == 8 ? 1024 : 512, KPW == 8 ? 4 : (MP == 1 ? 6 
     }
 }
 
-// Variant for 5..16 token rows of fp16 input.  With that many rows the activation
+// Variant for 9..16 token rows of fp16 input.  With that many rows the activation
 // is no longer small: every workgroup that covers the whole K reads all of it
 // from L2 (M x K x 2 bytes, times the number of workgroups: several times the
 // weight bytes) and quantizes all of it.  So here few, large workgroups each do
@@ -459,7 +459,11 @@ int agq_launch_gemm_decode(const void *x, int x_kind, int bits, int64_t M, int64
     if (per_wave < 1024) per_wave = 1024;
     const size_t lds = (size_t)waves * per_wave;
     hipStream_t st = (hipStream_t)stream;
-    if (x_kind == 0 && M > 4 && a.KT <= kSharedMaxKT && a.KT <= waves * kpw && waves >= 4) {
+    // Quantizing the activation once per workgroup pays when a CU serves several
+    // channel tiles and the activation is large (measured at K = 4096: from nine
+    // rows on and more than one tile per CU; below that the per-tile prologue,
+    // which overlaps better with the weight stream, is faster).
+    if (x_kind == 0 && M > 8 && tiles > 256 && a.KT <= kSharedMaxKT && a.KT <= waves * kpw && waves >= 4) {
         // one tile stream per workgroup, one workgroup per CU: measured faster than
         // fewer, larger workgroups with several streams
         const int nstreams = 1;
@@ -467,7 +471,6 @@ int agq_launch_gemm_decode(const void *x, int x_kind, int bits, int64_t M, int64
         const int cap = 256 / nstreams;
         if (g > cap) g = cap;
         const size_t lds_shared = (size_t)a.KT * 2048 + (size_t)waves * nstreams * 1024;
-        if (M <= 8) return launch_shared<2>(a, kpw, tiles, (unsigned)g, waves, nstreams, lds_shared, st);
         return launch_shared<4>(a, kpw, tiles, (unsigned)g, waves, nstreams, lds_shared, st);
     }
     if (x_kind == 0) {
