@@ -51,6 +51,8 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-prefill", action="store_true")
     ap.add_argument("--no-attention", action="store_true")
+    ap.add_argument("--copy-probe", action="store_true",
+                    help="also run a 256 MiB device copy: the known traffic that scales the FETCH_SIZE / WRITE_SIZE counters")
     ap.add_argument("--per-projection", action="store_true", help="seven single calls per block instead of four")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -67,6 +69,14 @@ def main():
     dev = torch.device("cuda:0")
     gen = torch.Generator(device=dev)
     gen.manual_seed(1)
+
+    if args.copy_probe:
+        src = torch.empty(256 << 20, dtype=torch.uint8, device=dev).fill_(7)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     def make_packed(N, K):
         """N(0, 0.02) weights -> symmetric 4-bit per output channel -> packed blob (all on the GPU; input recipe)."""
