@@ -33,9 +33,10 @@ INT8_PEAK_TOPS = 5000.0        # MI355X dense int8 MFMA
 DECODE_M = (1, 4, 16)
 PREFILL_M = 2048
 
-# HBM traffic per launch of the decode kernel from rocprofv3 --pmc (FETCH_SIZE,
-# WRITE_SIZE), scaled by a copy kernel of known size; see profiles/.  None until measured.
-MEASURED_TRAFFIC_BYTES_PER_LAUNCH = None
+# HBM traffic per launch of the decode kernels from rocprofv3 --pmc (FETCH_SIZE x 2.0 KiB +
+# WRITE_SIZE x 1.0 KiB, the factors a 256 MiB copy gives); see profiles/.
+MEASURED_TRAFFIC_BYTES_PER_LAUNCH = 26.3e6
+MEASURED_ATTN_TRAFFIC_BYTES = 234.8e6   # log2_attn_kernel, one call of the bench's attention block
 
 
 def algorithmic_bytes(M, K, N):
@@ -292,7 +293,8 @@ def main():
             "log2_softmax_v": {"us": round(us_attn, 1), "GB/s": round(by_attn / us_attn / 1e3, 1),
                                "roofline": {"bound": "hbm", "achieved": round(by_attn / us_attn / 1e3, 1),
                                             "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                                            "frac": round(by_attn / us_attn / 1e3 / HBM_PEAK_GBS, 4), "traffic": None,
+                                            "frac": round(by_attn / us_attn / 1e3 / HBM_PEAK_GBS, 4),
+                                            "traffic": MEASURED_ATTN_TRAFFIC_BYTES,
                                             "kernel": "vt_prepack_kernel + log2_attn_kernel"}},
             "prune_tokens": {"us": round(us_prune, 1), "GB/s": round(by_prune / us_prune / 1e3, 1)}}
         del probs, p0
