@@ -39,13 +39,22 @@ struct DecodeProj {
     int N, pad;
 };
 
+// What a workgroup needs before its first vector load comes first and packed, so
+// that a few wide scalar loads (one round trip) bring it in; the projection
+// records, needed again only for the store, follow.
 struct DecodeArgs {
     const void *x;
     int64_t ldx;      // elements (fp16 / int8) or codes (nibbles)
     int M, KT, count;
-    AgqQuant q;
     float scale_e;    // 2^e
     int tile_start[kMaxProj + 1];   // entries from `count` on hold the total
+    int waves;                      // wavefronts per workgroup (= blockDim.x / 64, without a trip to the dispatch packet)
+    int pad0[2];
+    const uint4 *blob4[kMaxProj];   // copies of proj[p].blob, .sw, .N
+    const __half *sw4[kMaxProj];
+    int N4[kMaxProj];
+    AgqQuant q;
+    int pad1;
     DecodeProj proj[kMaxProj];
 };
 
@@ -88,19 +97,26 @@ __global__ __launch_bounds__(KPW == 8 ? 1024 : 512, KPW == 8 ? 4 : (MP == 1 ? 6 
     extern __shared__ __align__(16) unsigned char smem[];
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int nwaves = blockDim.x >> 6;
-    // all scalar arguments are requested in the first round of loads; only the
-    // projection record depends on one of them
+    const int nwaves = a.waves;
+    // Everything the first vector loads depend on is requested in one round of
+    // scalar loads; the weight pointer, scale pointer and width of this workgroup's
+    // projection are picked by scalar selects instead of a second, dependent round
+    // (~500 cycles).  The rest of the record is fetched now and used at the store.
     const int KT = a.KT;
     const int t1 = a.tile_start[1], t2 = a.tile_start[2], t3 = a.tile_start[3];
-    asm volatile("" ::"s"(a.x), "s"(a.ldx), "s"(a.M), "s"(KT), "s"(t1), "s"(t2), "s"(t3), "s"(a.q.scale), "s"(a.q.lo),
-                 "s"(a.q.hi), "s"(a.q.h_scale2), "s"(a.q.h_lo2), "s"(a.q.h_hi2), "s"(a.scale_e));
+    const uint4 *bl0 = a.blob4[0], *bl1 = a.blob4[1], *bl2 = a.blob4[2], *bl3 = a.blob4[3];
+    const __half *sc0 = a.sw4[0], *sc1 = a.sw4[1], *sc2 = a.sw4[2], *sc3 = a.sw4[3];
+    const int n0 = a.N4[0], n1 = a.N4[1], n2 = a.N4[2], n3 = a.N4[3];
+    asm volatile("" ::"s"(a.x), "s"(a.ldx), "s"(a.M), "s"(KT), "s"(nwaves), "s"(t1), "s"(t2), "s"(t3), "s"(a.scale_e), "s"(bl0),
+                 "s"(bl1), "s"(bl2), "s"(bl3), "s"(sc0), "s"(sc1), "s"(sc2), "s"(sc3), "s"(n0), "s"(n1), "s"(n2), "s"(n3),
+                 "s"(a.q.scale), "s"(a.q.lo), "s"(a.q.hi), "s"(a.q.h_scale2), "s"(a.q.h_lo2), "s"(a.q.h_hi2));
     int nt;
     const int pj = find_proj(a, blockIdx.x, nt);   // which projection this workgroup serves (uniform)
     const DecodeProj pr = a.proj[pj];
-    const int pN = pr.N;
-    const __half *psw = pr.sw;
-    const agq_u4 *wptr = reinterpret_cast<const agq_u4 *>(pr.blob) + ((int64_t)nt * KT) * 64 + lane;
+    const int pN = pj == 0 ? n0 : (pj == 1 ? n1 : (pj == 2 ? n2 : n3));
+    const __half *psw = pj == 0 ? sc0 : (pj == 1 ? sc1 : (pj == 2 ? sc2 : sc3));
+    const uint4 *pblob = pj == 0 ? bl0 : (pj == 1 ? bl1 : (pj == 2 ? bl2 : bl3));
+    const agq_u4 *wptr = reinterpret_cast<const agq_u4 *>(pblob) + ((int64_t)nt * KT) * 64 + lane;
 
     agq_v4i acc0 = {0, 0, 0, 0}, acc1 = {0, 0, 0, 0};
     // Staging of the quantized activation: one region per chunk of a batch, in MFMA
@@ -226,7 +242,7 @@ __global__ __launch_bounds__(KPW == 8 ? 1024 : 512, KPW == 8 ? 4 : (MP == 1 ? 6 
     for (int r = 0; r < 4; ++r) red[(wave * 4 + r) * 64 + lane] = acc[r];
     __syncthreads();
     const int shift = AGQ_W_SHIFT + (XK == XK_I4 ? 4 : 0);
-    for (int o = threadIdx.x; o < 256; o += blockDim.x) {
+    for (int o = threadIdx.x; o < 256; o += nwaves * 64) {
         const int l = o & 63, r = o >> 6;
         const int m = 4 * (l >> 4) + r;
         const int n = nt * 16 + (l & 15);
@@ -235,7 +251,7 @@ __global__ __launch_bounds__(KPW == 8 ? 1024 : 512, KPW == 8 ? 4 : (MP == 1 ? 6 
             for (int w = 0; w < nwaves; ++w) sum += red[(w * 4 + r) * 64 + l];
             const int v = sum >> shift;   // exact: every term carries the factor
             if (pr.acc_out) pr.acc_out[(int64_t)m * pN + n] = v;
-            const uint32_t sb = blockDim.x >= 256 ? sw_bits : (uint32_t) reinterpret_cast<const uint16_t *>(psw)[n];
+            const uint32_t sb = nwaves >= 4 ? sw_bits : (uint32_t) reinterpret_cast<const uint16_t *>(psw)[n];
             pr.y[(int64_t)m * pr.ldy + n] = agq_dequant(v, a.scale_e * __half2float(__ushort_as_half((unsigned short)sb)));
         }
     }
@@ -427,6 +443,9 @@ int agq_launch_gemm_decode(const void *x, int x_kind, int bits, int64_t M, int64
     a.M = (int)M;
     a.KT = (int)agq_k_tiles(K);
     a.count = count;
+    a.waves = 0;
+    a.pad0[0] = a.pad0[1] = 0;
+    a.pad1 = 0;
     a.q = agq_make_quant(bits, e, 0);
     a.scale_e = ldexpf(1.0f, e);
     int tiles = 0;
@@ -434,6 +453,9 @@ int agq_launch_gemm_decode(const void *x, int x_kind, int bits, int64_t M, int64
         const agq_proj &pr = projs[p < count ? p : count - 1];
         a.tile_start[p] = tiles;
         if (p < count) tiles += (int)((pr.N + 15) / 16);
+        a.blob4[p] = (const uint4 *)pr.w_packed;
+        a.sw4[p] = (const __half *)pr.w_scale_f16;
+        a.N4[p] = (int)pr.N;
         a.proj[p].N = (int)pr.N;
         a.proj[p].pad = 0;
         a.proj[p].blob = (const uint4 *)pr.w_packed;
@@ -451,6 +473,7 @@ int agq_launch_gemm_decode(const void *x, int x_kind, int bits, int64_t M, int64
     int waves = (a.KT + kpw - 1) / kpw;
     if (waves > 16) waves = 16;
     const unsigned grid = (unsigned)tiles;
+    a.waves = waves;
     // staging: per wavefront HB chunks x (8 x 4 MP) 16-byte pieces (see the kernel);
     // reused as waves x 1 KiB of partial sums
     const int mp = M <= 4 ? 1 : (M <= 8 ? 2 : 4);
