@@ -67,7 +67,7 @@ __device__ __forceinline__ int find_proj(const DecodeArgs &a, int tile, int &nt)
     return pj;
 }
 
-enum { XK_F16 = 0, XK_I8 = 1, XK_I4 = 2 };
+enum { XK_F16 = 0, XK_I8 = 1, XK_I4 = 2, XK_F16_ONE = 3 };   // ONE: fp16 with a single token row
 
 typedef unsigned int agq_u4 __attribute__((ext_vector_type(4)));
 typedef unsigned int agq_u2 __attribute__((ext_vector_type(2)));
@@ -124,8 +124,11 @@ __global__ __launch_bounds__(KPW == 8 ? 1024 : 512, KPW == 8 ? 4 : (MP == 1 ? 6 
     // rows the prologue writes (operand rows beyond R alias lower rows; they never
     // reach a stored result).  A batch is HB chunks: all of them are written, then
     // all operands are read back, so the LDS round trip is paid once per batch.
+    constexpr bool F16 = XK == XK_F16 || XK == XK_F16_ONE;
+    constexpr bool ONE = XK == XK_F16_ONE;   // one row: a lane's 16 bytes are its own chunk's, four chunks per load
     constexpr int R = 4 * MP;
-    constexpr int HB = XK != XK_F16 ? KPW : (8 / MP < KPW ? 8 / MP : KPW);
+    constexpr int HB = !F16 ? KPW : (8 / MP < KPW ? 8 / MP : KPW);
+    constexpr int NX = ONE ? (HB + 3) / 4 : HB;                       // activation loads per batch and row pass
     constexpr int kRegion = 8 * R;                                     // 16-byte pieces per chunk
     agq_u4 *stage = reinterpret_cast<agq_u4 *>(smem) + wave * (HB * kRegion);
     const int arow = min(lane & 15, a.M - 1);   // operand row of this lane, clamped into the tensor
@@ -141,11 +144,16 @@ __global__ __launch_bounds__(KPW == 8 ? 1024 : 512, KPW == 8 ? 4 : (MP == 1 ? 6 
         // loaded again and its weights are zeroed.  With many token rows the
         // activation is fetched HB chunks at a time to bound the registers.
         const int c16 = lane & 15, rr = lane >> 4;
-        agq_u4 xv[XK == XK_F16 ? HB : 1][XK == XK_F16 ? MP : 1];
-        agq_v4i fa0[XK == XK_F16 ? HB : KPW], fa1[XK == XK_F16 ? HB : KPW];
+        agq_u4 xv[F16 ? NX : 1][F16 ? MP : 1];
+        agq_v4i fa0[F16 ? HB : KPW], fa1[F16 ? HB : KPW];
         auto load_x = [&](int i0) {
 #pragma unroll
-            for (int i = 0; i < HB; ++i) {
+            for (int i = 0; i < NX; ++i) {
+                if (ONE) {   // lane = (chunk 4 i + rr of the batch, eight k): one row only
+                    const int64_t kc = min(kb + i0 + 4 * i + rr, KT - 1);
+                    xv[i][0] = *reinterpret_cast<const agq_u4 *>(reinterpret_cast<const __half *>(a.x) + kc * 128 + c16 * 8);
+                    continue;
+                }
                 const int64_t kc = min(kb + i0 + i, KT - 1);
                 const __half *xh = reinterpret_cast<const __half *>(a.x) + kc * 128 + c16 * 8;
 #pragma unroll
@@ -153,7 +161,7 @@ __global__ __launch_bounds__(KPW == 8 ? 1024 : 512, KPW == 8 ? 4 : (MP == 1 ? 6 
                     xv[i][it] = *reinterpret_cast<const agq_u4 *>(xh + (int64_t)min(it * 4 + rr, a.M - 1) * a.ldx);
             }
         };
-        if (XK == XK_F16) {
+        if (F16) {
             load_x(0);
         } else {
 #pragma unroll
@@ -193,19 +201,24 @@ __global__ __launch_bounds__(KPW == 8 ? 1024 : 512, KPW == 8 ? 4 : (MP == 1 ? 6 
 
 #pragma unroll
         for (int b0 = 0; b0 < KPW; b0 += HB) {
-            if (XK == XK_F16) {
+            if (F16) {
                 if (b0 > 0) load_x(b0);
                 // Eq.2 on the M x 128 slice of each chunk: lane = 8 consecutive k of one
                 // row, four rows per pass; rows were clamped for the load and are
                 // masked for the LDS store
                 const int s = c16 >> 3, g = (c16 & 7) >> 1, hf = c16 & 1;
 #pragma unroll
-                for (int i = 0; i < HB; ++i)
+                for (int i = 0; i < NX; ++i)
 #pragma unroll
                     for (int it = 0; it < MP; ++it) {
-                        const int m = it * 4 + rr;
                         const agq_u2 codes = quant8v(xv[i][it], a.q);
-                        if (m < a.M) reinterpret_cast<agq_u2 *>(stage + i * kRegion + (s * 4 + g) * R + m)[hf] = codes;
+                        if (ONE) {
+                            const int ch = 4 * i + rr;   // chunk of the batch, row 0
+                            if (ch < HB) reinterpret_cast<agq_u2 *>(stage + ch * kRegion + (s * 4 + g) * R)[hf] = codes;
+                        } else {
+                            const int m = it * 4 + rr;
+                            if (m < a.M) reinterpret_cast<agq_u2 *>(stage + i * kRegion + (s * 4 + g) * R + m)[hf] = codes;
+                        }
                     }
                 // the same wavefront wrote and now reads: LDS keeps program order per wave
                 __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
@@ -222,7 +235,7 @@ __global__ __launch_bounds__(KPW == 8 ? 1024 : 512, KPW == 8 ? 4 : (MP == 1 ? 6 
 #pragma unroll
             for (int i = 0; i < HB; ++i) {
                 const bool valid = kb + b0 + i < KT;            // wave-uniform
-                const agq_v4i a0 = fa0[XK == XK_F16 ? i : b0 + i], a1 = fa1[XK == XK_F16 ? i : b0 + i];
+                const agq_v4i a0 = fa0[F16 ? i : b0 + i], a1 = fa1[F16 ? i : b0 + i];
                 const agq_u4 wv = valid ? w[b0 + i] : agq_u4{0u, 0u, 0u, 0u};
                 const agq_v4i b0v = __builtin_bit_cast(agq_v4i, (wv << 4) & 0xF0F0F0F0u);
                 const agq_v4i b1v = __builtin_bit_cast(agq_v4i, wv & 0xF0F0F0F0u);
@@ -497,6 +510,7 @@ int agq_launch_gemm_decode(const void *x, int x_kind, int bits, int64_t M, int64
         return launch_shared<4>(a, kpw, tiles, (unsigned)g, waves, nstreams, lds_shared, st);
     }
     if (x_kind == 0) {
+        if (M == 1) return launch_xk<XK_F16_ONE, 1>(a, kpw, grid, waves, lds, st);
         if (M <= 4) return launch_xk<XK_F16, 1>(a, kpw, grid, waves, lds, st);
         if (M <= 8) return launch_xk<XK_F16, 2>(a, kpw, grid, waves, lds, st);
         return launch_xk<XK_F16, 4>(a, kpw, grid, waves, lds, st);
