@@ -93,7 +93,7 @@ __device__ __forceinline__ agq_u2 quant8v(const agq_u4 &h, const AgqQuant &q) {
 // XK: what x holds; KPW: weight chunks per wavefront and pass over K;
 // MP: passes of four token rows the Eq.2 prologue makes (M <= 4 MP).
 template <int XK, int KPW, int MP>
-__global__ __launch_bounds__(KPW == 8 ? 1024 : 512, KPW == 8 ? 4 : (MP == 1 ? 6 : (MP == 2 ? 5 : 4))) void gemm_decode_kernel(const DecodeArgs a) {
+__global__ __launch_bounds__(1024) void gemm_decode_kernel(const DecodeArgs a) {
     extern __shared__ __align__(16) unsigned char smem[];
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -485,6 +485,15 @@ int agq_launch_gemm_decode(const void *x, int x_kind, int bits, int64_t M, int64
     while (kpw < 8 && (a.KT + kpw - 1) / kpw > 8) kpw *= 2;
     int waves = (a.KT + kpw - 1) / kpw;
     if (waves > 16) waves = 16;
+    if (x_kind == 0 && (M > 4 || a.KT > 64)) {
+        // several token rows or a long K: the Eq.2 prologue weighs more, so spread it
+        // over as many wavefronts as a workgroup holds (K in rounds when it is very
+        // long); measured faster than eight fatter wavefronts for these cases only
+        kpw = 1;
+        while (kpw < 4 && (a.KT + kpw - 1) / kpw > 16) kpw *= 2;
+        waves = (a.KT + kpw - 1) / kpw;
+        if (waves > 16) waves = 16;
+    }
     const unsigned grid = (unsigned)tiles;
     a.waves = waves;
     // staging: per wavefront HB chunks x (8 x 4 MP) 16-byte pieces (see the kernel);
