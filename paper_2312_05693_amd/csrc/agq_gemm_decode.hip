@@ -4,17 +4,20 @@
 // One workgroup owns one 16-row tile of output channels and the whole K, so no
 // partial sum ever leaves the CU.  Its wavefronts split K: each streams KPW
 // consecutive 1 KiB weight chunks (one coalesced 16-byte load per lane and
-// chunk), all issued before anything else so that the HBM latency is paid once
-// and overlaps the prologue.  Small workgroups with few registers keep several
-// of them resident per CU: the chip holds every chunk of a LLaMA-sized matrix
-// in flight at once, which is what a 10-20 MB read needs to approach HBM rate.
+// chunk), all requested up front so that the HBM latency is paid once and
+// overlaps the prologue: the chip holds every chunk of a LLaMA-sized matrix in
+// flight at once, which is what a 10-20 MB read needs to approach HBM rate.
+// The kernel is a chain of latencies (arguments, load issue through the CU's one
+// address unit, activation from L2, LDS staging, weights, reduction, store), and
+// what is tuned here is the length of that chain: one round of scalar loads,
+// as few vector-memory instructions as the bytes allow, one LDS round trip.
 //
 // Eq.2 runs as a prologue while the weights fly: a wavefront quantizes exactly
-// the slice of the activation it multiplies (M x 128 values per chunk) into a
-// private LDS region laid out in MFMA operand order.  Rows beyond M are never
-// written, and never reach a stored result, because an MFMA output row depends
-// on the matching operand row only.  A single LDS reduction joins the
-// wavefronts before the fused per-channel dequantisation.
+// the slice of the activation it multiplies (M x 128 values per chunk, packed
+// fp16 arithmetic) into a private LDS region laid out in MFMA operand order.
+// Rows beyond M are never written, and never reach a stored result, because an
+// MFMA output row depends on the matching operand row only.  A single LDS
+// reduction joins the wavefronts before the fused per-channel dequantisation.
 #include "../../include/agq.h"
 #include "agq_device.h"
 #include "agq_internal.h"
@@ -485,10 +488,12 @@ int agq_launch_gemm_decode(const void *x, int x_kind, int bits, int64_t M, int64
     while (kpw < 8 && (a.KT + kpw - 1) / kpw > 8) kpw *= 2;
     int waves = (a.KT + kpw - 1) / kpw;
     if (waves > 16) waves = 16;
-    if (x_kind == 0 && (M > 4 || a.KT > 64)) {
-        // several token rows or a long K: the Eq.2 prologue weighs more, so spread it
-        // over as many wavefronts as a workgroup holds (K in rounds when it is very
-        // long); measured faster than eight fatter wavefronts for these cases only
+    if (x_kind == 0 && ((M > 4 && tiles <= 256) || a.KT > 64)) {
+        // Several token rows with one workgroup per CU, or a long K: the Eq.2 prologue
+        // weighs more, so spread it over as many wavefronts as a workgroup holds (K in
+        // rounds when it is very long).  Measured: faster than eight fatter wavefronts
+        // in exactly these cases; with several workgroups per CU and K <= 8192 the
+        // smaller workgroups win.
         kpw = 1;
         while (kpw < 4 && (a.KT + kpw - 1) / kpw > 16) kpw *= 2;
         waves = (a.KT + kpw - 1) / kpw;
