@@ -513,15 +513,19 @@ int agq_launch_gemm_decode(const void *x, int x_kind, int bits, int64_t M, int64
     // channel tiles and the activation is large (measured at K = 4096: from nine
     // rows on and more than one tile per CU; below that the per-tile prologue,
     // which overlaps better with the weight stream, is faster).
-    if (x_kind == 0 && M > 8 && tiles > 256 && a.KT <= kSharedMaxKT && a.KT <= waves * kpw && waves >= 4) {
-        // one tile stream per workgroup, one workgroup per CU: measured faster than
-        // fewer, larger workgroups with several streams
+    if (x_kind == 0 && M > 8 && tiles > 256 && a.KT <= kSharedMaxKT && a.KT >= 4) {
+        // one tile stream per workgroup, one workgroup per CU (measured faster than
+        // fewer, larger workgroups with several streams); K split over up to sixteen
+        // wavefronts, which also share the Eq.2 pass
+        int skpw = 1;
+        while ((a.KT + skpw - 1) / skpw > 16) skpw *= 2;
+        const int swaves = (a.KT + skpw - 1) / skpw;
         const int nstreams = 1;
         int g = (tiles + nstreams - 1) / nstreams;
         const int cap = 256 / nstreams;
         if (g > cap) g = cap;
-        const size_t lds_shared = (size_t)a.KT * 2048 + (size_t)waves * nstreams * 1024;
-        return launch_shared<4>(a, kpw, tiles, (unsigned)g, waves, nstreams, lds_shared, st);
+        const size_t lds_shared = (size_t)a.KT * 2048 + (size_t)swaves * nstreams * 1024;
+        return launch_shared<4>(a, skpw, tiles, (unsigned)g, swaves, nstreams, lds_shared, st);
     }
     if (x_kind == 0) {
         if (M == 1) return launch_xk<XK_F16_ONE, 1>(a, kpw, grid, waves, lds, st);
