@@ -247,6 +247,26 @@ def test_decode_prologue_every_fp16_value(agq, oracle, M, e, bits):
     run_linear(agq, oracle, x, wq, sw, bits, e=e, check_y=False)
 
 
+@pytest.mark.parametrize("M,K,N", [(1, 4096, 272), (4, 1024, 100), (7, 768, 64), (16, 4096, 64), (16, 1024, 4200),
+                                   (150, 512, 300)])
+def test_strided_input_and_output(agq, oracle, M, K, N):
+    """Activation rows and output rows with a pitch larger than their width
+    (views into wider buffers): every kernel variant must honour ldx and ldy,
+    and must leave the columns beyond N untouched."""
+    x, wq, sw = make_case(M, K, N, seed=300 + M + K + N)
+    e = oracle.calibrate_act_exp(x, 8)
+    acc_want, y_want = oracle.linear_w4(x, 8, e, 0, wq, sw)
+    xbuf = torch.full((M, K + 64), 77.0, dtype=torch.float16, device="cuda")
+    xbuf[:, :K] = dev(x)
+    ybuf = torch.full((M, N + 40), -5.0, dtype=torch.float16, device="cuda")
+    acc = torch.full((M, N), -12345, dtype=torch.int32, device="cuda")
+    agq.gemm_w4a8(xbuf[:, :K], e, agq.pack_w4(dev(wq)), dev(sw), N, K, y=ybuf[:, :N], acc_out=acc)
+    assert np.array_equal(host(acc).astype(np.int64), acc_want)
+    yh = host(ybuf)
+    assert_f16_close(yh[:, :N], y_want, "strided y")
+    assert np.all(yh[:, N:] == np.float16(-5.0)), "wrote past the row"
+
+
 def test_extreme_operands_hit_the_bound(agq, oracle):
     # all codes at -128 and all weights at -8: acc = 128 * 8 * K exactly, the
     # largest value the accumulator can take (times 16 inside the kernel)
