@@ -97,7 +97,12 @@ int agq_unpack_w4(const void *packed, int64_t N, int64_t K, int8_t *wq_out,
  * workspace: agq_gemm_workspace_bytes(M,N,K) bytes, 16-byte aligned, may be
  *            NULL when that is 0.  Holds the quantized activation when M is
  *            large enough for the tiled kernel; contents are scratch.
- * K % 128 == 0, K <= 65536 (keeps every partial sum inside int32), M >= 0.    */
+ * K % 128 == 0, K <= 65536 (keeps every partial sum inside int32), M >= 0.
+ * Graph capture: the calls enqueue kernels only and may be captured, with one
+ * exception: the first call in a process that needs the kernel with the
+ * activation kept in LDS (9 <= M <= 16, more than 4096 output channels in the
+ * call) raises that kernel's LDS limit, a host-side setting; make one such
+ * call eagerly before capturing.                                             */
 size_t agq_gemm_workspace_bytes(int64_t M, int64_t N, int64_t K);
 int agq_gemm_w4a8(const void *x, int x_kind, int64_t M, int64_t K, int64_t ldx,
                   int e, int zp, const void *w_packed, const void *w_scale_f16,

@@ -267,6 +267,44 @@ def test_strided_input_and_output(agq, oracle, M, K, N):
     assert np.all(yh[:, N:] == np.float16(-5.0)), "wrote past the row"
 
 
+def test_graph_replay_matches_eager(agq, oracle):
+    """The decode calls are meant to be replayed from a HIP graph (a decode step is
+    launch-bound).  Capture one call of each few-token kernel variant after an
+    eager warm-up, replay several times with eager work in between, and compare
+    every replay with the eager result and with the oracle."""
+    cases = []
+    for M, K, Ns in ((1, 4096, [272]), (4, 1024, [100, 64]), (16, 4096, [64]), (16, 1024, [4096, 300])):
+        x = synth.make_activation(M, K, 4, seed=400 + M + K)
+        e = oracle.calibrate_act_exp(x, 8)
+        projs, wants = [], []
+        for i, N in enumerate(Ns):
+            wq, sw = synth.make_weight_q4(N, K, seed=410 + i)
+            projs.append((agq.pack_w4(dev(wq)), dev(sw), N, torch.zeros((M, N), dtype=torch.float16, device="cuda"), None))
+            wants.append(oracle.linear_w4(x, 8, e, 0, wq, sw)[1])
+        cases.append((dev(x), e, projs, K, wants))
+
+    def run_all():
+        for xd, e, projs, K, _ in cases:
+            agq.gemm_w4a8_multi(xd, e, projs, K)
+
+    run_all()                                   # eager: one-time set-up happens here
+    eager = [[host(p[3]).copy() for p in projs] for _, _, projs, _, _ in cases]
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        run_all()
+    for rep in range(3):
+        for _, _, projs, _, _ in cases:
+            for p in projs:
+                p[3].fill_(float(rep))          # eager work between replays; also proves the replay writes
+        torch.cuda.synchronize()
+        graph.replay()
+        for (_, _, projs, _, wants), eag in zip(cases, eager):
+            for p, y_e, y_w in zip(projs, eag, wants):
+                got = host(p[3])
+                assert np.array_equal(got.view(np.uint16), y_e.view(np.uint16)), "replay differs from eager"
+                assert_f16_close(got, y_w, "graph replay")
+
+
 def test_extreme_operands_hit_the_bound(agq, oracle):
     # all codes at -128 and all weights at -8: acc = 128 * 8 * K exactly, the
     # largest value the accumulator can take (times 16 inside the kernel)
