@@ -264,12 +264,11 @@ def main():
         del qh, kh, logits, causal
         probs = [p0, p0.clone(), p0.clone()]                              # 1 GB in rotation: no cache reuse between calls
         vq = torch.randint(-127, 128, (H, S, D), generator=g2, device=dev, dtype=torch.int8)
-        ws_a = torch.empty(agq.log2_quant_softmax_workspace_bytes(H, S, D), dtype=torch.uint8, device=dev)
         turn = [0]
 
         def attn():
             turn[0] += 1
-            return agq.log2_quant_softmax(probs[turn[0] % 3], vq, -5, workspace=ws_a)
+            return agq.log2_quant_softmax(probs[turn[0] % 3], vq, -5)
 
         def time_plain(f, reps=12):
             for _ in range(3):
@@ -295,7 +294,7 @@ def main():
                                             "peak": HBM_PEAK_GBS, "unit": "GB/s",
                                             "frac": round(by_attn / us_attn / 1e3 / HBM_PEAK_GBS, 4),
                                             "traffic": MEASURED_ATTN_TRAFFIC_BYTES,
-                                            "kernel": "vt_prepack_kernel + log2_attn_kernel"}},
+                                            "kernel": "log2_attn_kernel"}},
             "prune_tokens": {"us": round(us_prune, 1), "GB/s": round(by_prune / us_prune / 1e3, 1)}}
         del probs, p0
 

@@ -152,18 +152,13 @@ int agq_gemm_w4a4_multi(const void *x, int x_kind, int64_t M, int64_t K, int64_t
  * o_f16   : fp16 [S, H*D].   codes_out: optional [H,S,S/2] bytes, two codes per
  *           byte, low nibble = even j, entries above the diagonal carry qmax.
  * score_out: optional int32 [S]; needs H <= 127.
- * workspace: agq_log2_quant_softmax_workspace_bytes(H,S,D) bytes (0 = invalid
- *           sizes), 16-byte aligned; holds V transposed into the order the
- *           matrix cores read it, written by a pre-pass of this call;
- *           contents are scratch.  Too small a workspace returns AGQ_ESIZE.
  * Precondition: rows are softmax outputs (values in [0,1], sum <= ~1), which
  * keeps the integer sum below 2^24; a value above 1 gives an unspecified
- * result, and arbitrary inputs may lose low bits.                            */
-size_t agq_log2_quant_softmax_workspace_bytes(int64_t H, int64_t S, int64_t D);
+ * result, and arbitrary inputs may lose low bits.                           */
 int agq_log2_quant_softmax(const void *p_f16, int64_t H, int64_t S, int64_t D,
                            int causal, int qmax, const int8_t *v_q, int e_v,
                            void *o_f16, void *codes_out, int32_t *score_out,
-                           void *workspace, size_t workspace_bytes, void *stream);
+                           void *stream);
 
 /* Token pruning, Section 4.3 Eq.4: keep the n_keep tokens with the largest
  * score (equal scores: lower index first), in their original order.

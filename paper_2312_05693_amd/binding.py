@@ -31,8 +31,7 @@ SIGNATURES = {
     "agq_gemm_w4a4": (_int, _GEMM_ARGS),
     "agq_gemm_w4a8_multi": (_int, [_vp, _int, _i64, _i64, _i64, _int, _int, _vp, _int, _vp, _sz, _vp]),
     "agq_gemm_w4a4_multi": (_int, [_vp, _int, _i64, _i64, _i64, _int, _int, _vp, _int, _vp, _sz, _vp]),
-    "agq_log2_quant_softmax_workspace_bytes": (_sz, [_i64, _i64, _i64]),
-    "agq_log2_quant_softmax": (_int, [_vp, _i64, _i64, _i64, _int, _int, _vp, _int, _vp, _vp, _vp, _vp, _sz, _vp]),
+    "agq_log2_quant_softmax": (_int, [_vp, _i64, _i64, _i64, _int, _int, _vp, _int, _vp, _vp, _vp, _vp]),
     "agq_prune_tokens": (_int, [_vp, _i64, _i64, _vp, _i64, _vp, _vp, _vp]),
 }
 
@@ -183,22 +182,15 @@ def gemm_w4a4_multi(x, e, projs, K, x_kind=AGQ_X_F16, workspace=None, zp=0):
     return _gemm_multi("agq_gemm_w4a4_multi", x, x_kind, M, K, ldx, e, zp, projs, workspace)
 
 
-def log2_quant_softmax_workspace_bytes(H, S, D):
-    return lib().agq_log2_quant_softmax_workspace_bytes(H, S, D)
-
-
-def log2_quant_softmax(p, v_q, e_v, qmax=15, causal=True, want_codes=False, want_score=True, workspace=None):
+def log2_quant_softmax(p, v_q, e_v, qmax=15, causal=True, want_codes=False, want_score=True):
     """p fp16 [H,S,S], v_q int8 [H,S,D] -> (o fp16 [S,H*D], codes or None, score or None)."""
     H, S, _ = p.shape
     D = v_q.shape[2]
     o = torch.empty((S, H * D), dtype=torch.float16, device=p.device)
     codes = torch.empty((H, S, S // 2), dtype=torch.uint8, device=p.device) if want_codes else None
     score = torch.empty(S, dtype=torch.int32, device=p.device) if want_score else None
-    if workspace is None:
-        workspace = torch.empty(max(log2_quant_softmax_workspace_bytes(H, S, D), 16), dtype=torch.uint8, device=p.device)
     _ok(lib().agq_log2_quant_softmax(_ptr(p), H, S, D, int(causal), qmax, _ptr(v_q), e_v, _ptr(o), _ptr(codes),
-                                     _ptr(score), _ptr(workspace), workspace.numel(), _stream()),
-        "agq_log2_quant_softmax")
+                                     _ptr(score), _stream()), "agq_log2_quant_softmax")
     return o, codes, score
 
 

@@ -143,14 +143,9 @@ int agq_gemm_w4a4_multi(const void *x, int x_kind, int64_t M, int64_t K, int64_t
     return gemm_w4_multi(4, x, x_kind, M, K, ldx, e, zp, projs, count, workspace, workspace_bytes, stream);
 }
 
-size_t agq_log2_quant_softmax_workspace_bytes(int64_t H, int64_t S, int64_t D) {
-    if (H < 1 || H > 65535 || S < 8 || S > kMaxAttnS || (S % 8) != 0 || D < 16 || D > 256 || (D % 16) != 0) return 0;
-    return (size_t)H * (size_t)((S + 63) / 64) * (size_t)((D * 64 + 4095) & ~(int64_t)4095);
-}
-
 int agq_log2_quant_softmax(const void *p_f16, int64_t H, int64_t S, int64_t D, int causal, int qmax,
                            const int8_t *v_q, int e_v, void *o_f16, void *codes_out, int32_t *score_out,
-                           void *workspace, size_t workspace_bytes, void *stream) {
+                           void *stream) {
     if (H < 1 || H > 65535 || S < 8 || S > kMaxAttnS || (S % 8) != 0 || D < 16 || D > 256 || (D % 16) != 0)
         return AGQ_EINVAL;
     if (qmax != 15 && qmax != 7) return AGQ_EINVAL;
@@ -158,10 +153,8 @@ int agq_log2_quant_softmax(const void *p_f16, int64_t H, int64_t S, int64_t D, i
     if (score_out && H > 127) return AGQ_EINVAL;
     if (!aligned16(p_f16) || !aligned16(v_q) || !aligned16(o_f16)) return AGQ_EINVAL;
     if (codes_out && !aligned16(codes_out)) return AGQ_EINVAL;
-    if (!workspace || !aligned16(workspace)) return AGQ_EINVAL;
-    if (workspace_bytes < agq_log2_quant_softmax_workspace_bytes(H, S, D)) return AGQ_ESIZE;
     return hip_status(agq_launch_log2_attn(p_f16, H, S, D, causal != 0, qmax, v_q, e_v, o_f16, codes_out, score_out,
-                                           workspace, stream));
+                                           stream));
 }
 
 int agq_prune_tokens(const int32_t *score, int64_t S, int64_t n_keep, const void *x_f16, int64_t d,

@@ -33,7 +33,6 @@ constexpr int kMaxD = 256;
 struct AttnArgs {
     const uint16_t *p;   // fp16 bits [H,S,S]
     const int8_t *v;     // [H,S,D]
-    const uint8_t *vt;   // byte images of V written by vt_prepack_kernel
     __half *o;           // [S, H*D]
     uint8_t *codes;      // [H,S,S/2] or null
     int32_t *score;      // [S] or null
@@ -57,63 +56,23 @@ __device__ __forceinline__ uint32_t log2_weight2(uint32_t p2, uint32_t kmin, uin
     return __builtin_bit_cast(uint32_t, e) + kadd;
 }
 
-constexpr int kImgRow = 64;     // bytes per channel row of a V image in memory: 64 keys, one byte each
-
 // Byte offset of the 16-byte piece (eight keys in fp16) `chunk` of row `slot`
 // inside the LDS tile; rows are padded to 144 bytes so that sixteen lanes
 // reading the same chunk of consecutive rows hit sixteen different bank groups.
 __device__ __forceinline__ int vt_offset(int slot, int chunk) { return slot * kVRow + (chunk << 4); }
-
-// Bytes of one V image in memory: D rows of 64, rounded up to whole 4 KiB so that
-// 256 threads copy it in 16-byte pieces without a bounds test.
-__host__ __device__ constexpr int vt_image_bytes(int D) { return (D * kImgRow + 4095) & ~4095; }
-
-// int8 V [H,S,D] -> per (head, 64-key tile) an image of D rows x 64 bytes:
-// [row of d][key], bytes v + 128, rows in the order the multiply kernel reads
-// (channel d in row (d & 3) * D/4 + (d >> 2)).  Thread unit = (eight keys kg,
-// four channels 4 c .. 4 c + 3): eight dword loads and a byte transpose by
-// v_perm.  The image is built in LDS and written out linearly.
-__global__ __launch_bounds__(256) void vt_prepack_kernel(const int8_t *__restrict__ v, int S, int D,
-                                                         uint8_t *__restrict__ vt) {
-    __shared__ __align__(16) uint8_t imgbuf[vt_image_bytes(kMaxD)];
-    const int DQ = D >> 2, img = vt_image_bytes(D);
-    const int tile = blockIdx.x, h = blockIdx.y, ntile = gridDim.x;
-    const int8_t *vh = v + (int64_t)h * S * D;
-    for (int unit = threadIdx.x; unit < 8 * DQ; unit += 256) {
-        const int c = unit % DQ, kg = unit / DQ;
-        uint32_t x[8];
-#pragma unroll
-        for (int i = 0; i < 8; ++i) {
-            const int key = min(tile * kKeys + 8 * kg + i, S - 1);   // keys past S get weight 0 downstream
-            x[i] = *reinterpret_cast<const uint32_t *>(vh + (int64_t)key * D + 4 * c) ^ 0x80808080u;
-        }
-#pragma unroll
-        for (int bb = 0; bb < 4; ++bb) {
-            const uint32_t sel = 0x0C0C0000u | (uint32_t)bb | ((uint32_t)(4 + bb) << 8);   // byte bb of two words
-            uint2 out;
-            out.x = __builtin_amdgcn_perm(__builtin_amdgcn_perm(x[3], x[2], sel), __builtin_amdgcn_perm(x[1], x[0], sel),
-                                          0x05040100u);
-            out.y = __builtin_amdgcn_perm(__builtin_amdgcn_perm(x[7], x[6], sel), __builtin_amdgcn_perm(x[5], x[4], sel),
-                                          0x05040100u);
-            *reinterpret_cast<uint2 *>(imgbuf + (bb * DQ + c) * kImgRow + 8 * kg) = out;
-        }
-    }
-    __syncthreads();
-    uint8_t *dst = vt + ((int64_t)h * ntile + tile) * img;
-    for (int off = threadIdx.x * 16; off < img; off += 256 * 16)
-        *reinterpret_cast<agq_u4 *>(dst + off) = *reinterpret_cast<const agq_u4 *>(imgbuf + off);
-}
 
 // One workgroup = 128 query rows of one head; wavefront w owns rows 32 w .. 32 w + 31
 // as the A operand of the 32x32x16 fp16 MFMA (lane: row l & 31, eight keys of
 // k-group l >> 5).  Inside a 64-key tile the keys are dealt to the MFMA steps so
 // that a lane's four steps cover 32 consecutive keys (64 contiguous bytes of its
 // row): step t of k-group g uses keys 32 g + 8 t .. + 7, for both operands.
-// V arrives as the byte images of vt_prepack_kernel: per tile a thread copies
-// 16 bytes per 4 KiB of image, widening each byte u = v + 128 to fp16 on the way
-// (0x6400 | u is 1024 + u; minus 1152) into the LDS tile [row of d][key].
-// The MFMA reads walk consecutive rows, and a lane ends up with four
-// consecutive channels of its query rows.
+// V tile: int8 [key][d] -> fp16 [d][key] in LDS, once per workgroup and tile.  A
+// thread unit is (eight keys, four channels): eight dword loads, a byte
+// transpose by v_perm that puts each byte u = v + 128 under 0x64 (the fp16
+// pattern of 1024 + u), minus 1152, four 16-byte LDS writes.  Channel d sits in
+// row (d & 3) * D/4 + (d >> 2), so the conversion writes and the MFMA reads both
+// walk consecutive rows, and a lane ends up with four consecutive channels of
+// its query rows.
 // P runs two tiles ahead in registers, V one tile ahead; V loads are issued
 // before the P loads so that waiting for V leaves the P loads in flight.
 template <int CB, bool CODES>
@@ -155,45 +114,46 @@ __global__ __launch_bounds__(256, CB == 1 ? 3 : 1) void log2_attn_kernel(const A
     // P is below 4 GiB: S <= 32768).
     const uint8_t *phead = reinterpret_cast<const uint8_t *>(a.p + (int64_t)h * S * S);
     const uint32_t prow_off = (uint32_t)min(row, S - 1) * (uint32_t)S * 2u;
-    const int img = vt_image_bytes(D);
-    const uint8_t *vimg = a.vt + (int64_t)h * ((S + kKeys - 1) / kKeys) * img;
-
-    // V image of a tile: thread i-th piece = bytes [16 (tid + 256 i), + 16) = 16 keys of one row
-    agq_u4 vr[2 * CB];
-    const uint32_t voff = threadIdx.x * 16u;
-    auto load_v = [&](int t) {
-        const uint8_t *src = vimg + (int64_t)tile_of(t) * img;
+    // V conversion units of this thread: (eight keys kg, four channels 4 c .. 4 c + 3)
+    uint32_t vraw[CB][8];
+    int vu_c[CB], vu_kg[CB];
+    bool vu_ok[CB];
 #pragma unroll
-        for (int i = 0; i < 2 * CB; ++i)
-            vr[i] = *reinterpret_cast<const agq_u4 *>(src + (voff + (i * 4096 < img ? i * 4096u : 0u)));
+    for (int u = 0; u < CB; ++u) {
+        const int unit = threadIdx.x + 256 * u;
+        vu_ok[u] = unit < 8 * DQ;
+        vu_c[u] = unit % DQ;
+        vu_kg[u] = vu_ok[u] ? unit / DQ : 0;
+    }
+    const int8_t *vh = a.v + (int64_t)h * S * D;
+    auto load_v = [&](int t) {
+        const int k0 = tile_of(t) * kKeys;
+#pragma unroll
+        for (int u = 0; u < CB; ++u)
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                const int key = min(k0 + 8 * vu_kg[u] + i, S - 1);   // keys past S get weight 0
+                vraw[u][i] = *reinterpret_cast<const uint32_t *>(vh + (uint32_t)(key * D + 4 * vu_c[u]));
+            }
     };
     auto store_v = [&](uint8_t *buf) {
         const agq_v2h bias = {(_Float16)1152.0f, (_Float16)1152.0f};
 #pragma unroll
-        for (int i = 0; i < 2 * CB; ++i) {
-            const int piece = (int)threadIdx.x + 256 * i;
-            const int slot = piece >> 2, chunk = (piece & 3) * 2;
-            agq_u4 lo, hi;
+        for (int u = 0; u < CB; ++u) {
+            uint32_t x[8];
 #pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                // bytes (u0 u1 u2 u3) -> halves 0x64u0 0x64u1 | 0x64u2 0x64u3
-                const uint32_t w = vr[i][j];
-                const uint32_t e0 = __builtin_amdgcn_perm(0x64646464u, w, 0x04010400u);
-                const uint32_t e1 = __builtin_amdgcn_perm(0x64646464u, w, 0x04030402u);
-                const uint32_t h0 = __builtin_bit_cast(uint32_t, __builtin_bit_cast(agq_v2h, e0) - bias);
-                const uint32_t h1 = __builtin_bit_cast(uint32_t, __builtin_bit_cast(agq_v2h, e1) - bias);
-                if (j < 2) {
-                    lo[2 * j] = h0;
-                    lo[2 * j + 1] = h1;
-                } else {
-                    hi[2 * (j - 2)] = h0;
-                    hi[2 * (j - 2) + 1] = h1;
+            for (int i = 0; i < 8; ++i) x[i] = vraw[u][i] ^ 0x80808080u;     // bytes v + 128
+#pragma unroll
+            for (int bb = 0; bb < 4; ++bb) {
+                // halves 0x64uu = 1024 + (v + 128) of keys 2 i and 2 i + 1 of channel 4 c + bb
+                const uint32_t sel = 0x0C000C00u | (uint32_t)bb | ((uint32_t)(4 + bb) << 16);
+                agq_u4 out;
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    const uint32_t w = __builtin_amdgcn_perm(x[2 * i + 1], x[2 * i], sel) | 0x64006400u;
+                    out[i] = __builtin_bit_cast(uint32_t, __builtin_bit_cast(agq_v2h, w) - bias);
                 }
-            }
-            if (piece * 16 < D * kImgRow) {
-                uint8_t *dst = buf + vt_offset(slot, chunk);
-                *reinterpret_cast<agq_u4 *>(dst) = lo;
-                *reinterpret_cast<agq_u4 *>(dst + 16) = hi;
+                if (vu_ok[u]) *reinterpret_cast<agq_u4 *>(buf + vt_offset(bb * DQ + vu_c[u], vu_kg[u])) = out;
             }
         }
     };
@@ -458,11 +418,10 @@ __global__ __launch_bounds__(256) void gather_rows_kernel(const uint4 *__restric
 }  // namespace
 
 int agq_launch_log2_attn(const void *p, int64_t H, int64_t S, int64_t D, int causal, int qmax, const int8_t *vq,
-                         int e_v, void *o, void *codes, int32_t *score, void *workspace, void *stream) {
+                         int e_v, void *o, void *codes, int32_t *score, void *stream) {
     AttnArgs a;
     a.p = (const uint16_t *)p;
     a.v = vq;
-    a.vt = (const uint8_t *)workspace;
     a.o = (__half *)o;
     a.codes = (uint8_t *)codes;
     a.score = score;
@@ -473,8 +432,6 @@ int agq_launch_log2_attn(const void *p, int64_t H, int64_t S, int64_t D, int cau
     a.qmax = qmax;
     a.out_scale = ldexpf(1.0f, e_v - qmax);
     hipStream_t st = (hipStream_t)stream;
-    vt_prepack_kernel<<<dim3((unsigned)((S + kKeys - 1) / kKeys), (unsigned)H), 256, 0, st>>>(vq, (int)S, (int)D,
-                                                                                            (uint8_t *)workspace);
     const unsigned grid = (unsigned)(((S + kQRows - 1) / kQRows) * H);
     if (D <= 128) {
         if (codes) log2_attn_kernel<1, true><<<grid, 256, 0, st>>>(a);

@@ -24,7 +24,6 @@ int agq_launch_gemm_tiled(const void *x_tiles, int64_t M, int64_t K, int e,
                           const void *w_packed, const void *sw, int64_t N, void *y, int64_t ldy,
                           int32_t *acc_out, void *stream);
 int agq_launch_log2_attn(const void *p, int64_t H, int64_t S, int64_t D, int causal, int qmax,
-                         const int8_t *vq, int e_v, void *o, void *codes, int32_t *score, void *workspace,
-                         void *stream);
+                         const int8_t *vq, int e_v, void *o, void *codes, int32_t *score, void *stream);
 int agq_launch_prune(const int32_t *score, int64_t S, int64_t n_keep, const void *x, int64_t d,
                      int32_t *idx, void *x_out, void *stream);
