@@ -285,6 +285,23 @@ def main():
         us_attn = time_plain(attn) * 1e3
         o_a, _, score_a = attn()
         us_prune = time_plain(lambda: agq.prune_tokens(score_a, S // 2, o_a)) * 1e3
+        # the two W4A8 projections that follow on the 1024 surviving tokens (int8 MFMA bound)
+        hid, ffn, keep = H * D, 13824, S // 2
+        _, xp = agq.prune_tokens(score_a, keep, o_a)
+        tail_w = [make_packed(hid, hid), make_packed(ffn, hid)]
+        y1 = torch.empty((keep, hid), dtype=torch.float16, device=dev)
+        y2 = torch.empty((keep, ffn), dtype=torch.float16, device=dev)
+        e1 = int(agq.calibrate_act_exp(xp, 8).item())
+        ws_t = torch.empty(agq.gemm_workspace_bytes(keep, ffn, hid), dtype=torch.uint8, device=dev)
+        agq.gemm_w4a8(xp, e1, tail_w[0][0], tail_w[0][1], hid, hid, y=y1, workspace=ws_t)
+        e2 = int(agq.calibrate_act_exp(y1, 8).item())
+
+        def tail():
+            agq.gemm_w4a8(xp, e1, tail_w[0][0], tail_w[0][1], hid, hid, y=y1, workspace=ws_t)
+            agq.gemm_w4a8(y1, e2, tail_w[1][0], tail_w[1][1], ffn, hid, y=y2, workspace=ws_t)
+
+        us_tail = time_plain(tail, reps=20) * 1e3
+        ops_tail = 2.0 * keep * hid * (hid + ffn)
         by_attn = H * S * (S + 1) // 2 * 2 + H * S * D + S * H * D * 2       # causal half of P, V, O
         by_prune = 4 * S + 2 * (S // 2) * H * D * 2
         result["attention"] = {
@@ -295,7 +312,10 @@ def main():
                                             "frac": round(by_attn / us_attn / 1e3 / HBM_PEAK_GBS, 4),
                                             "traffic": MEASURED_ATTN_TRAFFIC_BYTES,
                                             "kernel": "log2_attn_kernel"}},
-            "prune_tokens": {"us": round(us_prune, 1), "GB/s": round(by_prune / us_prune / 1e3, 1)}}
+            "prune_tokens": {"us": round(us_prune, 1), "GB/s": round(by_prune / us_prune / 1e3, 1)},
+            "tail_gemms_w4a8": {"M": keep, "shapes": "5120->5120, 5120->13824", "us": round(us_tail, 1),
+                                "TOP/s": round(ops_tail / us_tail / 1e6, 1),
+                                "frac_mfma": round(ops_tail / us_tail / 1e6 / INT8_PEAK_TOPS, 4)}}
         del probs, p0
 
     # ---- CPU baseline: the oracle as it stands, on a bounded sample of the decode workload
