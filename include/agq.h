@@ -67,8 +67,9 @@ int agq_quantize_act(const void *x_f16, int64_t M, int64_t K, int64_t ldx,
 
 /* 4-bit weight storage (Section 4.4 stores two 4-bit weights per byte).  The
  * order of nibbles inside `packed` is private to the library: it is laid out
- * for 64-lane coalesced loads and the int8 MFMA operand order.  Only
- * agq_unpack_w4(agq_pack_w4(W)) == W is contractual.
+ * for 64-lane coalesced loads and the int8 MFMA operand order, followed by the
+ * sum of each output channel's weights (used by the unsigned activation grid).
+ * Only agq_unpack_w4(agq_pack_w4(W)) == W is contractual.
  * wq     : int8 [N,K], K contiguous, values in [-8,7]; K % 128 == 0, N >= 1.
  *          Values outside [-8,7] are saturated and counted into *bad_count_dev
  *          (device int32, may be NULL; the caller zeroes it and reads it after
@@ -83,14 +84,18 @@ int agq_unpack_w4(const void *packed, int64_t N, int64_t K, int8_t *wq_out,
 /* The quantized linear layer (Sections 4.2 and 4.4): the activation on the
  * b-bit grid of Eq.2 with the layer-wise scale 2^e, times the 4-bit weights,
  * accumulated in int32, dequantized per output channel:
- *   acc[m,n] = sum_k q[m,k] * Wq[n,k]              (int32, exact)
+ *   acc[m,n] = sum_k (q[m,k] - zp) * Wq[n,k]       (int32, exact)
  *   y[m,n]   = fp16( float(acc[m,n]) * (2^e * sw[n]) )
  * agq_gemm_w4a8 uses b = 8, agq_gemm_w4a4 b = 4 (codes widened to int8 for the
  * MFMA; CDNA4 has no 4-bit matrix instruction).
  * x        : see agq_x_kind.  fp16: ldx % 8 == 0; codes: ldx in code units,
  *            ldx % 16 == 0 (8 bit) or ldx % 32 == 0 (4 bit); 16-byte aligned.
  *            w_packed, w_scale_f16 and y_f16 are 16-byte aligned too.
- * zp       : must be 0 (signed grid); other values return AGQ_EINVAL.
+ * zp       : 0 = the signed grid of Eq.1 (the measured configuration); 1 .. 2^b-1 =
+ *            the unsigned grid of Eq.2 with that zero point.  Inside the kernels
+ *            the unsigned code travels as q - 2^(b-1), which the int8 matrix
+ *            instruction takes, and sum_k (q - zp) w = sum_k (q - 2^(b-1)) w +
+ *            (2^(b-1) - zp) * sum_k w, the last sum precomputed by agq_pack_w4.
  * w_packed : output of agq_pack_w4 for [N,K].   w_scale_f16: fp16 [N].
  * y_f16    : fp16 [M,N], ldy >= N.   acc_out: optional int32 [M,N] contiguous
  *            copy of the accumulators (NULL to skip).

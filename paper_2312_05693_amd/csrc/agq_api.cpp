@@ -18,13 +18,14 @@ int gemm_w4_multi(int bits, const void *x, int x_kind, int64_t M, int64_t K, int
                   const agq_proj *projs, int count, void *workspace, size_t workspace_bytes, void *stream) {
     if (M < 0 || M > kMaxDim || K < 128 || K > 65536 || (K % 128) != 0) return AGQ_EINVAL;
     if (x_kind != AGQ_X_F16 && x_kind != AGQ_X_Q) return AGQ_EINVAL;
-    if (!e_ok(e) || zp != 0 || ldx < K) return AGQ_EINVAL;
+    if (!e_ok(e) || zp < 0 || zp > (1 << bits) - 1 || ldx < K) return AGQ_EINVAL;
     if (x_kind == AGQ_X_F16 && (ldx % 8) != 0) return AGQ_EINVAL;
     if (x_kind == AGQ_X_Q && (ldx % (bits == 8 ? 16 : 32)) != 0) return AGQ_EINVAL;
     if (!projs || count < 1 || count > AGQ_MAX_PROJ) return AGQ_EINVAL;
     int64_t tiles = 0;
     for (int p = 0; p < count; ++p) {
-        if (projs[p].N < 1 || projs[p].N > kMaxDim || projs[p].ldy < projs[p].N) return AGQ_EINVAL;
+        if (projs[p].N < 1 || projs[p].N > kMaxDim || projs[p].ldy < projs[p].N || projs[p].ldy > kMaxDim)
+            return AGQ_EINVAL;
         tiles += (projs[p].N + 15) / 16;
     }
     if (tiles > kMaxDim) return AGQ_EINVAL;
@@ -41,13 +42,14 @@ int gemm_w4_multi(int bits, const void *x, int x_kind, int64_t M, int64_t K, int
         if (workspace_bytes < need) return AGQ_ESIZE;
     }
     if (M <= AGQ_DECODE_MAX_M)
-        return hip_status(agq_launch_gemm_decode(x, x_kind, bits, M, K, ldx, e, projs, count, stream));
+        return hip_status(agq_launch_gemm_decode(x, x_kind, bits, M, K, ldx, e, zp, projs, count, stream));
 
     // many tokens: lay the codes out in MFMA operand order once (quantizing on the
     // way when x is fp16), then run the tiled kernel per projection on that copy
-    if (agq_launch_prepack_act(x, x_kind, bits, M, K, ldx, e, workspace, stream)) return AGQ_EHIP;
+    if (agq_launch_prepack_act(x, x_kind, bits, M, K, ldx, e, zp, workspace, stream)) return AGQ_EHIP;
     for (int p = 0; p < count; ++p) {
-        if (agq_launch_gemm_tiled(workspace, M, K, e, projs[p].w_packed, projs[p].w_scale_f16, projs[p].N,
+        if (agq_launch_gemm_tiled(workspace, M, K, e, agq_zp_corr(bits, zp), projs[p].w_packed, projs[p].w_scale_f16,
+                                  projs[p].N,
                                   projs[p].y_f16, projs[p].ldy, projs[p].acc_out, stream))
             return AGQ_EHIP;
     }
@@ -98,7 +100,7 @@ int agq_quantize_act(const void *x_f16, int64_t M, int64_t K, int64_t ldx, int b
 
 size_t agq_pack_w4_bytes(int64_t N, int64_t K) {
     if (N < 1 || N > kMaxDim || K < 128 || K > 65536 || (K % 128) != 0) return 0;
-    return (size_t)agq_n_tiles_padded(N) * (size_t)agq_k_tiles(K) * 1024;
+    return agq_blob_nibble_bytes(N, K) + (size_t)agq_n_tiles_padded(N) * 16 * sizeof(int32_t);
 }
 
 int agq_pack_w4(const int8_t *wq, int64_t N, int64_t K, void *packed, int32_t *bad_count_dev, void *stream) {

@@ -19,9 +19,10 @@ struct AgqQuant {
     float lo;     // MAGIC + lower grid bound - zp
     float hi;     // MAGIC + upper grid bound - zp
     int zp;
-    // the same in packed fp16 pairs for the signed grid (zp = 0): 2^-e, lower and
-    // upper bound; h_scale2 == 0 when 2^-e is not a normal fp16 number
-    uint32_t h_scale2, h_lo2, h_hi2;
+    // the same in packed fp16 pairs: 2^-e, lower and upper bound (minus zp);
+    // h_scale2 == 0 when 2^-e is not a normal fp16 number.  h_zp2: the low byte
+    // of zp in both halves, added to the bit patterns after rounding.
+    uint32_t h_scale2, h_lo2, h_hi2, h_zp2;
 };
 #define AGQ_MAGIC 12582912.0f  // 1.5 * 2^23
 
@@ -43,17 +44,23 @@ __device__ __forceinline__ uint32_t agq_pack4(uint32_t b0, uint32_t b1, uint32_t
 // then it rounds to code 0 either way; clamping to the (integer) grid bounds
 // before rounding gives the same code as clamping after; adding 1536 = 1.5 * 2^10
 // rounds half-to-even to an integer k and leaves k's two's complement in the low
-// byte of the bit pattern 0x6600 + k.  Requires q.h_scale2 != 0.
+// byte of the bit pattern 0x6600 + k.  Requires q.h_scale2 != 0.  Built by
+// agq_make_quant_signed: codes on the signed grid, zero point q.zp (may be negative).
 typedef _Float16 agq_h2v __attribute__((ext_vector_type(2)));
+template <bool ZP>
 __device__ __forceinline__ uint32_t agq_quant2h(uint32_t two, const AgqQuant &q) {
     agq_h2v v = __builtin_bit_cast(agq_h2v, two) * __builtin_bit_cast(agq_h2v, q.h_scale2);
     v = __builtin_elementwise_min(__builtin_elementwise_max(v, __builtin_bit_cast(agq_h2v, q.h_lo2)),
                                   __builtin_bit_cast(agq_h2v, q.h_hi2));
     v = v + agq_h2v{(_Float16)1536.0f, (_Float16)1536.0f};
-    return __builtin_bit_cast(uint32_t, v);
+    // the zero point is added after the rounding (Eq.2 as printed); 0x66xx + zp stays
+    // inside its half, so one 32-bit add serves both
+    return ZP ? __builtin_bit_cast(uint32_t, v) + q.h_zp2 : __builtin_bit_cast(uint32_t, v);
 }
+template <bool ZP>
 __device__ __forceinline__ uint2 agq_quant8h(uint32_t h0, uint32_t h1, uint32_t h2, uint32_t h3, const AgqQuant &q) {
-    const uint32_t t0 = agq_quant2h(h0, q), t1 = agq_quant2h(h1, q), t2 = agq_quant2h(h2, q), t3 = agq_quant2h(h3, q);
+    const uint32_t t0 = agq_quant2h<ZP>(h0, q), t1 = agq_quant2h<ZP>(h1, q), t2 = agq_quant2h<ZP>(h2, q),
+                   t3 = agq_quant2h<ZP>(h3, q);
     return make_uint2(__builtin_amdgcn_perm(t1, t0, 0x06040200u), __builtin_amdgcn_perm(t3, t2, 0x06040200u));
 }
 

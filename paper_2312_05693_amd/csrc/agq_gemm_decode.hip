@@ -22,7 +22,7 @@
 #include "agq_device.h"
 #include "agq_internal.h"
 
-AgqQuant agq_make_quant(int bits, int e, int zp);
+AgqQuant agq_make_quant_signed(int bits, int e, int zp);
 
 namespace {
 
@@ -31,20 +31,18 @@ namespace {
 // projection p whose tile range contains b.
 constexpr int kMaxProj = AGQ_MAX_PROJ;
 
-// Everything about one projection sits together so that a workgroup fetches it
-// with one round of scalar loads once it knows which projection it serves.
+// One projection as a workgroup holds it once it knows which one it serves.
 struct DecodeProj {
     const uint4 *blob;
     const __half *sw;
     __half *y;
     int32_t *acc_out;
-    int64_t ldy;
-    int N, pad;
+    int ldy, N;
 };
 
-// What a workgroup needs before its first vector load comes first and packed, so
-// that a few wide scalar loads (one round trip) bring it in; the projection
-// records, needed again only for the store, follow.
+// The kernel arguments.  What a workgroup needs before that load comes first and packed, so that a few
+// wide scalar loads (one round trip) bring it in; the output pointers, needed
+// only for the store, follow as one array per field.
 struct DecodeArgs {
     const void *x;
     int64_t ldx;      // elements (fp16 / int8) or codes (nibbles)
@@ -52,14 +50,38 @@ struct DecodeArgs {
     float scale_e;    // 2^e
     int tile_start[kMaxProj + 1];   // entries from `count` on hold the total
     int waves;                      // wavefronts per workgroup (= blockDim.x / 64, without a trip to the dispatch packet)
-    int pad0[2];
-    const uint4 *blob4[kMaxProj];   // copies of proj[p].blob, .sw, .N
+    int corr;                       // unsigned grid: acc += corr * sum_k w[n,k]; 0 on the signed grid
+    uint32_t flip;                  // unsigned grid, codes given: xor that turns q into q - 2^(b-1); else 0
+    const uint4 *blob4[kMaxProj];   // per projection: weight blob, channel scales, width
     const __half *sw4[kMaxProj];
     int N4[kMaxProj];
     AgqQuant q;
-    int pad1;
-    DecodeProj proj[kMaxProj];
+    __half *y4[kMaxProj];
+    int32_t *acc4[kMaxProj];
+    int ldy4[kMaxProj];
+    // Never read.  With the record at 368 or 384 bytes every launch of a replayed graph
+    // measured 0.1-0.15 us shorter than at 256, 400 or 408 bytes (same instructions; the
+    // cause is in how the runtime lays consecutive argument records out, not in the kernel).
+    int reserved[32];
 };
+static_assert(sizeof(DecodeArgs) == 384, "see the note on `reserved`");
+
+__device__ __forceinline__ DecodeProj load_proj(const DecodeArgs &a, int pj) {
+    DecodeProj pr;
+    pr.blob = a.blob4[pj];
+    pr.sw = a.sw4[pj];
+    pr.y = a.y4[pj];
+    pr.acc_out = a.acc4[pj];
+    pr.ldy = a.ldy4[pj];
+    pr.N = a.N4[pj];
+    return pr;
+}
+
+// Per-channel weight sums at the end of a blob (after the padded nibble tiles);
+// read on the unsigned grid only.
+__device__ __forceinline__ const int32_t *blob_wsum(const uint4 *blob, int N, int KT) {
+    return reinterpret_cast<const int32_t *>(blob + (int64_t)((N + 255) / 256) * 16 * KT * 64);
+}
 
 // Which projection a tile belongs to, and its index inside it, without a loop of
 // dependent loads: the three inner boundaries are compared at once.
@@ -70,16 +92,18 @@ __device__ __forceinline__ int find_proj(const DecodeArgs &a, int tile, int &nt)
     return pj;
 }
 
-enum { XK_F16 = 0, XK_I8 = 1, XK_I4 = 2, XK_F16_ONE = 3 };   // ONE: fp16 with a single token row
+// ONE: fp16 with a single token row; Z: fp16 on the unsigned grid (a zero point is added to every code)
+enum { XK_F16 = 0, XK_I8 = 1, XK_I4 = 2, XK_F16_ONE = 3, XK_F16_Z = 4, XK_F16_ONE_Z = 5 };
 
 typedef unsigned int agq_u4 __attribute__((ext_vector_type(4)));
 typedef unsigned int agq_u2 __attribute__((ext_vector_type(2)));
 
 // eight fp16 -> eight int8 codes (signed grid), k ascending
+template <bool ZP>
 __device__ __forceinline__ agq_u2 quant8v(const agq_u4 &h, const AgqQuant &q) {
     if (q.h_scale2 != 0) {       // uniform: the packed fp16 quantizer covers every usual exponent
         const uint32_t h0 = h[0], h1 = h[1], h2 = h[2], h3 = h[3];
-        const uint2 c = agq_quant8h(h0, h1, h2, h3, q);
+        const uint2 c = agq_quant8h<ZP>(h0, h1, h2, h3, q);
         return agq_u2{c.x, c.y};
     }
     uint32_t c[8];
@@ -87,8 +111,8 @@ __device__ __forceinline__ agq_u2 quant8v(const agq_u4 &h, const AgqQuant &q) {
     for (int i = 0; i < 4; ++i) {
         const uint32_t two = h[i];           // copy out first: a vector element is not addressable
         const float2 f = __half22float2(__builtin_bit_cast(__half2, two));
-        c[2 * i] = agq_quant1(f.x, q);
-        c[2 * i + 1] = agq_quant1(f.y, q);
+        c[2 * i] = agq_quant1(f.x, q) + (ZP ? (uint32_t)q.zp : 0u);
+        c[2 * i + 1] = agq_quant1(f.y, q) + (ZP ? (uint32_t)q.zp : 0u);
     }
     return agq_u2{agq_pack4(c[0], c[1], c[2], c[3]), agq_pack4(c[4], c[5], c[6], c[7])};
 }
@@ -101,6 +125,9 @@ __global__ __launch_bounds__(1024) void gemm_decode_kernel(const DecodeArgs a) {
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int nwaves = a.waves;
+    constexpr bool F16 = XK == XK_F16 || XK == XK_F16_ONE || XK == XK_F16_Z || XK == XK_F16_ONE_Z;
+    constexpr bool ONE = XK == XK_F16_ONE || XK == XK_F16_ONE_Z;   // one row: a lane's 16 bytes are its own chunk's, four chunks per load
+    constexpr bool ZP = XK == XK_F16_Z || XK == XK_F16_ONE_Z;      // fp16 input on the unsigned grid
     // Everything the first vector loads depend on is requested in one round of
     // scalar loads; the weight pointer, scale pointer and width of this workgroup's
     // projection are picked by scalar selects instead of a second, dependent round
@@ -112,10 +139,13 @@ __global__ __launch_bounds__(1024) void gemm_decode_kernel(const DecodeArgs a) {
     const int n0 = a.N4[0], n1 = a.N4[1], n2 = a.N4[2], n3 = a.N4[3];
     asm volatile("" ::"s"(a.x), "s"(a.ldx), "s"(a.M), "s"(KT), "s"(nwaves), "s"(t1), "s"(t2), "s"(t3), "s"(a.scale_e), "s"(bl0),
                  "s"(bl1), "s"(bl2), "s"(bl3), "s"(sc0), "s"(sc1), "s"(sc2), "s"(sc3), "s"(n0), "s"(n1), "s"(n2), "s"(n3),
-                 "s"(a.q.scale), "s"(a.q.lo), "s"(a.q.hi), "s"(a.q.h_scale2), "s"(a.q.h_lo2), "s"(a.q.h_hi2));
+                 "s"(a.q.scale), "s"(a.q.lo), "s"(a.q.hi), "s"(a.q.h_scale2), "s"(a.q.h_lo2), "s"(a.q.h_hi2),
+                 "s"(ZP ? a.q.h_zp2 : 0u), "s"(F16 ? 0u : a.flip), "s"(a.corr));
     int nt;
     const int pj = find_proj(a, blockIdx.x, nt);   // which projection this workgroup serves (uniform)
-    const DecodeProj pr = a.proj[pj];
+    __half *const py = a.y4[pj];
+    int32_t *const pacc = a.acc4[pj];
+    const int pldy = a.ldy4[pj];
     const int pN = pj == 0 ? n0 : (pj == 1 ? n1 : (pj == 2 ? n2 : n3));
     const __half *psw = pj == 0 ? sc0 : (pj == 1 ? sc1 : (pj == 2 ? sc2 : sc3));
     const uint4 *pblob = pj == 0 ? bl0 : (pj == 1 ? bl1 : (pj == 2 ? bl2 : bl3));
@@ -127,8 +157,6 @@ __global__ __launch_bounds__(1024) void gemm_decode_kernel(const DecodeArgs a) {
     // rows the prologue writes (operand rows beyond R alias lower rows; they never
     // reach a stored result).  A batch is HB chunks: all of them are written, then
     // all operands are read back, so the LDS round trip is paid once per batch.
-    constexpr bool F16 = XK == XK_F16 || XK == XK_F16_ONE;
-    constexpr bool ONE = XK == XK_F16_ONE;   // one row: a lane's 16 bytes are its own chunk's, four chunks per load
     constexpr int R = 4 * MP;
     constexpr int HB = !F16 ? KPW : (8 / MP < KPW ? 8 / MP : KPW);
     constexpr int NX = ONE ? (HB + 3) / 4 : HB;                       // activation loads per batch and row pass
@@ -172,14 +200,14 @@ __global__ __launch_bounds__(1024) void gemm_decode_kernel(const DecodeArgs a) {
                 const int64_t kc = min(kb + i, KT - 1);
                 if (XK == XK_I8) {
                     const int8_t *xq = reinterpret_cast<const int8_t *>(a.x) + (int64_t)arow * a.ldx + ag * 16 + kc * 128;
-                    fa0[i] = __builtin_bit_cast(agq_v4i, *reinterpret_cast<const agq_u4 *>(xq));
-                    fa1[i] = __builtin_bit_cast(agq_v4i, *reinterpret_cast<const agq_u4 *>(xq + 64));
+                    fa0[i] = __builtin_bit_cast(agq_v4i, *reinterpret_cast<const agq_u4 *>(xq) ^ a.flip);
+                    fa1[i] = __builtin_bit_cast(agq_v4i, *reinterpret_cast<const agq_u4 *>(xq + 64) ^ a.flip);
                 } else {
                     // nibble codes, low nibble = even k: widen to 16 * code in k order
                     const uint8_t *xq = reinterpret_cast<const uint8_t *>(a.x) + (int64_t)arow * (a.ldx >> 1) + ag * 8 + kc * 64;
                     const agq_u2 p0 = *reinterpret_cast<const agq_u2 *>(xq);
                     const agq_u2 p1 = *reinterpret_cast<const agq_u2 *>(xq + 32);
-                    const uint32_t pw[4] = {p0.x, p0.y, p1.x, p1.y};
+                    const uint32_t pw[4] = {p0.x ^ a.flip, p0.y ^ a.flip, p1.x ^ a.flip, p1.y ^ a.flip};
                     uint32_t o[8];
 #pragma unroll
                     for (int j = 0; j < 4; ++j) {
@@ -214,7 +242,7 @@ __global__ __launch_bounds__(1024) void gemm_decode_kernel(const DecodeArgs a) {
                 for (int i = 0; i < NX; ++i)
 #pragma unroll
                     for (int it = 0; it < MP; ++it) {
-                        const agq_u2 codes = quant8v(xv[i][it], a.q);
+                        const agq_u2 codes = quant8v<ZP>(xv[i][it], a.q);
                         if (ONE) {
                             const int ch = 4 * i + rr;   // chunk of the batch, row 0
                             if (ch < HB) reinterpret_cast<agq_u2 *>(stage + ch * kRegion + (s * 4 + g) * R)[hf] = codes;
@@ -265,10 +293,11 @@ __global__ __launch_bounds__(1024) void gemm_decode_kernel(const DecodeArgs a) {
         if (m < a.M && n < pN) {
             int sum = 0;
             for (int w = 0; w < nwaves; ++w) sum += red[(w * 4 + r) * 64 + l];
-            const int v = sum >> shift;   // exact: every term carries the factor
-            if (pr.acc_out) pr.acc_out[(int64_t)m * pN + n] = v;
+            int v = sum >> shift;   // exact: every term carries the factor
+            if (a.corr) v += a.corr * blob_wsum(pblob, pN, KT)[n];
+            if (pacc) pacc[(int64_t)m * pN + n] = v;
             const uint32_t sb = nwaves >= 4 ? sw_bits : (uint32_t) reinterpret_cast<const uint16_t *>(psw)[n];
-            pr.y[(int64_t)m * pr.ldy + n] = agq_dequant(v, a.scale_e * __half2float(__ushort_as_half((unsigned short)sb)));
+            py[(int64_t)m * pldy + n] = agq_dequant(v, a.scale_e * __half2float(__ushort_as_half((unsigned short)sb)));
         }
     }
 }
@@ -285,7 +314,7 @@ __global__ __launch_bounds__(1024) void gemm_decode_kernel(const DecodeArgs a) {
 // tile is multiplied, so the weight stream never drains.
 constexpr int kSharedMaxKT = 64;     // 64 chunks x 2 KiB = 128 KiB of LDS for the activation
 
-template <int KPW, int MP>
+template <int KPW, int MP, bool ZP>
 __global__ __launch_bounds__(1024) void gemm_decode_shared_kernel(const DecodeArgs a, int total_tiles, int wpt) {
     extern __shared__ __align__(16) unsigned char smem[];
     const int lane = threadIdx.x & 63;
@@ -296,13 +325,14 @@ __global__ __launch_bounds__(1024) void gemm_decode_shared_kernel(const DecodeAr
     const int KT = a.KT;
     // all scalar arguments are requested in the first round of loads
     asm volatile("" ::"s"(a.x), "s"(a.ldx), "s"(a.M), "s"(KT), "s"(a.tile_start[1]), "s"(a.tile_start[2]),
-                 "s"(a.tile_start[3]), "s"(a.q.h_scale2), "s"(a.q.h_lo2), "s"(a.q.h_hi2), "s"(a.scale_e));
+                 "s"(a.tile_start[3]), "s"(a.q.h_scale2), "s"(a.q.h_lo2), "s"(a.q.h_hi2), "s"(a.scale_e),
+                 "s"(ZP ? a.q.h_zp2 : 0u), "s"(a.corr));
     agq_u4 *xq = reinterpret_cast<agq_u4 *>(smem);                    // [KT][128] 16-byte operand pieces
     int *red = reinterpret_cast<int *>(smem + (size_t)KT * 2048) + stream * wpt * 256;   // [wpt][4][64] per stream
 
     const int kb = ws * KPW;                                           // this wavefront's chunks, every tile
     auto tile_ptr = [&](int tile, DecodeProj &pr, int &nt) {
-        pr = a.proj[find_proj(a, min(tile, total_tiles - 1), nt)];
+        pr = load_proj(a, find_proj(a, min(tile, total_tiles - 1), nt));
         return reinterpret_cast<const agq_u4 *>(pr.blob) + ((int64_t)nt * KT) * 64 + lane;
     };
 
@@ -345,7 +375,7 @@ __global__ __launch_bounds__(1024) void gemm_decode_shared_kernel(const DecodeAr
             const int u = unit_of(min(u0 + i * nwaves, units - 1));
             const int kc = u / MP, it = u - kc * MP;
             const int m = it * 4 + rr;
-            const agq_u2 codes = quant8v(xv[i], a.q);
+            const agq_u2 codes = quant8v<ZP>(xv[i], a.q);
             if (u0 + i * nwaves < units && m < a.M)
                 reinterpret_cast<agq_u2 *>(xq + (int64_t)kc * 128 + s * 64 + g * 16 + m)[hf] = codes;
         }
@@ -396,7 +426,8 @@ __global__ __launch_bounds__(1024) void gemm_decode_shared_kernel(const DecodeAr
             if (m < a.M && n < pN) {
                 int sum = 0;
                 for (int wv = 0; wv < wpt; ++wv) sum += red[(wv * 4 + r) * 64 + lane];
-                const int v = sum >> AGQ_W_SHIFT;   // exact: every term carries the factor
+                int v = sum >> AGQ_W_SHIFT;   // exact: every term carries the factor
+                if (a.corr) v += a.corr * blob_wsum(pr.blob, pN, KT)[n];
                 if (pr.acc_out) pr.acc_out[(int64_t)m * pN + n] = v;
                 pr.y[(int64_t)m * pr.ldy + n] =
                     agq_dequant(v, a.scale_e * __half2float(__ushort_as_half((unsigned short)sw_bits)));
@@ -415,26 +446,26 @@ __global__ __launch_bounds__(1024) void gemm_decode_shared_kernel(const DecodeAr
 // More than 48 KiB of dynamic LDS needs the limit of the kernel raised, once per
 // process and kernel (the first call does it; it is a host-side setting, not a
 // stream operation).
-template <int KPW, int MP>
+template <int KPW, int MP, bool ZP>
 int launch_shared_kpw(const DecodeArgs &a, int tiles, unsigned grid, int wpt, int nstreams, size_t lds, hipStream_t st) {
     static bool raised = false;
     if (!raised) {
-        hipError_t err = hipFuncSetAttribute(reinterpret_cast<const void *>(gemm_decode_shared_kernel<KPW, MP>),
+        hipError_t err = hipFuncSetAttribute(reinterpret_cast<const void *>(gemm_decode_shared_kernel<KPW, MP, ZP>),
                                              hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024 - 512);
         if (err != hipSuccess) return (int)err;
         raised = true;
     }
-    gemm_decode_shared_kernel<KPW, MP><<<grid, wpt * nstreams * 64, lds, st>>>(a, tiles, wpt);
+    gemm_decode_shared_kernel<KPW, MP, ZP><<<grid, wpt * nstreams * 64, lds, st>>>(a, tiles, wpt);
     return (int)hipGetLastError();
 }
 
-template <int MP>
+template <int MP, bool ZP>
 int launch_shared(const DecodeArgs &a, int kpw, int tiles, unsigned grid, int wpt, int nstreams, size_t lds, hipStream_t st) {
     switch (kpw) {
-        case 1: return launch_shared_kpw<1, MP>(a, tiles, grid, wpt, nstreams, lds, st);
-        case 2: return launch_shared_kpw<2, MP>(a, tiles, grid, wpt, nstreams, lds, st);
-        case 4: return launch_shared_kpw<4, MP>(a, tiles, grid, wpt, nstreams, lds, st);
-        default: return launch_shared_kpw<8, MP>(a, tiles, grid, wpt, nstreams, lds, st);
+        case 1: return launch_shared_kpw<1, MP, ZP>(a, tiles, grid, wpt, nstreams, lds, st);
+        case 2: return launch_shared_kpw<2, MP, ZP>(a, tiles, grid, wpt, nstreams, lds, st);
+        case 4: return launch_shared_kpw<4, MP, ZP>(a, tiles, grid, wpt, nstreams, lds, st);
+        default: return launch_shared_kpw<8, MP, ZP>(a, tiles, grid, wpt, nstreams, lds, st);
     }
 }
 
@@ -451,18 +482,18 @@ int launch_xk(const DecodeArgs &a, int kpw, unsigned grid, int waves, size_t lds
 
 }  // namespace
 
-int agq_launch_gemm_decode(const void *x, int x_kind, int bits, int64_t M, int64_t K, int64_t ldx, int e,
+int agq_launch_gemm_decode(const void *x, int x_kind, int bits, int64_t M, int64_t K, int64_t ldx, int e, int zp,
                            const agq_proj *projs, int count, void *stream) {
-    DecodeArgs a;
+    DecodeArgs a = {};
     a.x = x;
     a.ldx = ldx;
     a.M = (int)M;
     a.KT = (int)agq_k_tiles(K);
     a.count = count;
     a.waves = 0;
-    a.pad0[0] = a.pad0[1] = 0;
-    a.pad1 = 0;
-    a.q = agq_make_quant(bits, e, 0);
+    a.q = agq_make_quant_signed(bits, e, zp);
+    a.corr = agq_zp_corr(bits, zp);
+    a.flip = zp ? (bits == 8 ? 0x80808080u : 0x88888888u) : 0u;
     a.scale_e = ldexpf(1.0f, e);
     int tiles = 0;
     for (int p = 0; p < kMaxProj; ++p) {
@@ -472,13 +503,9 @@ int agq_launch_gemm_decode(const void *x, int x_kind, int bits, int64_t M, int64
         a.blob4[p] = (const uint4 *)pr.w_packed;
         a.sw4[p] = (const __half *)pr.w_scale_f16;
         a.N4[p] = (int)pr.N;
-        a.proj[p].N = (int)pr.N;
-        a.proj[p].pad = 0;
-        a.proj[p].blob = (const uint4 *)pr.w_packed;
-        a.proj[p].sw = (const __half *)pr.w_scale_f16;
-        a.proj[p].y = (__half *)pr.y_f16;
-        a.proj[p].ldy = pr.ldy;
-        a.proj[p].acc_out = pr.acc_out;
+        a.y4[p] = (__half *)pr.y_f16;
+        a.acc4[p] = pr.acc_out;
+        a.ldy4[p] = (int)pr.ldy;
     }
     a.tile_start[kMaxProj] = tiles;
     for (int p = count; p <= kMaxProj; ++p) a.tile_start[p] = tiles;
@@ -524,9 +551,16 @@ int agq_launch_gemm_decode(const void *x, int x_kind, int bits, int64_t M, int64
         int g = (tiles + nstreams - 1) / nstreams;
         if (g > 256) g = 256;
         const size_t lds_shared = (size_t)a.KT * 2048 + (size_t)swaves * nstreams * 1024;
-        return launch_shared<4>(a, skpw, tiles, (unsigned)g, swaves, nstreams, lds_shared, st);
+        if (zp) return launch_shared<4, true>(a, skpw, tiles, (unsigned)g, swaves, nstreams, lds_shared, st);
+        return launch_shared<4, false>(a, skpw, tiles, (unsigned)g, swaves, nstreams, lds_shared, st);
     }
     if (x_kind == 0) {
+        if (zp) {
+            if (M == 1) return launch_xk<XK_F16_ONE_Z, 1>(a, kpw, grid, waves, lds, st);
+            if (M <= 4) return launch_xk<XK_F16_Z, 1>(a, kpw, grid, waves, lds, st);
+            if (M <= 8) return launch_xk<XK_F16_Z, 2>(a, kpw, grid, waves, lds, st);
+            return launch_xk<XK_F16_Z, 4>(a, kpw, grid, waves, lds, st);
+        }
         if (M == 1) return launch_xk<XK_F16_ONE, 1>(a, kpw, grid, waves, lds, st);
         if (M <= 4) return launch_xk<XK_F16, 1>(a, kpw, grid, waves, lds, st);
         if (M <= 8) return launch_xk<XK_F16, 2>(a, kpw, grid, waves, lds, st);

@@ -59,6 +59,8 @@ struct TiledArgs {
     int64_t ldy;
     int32_t *acc_out;
     float scale_e;
+    int corr;               // unsigned activation grid: acc += corr * wsum[n]; 0 on the signed grid
+    const int32_t *wsum;    // per-channel weight sums (end of the blob)
 };
 
 // Direct global-to-LDS copy: lane i's 16 bytes land at lds_chunk + 16 i (the LDS
@@ -243,6 +245,23 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_tiled_kernel(const TiledArgs
     // consecutive channels of one token (8 bytes), the store wants eight lanes
     // per 128-byte row.  Each wavefront uses a private 64 x 144-byte region.
     const int mrow = m0 + wm * 64 + (lane & 31);
+    if (a.corr) {
+        // unsigned activation grid: add corr * sum_k w[n,k], times the 16 the
+        // accumulators still carry (|16 acc| <= 16 * 255 * 8 * K < 2^31 for K <= 65536)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const int4 ws = *reinterpret_cast<const int4 *>(a.wsum + ncol + j * 32 + q * 8);   // padded to 256 channels
+                const int t[4] = {ws.x, ws.y, ws.z, ws.w};
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    const int add = (a.corr * t[r]) << AGQ_W_SHIFT;
+                    acc[0][j][4 * q + r] += add;
+                    acc[1][j][4 * q + r] += add;
+                }
+            }
+    }
     if (a.acc_out) {   // exact accumulators for parity checks (plain stores)
 #pragma unroll
         for (int i = 0; i < 2; ++i)
@@ -299,7 +318,7 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_tiled_kernel(const TiledArgs
 
 }  // namespace
 
-int agq_launch_gemm_tiled(const void *x_tiles, int64_t M, int64_t K, int e, const void *w_packed,
+int agq_launch_gemm_tiled(const void *x_tiles, int64_t M, int64_t K, int e, int corr, const void *w_packed,
                           const void *sw, int64_t N, void *y, int64_t ldy, int32_t *acc_out, void *stream) {
     TiledArgs a;
     a.xt = (const agq_u4 *)x_tiles;
@@ -315,6 +334,8 @@ int agq_launch_gemm_tiled(const void *x_tiles, int64_t M, int64_t K, int e, cons
     a.ldy = ldy;
     a.acc_out = acc_out;
     a.scale_e = ldexpf(1.0f, e);
+    a.corr = corr;
+    a.wsum = agq_blob_wsum(w_packed, N, K);
     gemm_tiled_kernel<<<(unsigned)(a.tiles_m * a.tiles_n), kThreads, 0, (hipStream_t)stream>>>(a);
     return (int)hipGetLastError();
 }

@@ -86,7 +86,8 @@ enum { PRE_F16 = 0, PRE_I8 = 1, PRE_I4 = 2 };
 
 template <int MODE>
 __global__ __launch_bounds__(kThreads) void prepack_act_kernel(const void *__restrict__ x, int64_t M, int64_t KT,
-                                                                int64_t ldx, AgqQuant q, uint4 *__restrict__ out) {
+                                                                int64_t ldx, AgqQuant q, uint32_t flip,
+                                                                uint4 *__restrict__ out) {
     __shared__ uint4 tile[256];                       // 4 KiB in operand order
     const int tid = threadIdx.x;
     const int64_t kt = blockIdx.x, mt = blockIdx.y;  // K step, 32-token tile
@@ -95,16 +96,21 @@ __global__ __launch_bounds__(kThreads) void prepack_act_kernel(const void *__res
     uint4 codes = make_uint4(0, 0, 0, 0);
     if (m < M) {
         const int64_t k0 = kt * 128 + c * 16;
+        // `flip` is non-zero for the unsigned grid: stored codes q become q - 2^(b-1)
         if (MODE == PRE_F16) {
             const __half *xp = reinterpret_cast<const __half *>(x) + m * ldx + k0;
-            const uint2 lo = agq_quant8(*reinterpret_cast<const uint4 *>(xp), q);
-            const uint2 hi = agq_quant8(*reinterpret_cast<const uint4 *>(xp + 8), q);
+            const uint2 lo = agq_quant8<true>(*reinterpret_cast<const uint4 *>(xp), q);
+            const uint2 hi = agq_quant8<true>(*reinterpret_cast<const uint4 *>(xp + 8), q);
             codes = make_uint4(lo.x, lo.y, hi.x, hi.y);
         } else if (MODE == PRE_I8) {
             codes = *reinterpret_cast<const uint4 *>(reinterpret_cast<const int8_t *>(x) + m * ldx + k0);
+            codes.x ^= flip;
+            codes.y ^= flip;
+            codes.z ^= flip;
+            codes.w ^= flip;
         } else {
             const uint2 v = *reinterpret_cast<const uint2 *>(reinterpret_cast<const uint8_t *>(x) + m * (ldx >> 1) + (k0 >> 1));
-            const uint32_t w[2] = {v.x, v.y};
+            const uint32_t w[2] = {v.x ^ flip, v.y ^ flip};
             uint32_t o[4];
 #pragma unroll
             for (int j = 0; j < 2; ++j)
@@ -186,6 +192,25 @@ __global__ __launch_bounds__(kThreads) void unpack_kernel(const uint32_t *__rest
     *reinterpret_cast<uint32_t *>(wq + n * K + k0) = o;
 }
 
+// Sum of the (saturated) 4-bit weights of every output channel, padded channels 0:
+// the term the asymmetric activation grid needs, one wavefront per channel.
+__global__ __launch_bounds__(64) void wsum_kernel(const int8_t *__restrict__ wq, int64_t N, int64_t K,
+                                                   int32_t *__restrict__ wsum) {
+    const int64_t n = blockIdx.x;
+    int sum = 0;
+    if (n < N) {
+        const uint32_t *row = reinterpret_cast<const uint32_t *>(wq + n * K);
+        for (int64_t i = threadIdx.x; i < (K >> 2); i += 64) {
+            const uint32_t w = row[i];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) sum += min(max((int)(int8_t)(w >> (8 * j)), -8), 7);
+        }
+    }
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) sum += __shfl_down(sum, off);
+    if (threadIdx.x == 0) wsum[n] = sum;
+}
+
 inline int64_t blocks_for(int64_t n) { return (n + kThreads - 1) / kThreads; }
 
 }  // namespace
@@ -198,12 +223,29 @@ AgqQuant agq_make_quant(int bits, int e, int zp) {
     q.lo = AGQ_MAGIC + (float)(lo - zp);
     q.hi = AGQ_MAGIC + (float)(hi - zp);
     q.zp = zp;
-    // fp16 images: 2^-e has exponent field 15 - e, a normal number for 1 <= 15 - e <= 30
+    q.h_scale2 = q.h_lo2 = q.h_hi2 = q.h_zp2 = 0;   // the packed fp16 form serves the GEMM prologues only
+    return q;
+}
+
+// Quantizer of the GEMM prologues: codes on the signed grid [-2^(b-1), 2^(b-1)-1]
+// that the int8 MFMA takes.  zp == 0: Eq.1's signed grid as it is.  zp > 0: Eq.2's
+// unsigned code minus 2^(b-1), i.e. the signed grid with zero point zp - 2^(b-1).
+AgqQuant agq_make_quant_signed(int bits, int e, int zp) {
+    const int lo = -(1 << (bits - 1)), hi = (1 << (bits - 1)) - 1;
+    const int off = zp ? zp - (1 << (bits - 1)) : 0;
+    AgqQuant q;
+    q.scale = ldexpf(1.0f, -e);
+    q.lo = AGQ_MAGIC + (float)(lo - off);
+    q.hi = AGQ_MAGIC + (float)(hi - off);
+    q.zp = off;
+    // fp16 images: 2^-e has exponent field 15 - e, a normal number for 1 <= 15 - e <= 30;
+    // the bounds are integers of magnitude <= 255, exact in fp16
     auto pair = [](uint32_t h) { return h | (h << 16); };
     const int field = 15 - e;
     q.h_scale2 = (field >= 1 && field <= 30) ? pair((uint32_t)field << 10) : 0u;
-    q.h_lo2 = pair(bits == 8 ? 0xD800u : 0xC800u);   // -128, -8
-    q.h_hi2 = pair(bits == 8 ? 0x57F0u : 0x4700u);   //  127,  7
+    q.h_lo2 = pair((uint32_t)__half_as_ushort(__float2half((float)(lo - off))));
+    q.h_hi2 = pair((uint32_t)__half_as_ushort(__float2half((float)(hi - off))));
+    q.h_zp2 = pair((uint32_t)(off & 0xFF));
     return q;
 }
 
@@ -235,18 +277,19 @@ int agq_launch_quantize(const void *x, int64_t M, int64_t K, int64_t ldx, int bi
     return (int)hipGetLastError();
 }
 
-int agq_launch_prepack_act(const void *x, int x_kind, int bits, int64_t M, int64_t K, int64_t ldx, int e, void *out,
-                           void *stream) {
-    const AgqQuant q = agq_make_quant(bits, e, 0);
+int agq_launch_prepack_act(const void *x, int x_kind, int bits, int64_t M, int64_t K, int64_t ldx, int e, int zp,
+                           void *out, void *stream) {
+    const AgqQuant q = agq_make_quant_signed(bits, e, zp);
+    const uint32_t flip = zp ? (bits == 8 ? 0x80808080u : 0x88888888u) : 0u;
     const int64_t KT = K / 128;
     const dim3 grid((unsigned)KT, (unsigned)(((M + 127) / 128) * 4));
     hipStream_t st = (hipStream_t)stream;
     if (x_kind == 0)
-        prepack_act_kernel<PRE_F16><<<grid, kThreads, 0, st>>>(x, M, KT, ldx, q, (uint4 *)out);
+        prepack_act_kernel<PRE_F16><<<grid, kThreads, 0, st>>>(x, M, KT, ldx, q, flip, (uint4 *)out);
     else if (bits == 8)
-        prepack_act_kernel<PRE_I8><<<grid, kThreads, 0, st>>>(x, M, KT, ldx, q, (uint4 *)out);
+        prepack_act_kernel<PRE_I8><<<grid, kThreads, 0, st>>>(x, M, KT, ldx, q, flip, (uint4 *)out);
     else
-        prepack_act_kernel<PRE_I4><<<grid, kThreads, 0, st>>>(x, M, KT, ldx, q, (uint4 *)out);
+        prepack_act_kernel<PRE_I4><<<grid, kThreads, 0, st>>>(x, M, KT, ldx, q, flip, (uint4 *)out);
     return (int)hipGetLastError();
 }
 
@@ -255,6 +298,8 @@ int agq_launch_pack(const int8_t *wq, int64_t N, int64_t K, void *packed, int32_
     const int64_t total_words = agq_n_tiles_padded(N) * KT * 256;
     pack_kernel<<<(unsigned)blocks_for(total_words), kThreads, 0, (hipStream_t)stream>>>(wq, N, K, KT, total_words,
                                                                                          (uint32_t *)packed, bad);
+    wsum_kernel<<<(unsigned)(agq_n_tiles_padded(N) * 16), 64, 0, (hipStream_t)stream>>>(
+        wq, N, K, const_cast<int32_t *>(agq_blob_wsum(packed, N, K)));
     return (int)hipGetLastError();
 }
 

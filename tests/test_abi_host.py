@@ -35,12 +35,13 @@ def test_exports_every_declared_symbol(lib):
 
 
 def test_sizes(lib):
-    assert lib.agq_pack_w4_bytes(768, 768) == 768 * 768 // 2
-    assert lib.agq_pack_w4_bytes(4096, 4096) == 8388608
-    assert lib.agq_pack_w4_bytes(11008, 4096) == 22544384
-    assert lib.agq_pack_w4_bytes(4096, 11008) == 22544384
-    assert lib.agq_pack_w4_bytes(13824, 5120) == 35389440
-    assert lib.agq_pack_w4_bytes(100, 128) == 256 * 128 // 2          # rows padded to 256
+    # nibbles (rows padded to 256) plus one int32 weight sum per padded row
+    assert lib.agq_pack_w4_bytes(768, 768) == 768 * 768 // 2 + 768 * 4
+    assert lib.agq_pack_w4_bytes(4096, 4096) == 8388608 + 4096 * 4
+    assert lib.agq_pack_w4_bytes(11008, 4096) == 22544384 + 11008 * 4
+    assert lib.agq_pack_w4_bytes(4096, 11008) == 22544384 + 4096 * 4
+    assert lib.agq_pack_w4_bytes(13824, 5120) == 35389440 + 13824 * 4
+    assert lib.agq_pack_w4_bytes(100, 128) == 256 * 128 // 2 + 256 * 4
     assert lib.agq_pack_w4_bytes(16, 100) == 0                        # K must be a multiple of 128
     assert lib.agq_pack_w4_bytes(0, 128) == 0
     assert lib.agq_gemm_workspace_bytes(16, 4096, 4096) == 0
@@ -68,7 +69,8 @@ def test_argument_errors_need_no_gpu(lib):
     assert call(N=0) == EINVAL and call(M=-1) == EINVAL
     assert call(ldx=128) == EINVAL and call(ldx=260) == EINVAL and call(ldy=32) == EINVAL
     assert call(e=41) == EINVAL and call(e=-41) == EINVAL
-    assert call(zp=128) == EINVAL                    # asymmetric product is not built
+    assert call(zp=256) == EINVAL and call(zp=-1) == EINVAL   # outside Eq.2's unsigned 8-bit grid
+    assert call(fn=lib.agq_gemm_w4a4, zp=16) == EINVAL
     assert call(kind=7) == EINVAL
     assert call(kind=1, ldx=264) == EINVAL           # int8 codes need ldx % 16 == 0
     assert call(fn=lib.agq_gemm_w4a4, kind=1, ldx=272) == EINVAL

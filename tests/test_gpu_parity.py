@@ -71,12 +71,17 @@ def test_pack_roundtrip(agq, oracle):
         packed = agq.pack_w4(dev(wq))
         assert packed.numel() == agq.pack_w4_bytes(N, K)
         assert np.array_equal(host(agq.unpack_w4(packed, N, K)), wq)
-        # a 4-bit blob holds exactly the multiset of nibbles of W (plus zero padding)
-        nib = host(packed)
+        # the nibble part of the blob holds exactly the multiset of nibbles of W (plus zero padding) ...
+        npad = (N + 255) // 256 * 256
+        nib = host(packed)[: npad * K // 2]
         counts = np.bincount(np.concatenate([nib & 0xF, nib >> 4]), minlength=16)
         want = np.bincount((wq.astype(np.int64) & 0xF).ravel(), minlength=16)
         want[0] += nib.size * 2 - wq.size
         assert np.array_equal(counts, want)
+        # ... and its tail the sum of every output channel's weights, padded channels 0
+        wsum = host(packed)[npad * K // 2:].view(np.int32)
+        assert wsum.size == npad
+        assert np.array_equal(wsum[:N], wq.astype(np.int64).sum(axis=1)) and not wsum[N:].any()
     # out-of-range values are saturated and counted
     wq = rng.integers(-8, 8, size=(16, 128)).astype(np.int8)
     wq[3, 5], wq[9, 100], wq[0, 0] = 9, -100, 127
@@ -131,20 +136,20 @@ def test_calibrate(agq, oracle):
 
 # ------------------------------------------------------------------ the linear layer
 
-def run_linear(agq, oracle, x, wq, sw, bits, x_kind="f16", e=None, check_y=True):
+def run_linear(agq, oracle, x, wq, sw, bits, x_kind="f16", e=None, check_y=True, zp=0):
     M, K = x.shape
     N = wq.shape[0]
     if e is None:
         e = oracle.calibrate_act_exp(x, bits) if M else 0
-    acc_want, y_want = oracle.linear_w4(x, bits, e, 0, wq, sw)
+    acc_want, y_want = oracle.linear_w4(x, bits, e, zp, wq, sw)
     packed = agq.pack_w4(dev(wq))
     acc = torch.full((M, N), -12345, dtype=torch.int32, device="cuda")
     fn = agq.gemm_w4a8 if bits == 8 else agq.gemm_w4a4
     if x_kind == "f16":
         xin, kind = dev(x), agq.AGQ_X_F16
     else:
-        xin, kind = agq.quantize_act(dev(x), bits, e, 0), agq.AGQ_X_Q
-    y = fn(xin, e, packed, dev(sw), N, K, x_kind=kind, acc_out=acc)
+        xin, kind = agq.quantize_act(dev(x), bits, e, zp), agq.AGQ_X_Q
+    y = fn(xin, e, packed, dev(sw), N, K, x_kind=kind, acc_out=acc, zp=zp)
     assert np.array_equal(host(acc).astype(np.int64), acc_want), "accumulators differ"
     if check_y:
         assert_f16_close(host(y), y_want, "y")
@@ -303,6 +308,38 @@ def test_graph_replay_matches_eager(agq, oracle):
                 got = host(p[3])
                 assert np.array_equal(got.view(np.uint16), y_e.view(np.uint16)), "replay differs from eager"
                 assert_f16_close(got, y_w, "graph replay")
+
+
+@pytest.mark.parametrize("x_kind", ["f16", "q"])
+@pytest.mark.parametrize("bits,zp", [(8, 128), (8, 117), (8, 1), (8, 255), (4, 8), (4, 5), (4, 15)])
+@pytest.mark.parametrize("M,K,N", [(1, 512, 48), (4, 1024, 100), (7, 768, 64), (16, 768, 4200), (150, 512, 300)])
+def test_unsigned_grid_with_zero_point(agq, oracle, M, K, N, bits, zp, x_kind):
+    """Eq.2's unsigned grid inside the GEMMs: acc = sum_k (q - zp) w with q in
+    [0, 2^b - 1], through every kernel variant and both input kinds, including
+    odd zero points (ties) and zero points at both ends of the grid."""
+    x, wq, sw = make_case(M, K, N, seed=500 + M + K + N + zp)
+    e = oracle.calibrate_act_exp(x, bits) + 1          # the data then spans about half the unsigned grid around zp
+    run_linear(agq, oracle, x, wq, sw, bits, x_kind=x_kind, e=e, zp=zp)
+
+
+def test_unsigned_grid_every_fp16_value(agq, oracle):
+    """The unsigned-grid prologue over every finite fp16 bit pattern, for an even
+    and an odd zero point, in and out of the range of the half-precision path."""
+    pat = np.arange(65536, dtype=np.uint32).astype(np.uint16)
+    vals = pat.view(np.float16)
+    vals = vals[~np.isnan(vals)]
+    M = 16
+    K = 128 * ((vals.size + M * 128 - 1) // (M * 128))
+    x = np.zeros(M * K, np.float16)
+    x[: vals.size] = vals
+    x = x.reshape(M, K)
+    rng = np.random.default_rng(77)
+    wq = rng.integers(-8, 8, size=(32, K)).astype(np.int8)
+    wq[wq == 0] = 1
+    sw = np.full(32, 2.0 ** -12, np.float16)
+    for e, zp in ((-3, 128), (0, 99), (5, 200), (-16, 131)):
+        run_linear(agq, oracle, x, wq, sw, 8, e=e, zp=zp, check_y=False)
+    run_linear(agq, oracle, x[:4], wq, sw, 4, e=-2, zp=7, check_y=False)
 
 
 def test_extreme_operands_hit_the_bound(agq, oracle):
