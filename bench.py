@@ -36,7 +36,7 @@ PREFILL_M = 2048
 # HBM traffic per launch of the decode kernels from rocprofv3 --pmc (FETCH_SIZE x 2.0 KiB +
 # WRITE_SIZE x 1.0 KiB, the factors a 256 MiB copy gives); see profiles/.
 MEASURED_TRAFFIC_BYTES_PER_LAUNCH = 26.3e6
-MEASURED_ATTN_TRAFFIC_BYTES = 234.8e6   # log2_attn_kernel, one call of the bench's attention block
+MEASURED_ATTN_TRAFFIC_BYTES = 236.8e6   # log2_attn_kernel, one call of the bench's attention block
 
 
 def algorithmic_bytes(M, K, N):
@@ -193,7 +193,7 @@ def main():
                    "algorithmic_bytes_per_step": int(bytes_per_step)},
         "roofline": {"bound": "hbm", "achieved": round(gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": round(gbs / HBM_PEAK_GBS, 4), "traffic": MEASURED_TRAFFIC_BYTES_PER_LAUNCH,
-                     "kernel": "gemm_decode_kernel (M <= 4, K > 8192) and gemm_decode_shared_kernel (5..16 rows): "
+                     "kernel": "gemm_decode_kernel (M <= 8, K > 8192, one workgroup per CU) and gemm_decode_shared_kernel (9..16 rows): "
                                "every launch of a step", "avg_launch_us": round(avg_launch_us, 3),
                      "algorithmic_bytes_per_launch": int(bytes_per_step / launches_per_step)},
         "decode_by_M": per_m,
