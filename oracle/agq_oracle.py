@@ -16,7 +16,9 @@ Readings taken where the paper is silent (each is repeated at its function):
   * zp == 0 selects the signed grid of Eq.1, zp > 0 the unsigned grid of Eq.2;
   * weights: symmetric round-to-nearest per output channel stands in for GPTQ;
   * Eq.3 is applied to softmax probabilities with max|X| taken as 1.0;
-  * token importance is the attention paid to the first token, summed over heads.
+  * token importance is the attention paid to the first token, summed over heads;
+  * TRIP: Eq.6's step is the layer-wise one divided by 2^K (K the largest
+    refinement), and Eq.8's rounding term includes Eq.5's clip.
 NaN inputs are outside every quantizer's domain: the oracle raises on them.
 """
 from __future__ import annotations
@@ -177,6 +179,108 @@ def linear_w4(x, bits: int, e: int, zp: int, wq, sw):
     4-bit weights, per-channel dequantisation.  Returns (acc int64, y fp16)."""
     q = quantize_act(x, bits, e, zp)
     acc = gemm_int(q, zp, wq)
+    return acc, dequant_out(acc, e, sw)
+
+
+# --------------------------------------------------------------------------
+# Eq.5-8  TRIP: per-channel power-of-two factors on top of the layer-wise step
+# --------------------------------------------------------------------------
+
+def _check_alpha(alpha, K: int) -> np.ndarray:
+    alpha = np.asarray(alpha, dtype=np.int64)
+    if alpha.shape != (K,):
+        raise ValueError("one factor per channel")
+    if alpha.size and (alpha.min() < 0 or alpha.max() > 4):
+        raise ValueError("factors lie in 0..4")
+    return alpha
+
+
+def trip_base_exp(x, bits: int, kmax: int) -> int:
+    """Section 4.3, Eq.6 with s a power of two.  As printed the equation makes
+    2^alpha * s independent of alpha; it is read with the largest refinement K
+    in the denominator: s is the layer-wise step that covers the whole range,
+    divided by 2^K, so that a channel with factor alpha_c = K gets the
+    layer-wise step back and the others a finer one.  Returns e with s = 2^e."""
+    if kmax < 0 or kmax > 4:
+        raise ValueError("K lies in 0..4")
+    return calibrate_act_exp(x, bits) - int(kmax)
+
+
+def trip_quantize(x, bits: int, e: int, zp: int, alpha) -> np.ndarray:
+    """Section 4.3, Eq.5: q[m,c] = CLIP(round(x[m,c] / (2^alpha[c] * s)) + zp, lo, hi)
+    with s = 2^e shared by all channels and one factor alpha[c] per channel
+    (column) of x.  Grid and rounding as in Eq.2."""
+    x64 = _as_f64(x)
+    alpha = _check_alpha(alpha, x64.shape[-1])
+    lo, hi = grid_bounds(bits, zp)
+    r = np.ldexp(x64, -(int(e) + alpha))             # exact; the factors run along the last axis
+    q = np.clip(np.rint(r) + float(zp), float(lo), float(hi))
+    return q.astype(np.int32)
+
+
+def trip_dequantize(q, e: int, zp: int, alpha) -> np.ndarray:
+    """Inverse map of Eq.5: x_hat[m,c] = (q[m,c] - zp) * 2^(e + alpha[c]), exact."""
+    q = np.asarray(q, dtype=np.int64)
+    alpha = _check_alpha(alpha, q.shape[-1])
+    return np.ldexp((q - int(zp)).astype(np.float64), int(e) + alpha)
+
+
+def trip_search(x, bits: int, e: int, zp: int, kmax: int) -> np.ndarray:
+    """Section 4.3, Eq.8: alpha_c = argmin over {0..K} of
+    || X_c - dequant(quant(X_c | alpha_c)) ||_2  for every channel c of x [M, C].
+
+    The rounding term of Eq.8 is read as Eq.5's quantizer (clip included)
+    followed by its inverse: without the clip the finest step would win for
+    every channel and the search would be vacuous.  The squared norm is
+    summed in float64 over the tokens m = 0, 1, .. in that order (every
+    residual is exact; each square and each addition is rounded once), equal
+    errors go to the smaller factor.  Returns int8 [C]."""
+    if kmax < 0 or kmax > 4:
+        raise ValueError("K lies in 0..4")
+    x64 = _as_f64(x)
+    if x64.ndim != 2:
+        raise ValueError("x is [tokens, channels]")
+    M, C = x64.shape
+    err = np.zeros((kmax + 1, C), dtype=np.float64)
+    for a in range(kmax + 1):
+        al = np.full(C, a, dtype=np.int64)
+        xh = trip_dequantize(trip_quantize(x, bits, e, zp, al), e, zp, al)
+        with np.errstate(invalid="ignore", over="ignore"):
+            r = x64 - xh                                  # exact; +-Inf stays +-Inf
+            for m in range(M):
+                err[a] = err[a] + r[m] * r[m]
+    best = np.zeros(C, dtype=np.int8)
+    best_err = err[0].copy()
+    for a in range(1, kmax + 1):
+        better = err[a] < best_err                        # strict: ties keep the smaller factor
+        best = np.where(better, np.int8(a), best)
+        best_err = np.where(better, err[a], best_err)
+    return best
+
+
+def gemm_int_trip(q, zp: int, wq, alpha) -> np.ndarray:
+    """Section 4.4, the TRIP matrix product: the factor of input channel k moves
+    onto row k of the weights,
+        acc[m,n] = sum_k (q[m,k] - zp) * 2^alpha[k] * Wq[n,k],
+    so that the activation keeps one layer-wise step.  int64, asserted to fit
+    the 32-bit accumulator."""
+    a = np.asarray(q, dtype=np.int64) - int(zp)
+    b = np.asarray(wq, dtype=np.int64)
+    if a.shape[-1] != b.shape[-1]:
+        raise ValueError("K mismatch")
+    alpha = _check_alpha(alpha, a.shape[-1])
+    acc = (a << alpha[None, :]) @ b.T
+    if acc.size and max(int(acc.max()), -int(acc.min())) > INT32_MAX:
+        raise OverflowError("accumulator leaves int32")
+    return acc
+
+
+def linear_w4_trip(x, bits: int, e: int, zp: int, alpha, wq, sw):
+    """The linear layer with TRIP factors: Eq.5 on the activation, the integer
+    product with the factors folded in, and the per-channel dequantisation with
+    the base step 2^e.  Returns (acc int64, y fp16)."""
+    q = trip_quantize(x, bits, e, zp, alpha)
+    acc = gemm_int_trip(q, zp, wq, alpha)
     return acc, dequant_out(acc, e, sw)
 
 

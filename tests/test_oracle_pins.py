@@ -435,3 +435,151 @@ def test_progressive_ratio_eq9(oracle):
     assert oracle.n_keep(2048, 0.5) == 1024
     assert oracle.n_keep(10, 0.25) == 8          # 10 - floor(2.5)
     assert oracle.n_keep(7, 0.0) == 7
+
+
+# ---------------------------------------------------------------- Eq.5 - Eq.8 (TRIP)
+
+def test_trip_golden_eq5_eq8(oracle):
+    rows = [[float(v) for v in r] for r in _rows("eq8_trip_examples.txt")]
+    x = np.array([r[:3] for r in rows], dtype=np.float16).T          # [3 tokens, 4 channels]
+    bits, e, zp, kmax = 4, -2, 0, 2
+    for a in range(kmax + 1):
+        al = np.full(x.shape[1], a)
+        xh = oracle.trip_dequantize(oracle.trip_quantize(x, bits, e, zp, al), e, zp, al)
+        err = ((x.astype(np.float64) - xh) ** 2).sum(axis=0)
+        assert err.tolist() == [r[3 + a] for r in rows]
+    assert oracle.trip_search(x, bits, e, zp, kmax).tolist() == [int(r[6]) for r in rows]
+
+
+def test_trip_quantize_reduces_to_eq2(oracle):
+    rng = np.random.default_rng(21)
+    x = (rng.standard_normal((7, 40)) * 6).astype(np.float16)
+    for bits, zp in ((8, 0), (4, 0), (8, 100), (4, 9)):
+        # all factors zero: Eq.5 is Eq.2
+        assert np.array_equal(oracle.trip_quantize(x, bits, -3, zp, np.zeros(40, dtype=int)),
+                              oracle.quantize_act(x, bits, -3, zp))
+        # one common factor a: Eq.2 with the step 2^(e+a)
+        for a in (1, 4):
+            assert np.array_equal(oracle.trip_quantize(x, bits, -3, zp, np.full(40, a)),
+                                  oracle.quantize_act(x, bits, -3 + a, zp))
+        # mixed factors: every column on its own against Eq.2 with that column's step
+        alpha = rng.integers(0, 5, size=40)
+        q = oracle.trip_quantize(x, bits, -3, zp, alpha)
+        for c in range(40):
+            assert np.array_equal(q[:, c], oracle.quantize_act(x[:, c], bits, -3 + int(alpha[c]), zp))
+        xh = oracle.trip_dequantize(q, -3, zp, alpha)
+        for c in range(40):
+            assert np.array_equal(xh[:, c], oracle.dequantize_act(q[:, c], -3 + int(alpha[c]), zp))
+
+
+def test_trip_base_exp(oracle):
+    x = np.array([[1.0, -100.0], [0.5, 3.0]], dtype=np.float16)
+    e_layer = oracle.calibrate_act_exp(x, 8)
+    assert 127 * 2.0 ** e_layer >= 100.0 > 127 * 2.0 ** (e_layer - 1)
+    for k in range(5):
+        assert oracle.trip_base_exp(x, 8, k) == e_layer - k
+    # a channel with the factor K gets the layer-wise step back
+    assert np.array_equal(oracle.trip_quantize(x, 8, e_layer - 3, 0, np.array([3, 3])), oracle.quantize_act(x, 8, e_layer, 0))
+
+
+def test_trip_search_bruteforce_rational(oracle):
+    """Eq.8 in exact rational arithmetic, pure Python, on small inputs."""
+    rng = np.random.default_rng(22)
+    M, C = 9, 24
+    x = (rng.standard_normal((M, C)) * np.where(rng.random(C) < 0.3, 12.0, 1.0)).astype(np.float16)
+    for bits, e, zp, kmax in ((8, -7, 0, 4), (4, -3, 0, 3), (8, -6, 77, 4), (4, -2, 5, 2)):
+        lo, hi = oracle.grid_bounds(bits, zp)
+        got = oracle.trip_search(x, bits, e, zp, kmax)
+        for c in range(C):
+            errs = []
+            for a in range(kmax + 1):
+                step = Fraction(2) ** (e + a)
+                tot = Fraction(0)
+                for m in range(M):
+                    v = f16_fraction(x[m, c])
+                    q = min(max(round_half_even(v / step) + zp, lo), hi)
+                    tot += (v - (q - zp) * step) ** 2
+                errs.append(tot)
+            best = min(errs)
+            # the float64 sums of the oracle may differ from the exact ones in the last
+            # bits: the factor it picked must be optimal up to that, and exactly the
+            # first optimum when the optimum is separated
+            assert errs[int(got[c])] <= best * (1 + Fraction(1, 10 ** 12))
+            sep = [a for a in range(kmax + 1) if errs[a] <= best * (1 + Fraction(1, 10 ** 9))]
+            if len(sep) == 1 or all(errs[a] == best for a in sep):
+                assert int(got[c]) == sep[0]
+
+
+def test_trip_search_properties(oracle):
+    rng = np.random.default_rng(23)
+    M, C, bits, kmax = 64, 32, 8, 4
+    base = rng.standard_normal((M, C))
+    x = base.astype(np.float16)
+    e = oracle.trip_base_exp(x, bits, kmax)
+    a0 = oracle.trip_search(x, bits, e, 0, kmax)
+    # values that all sit on the finest grid without clipping: factor 0 for every channel
+    on_grid = (rng.integers(-127, 128, size=(M, C)) * 2.0 ** e).astype(np.float16)
+    assert oracle.trip_search(on_grid, bits, e, 0, kmax).tolist() == [0] * C
+    # scaling a channel up by 2^j moves its best factor up by exactly j (the residuals
+    # scale with it), as long as the result still lies in 0..K
+    x2 = x.copy()
+    x2[:, :8] = (base[:, :8].astype(np.float16).astype(np.float64) * 4.0).astype(np.float16)
+    a2 = oracle.trip_search(x2, bits, e, 0, kmax)
+    for c in range(8):
+        if a0[c] + 2 <= kmax:
+            assert a2[c] == a0[c] + 2
+    assert np.array_equal(a2[8:], a0[8:])                     # channels are independent
+    # a channel whose magnitudes need the layer-wise step picks the largest factor
+    big = x.copy()
+    big[:, 3] = (base[:, 3] * 30).astype(np.float16)
+    eb = oracle.trip_base_exp(big, bits, kmax)
+    ab = oracle.trip_search(big, bits, eb, 0, kmax)
+    assert ab[3] == kmax and ab.max() == kmax and (ab[np.arange(C) != 3] < kmax).all()
+    # token order matters only through float64 rounding: a reversed tensor gives the same factors here
+    assert np.array_equal(oracle.trip_search(x[::-1].copy(), bits, e, 0, kmax), a0)
+    # +-Inf makes every candidate's error infinite: the smaller factor is kept
+    xi = x.copy()
+    xi[5, 2] = np.inf
+    assert oracle.trip_search(xi, bits, e, 0, kmax)[2] == 0
+
+
+def test_trip_gemm_folding_identity(oracle):
+    """Section 4.4: the factors move onto the weight rows.  The folded product through
+    the plain integer contraction, a pure-Python big-integer sum, and the factor-free
+    special case pin `gemm_int_trip`."""
+    rng = np.random.default_rng(24)
+    M, K, N = 6, 96, 10
+    w = rng.integers(-8, 8, size=(N, K))
+    alpha = np.where(rng.random(K) < 0.2, rng.integers(1, 5, size=K), 0)
+    for zp, (lo, hi) in ((0, (-128, 128)), (128, (0, 256))):
+        q = rng.integers(lo, hi, size=(M, K))
+        got = oracle.gemm_int_trip(q, zp, w, alpha)
+        assert np.array_equal(got, oracle.gemm_int(q, zp, w * (1 << alpha)[None, :]))
+        want = [[sum((int(q[m, k]) - zp) * (1 << int(alpha[k])) * int(w[n, k]) for k in range(K)) for n in range(N)]
+                for m in range(M)]
+        assert got.tolist() == want
+        assert np.array_equal(oracle.gemm_int_trip(q, zp, w, np.zeros(K, dtype=int)), oracle.gemm_int(q, zp, w))
+    with pytest.raises(ValueError):
+        oracle.gemm_int_trip(q, 0, w, np.full(K, 5))
+
+
+def test_trip_linear_approximates_the_real_product(oracle):
+    """With outlier channels the TRIP layer must be closer to the float product than the
+    layer-wise quantizer at the same bits: the reason the factors exist (Section 4.3)."""
+    x = synth.make_activation(32, 512, 4, seed=3)
+    w = synth.make_weight(48, 512, seed=3)
+    wq, sw = oracle.quantize_weight_rtn(w)
+    ref = x.astype(np.float64) @ (wq.astype(np.float64) * sw.astype(np.float64)[:, None]).T
+    bits, kmax = 8, 4
+    e_layer = oracle.calibrate_act_exp(x, bits)
+    _, y_plain = oracle.linear_w4(x, bits, e_layer, 0, wq, sw)
+    e = oracle.trip_base_exp(x, bits, kmax)
+    alpha = oracle.trip_search(x, bits, e, 0, kmax)
+    acc, y_trip = oracle.linear_w4_trip(x, bits, e, 0, alpha, wq, sw)
+    # the folded accumulator equals the dequantized activation times the integer weights
+    xh = oracle.trip_dequantize(oracle.trip_quantize(x, bits, e, 0, alpha), e, 0, alpha)
+    assert np.array_equal(np.ldexp(acc.astype(np.float64), e), xh @ wq.astype(np.float64).T)
+    err_plain = np.abs(y_plain.astype(np.float64) - ref).mean()
+    err_trip = np.abs(y_trip.astype(np.float64) - ref).mean()
+    assert err_trip < 0.5 * err_plain
+    assert 0 < (alpha > 0).sum() < 64                         # the outlier channels and few others
