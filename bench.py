@@ -52,6 +52,7 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-prefill", action="store_true")
     ap.add_argument("--no-attention", action="store_true")
+    ap.add_argument("--no-trip", action="store_true")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also run a 256 MiB device copy: the known traffic that scales the FETCH_SIZE / WRITE_SIZE counters")
     ap.add_argument("--per-projection", action="store_true", help="seven single calls per block instead of four")
@@ -248,6 +249,75 @@ def main():
                                           "note": "fp16 input: time includes the 4 quantize/layout pre-passes of a block"},
                              "single_calls": shapes}
         result["prefill"] = prefill
+
+    # ---- TRIP (Section 4.3 / 4.4): the same three shapes with per-channel factors found by Eq.8 on a
+    #      2048-token activation with 1 % outlier channels; decode launches (single calls, 12 distinct
+    #      blobs per shape in rotation) and the M = 2048 GEMM, beside the plain layer on the same inputs
+    if not args.no_trip:
+        trip = {"workload": "llama7b shapes, W4A8 with TRIP factors (K = 4 refinements), fp16 input", "shapes": []}
+        kmax, copies = 4, 12
+        for (pname, K, N) in (synth.LLAMA7B_PROJ[0], synth.LLAMA7B_PROJ[4], synth.LLAMA7B_PROJ[6]):
+            xcal = torch.from_numpy(synth.make_activation(PREFILL_M, K, synth.n_outlier_channels(K), seed=2)).to(dev)
+            e_layer = int(agq.calibrate_act_exp(xcal, 8).item())
+            alpha = agq.trip_search(xcal, 8, e_layer - kmax, kmax).cpu().numpy()
+            blobs_t, blobs_p = [], []
+            for _ in range(copies):
+                w = torch.randn((N, K), generator=gen, device=dev, dtype=torch.float32) * 0.02
+                sw = (w.abs().amax(dim=1) / 7.0).to(torch.float16)
+                wq = torch.clamp(torch.round(w / sw.float()[:, None]), -8, 7).to(torch.int8)
+                bt, n_extra = agq.pack_w4_trip(wq, alpha)
+                blobs_t.append((bt, sw))
+                blobs_p.append((agq.pack_w4(wq), sw))
+                del w, wq
+            entry = {"proj": pname, "K": K, "N": N, "channels_with_factor": int((alpha > 0).sum()),
+                     "extra_chunks": n_extra, "decode": {}}
+            for M in DECODE_M:
+                xm = xcal[:M].contiguous()
+                ym = torch.empty((M, N), dtype=torch.float16, device=dev)
+
+                def run_t():
+                    for (b, sw) in blobs_t:
+                        agq.gemm_trip(xm, 8, e_layer - kmax, b, n_extra, sw, N, K, y=ym)
+
+                def run_p():
+                    for (b, sw) in blobs_p:
+                        agq.gemm_w4a8(xm, e_layer, b, sw, N, K, y=ym)
+
+                us_t = timed(run_t, 2, 10) / 10 / copies * 1e3
+                us_p = timed(run_p, 2, 10) / 10 / copies * 1e3
+                by = algorithmic_bytes(M, K, N) + n_extra * 64 * N + n_extra * 128 * (4 + 2 * M)
+                entry["decode"]["M%d" % M] = {"us": round(us_t, 2), "us_plain": round(us_p, 2),
+                                               "GB/s": round(by / us_t / 1e3, 1),
+                                               "frac_hbm": round(by / us_t / 1e3 / HBM_PEAK_GBS, 4)}
+            ws_t = torch.empty(agq.lib().agq_gemm_trip_workspace_bytes(PREFILL_M, N, K, n_extra), dtype=torch.uint8, device=dev)
+            yp = torch.empty((PREFILL_M, N), dtype=torch.float16, device=dev)
+
+            def pre_t():
+                agq.gemm_trip(xcal, 8, e_layer - kmax, blobs_t[0][0], n_extra, blobs_t[0][1], N, K, y=yp, workspace=ws_t)
+
+            def pre_p():
+                agq.gemm_w4a8(xcal, e_layer, blobs_p[0][0], blobs_p[0][1], N, K, y=yp, workspace=ws_t)
+
+            def time_eager(f, reps=20):
+                for _ in range(3):
+                    f()
+                torch.cuda.synchronize()
+                a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                a.record()
+                for _ in range(reps):
+                    f()
+                b.record()
+                torch.cuda.synchronize()
+                return a.elapsed_time(b) / reps * 1e3
+
+            us_t, us_p = time_eager(pre_t), time_eager(pre_p)
+            ops = 2.0 * PREFILL_M * N * (K + 128 * n_extra)
+            entry["prefill_M%d" % PREFILL_M] = {"us": round(us_t, 1), "us_plain": round(us_p, 1),
+                                                "TOP/s": round(ops / us_t / 1e6, 1),
+                                                "frac_mfma": round(ops / us_t / 1e6 / INT8_PEAK_TOPS, 4)}
+            trip["shapes"].append(entry)
+            del blobs_t, blobs_p, xcal
+        result["trip"] = trip
 
     # ---- attention side path at LLaMA-13B size: log2-quantized softmax x V with the start-token score,
     #      then Eq.4 pruning to half the tokens (HBM bound: the probabilities are read once)

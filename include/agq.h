@@ -143,6 +143,62 @@ int agq_gemm_w4a4_multi(const void *x, int x_kind, int64_t M, int64_t K, int64_t
                         int e, int zp, const agq_proj *projs, int count,
                         void *workspace, size_t workspace_bytes, void *stream);
 
+/* TRIP: per-channel power-of-two factors on top of the layer-wise step
+ * (Section 4.3, Eq.5-8) and the matrix product that carries them on the weight
+ * rows (Section 4.4, "efficient TRIP matrix multiplication").
+ *
+ * Eq.5 quantizes input channel k with the step 2^(e + alpha[k]), alpha[k] in
+ * 0..AGQ_TRIP_MAX_FACTOR, grid and rounding as in Eq.2:
+ *   q[m,k]   = CLIP(round(x[m,k] / 2^(e + alpha[k])) + zp, lo, hi)
+ *   acc[m,n] = sum_k (q[m,k] - zp) * 2^alpha[k] * Wq[n,k]      (int32, exact)
+ *   y[m,n]   = fp16( float(acc[m,n]) * (2^e * sw[n]) )
+ * e is the base (finest) step: Eq.6 is read as the layer-wise step divided by
+ * 2^kmax, i.e. e = agq_calibrate_act_exp's result minus kmax.
+ *
+ * agq_trip_search (Eq.8): alpha[k] = the factor in 0..kmax with the smallest
+ * squared error || x[:,k] - dequant(quant(x[:,k])) ||^2 over the M tokens, the
+ * quantizer being Eq.5 with its clip; equal errors give the smaller factor.
+ * Errors are summed in float64 in token order, so the result is reproducible
+ * bit for bit.  x_f16: fp16 [M,K], ldx >= K; alpha_dev: device int8 [K].
+ * M == 0 gives all zeros.  A calibration-time call, not tuned for speed.
+ *
+ * The weight blob for a set of factors: channels with alpha > 0 are served by
+ * extra 128-wide chunks (at most AGQ_TRIP_MAX_EXTRA of them, each holding
+ * channels of one factor), the other channels by the ordinary chunks.
+ * alpha_host is a HOST array int8 [K] (copy agq_trip_search's result back: packing
+ * is set-up work).  agq_trip_extra_chunks returns the number of extra chunks
+ * (>= 0) these factors need, or AGQ_EINVAL (a factor outside 0..4, more chunks
+ * than the maximum, bad K).  agq_pack_w4_trip_bytes(N, K, n_extra) is the blob
+ * size (0 = invalid arguments).  agq_pack_w4_trip copies small tables to the
+ * device and WAITS for `stream` before it launches its kernels (not capturable).
+ * agq_unpack_w4_trip(agq_pack_w4_trip(W)) == W (after saturation to [-8,7]).
+ * K % 128 == 0, K <= 32768 (keeps every partial sum inside int32).
+ *
+ * agq_gemm_w4a8_trip / agq_gemm_w4a4_trip: the layer above with b = 8 / 4.
+ * x_f16 is fp16 [M,K] (ldx % 8 == 0, 16-byte aligned): the quantizer runs inside
+ * the call.  n_extra: as returned by agq_trip_extra_chunks for the factors the
+ * blob was packed with.  workspace: agq_gemm_trip_workspace_bytes(M,N,K,n_extra).
+ * Other arguments, alignment and errors as for agq_gemm_w4a8.                 */
+#define AGQ_TRIP_MAX_FACTOR 4
+#define AGQ_TRIP_MAX_EXTRA 16
+int agq_trip_search(const void *x_f16, int64_t M, int64_t K, int64_t ldx, int bits,
+                    int e, int zp, int kmax, int8_t *alpha_dev, void *stream);
+int agq_trip_extra_chunks(const int8_t *alpha_host, int64_t K);
+size_t agq_pack_w4_trip_bytes(int64_t N, int64_t K, int n_extra);
+int agq_pack_w4_trip(const int8_t *wq, int64_t N, int64_t K, const int8_t *alpha_host,
+                     void *packed, int32_t *bad_count_dev, void *stream);
+int agq_unpack_w4_trip(const void *packed, int64_t N, int64_t K, int n_extra,
+                       int8_t *wq_out, void *stream);
+size_t agq_gemm_trip_workspace_bytes(int64_t M, int64_t N, int64_t K, int n_extra);
+int agq_gemm_w4a8_trip(const void *x_f16, int64_t M, int64_t K, int64_t ldx, int e, int zp,
+                       const void *w_packed, int n_extra, const void *w_scale_f16,
+                       int64_t N, void *y_f16, int64_t ldy, int32_t *acc_out,
+                       void *workspace, size_t workspace_bytes, void *stream);
+int agq_gemm_w4a4_trip(const void *x_f16, int64_t M, int64_t K, int64_t ldx, int e, int zp,
+                       const void *w_packed, int n_extra, const void *w_scale_f16,
+                       int64_t N, void *y_f16, int64_t ldy, int32_t *acc_out,
+                       void *workspace, size_t workspace_bytes, void *stream);
+
 /* Log2 quantizer on softmax probabilities (Section 4.1 Eq.3 with max|X| = 1,
  * used for the softmax output per Section 5.1) fused with the product with the
  * int8 value matrix, plus the token importance of Section 4.3 (attention paid

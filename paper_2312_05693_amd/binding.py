@@ -18,6 +18,7 @@ AGQ_X_F16, AGQ_X_Q = 0, 1
 
 _i64, _int, _vp, _sz = ctypes.c_int64, ctypes.c_int, ctypes.c_void_p, ctypes.c_size_t
 _GEMM_ARGS = [_vp, _int, _i64, _i64, _i64, _int, _int, _vp, _vp, _i64, _vp, _i64, _vp, _vp, _sz, _vp]
+_TRIP_GEMM_ARGS = [_vp, _i64, _i64, _i64, _int, _int, _vp, _int, _vp, _i64, _vp, _i64, _vp, _vp, _sz, _vp]
 SIGNATURES = {
     "agq_status_string": (ctypes.c_char_p, [_int]),
     "agq_version": (_int, []),
@@ -31,6 +32,14 @@ SIGNATURES = {
     "agq_gemm_w4a4": (_int, _GEMM_ARGS),
     "agq_gemm_w4a8_multi": (_int, [_vp, _int, _i64, _i64, _i64, _int, _int, _vp, _int, _vp, _sz, _vp]),
     "agq_gemm_w4a4_multi": (_int, [_vp, _int, _i64, _i64, _i64, _int, _int, _vp, _int, _vp, _sz, _vp]),
+    "agq_trip_search": (_int, [_vp, _i64, _i64, _i64, _int, _int, _int, _int, _vp, _vp]),
+    "agq_trip_extra_chunks": (_int, [_vp, _i64]),
+    "agq_pack_w4_trip_bytes": (_sz, [_i64, _i64, _int]),
+    "agq_pack_w4_trip": (_int, [_vp, _i64, _i64, _vp, _vp, _vp, _vp]),
+    "agq_unpack_w4_trip": (_int, [_vp, _i64, _i64, _int, _vp, _vp]),
+    "agq_gemm_trip_workspace_bytes": (_sz, [_i64, _i64, _i64, _int]),
+    "agq_gemm_w4a8_trip": (_int, _TRIP_GEMM_ARGS),
+    "agq_gemm_w4a4_trip": (_int, _TRIP_GEMM_ARGS),
     "agq_log2_quant_softmax": (_int, [_vp, _i64, _i64, _i64, _int, _int, _vp, _int, _vp, _vp, _vp, _vp]),
     "agq_prune_tokens": (_int, [_vp, _i64, _i64, _vp, _i64, _vp, _vp, _vp]),
 }
@@ -180,6 +189,65 @@ def gemm_w4a4_multi(x, e, projs, K, x_kind=AGQ_X_F16, workspace=None, zp=0):
     M = x.shape[0]
     ldx = (x.stride(0) if M else K) * (2 if x_kind == AGQ_X_Q else 1)
     return _gemm_multi("agq_gemm_w4a4_multi", x, x_kind, M, K, ldx, e, zp, projs, workspace)
+
+
+def trip_search(x: torch.Tensor, bits: int, e: int, kmax: int, zp: int = 0, alpha: torch.Tensor | None = None):
+    """Eq.8: device int8 [K] of per-channel factors."""
+    M, K = x.shape
+    if alpha is None:
+        alpha = torch.empty(K, dtype=torch.int8, device=x.device)
+    _ok(lib().agq_trip_search(_ptr(x), M, K, x.stride(0) if M else K, bits, e, zp, kmax, _ptr(alpha), _stream()),
+        "agq_trip_search")
+    return alpha
+
+
+def _host_alpha(alpha):
+    """The factors as a contiguous host int8 array (kept alive by the caller for the call)."""
+    import numpy as np
+    if isinstance(alpha, torch.Tensor):
+        alpha = alpha.cpu().numpy()
+    return np.ascontiguousarray(alpha, dtype=np.int8)
+
+
+def trip_extra_chunks(alpha, K: int) -> int:
+    a = _host_alpha(alpha)
+    n = lib().agq_trip_extra_chunks(a.ctypes.data, K)
+    if n < 0:
+        raise AgqError(n, "agq_trip_extra_chunks")
+    return n
+
+
+def pack_w4_trip(wq: torch.Tensor, alpha, packed: torch.Tensor | None = None, bad_count: torch.Tensor | None = None):
+    """Returns (blob, n_extra)."""
+    N, K = wq.shape
+    a = _host_alpha(alpha)
+    n_extra = trip_extra_chunks(a, K)
+    if packed is None:
+        packed = torch.empty(lib().agq_pack_w4_trip_bytes(N, K, n_extra), dtype=torch.uint8, device=wq.device)
+    _ok(lib().agq_pack_w4_trip(_ptr(wq), N, K, a.ctypes.data, _ptr(packed), _ptr(bad_count), _stream()),
+        "agq_pack_w4_trip")
+    return packed, n_extra
+
+
+def unpack_w4_trip(packed: torch.Tensor, N: int, K: int, n_extra: int) -> torch.Tensor:
+    out = torch.zeros((N, K), dtype=torch.int8, device=packed.device)
+    _ok(lib().agq_unpack_w4_trip(_ptr(packed), N, K, n_extra, _ptr(out), _stream()), "agq_unpack_w4_trip")
+    return out
+
+
+def gemm_trip(x, bits, e, w_packed, n_extra, w_scale, N, K, y=None, acc_out=None, workspace=None, zp=0):
+    """The TRIP linear layer (Section 4.4) with b = bits; x is fp16 [M, K]."""
+    M = x.shape[0]
+    if y is None:
+        y = torch.empty((M, N), dtype=torch.float16, device=x.device)
+    need = lib().agq_gemm_trip_workspace_bytes(M, N, K, n_extra)
+    if workspace is None and need:
+        workspace = torch.empty(need, dtype=torch.uint8, device=x.device)
+    fn = lib().agq_gemm_w4a8_trip if bits == 8 else lib().agq_gemm_w4a4_trip
+    _ok(fn(_ptr(x), M, K, x.stride(0) if M else K, e, zp, _ptr(w_packed), n_extra, _ptr(w_scale), N, _ptr(y),
+           y.stride(0) if M else N, _ptr(acc_out), _ptr(workspace), workspace.numel() if workspace is not None else 0,
+           _stream()), "agq_gemm_w4a%d_trip" % bits)
+    return y
 
 
 def log2_quant_softmax(p, v_q, e_v, qmax=15, causal=True, want_codes=False, want_score=True):

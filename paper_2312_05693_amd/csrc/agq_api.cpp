@@ -42,7 +42,7 @@ int gemm_w4_multi(int bits, const void *x, int x_kind, int64_t M, int64_t K, int
         if (workspace_bytes < need) return AGQ_ESIZE;
     }
     if (M <= AGQ_DECODE_MAX_M)
-        return hip_status(agq_launch_gemm_decode(x, x_kind, bits, M, K, ldx, e, zp, projs, count, stream));
+        return hip_status(agq_launch_gemm_decode(x, x_kind, bits, M, K, ldx, e, zp, projs, count, -1, stream));
 
     // many tokens: lay the codes out in MFMA operand order once (quantizing on the
     // way when x is fp16), then run the tiled kernel per projection on that copy
@@ -50,7 +50,7 @@ int gemm_w4_multi(int bits, const void *x, int x_kind, int64_t M, int64_t K, int
     for (int p = 0; p < count; ++p) {
         if (agq_launch_gemm_tiled(workspace, M, K, e, agq_zp_corr(bits, zp), projs[p].w_packed, projs[p].w_scale_f16,
                                   projs[p].N,
-                                  projs[p].y_f16, projs[p].ldy, projs[p].acc_out, stream))
+                                  projs[p].y_f16, projs[p].ldy, projs[p].acc_out, -1, stream))
             return AGQ_EHIP;
     }
     return AGQ_OK;
@@ -61,6 +61,36 @@ int gemm_w4(int bits, const void *x, int x_kind, int64_t M, int64_t K, int64_t l
             void *workspace, size_t workspace_bytes, void *stream) {
     const agq_proj one = {w_packed, sw, N, y, ldy, acc_out};
     return gemm_w4_multi(bits, x, x_kind, M, K, ldx, e, zp, &one, 1, workspace, workspace_bytes, stream);
+}
+
+constexpr int64_t kTripMaxK = 32768;   // extra chunks included, every partial sum stays inside int32
+
+inline bool trip_dims_ok(int64_t N, int64_t K, int n_extra) {
+    return N >= 1 && N <= kMaxDim && K >= 128 && K <= kTripMaxK && (K % 128) == 0 && n_extra >= 0 &&
+           n_extra <= AGQ_TRIP_MAX_EXTRA;
+}
+
+int gemm_w4_trip(int bits, const void *x, int64_t M, int64_t K, int64_t ldx, int e, int zp, const void *w_packed,
+                 int n_extra, const void *sw, int64_t N, void *y, int64_t ldy, int32_t *acc_out, void *workspace,
+                 size_t workspace_bytes, void *stream) {
+    if (M < 0 || M > kMaxDim || !trip_dims_ok(N, K, n_extra)) return AGQ_EINVAL;
+    if (!e_ok(e) || zp < 0 || zp > (1 << bits) - 1 || ldx < K || (ldx % 8) != 0) return AGQ_EINVAL;
+    if (ldy < N || ldy > kMaxDim) return AGQ_EINVAL;
+    if (M == 0) return AGQ_OK;
+    if (!x || !w_packed || !sw || !y) return AGQ_EINVAL;
+    if (!aligned16(x) || !aligned16(w_packed) || !aligned16(sw) || !aligned16(y)) return AGQ_EINVAL;
+    const size_t need = agq_gemm_trip_workspace_bytes(M, N, K, n_extra);
+    if (need > 0) {
+        if (!workspace || !aligned16(workspace)) return AGQ_EINVAL;
+        if (workspace_bytes < need) return AGQ_ESIZE;
+    }
+    if (M <= AGQ_DECODE_MAX_M) {
+        const agq_proj one = {w_packed, sw, N, y, ldy, acc_out};
+        return hip_status(agq_launch_gemm_decode(x, AGQ_X_F16, bits, M, K, ldx, e, zp, &one, 1, n_extra, stream));
+    }
+    if (agq_launch_prepack_trip(x, bits, M, K, ldx, e, zp, w_packed, N, n_extra, workspace, stream)) return AGQ_EHIP;
+    return hip_status(agq_launch_gemm_tiled(workspace, M, K, e, agq_zp_corr(bits, zp), w_packed, sw, N, y, ldy, acc_out,
+                                            n_extra, stream));
 }
 
 }  // namespace
@@ -119,6 +149,60 @@ size_t agq_gemm_workspace_bytes(int64_t M, int64_t N, int64_t K) {
     (void)N;
     if (M <= AGQ_DECODE_MAX_M || K < 1) return 0;
     return (size_t)((M + 127) / 128) * 128 * (size_t)K;   // int8 codes, tokens padded to the 128-row tile
+}
+
+int agq_trip_search(const void *x_f16, int64_t M, int64_t K, int64_t ldx, int bits, int e, int zp, int kmax,
+                    int8_t *alpha_dev, void *stream) {
+    if (M < 0 || K < 0 || M > kMaxDim || K > kMaxDim || !bits_ok(bits)) return AGQ_EINVAL;
+    if (kmax < 0 || kmax > AGQ_TRIP_MAX_FACTOR || e < AGQ_E_MIN || e + kmax > AGQ_E_MAX) return AGQ_EINVAL;
+    if (zp < 0 || zp > (1 << bits) - 1 || ldx < K) return AGQ_EINVAL;
+    if (K == 0) return AGQ_OK;
+    if (!alpha_dev || (M > 0 && !x_f16)) return AGQ_EINVAL;
+    return hip_status(agq_launch_trip_search(x_f16, M, K, ldx, bits, e, zp, kmax, alpha_dev, stream));
+}
+
+int agq_trip_extra_chunks(const int8_t *alpha_host, int64_t K) {
+    if (!alpha_host || K < 128 || K > kTripMaxK || (K % 128) != 0) return AGQ_EINVAL;
+    const int E = agq_trip_count_extra(alpha_host, K);
+    return E < 0 ? AGQ_EINVAL : E;
+}
+
+size_t agq_pack_w4_trip_bytes(int64_t N, int64_t K, int n_extra) {
+    if (!trip_dims_ok(N, K, n_extra)) return 0;
+    return agq_trip_layout(N, K, n_extra).total;
+}
+
+int agq_pack_w4_trip(const int8_t *wq, int64_t N, int64_t K, const int8_t *alpha_host, void *packed,
+                     int32_t *bad_count_dev, void *stream) {
+    if (!alpha_host || !wq || !packed || !aligned16(wq) || !aligned16(packed)) return AGQ_EINVAL;
+    if (!trip_dims_ok(N, K, 0) || agq_trip_count_extra(alpha_host, K) < 0) return AGQ_EINVAL;
+    return hip_status(agq_launch_pack_trip(wq, N, K, alpha_host, packed, bad_count_dev, stream));
+}
+
+int agq_unpack_w4_trip(const void *packed, int64_t N, int64_t K, int n_extra, int8_t *wq_out, void *stream) {
+    if (!trip_dims_ok(N, K, n_extra) || !wq_out || !packed) return AGQ_EINVAL;
+    if (!aligned16(wq_out) || !aligned16(packed)) return AGQ_EINVAL;
+    return hip_status(agq_launch_unpack_trip(packed, N, K, n_extra, wq_out, stream));
+}
+
+size_t agq_gemm_trip_workspace_bytes(int64_t M, int64_t N, int64_t K, int n_extra) {
+    (void)N;
+    if (M <= AGQ_DECODE_MAX_M || K < 1 || n_extra < 0) return 0;
+    return (size_t)((M + 127) / 128) * 128 * (size_t)(K + 128 * (int64_t)n_extra);
+}
+
+int agq_gemm_w4a8_trip(const void *x_f16, int64_t M, int64_t K, int64_t ldx, int e, int zp, const void *w_packed,
+                       int n_extra, const void *w_scale_f16, int64_t N, void *y_f16, int64_t ldy, int32_t *acc_out,
+                       void *workspace, size_t workspace_bytes, void *stream) {
+    return gemm_w4_trip(8, x_f16, M, K, ldx, e, zp, w_packed, n_extra, w_scale_f16, N, y_f16, ldy, acc_out, workspace,
+                        workspace_bytes, stream);
+}
+
+int agq_gemm_w4a4_trip(const void *x_f16, int64_t M, int64_t K, int64_t ldx, int e, int zp, const void *w_packed,
+                       int n_extra, const void *w_scale_f16, int64_t N, void *y_f16, int64_t ldy, int32_t *acc_out,
+                       void *workspace, size_t workspace_bytes, void *stream) {
+    return gemm_w4_trip(4, x_f16, M, K, ldx, e, zp, w_packed, n_extra, w_scale_f16, N, y_f16, ldy, acc_out, workspace,
+                        workspace_bytes, stream);
 }
 
 int agq_gemm_w4a8(const void *x, int x_kind, int64_t M, int64_t K, int64_t ldx, int e, int zp, const void *w_packed,

@@ -104,3 +104,16 @@ __device__ __forceinline__ void agq_unpack_w(const uint4 &p, agq_v4i &b0, agq_v4
 __device__ __forceinline__ __half agq_dequant(int acc, float g) {
     return __float2half_rn((float)acc * g);
 }
+
+// Direct global-to-LDS copy: lane i's 16 bytes land at lds_chunk + 16 i (the LDS
+// address is wave-uniform and travels in M0).  Issued as inline assembly on
+// purpose: the compiler, seeing such a copy, drains every outstanding load
+// (vmcnt(0)) before any later LDS read, which would cancel the prefetch distance;
+// so a kernel that uses it waits for exactly the copies it needs with explicit
+// s_waitcnt vmcnt(n) (loads, these included, return in order).
+__device__ __forceinline__ void lds_dma16(const void *gsrc, uint32_t lds_addr) {
+    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off"
+                 :
+                 : "v"(gsrc), "s"(lds_addr)
+                 : "memory", "m0");
+}

@@ -59,10 +59,11 @@ struct DecodeArgs {
     __half *y4[kMaxProj];
     int32_t *acc4[kMaxProj];
     int ldy4[kMaxProj];
+    int n_extra;   // TRIP blob: extra chunks in front of the KT main chunks of every tile; else 0
     // Never read.  With the record at 368 or 384 bytes every launch of a replayed graph
     // measured 0.1-0.15 us shorter than at 256, 400 or 408 bytes (same instructions; the
     // cause is in how the runtime lays consecutive argument records out, not in the kernel).
-    int reserved[32];
+    int reserved[31];
 };
 static_assert(sizeof(DecodeArgs) == 384, "see the note on `reserved`");
 
@@ -93,7 +94,8 @@ __device__ __forceinline__ int find_proj(const DecodeArgs &a, int tile, int &nt)
 }
 
 // ONE: fp16 with a single token row; Z: fp16 on the unsigned grid (a zero point is added to every code)
-enum { XK_F16 = 0, XK_I8 = 1, XK_I4 = 2, XK_F16_ONE = 3, XK_F16_Z = 4, XK_F16_ONE_Z = 5 };
+// T: fp16 with a TRIP blob (Section 4.4): one more wavefront multiplies the extra chunks
+enum { XK_F16 = 0, XK_I8 = 1, XK_I4 = 2, XK_F16_ONE = 3, XK_F16_Z = 4, XK_F16_ONE_Z = 5, XK_F16_T = 6 };
 
 typedef unsigned int agq_u4 __attribute__((ext_vector_type(4)));
 typedef unsigned int agq_u2 __attribute__((ext_vector_type(2)));
@@ -125,9 +127,10 @@ __global__ __launch_bounds__(1024) void gemm_decode_kernel(const DecodeArgs a) {
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int nwaves = a.waves;
-    constexpr bool F16 = XK == XK_F16 || XK == XK_F16_ONE || XK == XK_F16_Z || XK == XK_F16_ONE_Z;
+    constexpr bool TRIP = XK == XK_F16_T;
+    constexpr bool F16 = XK == XK_F16 || XK == XK_F16_ONE || XK == XK_F16_Z || XK == XK_F16_ONE_Z || TRIP;
     constexpr bool ONE = XK == XK_F16_ONE || XK == XK_F16_ONE_Z;   // one row: a lane's 16 bytes are its own chunk's, four chunks per load
-    constexpr bool ZP = XK == XK_F16_Z || XK == XK_F16_ONE_Z;      // fp16 input on the unsigned grid
+    constexpr bool ZP = XK == XK_F16_Z || XK == XK_F16_ONE_Z || TRIP;   // fp16 input, zero point added (0 on the signed grid with TRIP)
     // Everything the first vector loads depend on is requested in one round of
     // scalar loads; the weight pointer, scale pointer and width of this workgroup's
     // projection are picked by scalar selects instead of a second, dependent round
@@ -140,7 +143,7 @@ __global__ __launch_bounds__(1024) void gemm_decode_kernel(const DecodeArgs a) {
     asm volatile("" ::"s"(a.x), "s"(a.ldx), "s"(a.M), "s"(KT), "s"(nwaves), "s"(t1), "s"(t2), "s"(t3), "s"(a.scale_e), "s"(bl0),
                  "s"(bl1), "s"(bl2), "s"(bl3), "s"(sc0), "s"(sc1), "s"(sc2), "s"(sc3), "s"(n0), "s"(n1), "s"(n2), "s"(n3),
                  "s"(a.q.scale), "s"(a.q.lo), "s"(a.q.hi), "s"(a.q.h_scale2), "s"(a.q.h_lo2), "s"(a.q.h_hi2),
-                 "s"(ZP ? a.q.h_zp2 : 0u), "s"(F16 ? 0u : a.flip), "s"(a.corr));
+                 "s"(ZP ? a.q.h_zp2 : 0u), "s"(F16 ? 0u : a.flip), "s"(a.corr), "s"(TRIP ? a.n_extra : 0));
     int nt;
     const int pj = find_proj(a, blockIdx.x, nt);   // which projection this workgroup serves (uniform)
     __half *const py = a.y4[pj];
@@ -149,7 +152,12 @@ __global__ __launch_bounds__(1024) void gemm_decode_kernel(const DecodeArgs a) {
     const int pN = pj == 0 ? n0 : (pj == 1 ? n1 : (pj == 2 ? n2 : n3));
     const __half *psw = pj == 0 ? sc0 : (pj == 1 ? sc1 : (pj == 2 ? sc2 : sc3));
     const uint4 *pblob = pj == 0 ? bl0 : (pj == 1 ? bl1 : (pj == 2 ? bl2 : bl3));
-    const agq_u4 *wptr = reinterpret_cast<const agq_u4 *>(pblob) + ((int64_t)nt * KT) * 64 + lane;
+    // TRIP: the last wavefront serves the extra chunks (channels with a factor), the
+    // others the KT main chunks that follow them in every tile of the blob
+    const int n_extra = TRIP ? a.n_extra : 0;
+    const int KTall = KT + n_extra;
+    const int nmain = TRIP ? nwaves - 1 : nwaves;
+    const agq_u4 *wptr = reinterpret_cast<const agq_u4 *>(pblob) + ((int64_t)nt * KTall + n_extra) * 64 + lane;
 
     agq_v4i acc0 = {0, 0, 0, 0}, acc1 = {0, 0, 0, 0};
     // Staging of the quantized activation: one region per chunk of a batch, in MFMA
@@ -167,7 +175,7 @@ __global__ __launch_bounds__(1024) void gemm_decode_kernel(const DecodeArgs a) {
     const int srow = (lane & 15) & (R - 1);     // staged row this lane's operand comes from
     uint32_t sw_bits = 0;                       // raw fp16 scale of this thread's output channel
 
-    for (int kb = wave * KPW; kb < KT; kb += nwaves * KPW) {
+    for (int kb = (TRIP && wave == nmain) ? KT : wave * KPW; kb < KT; kb += nmain * KPW) {
         // The activation slice is requested first and the weight chunks right after:
         // loads return in order, so the prologue can start as soon as the (L2-hot)
         // activation arrives while the weights are still on their way from HBM.
@@ -276,6 +284,76 @@ __global__ __launch_bounds__(1024) void gemm_decode_kernel(const DecodeArgs a) {
         }
     }
 
+    if (TRIP && wave == nmain) {
+        // Extra chunks: slot j of chunk c is input channel idx[c * 128 + j], quantized with
+        // the step 2^(e + factor of the chunk) (Eq.5); the chunk's partial product is
+        // shifted left by its factor (Section 4.4: the factor sits on the weight row).
+        // Same lane roles and staging as the main prologue (lane = eight slots of one
+        // row, four rows per pass), with a gather instead of a 16-byte load.  Two chunks
+        // at a time: their factors, indices and weights are requested in one round, the
+        // gathered activations in a second one.
+        const int32_t *meta = blob_wsum(pblob, pN, KTall) + ((pN + 255) / 256) * 256;
+        const int32_t *idx = meta + 32;
+        const agq_u4 *wx = reinterpret_cast<const agq_u4 *>(pblob) + ((int64_t)nt * KTall) * 64 + lane;
+        const __half *xh = reinterpret_cast<const __half *>(a.x);
+        const int c16 = lane & 15, rr = lane >> 4;
+        const int s = c16 >> 3, g = (c16 & 7) >> 1, hf = c16 & 1;
+        const int metav = meta[c16];                    // the factors of all (at most 16) chunks
+        for (int c0 = 0; c0 < n_extra; c0 += 2) {
+            int4 ia[2][2];
+            agq_u4 wv[2];
+#pragma unroll
+            for (int u = 0; u < 2; ++u) {
+                const int cc = min(c0 + u, n_extra - 1);
+                const int4 *ip = reinterpret_cast<const int4 *>(idx + cc * 128 + c16 * 8);
+                ia[u][0] = ip[0];
+                ia[u][1] = ip[1];
+                wv[u] = wx[(int64_t)cc * 64];
+            }
+            __half xg[2][MP][8];
+#pragma unroll
+            for (int u = 0; u < 2; ++u) {
+                const int kk[8] = {ia[u][0].x, ia[u][0].y, ia[u][0].z, ia[u][0].w,
+                                   ia[u][1].x, ia[u][1].y, ia[u][1].z, ia[u][1].w};
+#pragma unroll
+                for (int it = 0; it < MP; ++it) {
+                    const __half *xr = xh + (int64_t)min(it * 4 + rr, a.M - 1) * a.ldx;
+#pragma unroll
+                    for (int j = 0; j < 8; ++j) xg[u][it][j] = xr[max(kk[j], 0)];   // an unused slot (-1) meets zero weights
+                }
+            }
+#pragma unroll
+            for (int u = 0; u < 2; ++u) {
+                if (c0 + u >= n_extra) break;
+                const int factor = __builtin_amdgcn_readlane(metav, c0 + u);
+                AgqQuant qe = a.q;
+                qe.scale = ldexpf(a.q.scale, -factor);
+#pragma unroll
+                for (int it = 0; it < MP; ++it) {
+                    uint32_t b[8];
+#pragma unroll
+                    for (int j = 0; j < 8; ++j) b[j] = agq_quant1(__half2float(xg[u][it][j]), qe) + (uint32_t)qe.zp;
+                    const agq_u2 codes = {agq_pack4(b[0], b[1], b[2], b[3]), agq_pack4(b[4], b[5], b[6], b[7])};
+                    const int m = it * 4 + rr;
+                    if (m < a.M) reinterpret_cast<agq_u2 *>(stage + (s * 4 + g) * R + m)[hf] = codes;
+                }
+                __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+                __builtin_amdgcn_wave_barrier();
+                __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+                const agq_v4i a0 = __builtin_bit_cast(agq_v4i, stage[ag * R + srow]);
+                const agq_v4i a1 = __builtin_bit_cast(agq_v4i, stage[(4 + ag) * R + srow]);
+                __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+                __builtin_amdgcn_wave_barrier();
+                const agq_v4i b0v = __builtin_bit_cast(agq_v4i, (wv[u] << 4) & 0xF0F0F0F0u);
+                const agq_v4i b1v = __builtin_bit_cast(agq_v4i, wv[u] & 0xF0F0F0F0u);
+                const agq_v4i zero = {0, 0, 0, 0};
+                const agq_v4i t0 = __builtin_amdgcn_mfma_i32_16x16x64_i8(a0, b0v, zero, 0, 0, 0);
+                const agq_v4i t1 = __builtin_amdgcn_mfma_i32_16x16x64_i8(a1, b1v, zero, 0, 0, 0);
+                acc0 += (t0 + t1) << factor;
+            }
+        }
+    }
+
     // join the K-slices of the wavefronts, then dequantize (fused epilogue).
     // Partial sums are stored [wave][register][lane] so that both the write and
     // the read below are conflict-free.
@@ -294,9 +372,9 @@ __global__ __launch_bounds__(1024) void gemm_decode_kernel(const DecodeArgs a) {
             int sum = 0;
             for (int w = 0; w < nwaves; ++w) sum += red[(w * 4 + r) * 64 + l];
             int v = sum >> shift;   // exact: every term carries the factor
-            if (a.corr) v += a.corr * blob_wsum(pblob, pN, KT)[n];
+            if (a.corr) v += a.corr * blob_wsum(pblob, pN, KTall)[n];
             if (pacc) pacc[(int64_t)m * pN + n] = v;
-            const uint32_t sb = nwaves >= 4 ? sw_bits : (uint32_t) reinterpret_cast<const uint16_t *>(psw)[n];
+            const uint32_t sb = nmain >= 4 ? sw_bits : (uint32_t) reinterpret_cast<const uint16_t *>(psw)[n];
             py[(int64_t)m * pldy + n] = agq_dequant(v, a.scale_e * __half2float(__ushort_as_half((unsigned short)sb)));
         }
     }
@@ -483,7 +561,7 @@ int launch_xk(const DecodeArgs &a, int kpw, unsigned grid, int waves, size_t lds
 }  // namespace
 
 int agq_launch_gemm_decode(const void *x, int x_kind, int bits, int64_t M, int64_t K, int64_t ldx, int e, int zp,
-                           const agq_proj *projs, int count, void *stream) {
+                           const agq_proj *projs, int count, int n_extra, void *stream) {
     DecodeArgs a = {};
     a.x = x;
     a.ldx = ldx;
@@ -495,6 +573,8 @@ int agq_launch_gemm_decode(const void *x, int x_kind, int bits, int64_t M, int64
     a.corr = agq_zp_corr(bits, zp);
     a.flip = zp ? (bits == 8 ? 0x80808080u : 0x88888888u) : 0u;
     a.scale_e = ldexpf(1.0f, e);
+    a.n_extra = n_extra > 0 ? n_extra : 0;
+    const bool trip = n_extra >= 0;
     int tiles = 0;
     for (int p = 0; p < kMaxProj; ++p) {
         const agq_proj &pr = projs[p < count ? p : count - 1];
@@ -526,6 +606,16 @@ int agq_launch_gemm_decode(const void *x, int x_kind, int bits, int64_t M, int64
         waves = (a.KT + kpw - 1) / kpw;
         if (waves > 16) waves = 16;
     }
+    if (trip) {
+        // one more wavefront for the extra chunks: at most 15 for the main ones
+        if (waves > 15) {
+            kpw = 1;
+            while (kpw < 8 && (a.KT + kpw - 1) / kpw > 15) kpw *= 2;
+            waves = (a.KT + kpw - 1) / kpw;
+            if (waves > 15) waves = 15;
+        }
+        waves += 1;
+    }
     const unsigned grid = (unsigned)tiles;
     a.waves = waves;
     // staging: per wavefront HB chunks x (8 x 4 MP) 16-byte pieces (see the kernel);
@@ -540,6 +630,11 @@ int agq_launch_gemm_decode(const void *x, int x_kind, int bits, int64_t M, int64
     // channel tiles and the activation is large (measured at K = 4096: from nine
     // rows on and more than one tile per CU; below that the per-tile prologue,
     // which overlaps better with the weight stream, is faster).
+    if (trip) {
+        if (M <= 4) return launch_xk<XK_F16_T, 1>(a, kpw, grid, waves, lds, st);
+        if (M <= 8) return launch_xk<XK_F16_T, 2>(a, kpw, grid, waves, lds, st);
+        return launch_xk<XK_F16_T, 4>(a, kpw, grid, waves, lds, st);
+    }
     if (x_kind == 0 && M > 8 && tiles > 256 && a.KT <= kSharedMaxKT && a.KT >= 4) {
         // one workgroup per CU; its sixteen wavefronts form two tile streams when a
         // CU has four or more tiles to walk (measured: 9 % faster for gate/up, no

@@ -61,20 +61,17 @@ struct TiledArgs {
     float scale_e;
     int corr;               // unsigned activation grid: acc += corr * wsum[n]; 0 on the signed grid
     const int32_t *wsum;    // per-channel weight sums (end of the blob)
+    // TRIP blob: the first n_extra steps are the extra chunks of the channels with a factor;
+    // trip_shift[kt] (device) is the left shift of the running accumulators after step kt
+    int n_extra;
+    const int32_t *trip_shift;
 };
 
-// Direct global-to-LDS copy: lane i's 16 bytes land at lds_chunk + 16 i (the LDS
-// address is wave-uniform and travels in M0).  Issued as inline assembly on
-// purpose: the compiler, seeing such a copy, drains every outstanding load
-// (vmcnt(0)) before any later LDS read, which would cancel the prefetch distance;
-// here the kernel waits for exactly the copies it needs (see the step macro).
-__device__ __forceinline__ void lds_dma16(const void *gsrc, uint32_t lds_addr) {
-    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off"
-                 :
-                 : "v"(gsrc), "s"(lds_addr)
-                 : "memory", "m0");
-}
-
+// TRIP: the blob and the activation stages carry extra steps in front, ordered by
+// descending factor; after the last step of a factor the accumulators are shifted
+// left by the difference to the next factor (Horner), so that at the end every
+// extra step has been multiplied by 2^factor (Section 4.4) - exact in int32.
+template <bool TRIP>
 __global__ __launch_bounds__(kThreads, 2) void gemm_tiled_kernel(const TiledArgs a) {
     // Three pipeline stages of 24 KiB; the epilogue reuses the first 36 KiB.
     __shared__ __align__(16) unsigned char lds[kStages * kStageBytes];
@@ -195,6 +192,16 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_tiled_kernel(const TiledArgs
         }
     };
 
+    auto shift_acc = [&](int sh) {          // uniform
+        if (sh == 0) return;
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+#pragma unroll
+            for (int j = 0; j < 2; ++j)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) acc[i][j][r] <<= sh;
+    };
+
 #pragma unroll
     for (int p = 0; p < kCopies; ++p) copy_piece(p, 0, stage0);
 #pragma unroll
@@ -228,6 +235,7 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_tiled_kernel(const TiledArgs
             asm volatile("s_waitcnt vmcnt(0)" ::: "memory");                 \
         __syncthreads();                                                     \
         step((KT_), NXT, FILL, XC, BC, XN, BN);                              \
+        if (TRIP && (KT_) < a.n_extra) shift_acc(a.trip_shift[(KT_)]);       \
     }
     for (int kt = 0; kt < KT; kt += 6) {      // stage of step kt is kt % 3, register set kt % 2
         AGQ_STEP(kt, stage1, stage0, xa0, b0, xa1, b1)
@@ -319,7 +327,8 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_tiled_kernel(const TiledArgs
 }  // namespace
 
 int agq_launch_gemm_tiled(const void *x_tiles, int64_t M, int64_t K, int e, int corr, const void *w_packed,
-                          const void *sw, int64_t N, void *y, int64_t ldy, int32_t *acc_out, void *stream) {
+                          const void *sw, int64_t N, void *y, int64_t ldy, int32_t *acc_out, int n_extra,
+                          void *stream) {
     TiledArgs a;
     a.xt = (const agq_u4 *)x_tiles;
     a.M = (int)M;
@@ -336,6 +345,19 @@ int agq_launch_gemm_tiled(const void *x_tiles, int64_t M, int64_t K, int e, int 
     a.scale_e = ldexpf(1.0f, e);
     a.corr = corr;
     a.wsum = agq_blob_wsum(w_packed, N, K);
-    gemm_tiled_kernel<<<(unsigned)(a.tiles_m * a.tiles_n), kThreads, 0, (hipStream_t)stream>>>(a);
+    a.n_extra = 0;
+    a.trip_shift = nullptr;
+    const unsigned grid = (unsigned)(a.tiles_m * a.tiles_n);
+    if (n_extra >= 0) {
+        const AgqTripLayout L = agq_trip_layout(N, K, n_extra);
+        const char *base = (const char *)w_packed;
+        a.KT = (int)L.KTall;
+        a.wsum = (const int32_t *)(base + L.wsum_off);
+        a.n_extra = n_extra;
+        a.trip_shift = (const int32_t *)(base + L.meta_off) + 16;
+        gemm_tiled_kernel<true><<<grid, kThreads, 0, (hipStream_t)stream>>>(a);
+    } else {
+        gemm_tiled_kernel<false><<<grid, kThreads, 0, (hipStream_t)stream>>>(a);
+    }
     return (int)hipGetLastError();
 }

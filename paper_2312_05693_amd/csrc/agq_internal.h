@@ -15,6 +15,35 @@ static inline const int32_t *agq_blob_wsum(const void *packed, int64_t N, int64_
     return (const int32_t *)((const char *)packed + agq_blob_nibble_bytes(N, K));
 }
 
+// ---- TRIP blob (Section 4.4, efficient TRIP matrix multiplication).  The input channels whose
+// factor alpha is > 0 are served by E extra 128-wide chunks placed in front of the K/128 main
+// chunks of every 16-channel tile (their weights are zero in the main chunks): a chunk holds
+// channels of one factor only, chunks are ordered by descending factor.  After the nibbles:
+//   int32 wsum[Npad]      sum_k 2^alpha[k] w[n,k]
+//   int32 meta[32]        meta[c] = factor of extra chunk c; meta[16 + c] = left shift of the
+//                         running accumulator after chunk c (Horner: factor minus the next
+//                         chunk's factor, the main chunks counting as factor 0)
+//   int32 idx[E * 128]    input channel of every slot of the extra chunks, -1 = unused slot
+//   int8  alpha[K]        the factors (read by the packer and by unpack)
+#define AGQ_TRIP_MAX_E 16   // == AGQ_TRIP_MAX_EXTRA of the public header
+struct AgqTripLayout {
+    int64_t KT, KTall, Npad;
+    size_t nibble_bytes, wsum_off, meta_off, idx_off, alpha_off, total;
+};
+static inline AgqTripLayout agq_trip_layout(int64_t N, int64_t K, int E) {
+    AgqTripLayout L;
+    L.KT = agq_k_tiles(K);
+    L.KTall = L.KT + E;
+    L.Npad = agq_n_tiles_padded(N) * 16;
+    L.nibble_bytes = (size_t)agq_n_tiles_padded(N) * (size_t)L.KTall * 1024;
+    L.wsum_off = L.nibble_bytes;
+    L.meta_off = L.wsum_off + (size_t)L.Npad * 4;
+    L.idx_off = L.meta_off + 32 * 4;
+    L.alpha_off = L.idx_off + (size_t)E * 128 * 4;
+    L.total = L.alpha_off + (size_t)((K + 15) / 16) * 16;
+    return L;
+}
+
 // tokens up to which the weight-streaming kernel is used
 #define AGQ_DECODE_MAX_M 16
 
@@ -26,11 +55,21 @@ int agq_launch_prepack_act(const void *x, int x_kind, int bits, int64_t M, int64
 int agq_launch_pack(const int8_t *wq, int64_t N, int64_t K, void *packed, int32_t *bad, void *stream);
 int agq_launch_unpack(const void *packed, int64_t N, int64_t K, int8_t *wq, void *stream);
 struct agq_proj;
+// n_extra >= 0 with a TRIP blob (one projection, fp16 input); -1 for plain blobs
 int agq_launch_gemm_decode(const void *x, int x_kind, int bits, int64_t M, int64_t K, int64_t ldx, int e, int zp,
-                           const struct agq_proj *projs, int count, void *stream);
+                           const struct agq_proj *projs, int count, int n_extra, void *stream);
+// K counts the main chunks only; with a TRIP blob x_tiles and the blob hold n_extra more steps in front
 int agq_launch_gemm_tiled(const void *x_tiles, int64_t M, int64_t K, int e, int corr,
                           const void *w_packed, const void *sw, int64_t N, void *y, int64_t ldy,
-                          int32_t *acc_out, void *stream);
+                          int32_t *acc_out, int n_extra, void *stream);
+int agq_launch_trip_search(const void *x, int64_t M, int64_t K, int64_t ldx, int bits, int e, int zp, int kmax,
+                           int8_t *alpha, void *stream);
+int agq_trip_count_extra(const int8_t *alpha_host, int64_t K);   // number of extra chunks, -1 = bad factors or too many
+int agq_launch_pack_trip(const int8_t *wq, int64_t N, int64_t K, const int8_t *alpha_host, void *packed, int32_t *bad,
+                         void *stream);
+int agq_launch_unpack_trip(const void *packed, int64_t N, int64_t K, int n_extra, int8_t *wq, void *stream);
+int agq_launch_prepack_trip(const void *x, int bits, int64_t M, int64_t K, int64_t ldx, int e, int zp,
+                            const void *packed, int64_t N, int n_extra, void *out, void *stream);
 // Eq.2's unsigned grid (zp > 0) inside the GEMMs: codes travel as q - 2^(b-1) (signed, what the
 // int8 MFMA takes) and sum_k (q - zp) w = sum_k (q - 2^(b-1)) w + corr * sum_k w.
 static inline int agq_zp_corr(int bits, int zp) { return zp ? (1 << (bits - 1)) - zp : 0; }

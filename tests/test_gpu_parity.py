@@ -600,3 +600,171 @@ def test_config4_attention_block_full(agq, oracle):
             want = oracle.gemm_int_c(q[rows], wq, threads=oracle.c_max_threads())
             assert np.array_equal(host(acc)[rows], want)
             assert_f16_close(host(y)[rows], oracle.dequant_out(want, e, sw), name)
+
+
+# ------------------------------------------------------------------ TRIP (Eq.5-8, Section 4.4)
+
+def trip_case(M, K, N, seed, n_out, kmax, bits, oracle):
+    x, wq, sw = make_case(M, K, N, seed, n_out)
+    e = oracle.trip_base_exp(x, bits, kmax)
+    return x, wq, sw, e
+
+
+@pytest.mark.parametrize("M,K,bits,kmax,zp", [(1, 128, 8, 4, 0), (7, 384, 8, 4, 0), (64, 512, 8, 3, 0),
+                                              (300, 1024, 4, 2, 0), (33, 256, 8, 4, 131), (16, 4096, 8, 4, 0)])
+def test_trip_search_matches_oracle(agq, oracle, M, K, bits, kmax, zp):
+    x = synth.make_activation(M, K, max(2, K // 100), seed=31 + M)
+    e = oracle.trip_base_exp(x, bits, kmax)
+    want = oracle.trip_search(x, bits, e, zp, kmax)
+    got = host(agq.trip_search(dev(x), bits, e, kmax, zp=zp))
+    assert got.dtype == np.int8 and np.array_equal(got, want)
+    if zp == 0 and kmax == 4 and M >= 7:
+        assert want.max() == kmax and (want > 0).sum() < K // 4     # the recipe's outlier channels
+
+
+def test_trip_search_strided_infinite_and_empty(agq, oracle):
+    rng = np.random.default_rng(32)
+    big = (rng.standard_normal((40, 200)) * 3).astype(np.float16)
+    big[3, 17] = np.inf
+    big[9, 60] = -np.inf
+    x = big[:, 8:136]                                    # a view: row pitch 200, 128 channels
+    xd = dev(big)[:, 8:136]
+    want = oracle.trip_search(np.ascontiguousarray(x), 8, -5, 0, 4)
+    assert np.array_equal(host(agq.trip_search(xd, 8, -5, 4)), want)
+    assert want[9] == 0 and want[52] == 0                 # the channels holding the infinities
+    empty = torch.empty((0, 128), dtype=torch.float16, device="cuda")
+    assert not host(agq.trip_search(empty, 8, 0, 4)).any()
+
+
+def random_alpha(rng, K, counts):
+    """counts[a-1] channels get factor a (a = 1..4), the rest 0."""
+    alpha = np.zeros(K, dtype=np.int8)
+    pick = rng.choice(K, size=sum(counts), replace=False)
+    pos = 0
+    for a, c in enumerate(counts, start=1):
+        alpha[pick[pos:pos + c]] = a
+        pos += c
+    return alpha
+
+
+def test_trip_pack_roundtrip_and_tables(agq, oracle):
+    rng = np.random.default_rng(33)
+    for N, K, counts in ((16, 128, (0, 0, 0, 0)), (40, 256, (3, 0, 0, 2)), (300, 384, (130, 1, 0, 5)),
+                         (64, 2048, (0, 0, 129, 256))):
+        wq = rng.integers(-8, 8, size=(N, K)).astype(np.int8)
+        alpha = random_alpha(rng, K, counts)
+        E = sum((c + 127) // 128 for c in counts)
+        assert agq.trip_extra_chunks(alpha, K) == E
+        packed, n_extra = agq.pack_w4_trip(dev(wq), alpha)
+        assert n_extra == E and packed.numel() == agq.lib().agq_pack_w4_trip_bytes(N, K, E)
+        assert np.array_equal(host(agq.unpack_w4_trip(packed, N, K, E)), wq)
+        # the weight sums behind the nibbles carry the factors
+        npad = (N + 255) // 256 * 256
+        nib_bytes = npad * (K // 128 + E) * 64
+        wsum = host(packed)[nib_bytes: nib_bytes + 4 * npad].view(np.int32)
+        assert np.array_equal(wsum[:N], (wq.astype(np.int64) << alpha[None, :].astype(np.int64)).sum(axis=1))
+        assert not wsum[N:].any()
+    # invalid factor sets are refused on the host
+    bad = np.zeros(128, dtype=np.int8)
+    bad[3] = 5
+    with pytest.raises(agq.AgqError):
+        agq.trip_extra_chunks(bad, 128)
+    many = np.ones(128 * 17, dtype=np.int8)              # 17 chunks of factor 1
+    with pytest.raises(agq.AgqError):
+        agq.trip_extra_chunks(many, 128 * 17)
+
+
+def run_trip_linear(agq, oracle, x, wq, sw, bits, e, alpha, zp=0):
+    N, K = wq.shape
+    M = x.shape[0]
+    packed, n_extra = agq.pack_w4_trip(dev(wq), alpha)
+    acc = torch.empty((M, N), dtype=torch.int32, device="cuda")
+    y = agq.gemm_trip(dev(x), bits, e, packed, n_extra, dev(sw), N, K, acc_out=acc, zp=zp)
+    want_acc, want_y = oracle.linear_w4_trip(x, bits, e, zp, alpha, wq, sw)
+    assert np.array_equal(host(acc).astype(np.int64), want_acc), (M, K, N, bits, zp)
+    assert_f16_close(host(y), want_y, "trip linear %s" % ((M, K, N, bits, zp),))
+
+
+@pytest.mark.parametrize("bits", [8, 4])
+@pytest.mark.parametrize("M", [1, 3, 4, 7, 8, 13, 16])
+def test_trip_linear_decode(agq, oracle, M, bits):
+    K, N, kmax = 1024, 272, 4 if bits == 8 else 3
+    x, wq, sw, e = trip_case(M, K, N, 40 + M, 10, kmax, bits, oracle)
+    alpha = oracle.trip_search(x, bits, e, 0, kmax)
+    assert (alpha > 0).any()
+    run_trip_linear(agq, oracle, x, wq, sw, bits, e, alpha)
+
+
+@pytest.mark.parametrize("M,K,N", [(2, 128, 16), (16, 11008, 48), (5, 4096, 4096), (16, 8192, 64), (9, 256, 1000)])
+def test_trip_linear_decode_shapes(agq, oracle, M, K, N):
+    rng = np.random.default_rng(41)
+    x, wq, sw, e = trip_case(M, K, N, 50 + M, max(2, K // 100), 4, 8, oracle)
+    # factors of every level, more than one chunk of one of them, unused slots in all
+    alpha = random_alpha(rng, K, (min(130, K // 8), 3, 1, min(20, K // 16)))
+    run_trip_linear(agq, oracle, x, wq, sw, 8, e, alpha)
+
+
+@pytest.mark.parametrize("M,K,N,bits", [(17, 128, 16, 8), (100, 512, 200, 8), (256, 1024, 384, 4), (300, 4096, 130, 8)])
+def test_trip_linear_tiled(agq, oracle, M, K, N, bits):
+    rng = np.random.default_rng(42)
+    kmax = 4 if bits == 8 else 3
+    x, wq, sw, e = trip_case(M, K, N, 60 + M, max(2, K // 100), kmax, bits, oracle)
+    alpha = oracle.trip_search(x, bits, e, 0, kmax)
+    run_trip_linear(agq, oracle, x, wq, sw, bits, e, alpha)
+    # hand-made factors: all levels, a level that fills more than one chunk, skipped levels
+    run_trip_linear(agq, oracle, x, wq, sw, bits, e, random_alpha(rng, K, (K // 8 + 3, 0, 2, 7)))
+    run_trip_linear(agq, oracle, x, wq, sw, bits, e, random_alpha(rng, K, (0, 0, 0, 1)))
+
+
+@pytest.mark.parametrize("M", [4, 16, 200])
+def test_trip_linear_no_factors_equals_plain(agq, oracle, M):
+    """All factors zero: the TRIP layer is the plain layer (no extra chunks)."""
+    K, N = 512, 144
+    x, wq, sw = make_case(M, K, N, 70 + M)
+    e = oracle.calibrate_act_exp(x, 8)
+    alpha = np.zeros(K, dtype=np.int8)
+    run_trip_linear(agq, oracle, x, wq, sw, 8, e, alpha)
+    want_acc, _ = oracle.linear_w4(x, 8, e, 0, wq, sw)
+    got_acc, _ = oracle.linear_w4_trip(x, 8, e, 0, alpha, wq, sw)
+    assert np.array_equal(want_acc, got_acc)
+
+
+@pytest.mark.parametrize("M,bits,zp", [(3, 8, 128), (16, 8, 77), (150, 8, 131), (12, 4, 9), (130, 4, 8)])
+def test_trip_linear_unsigned_grid(agq, oracle, M, bits, zp):
+    rng = np.random.default_rng(43)
+    K, N = 640, 80
+    x, wq, sw, e = trip_case(M, K, N, 80 + M, 6, 3, bits, oracle)
+    run_trip_linear(agq, oracle, x, wq, sw, bits, e, random_alpha(rng, K, (9, 0, 4, 2)), zp=zp)
+
+
+def test_trip_linear_extreme_values(agq, oracle):
+    """Largest accumulators: every code and weight at its bound, sixteen extra chunks of factor 4."""
+    M, K, N = 16, 32768 - 2048, 16
+    x = np.full((M, K), 60000.0, dtype=np.float16)
+    x[1::2] = -60000.0
+    wq = np.full((N, K), -8, dtype=np.int8)
+    wq[1::2] = 7
+    sw = np.full(N, 2.0 ** -20, dtype=np.float16)
+    alpha = np.zeros(K, dtype=np.int8)
+    alpha[:2048] = 4
+    run_trip_linear(agq, oracle, x, wq, sw, 8, 0, alpha)
+
+
+def test_trip_argument_errors(agq):
+    L = agq.lib()
+    x = torch.zeros((4, 128), dtype=torch.float16, device="cuda")
+    y = torch.zeros((4, 16), dtype=torch.float16, device="cuda")
+    sw = torch.ones(16, dtype=torch.float16, device="cuda")
+    blob = torch.zeros(L.agq_pack_w4_trip_bytes(16, 128, 1), dtype=torch.uint8, device="cuda")
+    ok = lambda **kw: L.agq_gemm_w4a8_trip(kw.get("x", x.data_ptr()), 4, kw.get("K", 128), 128, kw.get("e", 0),
+                                            kw.get("zp", 0), blob.data_ptr(), kw.get("n_extra", 1), sw.data_ptr(), 16,
+                                            y.data_ptr(), kw.get("ldy", 16), None, None, 0, None)
+    assert ok() == agq.AGQ_OK
+    assert ok(n_extra=-1) == agq.AGQ_EINVAL and ok(n_extra=17) == agq.AGQ_EINVAL
+    assert ok(K=100) == agq.AGQ_EINVAL and ok(K=65536) == agq.AGQ_EINVAL
+    assert ok(zp=256) == agq.AGQ_EINVAL and ok(e=99) == agq.AGQ_EINVAL and ok(ldy=8) == agq.AGQ_EINVAL
+    assert ok(x=None) == agq.AGQ_EINVAL
+    assert L.agq_trip_search(x.data_ptr(), 4, 128, 128, 8, 0, 0, 5, blob.data_ptr(), None) == agq.AGQ_EINVAL
+    assert L.agq_trip_search(x.data_ptr(), 4, 128, 64, 8, 0, 0, 4, blob.data_ptr(), None) == agq.AGQ_EINVAL
+    assert L.agq_pack_w4_trip_bytes(16, 128, 17) == 0 and L.agq_pack_w4_trip_bytes(16, 100, 0) == 0
+    torch.cuda.synchronize()
