@@ -39,6 +39,7 @@ struct AttnArgs {
     int H, S, D;
     int causal, qmax;
     float out_scale;     // 2^(e_v - qmax)
+    int ncu;             // compute units of the device (ordering of the causal row blocks)
 };
 
 // Two probabilities (packed fp16) -> two weights 2^(qmax - c) as packed fp16 bit
@@ -83,9 +84,20 @@ __global__ __launch_bounds__(256, CB == 1 ? 3 : 1) void log2_attn_kernel(const A
     const int S = a.S, D = a.D, H = a.H, DQ = D >> 2;
     const int nb = (S + kQRows - 1) / kQRows;
 
-    // workgroup -> (head, row block), longest causal blocks first
-    const int h = blockIdx.x % H;
-    const int b = a.causal ? nb - 1 - (int)blockIdx.x / H : (int)blockIdx.x / H;
+    // workgroup -> (head, row block).  Causal: blocks ranked by length, longest first.
+    // All workgroups of a launch are resident at once when there are at most three
+    // per CU, and the dispatcher hands workgroup i and workgroup i + (number of CUs)
+    // to the same CU; every second run of that many workgroups therefore takes its
+    // blocks in ascending order, so that a CU's long first block is paired with a
+    // short second one and the CUs finish together (loads of 19-24 instead of 14-30
+    // units at H = 40, S = 2048).
+    int rank = (int)blockIdx.x;
+    if (a.causal) {
+        const int run = rank / a.ncu, base = run * a.ncu;
+        if (run & 1) rank = base + min(a.ncu, (int)gridDim.x - base) - 1 - (rank - base);
+    }
+    const int h = rank % H;
+    const int b = a.causal ? nb - 1 - rank / H : rank / H;
     const int q0 = b * kQRows;
     const int r0 = q0 + wave * 32;                        // first row of this wavefront
     const int row = r0 + (lane & 31);
@@ -431,6 +443,16 @@ int agq_launch_log2_attn(const void *p, int64_t H, int64_t S, int64_t D, int cau
     a.causal = causal;
     a.qmax = qmax;
     a.out_scale = ldexpf(1.0f, e_v - qmax);
+    // number of compute units of the current device, asked once per device
+    static int ncu_of[64] = {0};
+    int device = 0;
+    if (hipGetDevice(&device) != hipSuccess) return (int)hipGetLastError();
+    int ncu = (device >= 0 && device < 64) ? ncu_of[device] : 0;
+    if (ncu == 0) {
+        if (hipDeviceGetAttribute(&ncu, hipDeviceAttributeMultiprocessorCount, device) != hipSuccess || ncu < 1) ncu = 256;
+        if (device >= 0 && device < 64) ncu_of[device] = ncu;
+    }
+    a.ncu = ncu;
     hipStream_t st = (hipStream_t)stream;
     const unsigned grid = (unsigned)(((S + kQRows - 1) / kQRows) * H);
     if (D <= 128) {
