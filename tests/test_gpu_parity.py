@@ -768,3 +768,36 @@ def test_trip_argument_errors(agq):
     assert L.agq_trip_search(x.data_ptr(), 4, 128, 64, 8, 0, 0, 4, blob.data_ptr(), None) == agq.AGQ_EINVAL
     assert L.agq_pack_w4_trip_bytes(16, 128, 17) == 0 and L.agq_pack_w4_trip_bytes(16, 100, 0) == 0
     torch.cuda.synchronize()
+
+
+@pytest.mark.parametrize("K,N", [(4096, 4096), (4096, 11008), (11008, 4096)])
+def test_trip_llama7b_full_size_sampled(agq, oracle, K, N):
+    """The benchmark's TRIP configuration: factors from Eq.8 on the 2048-token activation
+    with 1 % outlier channels (searched on the GPU, compared with the oracle on sampled
+    channels and used from the GPU), the M = 2048 GEMM and the decode launches on its first
+    rows; the oracle computes whole sampled rows with the folded weights."""
+    M, bits, kmax = 2048, 8, 4
+    x, wq, sw = make_case(M, K, N, seed=2, n_out=synth.n_outlier_channels(K))
+    e = oracle.trip_base_exp(x, bits, kmax)
+    xd = dev(x)
+    alpha = host(agq.trip_search(xd, bits, e, kmax))
+    cols = sorted(set(list(range(0, K, 97)) + np.flatnonzero(alpha > 0).tolist()))
+    assert np.array_equal(alpha[cols], oracle.trip_search(x[:, cols], bits, e, 0, kmax))
+    assert 0 < (alpha > 0).sum() <= 3 * synth.n_outlier_channels(K)
+    packed, n_extra = agq.pack_w4_trip(dev(wq), alpha)
+    folded = (wq.astype(np.int16) << alpha[None, :].astype(np.int16))          # |w 2^alpha| <= 128
+    swd = dev(sw)
+
+    def check(Mrun, rows):
+        acc = torch.empty((Mrun, N), dtype=torch.int32, device="cuda")
+        y = agq.gemm_trip(xd[:Mrun], bits, e, packed, n_extra, swd, N, K, acc_out=acc)
+        acc_h, y_h = host(acc), host(y)
+        q = oracle.trip_quantize(x[rows], bits, e, 0, alpha).astype(np.int64)
+        want = q @ folded.T.astype(np.int64)
+        assert np.array_equal(want, oracle.gemm_int_trip(q, 0, wq, alpha))
+        assert np.array_equal(acc_h[rows].astype(np.int64), want)
+        assert_f16_close(y_h[rows], oracle.dequant_out(want, e, sw), "trip y")
+
+    check(M, [0, 1, 31, 32, 127, 128, 1023, 1024, 2047] + list(range(600, 612)))
+    for Mrun in (1, 4, 16):
+        check(Mrun, list(range(Mrun)))
