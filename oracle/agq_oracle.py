@@ -359,6 +359,83 @@ def log2_codes_packed(p, qmax: int, causal: bool = True) -> np.ndarray:
 
 
 # --------------------------------------------------------------------------
+# attention from quantized Q and K: integer QK^T, softmax, Eq.3, times V
+# --------------------------------------------------------------------------
+
+def qk_scores(qq, kq) -> np.ndarray:
+    """Section 4.2 lists QK among the quantized matrix products: s[h,i,j] =
+    sum_d qq[h,i,d] * kq[h,j,d] on the integer codes of Eq.2 (int8 [H,S,D] each).
+    int64, asserted to fit int32."""
+    qq = np.asarray(qq, dtype=np.int64)
+    kq = np.asarray(kq, dtype=np.int64)
+    if qq.shape != kq.shape or qq.ndim != 3:
+        raise ValueError("qq and kq are [H, S, D]")
+    s = np.einsum("hid,hjd->hij", qq, kq)
+    if s.size and max(int(s.max()), -int(s.min())) > INT32_MAX:
+        raise OverflowError("score leaves int32")
+    return s
+
+
+def qk_log2_codes(qq, kq, e_q: int, e_k: int, qmax: int, causal: bool = True):
+    """Softmax of the dequantized scores followed by Eq.3, without ever rounding
+    the probabilities to fp16 (non-linear operators stay in floating point,
+    Section 3.3; Eq.3 is used for the softmax output, Section 5.1):
+        z[h,i,j] = s[h,i,j] * 2^(e_q + e_k) / sqrt(D)
+        p        = softmax_j z        (over j <= i when causal)
+        c        = CLIP(round(-log2 p), 0, qmax)
+    computed in float64 as t = -log2 p = log2(sum_j 2^(z_j log2 e)) - z log2 e with
+    the row maximum taken out.  Returns (c int32 [H,S,S], margin float64 [H,S,S]):
+    margin is the distance of t from the nearest rounding boundary that can
+    change the code (half-integers below qmax); an implementation that evaluates
+    t in lower precision may differ from c only where margin is below its error.
+    Masked entries (j > i, causal) carry code qmax and margin +Inf."""
+    s = qk_scores(qq, kq).astype(np.float64)
+    H, S, _ = s.shape
+    D = np.asarray(qq).shape[2]
+    z2 = s * (2.0 ** (int(e_q) + int(e_k)) / np.sqrt(float(D)) * np.log2(np.e))   # logits in base-2 units
+    if causal:
+        z2 = np.where(np.tril(np.ones((S, S), dtype=bool))[None], z2, -np.inf)
+    m = z2.max(axis=2, keepdims=True)
+    L = m + np.log2(np.exp2(z2 - m).sum(axis=2, keepdims=True))
+    with np.errstate(invalid="ignore"):
+        t = L - z2                                               # -log2 p >= 0; +Inf where masked
+    c = np.clip(np.rint(t), 0.0, float(qmax))
+    # boundaries that matter: k + 0.5 for k = 0 .. qmax-1
+    with np.errstate(invalid="ignore"):
+        frac = np.abs(t - np.floor(t) - 0.5)
+        margin = np.where(t < qmax, frac, t - (qmax - 0.5))
+    margin = np.where(np.isfinite(t), margin, np.inf)
+    return c.astype(np.int32), margin
+
+
+def attn_v_from_codes(codes, vq, e_v: int, qmax: int, causal: bool = True):
+    """The product of Eq.3's weights with the value matrix, from given codes:
+    A[h,i,d] = sum_j 2^(qmax - c[h,i,j]) * vq[h,j,d] (j <= i when causal),
+    O[i, h*D+d] = fp16(A * 2^(e_v - qmax)).  Same arithmetic as `attn_v_log2`."""
+    codes = np.asarray(codes, dtype=np.int64)
+    vq = np.asarray(vq)
+    H, S, _ = codes.shape
+    D = vq.shape[2]
+    wgt = np.ldexp(1.0, (int(qmax) - codes).astype(np.int64))
+    if causal:
+        wgt = np.where(np.tril(np.ones((S, S), dtype=bool))[None], wgt, 0.0)
+    A = np.einsum("hij,hjd->hid", wgt, vq.astype(np.float64))     # exact: integers below 2^53
+    if A.size and float(np.abs(A).max()) > INT32_MAX:
+        raise OverflowError("accumulator leaves int32")
+    O = np.ldexp(A, int(e_v) - int(qmax))
+    with np.errstate(over="ignore"):
+        O = O.astype(np.float16)
+    return A.astype(np.int64), np.ascontiguousarray(O.transpose(1, 0, 2).reshape(S, H * D))
+
+
+def start_token_score_codes(codes, qmax: int) -> np.ndarray:
+    """Token importance on the quantized attention map (Section 4.3: attention to
+    the first token): score[i] = sum_h 2^(qmax - c[h,i,0]), an exact integer."""
+    c0 = np.asarray(codes, dtype=np.int64)[:, :, 0]
+    return (np.int64(1) << (int(qmax) - c0)).sum(axis=0)
+
+
+# --------------------------------------------------------------------------
 # token importance and pruning (Section 4.3, Eq.4; Section 5.2, Eq.9)
 # --------------------------------------------------------------------------
 

@@ -583,3 +583,106 @@ def test_trip_linear_approximates_the_real_product(oracle):
     err_trip = np.abs(y_trip.astype(np.float64) - ref).mean()
     assert err_trip < 0.5 * err_plain
     assert 0 < (alpha > 0).sum() < 64                         # the outlier channels and few others
+
+
+# ---------------------------------------------------------------- attention from quantized Q and K
+
+def test_qk_scores_bruteforce(oracle):
+    rng = np.random.default_rng(31)
+    H, S, D = 2, 5, 12
+    q = rng.integers(-128, 128, size=(H, S, D)).astype(np.int8)
+    k = rng.integers(-128, 128, size=(H, S, D)).astype(np.int8)
+    want = [[[sum(int(q[h, i, d]) * int(k[h, j, d]) for d in range(D)) for j in range(S)] for i in range(S)] for h in range(H)]
+    assert oracle.qk_scores(q, k).tolist() == want
+    # one-hot keys pick query components (catches a transposed operand)
+    eye = np.zeros((1, 4, 12), dtype=np.int8)
+    eye[0, np.arange(4), [3, 0, 7, 11]] = 1
+    assert np.array_equal(oracle.qk_scores(q[:1, :4], eye)[0], q[0, :4][:, [3, 0, 7, 11]].astype(np.int64))
+
+
+def test_qk_log2_codes_closed_forms(oracle):
+    H, S, D, qmax = 1, 40, 16, 15
+    # equal scores: p = 1/n over the n allowed keys, code = round(log2 n) (n = i + 1 when causal)
+    q = np.zeros((H, S, D), dtype=np.int8)
+    k = np.ones((H, S, D), dtype=np.int8)
+    c, margin = oracle.qk_log2_codes(q, k, 0, 0, qmax, causal=True)
+    for i in range(S):
+        want = min(int(np.rint(np.log2(i + 1))), qmax)
+        assert (c[0, i, : i + 1] == want).all() and (c[0, i, i + 1:] == qmax).all()
+        assert np.isinf(margin[0, i, i + 1:]).all()
+    c, _ = oracle.qk_log2_codes(q, k, 0, 0, qmax, causal=False)
+    assert (c == int(np.rint(np.log2(S)))).all()
+    # one key far ahead of the rest: its code is 0, the others' the clipped distance in bits
+    q = np.full((H, S, D), 8, dtype=np.int8)
+    k = np.zeros((H, S, D), dtype=np.int8)
+    k[0, 3] = 8                                            # s = 8 * 8 * 16 = 1024 for key 3, 0 elsewhere
+    e = -2                                                 # z = 1024 * 2^-4 / 4 = 16 nats = 23.08 bits
+    c, margin = oracle.qk_log2_codes(q, k, e, e, qmax, causal=False)
+    assert (c[0, :, 3] == 0).all() and (np.delete(c[0], 3, axis=1) == qmax).all()
+    c, _ = oracle.qk_log2_codes(q, k, e - 1, e, 31, causal=False)   # half the logit: 11.54 bits
+    assert (c[0, :, 3] == 0).all() and (np.delete(c[0], 3, axis=1) == 12).all()
+
+
+def test_qk_log2_codes_against_library_and_rationals(oracle):
+    from scipy.special import log_softmax
+    rng = np.random.default_rng(32)
+    H, S, D, qmax = 3, 24, 32, 15
+    q = rng.integers(-40, 40, size=(H, S, D)).astype(np.int8)
+    k = rng.integers(-40, 40, size=(H, S, D)).astype(np.int8)
+    e_q, e_k = -3, -4
+    for causal in (True, False):
+        c, margin = oracle.qk_log2_codes(q, k, e_q, e_k, qmax, causal)
+        z = oracle.qk_scores(q, k).astype(np.float64) * 2.0 ** (e_q + e_k) / np.sqrt(D)
+        if causal:
+            z = np.where(np.tril(np.ones((S, S), dtype=bool))[None], z, -np.inf)
+        t = -log_softmax(z, axis=2) / np.log(2.0)           # library route to -log2 p
+        want = np.clip(np.rint(t), 0, qmax)
+        sure = margin > 1e-9
+        assert np.array_equal(c[sure], want[sure].astype(np.int32)) and sure.mean() > 0.999
+        # margin is what it says: moving t by less than the margin never changes the code
+        fin = np.isfinite(t) & (margin < np.inf)
+        for sign in (-1.0, 1.0):
+            moved = np.clip(np.rint(t[fin] + sign * 0.999 * margin[fin]), 0, qmax)
+            assert np.array_equal(moved, c[fin])
+        # softmax is invariant to a per-row shift of the scores: add a constant vector to every key
+        # of a head whose query components sum to zero -> s changes by 0; instead check scaling:
+        # doubling e_q + e_k by two steps equals quadrupling the scores
+        c2, _ = oracle.qk_log2_codes((q.astype(np.int16) * 2).clip(-128, 127).astype(np.int8), (k.astype(np.int16) * 2).astype(np.int8),
+                                     e_q - 1, e_k - 1, qmax, causal)
+        assert np.array_equal(c2, c)
+    # exact rational check of one row: p_j = 2^(a_j) / sum with integer bit-logits
+    qq = np.zeros((1, 4, 16), dtype=np.int8)
+    kk = np.zeros((1, 4, 16), dtype=np.int8)
+    qq[0, :, 0] = 1
+    kk[0, :, 0] = [0, 1, 2, 3]
+    # choose scale so that z log2 e is an integer number of bits: impossible exactly; so compare via fractions of exp
+    c, _ = oracle.qk_log2_codes(qq, kk, 2, 0, 15, causal=False)    # z = s * 4 / 4 = s nats
+    from math import e as E, log2
+    denom = sum(E ** s for s in range(4))
+    assert c[0, 0].tolist() == [min(int(np.rint(-log2(E ** s / denom))), 15) for s in range(4)]
+
+
+def test_attn_v_from_codes(oracle):
+    rng = np.random.default_rng(33)
+    H, S, D, qmax = 2, 9, 8, 15
+    codes = rng.integers(0, qmax + 1, size=(H, S, S))
+    v = rng.integers(-128, 128, size=(H, S, D)).astype(np.int8)
+    for causal in (True, False):
+        A, O = oracle.attn_v_from_codes(codes, v, -4, qmax, causal)
+        for h in range(H):
+            for i in range(S):
+                js = range(i + 1) if causal else range(S)
+                for d in range(D):
+                    want = sum((1 << (qmax - int(codes[h, i, j]))) * int(v[h, j, d]) for j in js)
+                    assert int(A[h, i, d]) == want
+                    assert O[i, h * D + d] == np.float16(want * 2.0 ** (-4 - qmax))
+    # consistent with the fp16-probability path when the codes are the same
+    p = synth.make_attention(2, 16, 8, seed=5)[0]
+    c = oracle.log2_quant(p, qmax)
+    vq = rng.integers(-128, 128, size=(2, 16, 8)).astype(np.int8)
+    A1, O1 = oracle.attn_v_log2(p, vq, -3, qmax, causal=True)
+    A2, O2 = oracle.attn_v_from_codes(c, vq, -3, qmax, causal=True)
+    assert np.array_equal(A1, A2) and np.array_equal(O1.view(np.uint16), O2.view(np.uint16))
+    # importance on the quantized map
+    sc = oracle.start_token_score_codes(codes, qmax)
+    assert sc.tolist() == [sum(1 << (qmax - int(codes[h, i, 0])) for h in range(H)) for i in range(S)]
