@@ -221,6 +221,32 @@ int agq_log2_quant_softmax(const void *p_f16, int64_t H, int64_t S, int64_t D,
                            void *o_f16, void *codes_out, int32_t *score_out,
                            void *stream);
 
+/* Attention from quantized Q and K in one call: the integer product Q K^T
+ * (Section 4.2 lists QK among the quantized products), softmax in floating point
+ * (Section 3.3), Eq.3 on the probabilities, the product with the int8 value
+ * matrix, and the token importance of Section 4.3 read on the quantized map.
+ * The probabilities are never written to memory.
+ *   s[h,i,j]  = sum_d q_q[h,i,d] * k_q[h,j,d]                    (int32, exact)
+ *   p[h,i,:]  = softmax_j( s * 2^(e_q+e_k) / sqrt(D) )           (j <= i if causal)
+ *   c[h,i,j]  = CLIP(round(-log2 p[h,i,j]), 0, qmax)
+ *   o[i,h*D+d]= fp16( 2^(e_v-qmax) * sum_j 2^(qmax-c[h,i,j]) * v_q[h,j,d] )
+ *   score[i] += sum_h 2^(qmax - c[h,i,0])
+ * -log2 p is evaluated in fp32 as log2(sum_j 2^(kappa s_j)) - kappa s with the
+ * hardware's exp2 / log2: a code may differ from an exact evaluation where
+ * -log2 p lies within about 1e-5 of a rounding boundary; o and score follow
+ * exactly from the codes.
+ * q_q, k_q, v_q : int8 [H,S,D] on the signed grid of Eq.2 with scales 2^e_q,
+ *           2^e_k, 2^e_v.  D = 64 or 128; S % 128 == 0, S <= 32768.
+ * qmax    : 15 or 7.   o_f16: fp16 [S, H*D].
+ * codes_out : optional [H,S,S/2] bytes as for agq_log2_quant_softmax.
+ * score_out : optional int32 [S], ACCUMULATED with atomic adds: the caller
+ *           zeroes it before the call.
+ * All pointers 16-byte aligned.                                               */
+int agq_qk_log2_softmax(const int8_t *q_q, const int8_t *k_q, int64_t H, int64_t S,
+                        int64_t D, int causal, int qmax, int e_q, int e_k,
+                        const int8_t *v_q, int e_v, void *o_f16, void *codes_out,
+                        int32_t *score_out, void *stream);
+
 /* Token pruning, Section 4.3 Eq.4: keep the n_keep tokens with the largest
  * score (equal scores: lower index first), in their original order.
  * score  : int32 [S], S <= 8192.   x_f16: fp16 [S,d] contiguous, d % 8 == 0.

@@ -41,6 +41,7 @@ SIGNATURES = {
     "agq_gemm_w4a8_trip": (_int, _TRIP_GEMM_ARGS),
     "agq_gemm_w4a4_trip": (_int, _TRIP_GEMM_ARGS),
     "agq_log2_quant_softmax": (_int, [_vp, _i64, _i64, _i64, _int, _int, _vp, _int, _vp, _vp, _vp, _vp]),
+    "agq_qk_log2_softmax": (_int, [_vp, _vp, _i64, _i64, _i64, _int, _int, _int, _int, _vp, _int, _vp, _vp, _vp, _vp]),
     "agq_prune_tokens": (_int, [_vp, _i64, _i64, _vp, _i64, _vp, _vp, _vp]),
 }
 
@@ -259,6 +260,18 @@ def log2_quant_softmax(p, v_q, e_v, qmax=15, causal=True, want_codes=False, want
     score = torch.empty(S, dtype=torch.int32, device=p.device) if want_score else None
     _ok(lib().agq_log2_quant_softmax(_ptr(p), H, S, D, int(causal), qmax, _ptr(v_q), e_v, _ptr(o), _ptr(codes),
                                      _ptr(score), _stream()), "agq_log2_quant_softmax")
+    return o, codes, score
+
+
+def qk_log2_softmax(qq, kq, vq, e_q, e_k, e_v, qmax=15, causal=True, want_codes=False, want_score=True):
+    """Attention from quantized Q, K, V (int8 [H,S,D]).  Returns (o, codes or None, score or None);
+    the score buffer is zeroed here because the call accumulates into it."""
+    H, S, D = qq.shape
+    o = torch.empty((S, H * D), dtype=torch.float16, device=qq.device)
+    codes = torch.empty((H, S, S // 2), dtype=torch.uint8, device=qq.device) if want_codes else None
+    score = torch.zeros(S, dtype=torch.int32, device=qq.device) if want_score else None
+    _ok(lib().agq_qk_log2_softmax(_ptr(qq), _ptr(kq), H, S, D, int(causal), qmax, e_q, e_k, _ptr(vq), e_v, _ptr(o),
+                                  _ptr(codes), _ptr(score), _stream()), "agq_qk_log2_softmax")
     return o, codes, score
 
 

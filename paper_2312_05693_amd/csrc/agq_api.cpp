@@ -243,6 +243,18 @@ int agq_log2_quant_softmax(const void *p_f16, int64_t H, int64_t S, int64_t D, i
                                            stream));
 }
 
+int agq_qk_log2_softmax(const int8_t *q_q, const int8_t *k_q, int64_t H, int64_t S, int64_t D, int causal, int qmax,
+                        int e_q, int e_k, const int8_t *v_q, int e_v, void *o_f16, void *codes_out, int32_t *score_out,
+                        void *stream) {
+    if (H < 1 || H > 65535 || S < 128 || S > kMaxAttnS || (S % 128) != 0 || (D != 64 && D != 128)) return AGQ_EINVAL;
+    if (qmax != 15 && qmax != 7) return AGQ_EINVAL;
+    if (!e_ok(e_q) || !e_ok(e_k) || !e_ok(e_v) || !q_q || !k_q || !v_q || !o_f16) return AGQ_EINVAL;
+    if (!aligned16(q_q) || !aligned16(k_q) || !aligned16(v_q) || !aligned16(o_f16)) return AGQ_EINVAL;
+    if (codes_out && !aligned16(codes_out)) return AGQ_EINVAL;
+    return hip_status(agq_launch_qk_log2_attn(q_q, k_q, v_q, H, S, D, causal != 0, qmax, e_q, e_k, e_v, o_f16, codes_out,
+                                              score_out, stream));
+}
+
 int agq_prune_tokens(const int32_t *score, int64_t S, int64_t n_keep, const void *x_f16, int64_t d,
                      int32_t *idx_out, void *x_out_f16, void *stream) {
     if (S < 1 || S > 8192 || n_keep < 0 || n_keep > S || d < 8 || d > kMaxDim || (d % 8) != 0) return AGQ_EINVAL;

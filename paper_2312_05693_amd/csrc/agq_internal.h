@@ -75,5 +75,7 @@ int agq_launch_prepack_trip(const void *x, int bits, int64_t M, int64_t K, int64
 static inline int agq_zp_corr(int bits, int zp) { return zp ? (1 << (bits - 1)) - zp : 0; }
 int agq_launch_log2_attn(const void *p, int64_t H, int64_t S, int64_t D, int causal, int qmax,
                          const int8_t *vq, int e_v, void *o, void *codes, int32_t *score, void *stream);
+int agq_launch_qk_log2_attn(const int8_t *q, const int8_t *k, const int8_t *v, int64_t H, int64_t S, int64_t D, int causal,
+                            int qmax, int e_q, int e_k, int e_v, void *o, void *codes, int32_t *score, void *stream);
 int agq_launch_prune(const int32_t *score, int64_t S, int64_t n_keep, const void *x, int64_t d,
                      int32_t *idx, void *x_out, void *stream);

@@ -78,6 +78,21 @@ def make_attention(H: int, S: int, D: int, seed: int):
     return p, v
 
 
+def make_qkv_int8(H: int, S: int, D: int, seed: int):
+    """int8 codes of Q, K, V [H,S,D] for the attention-from-Q-and-K path: unit normals in
+    steps of 1/32 (|x| < 4), with a direction shared by every query and the first key so
+    that most tokens attend to the start token (Section 4.3)."""
+    rng = np.random.default_rng([seed, 0x9B1])
+    q = rng.standard_normal((H, S, D))
+    k = rng.standard_normal((H, S, D))
+    u = rng.standard_normal((H, 1, D)) / np.sqrt(D)
+    q += u * (4.0 + rng.standard_normal((H, S, 1)))
+    k[:, :1] += 8.0 * u
+    v = rng.standard_normal((H, S, D))
+    to8 = lambda t: np.clip(np.rint(t * 32.0), -127, 127).astype(np.int8)
+    return to8(q), to8(k), to8(v)
+
+
 def n_outlier_channels(K: int, frac: float = 0.01) -> int:
     """About 1 % outlier channels, rounded up (prefill configurations)."""
     return int(np.ceil(frac * K))

@@ -801,3 +801,64 @@ def test_trip_llama7b_full_size_sampled(agq, oracle, K, N):
     check(M, [0, 1, 31, 32, 127, 128, 1023, 1024, 2047] + list(range(600, 612)))
     for Mrun in (1, 4, 16):
         check(Mrun, list(range(Mrun)))
+
+
+# ------------------------------------------------------------------ attention from quantized Q and K
+
+CODE_MARGIN = 1e-3      # the kernel evaluates -log2 p in fp32: codes are compared where the oracle's
+                        # distance from a rounding boundary exceeds this (its error is ~1e-5)
+
+
+def unpack_codes(codes_bytes, S):
+    b = np.asarray(codes_bytes)
+    out = np.empty(b.shape[:-1] + (S,), dtype=np.int32)
+    out[..., 0::2] = b & 0xF
+    out[..., 1::2] = b >> 4
+    return out
+
+
+def run_qk_attention(agq, oracle, H, S, D, qmax, causal, seed, e_q=-5, e_k=-5, e_v=-4):
+    qq, kq, vq = synth.make_qkv_int8(H, S, D, seed)
+    o, codes, score = agq.qk_log2_softmax(dev(qq), dev(kq), dev(vq), e_q, e_k, e_v, qmax=qmax, causal=causal,
+                                          want_codes=True, want_score=True)
+    got_c = unpack_codes(host(codes), S)
+    want_c, margin = oracle.qk_log2_codes(qq, kq, e_q, e_k, qmax, causal)
+    sure = margin > CODE_MARGIN
+    assert np.array_equal(got_c[sure], want_c[sure]), "codes differ away from every rounding boundary"
+    # near a boundary either neighbour is valid; everywhere the code stays on the grid
+    assert np.abs(got_c - want_c).max() <= 1 and got_c.min() >= 0 and got_c.max() <= qmax
+    assert sure.mean() > 0.99
+    if causal:
+        assert (got_c[:, np.triu_indices(S, 1)[0], np.triu_indices(S, 1)[1]] == qmax).all()
+    # everything behind the codes is exact: output and importance follow from the kernel's own codes
+    _, want_o = oracle.attn_v_from_codes(got_c, vq, e_v, qmax, causal)
+    assert np.array_equal(host(o).view(np.uint16), want_o.view(np.uint16))
+    assert np.array_equal(host(score).astype(np.int64), oracle.start_token_score_codes(got_c, qmax))
+    # and with its own codes the oracle gets the same output wherever no code was in doubt
+    _, oracle_o = oracle.attn_v_from_codes(want_c, vq, e_v, qmax, causal)
+    rows_sure = sure.all(axis=2)                              # [H, S]
+    for h in range(H):
+        r = np.flatnonzero(rows_sure[h])
+        assert np.array_equal(host(o)[r, h * D:(h + 1) * D].view(np.uint16), oracle_o[r, h * D:(h + 1) * D].view(np.uint16))
+    return float(sure.mean())
+
+
+@pytest.mark.parametrize("H,S,D,qmax,causal", [(1, 128, 128, 15, True), (2, 256, 64, 15, True), (3, 384, 128, 7, True),
+                                               (2, 256, 128, 15, False), (1, 512, 64, 7, False), (5, 640, 128, 15, True)])
+def test_qk_attention_small(agq, oracle, H, S, D, qmax, causal):
+    run_qk_attention(agq, oracle, H, S, D, qmax, causal, seed=90 + S)
+
+
+def test_qk_attention_scale_and_argument_errors(agq, oracle):
+    # sharper and flatter softmax through the exponents
+    run_qk_attention(agq, oracle, 2, 256, 128, 15, True, seed=97, e_q=-3, e_k=-4)
+    run_qk_attention(agq, oracle, 2, 256, 128, 15, True, seed=98, e_q=-8, e_k=-8)
+    L = agq.lib()
+    t = torch.zeros(128 * 128, dtype=torch.int8, device="cuda")
+    o = torch.zeros(128 * 128, dtype=torch.float16, device="cuda")
+    call = lambda **kw: L.agq_qk_log2_softmax(t.data_ptr(), t.data_ptr(), 1, kw.get("S", 128), kw.get("D", 128), 1,
+                                               kw.get("qmax", 15), 0, 0, t.data_ptr(), 0, o.data_ptr(), None, None, None)
+    assert call() == agq.AGQ_OK
+    assert call(S=100) == agq.AGQ_EINVAL and call(S=64) == agq.AGQ_EINVAL and call(D=96) == agq.AGQ_EINVAL
+    assert call(qmax=8) == agq.AGQ_EINVAL
+    torch.cuda.synchronize()
