@@ -28,6 +28,8 @@
 
 #include <math.h>
 
+#include <type_traits>
+
 typedef _Float16 agq_v8h __attribute__((ext_vector_type(8)));
 typedef _Float16 agq_v2h __attribute__((ext_vector_type(2)));
 typedef float agq_v16f __attribute__((ext_vector_type(16)));
@@ -54,10 +56,10 @@ struct QkArgs {
 
 // DT = D / 32: int8 MFMA steps per score tile and 32-channel blocks of the output
 template <int DT, bool CODES>
-__global__ __launch_bounds__(256, 2) void qk_log2_attn_kernel(const QkArgs a) {
+__global__ __launch_bounds__(256, 3) void qk_log2_attn_kernel(const QkArgs a) {
     constexpr int D = DT * 32, DQ = D / 4;
     constexpr int kKRow = D + 16;                                // bytes per key row of the K tile (padded)
-    __shared__ __align__(16) uint8_t kt[2][kKeys * kKRow];
+    __shared__ __align__(16) uint8_t kt[kKeys * kKRow];          // one K tile: three workgroups fit a CU
     __shared__ __align__(16) uint8_t vt[2][D * kVRow];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int S = a.S, H = a.H;
@@ -148,43 +150,60 @@ __global__ __launch_bounds__(256, 2) void qk_log2_attn_kernel(const QkArgs a) {
         return acc;
     };
 
-    // ---- pass 1: L = log2 sum_j 2^(kappa s_j) per row, running maximum taken out
-    float run_m = -1.0e30f, run_s = 0.f;
+    // ---- pass 1: per row the maximum score M (an integer) and sum_j 2^(kappa (s_j - M)).
+    // Differences of scores are exact integers, so the only roundings are the product
+    // with kappa and the exponential.
+    constexpr int kMasked = -(1 << 30);                          // stands for -infinity (|s| < 2^23)
+    int run_m = kMasked;
+    float run_s = 0.f;
+    auto stats = [&](agq_v16i acc, int kb, auto masked_tag) {
+        constexpr bool MASKED = decltype(masked_tag)::value;
+        if (MASKED) {                                            // diagonal sub-tile: keys past the query do not count
+#pragma unroll
+            for (int r = 0; r < 16; ++r)
+                if (kb + 8 * (r >> 2) + 4 * g + (r & 3) > row) acc[r] = kMasked;
+        }
+        int mx = acc[0];
+#pragma unroll
+        for (int r = 1; r < 16; ++r) mx = max(mx, acc[r]);
+        const int nm = max(run_m, mx);
+        float add = 0.f;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const float term = __builtin_amdgcn_exp2f(a.kappa * (float)(acc[r] - nm));
+            add += (MASKED && acc[r] == kMasked) ? 0.f : term;
+        }
+        // nothing counted so far (run_m == kMasked) means run_s == 0: the factor does not matter
+        run_s = run_s * __builtin_amdgcn_exp2f(a.kappa * (float)(run_m - nm)) + add;
+        run_m = nm;
+    };
     load_k(0);
     for (int t = 0; t < nt; ++t) {
-        uint8_t *kbuf = kt[t & 1];
-        store_k(kbuf);
+        if (t > 0) __syncthreads();                              // everyone is done with the previous K tile
+        store_k(kt);
         if (t + 1 < nt) load_k(t + 1);
         __syncthreads();
         const int k0 = t * kKeys;
-        if (k0 > wave_last) continue;                            // wave-uniform; the barrier above was joined
+        if (k0 > wave_last) continue;                            // wave-uniform; the barriers above were joined
 #pragma unroll
         for (int sub = 0; sub < 2; ++sub) {
             const int kb = k0 + 32 * sub;
             if (kb > wave_last) continue;
-            const agq_v16i acc = scores(kbuf, sub);
-            const bool masked = kb + 31 > wave_lim;
-            float z[16];
-            float mx = -1.0e30f;
-#pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int key = kb + 8 * (r >> 2) + 4 * g + (r & 3);
-                z[r] = (masked && key > row) ? -1.0e30f : a.kappa * (float)acc[r];
-                mx = fmaxf(mx, z[r]);
-            }
-            const float nm = fmaxf(run_m, mx);
-            float add = 0.f;
-#pragma unroll
-            for (int r = 0; r < 16; ++r) add += z[r] > -1.0e29f ? __builtin_amdgcn_exp2f(z[r] - nm) : 0.f;
-            run_s = run_s * __builtin_amdgcn_exp2f(run_m - nm) + add;
-            run_m = nm;
+            const agq_v16i acc = scores(kt, sub);
+            if (kb + 31 > wave_lim) stats(acc, kb, std::true_type{});
+            else stats(acc, kb, std::false_type{});
         }
     }
-    // the two lanes of a query (k-groups 0 and 1) join their halves
-    const float om = __shfl_xor(run_m, 32), os = __shfl_xor(run_s, 32);
-    const float M = fmaxf(run_m, om);
-    const float tot = run_s * __builtin_amdgcn_exp2f(run_m - M) + os * __builtin_amdgcn_exp2f(om - M);
-    const float L = M + __builtin_amdgcn_logf(tot);             // v_log_f32: base 2
+    // the two lanes of a query (k-groups 0 and 1) join their halves; every row has its own key, so M is a real score
+    const int om = __shfl_xor(run_m, 32);
+    const float os = __shfl_xor(run_s, 32);
+    const int M = max(run_m, om);
+    // (a half with nothing counted has sum 0, whatever its factor)
+    const float tot = run_s * __builtin_amdgcn_exp2f(a.kappa * (float)(run_m - M)) +
+                      os * __builtin_amdgcn_exp2f(a.kappa * (float)(om - M));
+    // -log2 p = kappa (M - s) + log2(tot); the code is that plus one half, truncated (ties go up:
+    // a tie has measure zero and lies inside the evaluation error anyway)
+    const float lsum05 = __builtin_amdgcn_logf(tot) + 0.5f;      // v_log_f32: base 2
 
     // ---- pass 2: codes, weights, product with V
     // four accumulators: block n holds the channels 4 c + n (c = column l & 31 < D / 4)
@@ -194,15 +213,57 @@ __global__ __launch_bounds__(256, 2) void qk_log2_attn_kernel(const QkArgs a) {
 #pragma unroll
         for (int r = 0; r < 16; ++r) acc_o[n][r] = 0.f;
     const int bslot = min(lane & 31, DQ - 1);
+    const uint32_t qmaxu = (uint32_t)a.qmax;
     const float qmaxf = (float)a.qmax;
-    const int wtop = 15 + a.qmax;                                // exponent field of the weight of code 0
+    const uint32_t wtop = 15u + qmaxu;                           // exponent field of the weight of code 0
 
-    __syncthreads();                                             // pass 1 is done with the K buffers
+    auto weights = [&](const agq_v16i &acc, int kb, const uint8_t *vbuf, int sub, auto masked_tag) {
+        constexpr bool MASKED = decltype(masked_tag)::value;
+        uint32_t ex[16];                                         // exponent fields of the weights (0 = weight 0)
+        uint32_t cw[4] = {0, 0, 0, 0};                           // codes of keys 8 q + 4 g + r, r = 0..3, as nibbles
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const float tt = fmaf(a.kappa, (float)(M - acc[r]), lsum05);
+            uint32_t code = (uint32_t)__builtin_amdgcn_fmed3f(tt, 0.f, qmaxf);   // truncation of [0, qmax]
+            uint32_t e = wtop - code;
+            if (MASKED && kb + 8 * (r >> 2) + 4 * g + (r & 3) > row) {
+                e = 0;
+                code = qmaxu;
+            }
+            ex[r] = e;
+            if (CODES) cw[r >> 2] |= code << (4 * (r & 3));
+            // importance on the quantized map: the weight of the first key (always live)
+            if (r == 0 && a.score && kb == 0 && g == 0) atomicAdd(&a.score[row], 1 << (a.qmax - (int)code));
+        }
+        if (CODES) {
+#pragma unroll
+            for (int q = 0; q < 4; ++q)
+                *reinterpret_cast<uint16_t *>(a.codes + ((int64_t)h * S + row) * (S >> 1) + ((kb + 8 * q + 4 * g) >> 1)) =
+                    (uint16_t)cw[q];
+        }
+#pragma unroll
+        for (int u = 0; u < 2; ++u) {
+            // first operand: slots 8 g .. 8 g + 7 of step u = registers 8 u .. 8 u + 7, as fp16 bit patterns
+            agq_u4 wq;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) wq[j] = (ex[8 * u + 2 * j] << 10) | (ex[8 * u + 2 * j + 1] << 26);
+            const agq_v8h af = __builtin_bit_cast(agq_v8h, wq);
+            const int chunk = 4 * sub + 2 * u + g;
+#pragma unroll
+            for (int n = 0; n < 4; ++n) {
+                const agq_v8h bf = *reinterpret_cast<const agq_v8h *>(vbuf + (n * DQ + bslot) * kVRow + (chunk << 4));
+                acc_o[n] = __builtin_amdgcn_mfma_f32_32x32x16_f16(af, bf, acc_o[n], 0, 0, 0);
+            }
+        }
+    };
+
+    __syncthreads();                                             // pass 1 is done with the K tile
     load_k(0);
     load_v(0);
     for (int t = 0; t < nt; ++t) {
-        uint8_t *kbuf = kt[t & 1], *vbuf = vt[t & 1];
-        store_k(kbuf);
+        uint8_t *vbuf = vt[t & 1];
+        if (t > 0) __syncthreads();                              // everyone is done with the previous K tile
+        store_k(kt);
         store_v(vbuf);
         if (t + 1 < nt) {
             load_k(t + 1);
@@ -210,49 +271,14 @@ __global__ __launch_bounds__(256, 2) void qk_log2_attn_kernel(const QkArgs a) {
         }
         __syncthreads();
         const int k0 = t * kKeys;
-        if (k0 > wave_last) continue;                            // wave-uniform; the barrier above was joined
+        if (k0 > wave_last) continue;                            // wave-uniform; the barriers above were joined
 #pragma unroll
         for (int sub = 0; sub < 2; ++sub) {
             const int kb = k0 + 32 * sub;
             if (kb > wave_last) continue;
-            const agq_v16i acc = scores(kbuf, sub);
-            const bool masked = kb + 31 > wave_lim;
-            uint32_t hb[16];                                     // fp16 bit patterns of the weights
-            uint32_t cw[4] = {0, 0, 0, 0};                       // codes of keys 8 q + 4 g + r, r = 0..3, as nibbles
-#pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int key = kb + 8 * (r >> 2) + 4 * g + (r & 3);
-                const float tt = fmaf(-a.kappa, (float)acc[r], L);
-                int code = (int)__builtin_amdgcn_fmed3f(__builtin_rintf(tt), 0.f, qmaxf);
-                uint32_t bits = (uint32_t)(wtop - code) << 10;
-                if (masked && key > row) {
-                    bits = 0;
-                    code = a.qmax;
-                }
-                hb[r] = bits;
-                if (CODES) cw[r >> 2] |= (uint32_t)code << (4 * (r & 3));
-                // importance on the quantized map: the weight of the first key (always live)
-                if (r == 0 && a.score && key == 0) atomicAdd(&a.score[row], 1 << (a.qmax - code));
-            }
-            if (CODES) {
-#pragma unroll
-                for (int q = 0; q < 4; ++q)
-                    *reinterpret_cast<uint16_t *>(a.codes + ((int64_t)h * S + row) * (S >> 1) + ((kb + 8 * q + 4 * g) >> 1)) =
-                        (uint16_t)cw[q];
-            }
-#pragma unroll
-            for (int u = 0; u < 2; ++u) {
-                // first operand: slots 8 g .. 8 g + 7 of step u = registers 8 u .. 8 u + 7
-                const agq_u4 wq = {hb[8 * u] | (hb[8 * u + 1] << 16), hb[8 * u + 2] | (hb[8 * u + 3] << 16),
-                                   hb[8 * u + 4] | (hb[8 * u + 5] << 16), hb[8 * u + 6] | (hb[8 * u + 7] << 16)};
-                const agq_v8h af = __builtin_bit_cast(agq_v8h, wq);
-                const int chunk = 4 * sub + 2 * u + g;
-#pragma unroll
-                for (int n = 0; n < 4; ++n) {
-                    const agq_v8h bf = *reinterpret_cast<const agq_v8h *>(vbuf + (n * DQ + bslot) * kVRow + (chunk << 4));
-                    acc_o[n] = __builtin_amdgcn_mfma_f32_32x32x16_f16(af, bf, acc_o[n], 0, 0, 0);
-                }
-            }
+            const agq_v16i acc = scores(kt, sub);
+            if (kb + 31 > wave_lim) weights(acc, kb, vbuf, sub, std::true_type{});
+            else weights(acc, kb, vbuf, sub, std::false_type{});
         }
     }
 

@@ -862,3 +862,30 @@ def test_qk_attention_scale_and_argument_errors(agq, oracle):
     assert call(S=100) == agq.AGQ_EINVAL and call(S=64) == agq.AGQ_EINVAL and call(D=96) == agq.AGQ_EINVAL
     assert call(qmax=8) == agq.AGQ_EINVAL
     torch.cuda.synchronize()
+
+
+def test_qk_attention_llama13b_full_size(agq, oracle):
+    """The benchmark's configuration (H = 40, S = 2048, D = 128, causal); the oracle checks two
+    whole heads, and the exact integer relations behind the codes are checked for every head."""
+    H, S, D, qmax, e_q, e_k, e_v = 40, 2048, 128, 15, -5, -5, -4
+    qq, kq, vq = synth.make_qkv_int8(H, S, D, seed=4)
+    o, codes, score = agq.qk_log2_softmax(dev(qq), dev(kq), dev(vq), e_q, e_k, e_v, qmax=qmax, causal=True,
+                                          want_codes=True, want_score=True)
+    codes_h, o_h = host(codes), host(o)
+    for h in (0, 39):
+        got_c = unpack_codes(codes_h[h:h + 1], S)
+        want_c, margin = oracle.qk_log2_codes(qq[h:h + 1], kq[h:h + 1], e_q, e_k, qmax, True)
+        sure = margin > CODE_MARGIN
+        assert np.array_equal(got_c[sure], want_c[sure]) and np.abs(got_c - want_c).max() <= 1 and sure.mean() > 0.99
+        _, want_o = oracle.attn_v_from_codes(got_c, vq[h:h + 1], e_v, qmax, True)
+        assert np.array_equal(o_h[:, h * D:(h + 1) * D].view(np.uint16), want_o.view(np.uint16))
+    # importance: from the first column of every head's codes
+    c0 = np.stack([unpack_codes(codes_h[h, :, :1], 2)[:, 0] for h in range(H)])
+    assert np.array_equal(host(score).astype(np.int64), (np.int64(1) << (qmax - c0.astype(np.int64))).sum(axis=0))
+    # every row's weights sum to about 2^qmax (the probabilities sum to one; rounding each to a
+    # power of two moves the sum by at most a factor sqrt(2) either way)
+    for h in (7, 23):
+        c = unpack_codes(codes_h[h], S).astype(np.int64)
+        w = np.where(np.tril(np.ones((S, S), dtype=bool)), np.int64(1) << (qmax - c), 0).sum(axis=1).astype(np.float64)
+        live = c.min(axis=1) < qmax                       # rows whose weights are not all clipped at 2^0
+        assert (w[live] > 2.0 ** qmax / 1.5).all() and (w[live] < 2.0 ** qmax * 1.5 + S).all()
