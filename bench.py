@@ -29,6 +29,7 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E
+F16_PEAK_TFLOPS = 2500.0   # dense fp16 MFMA
 INT8_PEAK_TOPS = 5000.0        # MI355X dense int8 MFMA
 DECODE_M = (1, 4, 16)
 PREFILL_M = 2048
@@ -387,6 +388,22 @@ def main():
                                 "TOP/s": round(ops_tail / us_tail / 1e6, 1),
                                 "frac_mfma": round(ops_tail / us_tail / 1e6 / INT8_PEAK_TOPS, 4)}}
         del probs, p0
+
+        # the same block from quantized Q and K in one kernel (no probabilities in memory): int8 Q K^T,
+        # softmax statistics, Eq.3 codes and the product with V
+        mk8 = lambda: torch.clamp(torch.round(torch.randn(H, S, D, generator=g2, device=dev) * 32), -127, 127).to(torch.int8)
+        q8, k8 = mk8(), mk8()
+        us_qk = time_plain(lambda: agq.qk_log2_softmax(q8, k8, vq, -5, -5, -5)) * 1e3
+        pairs = H * S * (S + 1) // 2
+        ops_i8, ops_f16 = 2.0 * pairs * D, 2.0 * pairs * D            # one Q K^T (int8) and one P V (fp16), algorithmic
+        ideal_us = ops_i8 / (INT8_PEAK_TOPS * 1e6) + ops_f16 / (F16_PEAK_TFLOPS * 1e6)
+        result["attention"]["qk_log2_softmax_v"] = {
+            "us": round(us_qk, 1), "inputs": "int8 Q, K, V [40, 2048, 128]",
+            "roofline": {"bound": "mfma", "achieved": round((ops_i8 + ops_f16) / us_qk / 1e6, 1),
+                         "peak": round((ops_i8 + ops_f16) / ideal_us / 1e6, 1), "unit": "TOP/s",
+                         "frac": round(ideal_us / us_qk, 4), "traffic": None, "kernel": "qk_log2_attn_kernel",
+                         "note": "algorithmic ops: one int8 Q K^T and one fp16 P V over the causal pairs; peak = "
+                                 "those ops at 5.0 POP/s and 2.5 PFLOP/s; the kernel computes Q K^T twice (two passes)"}}
 
     # ---- CPU baseline: the oracle as it stands, on a bounded sample of the decode workload
     if not args.no_cpu_baseline:

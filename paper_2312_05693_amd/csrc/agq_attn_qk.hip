@@ -179,17 +179,17 @@ __global__ __launch_bounds__(256, 3) void qk_log2_attn_kernel(const QkArgs a) {
     };
     load_k(0);
     for (int t = 0; t < nt; ++t) {
-        if (t > 0) __syncthreads();                              // everyone is done with the previous K tile
-        store_k(kt);
+        uint8_t *kbuf = (t & 1) ? vt[0] : kt;                    // the V buffers are idle in this pass: two K tiles, one barrier
+        store_k(kbuf);
         if (t + 1 < nt) load_k(t + 1);
         __syncthreads();
         const int k0 = t * kKeys;
-        if (k0 > wave_last) continue;                            // wave-uniform; the barriers above were joined
+        if (k0 > wave_last) continue;                            // wave-uniform; the barrier above was joined
 #pragma unroll
         for (int sub = 0; sub < 2; ++sub) {
             const int kb = k0 + 32 * sub;
             if (kb > wave_last) continue;
-            const agq_v16i acc = scores(kt, sub);
+            const agq_v16i acc = scores(kbuf, sub);
             if (kb + 31 > wave_lim) stats(acc, kb, std::true_type{});
             else stats(acc, kb, std::false_type{});
         }
@@ -201,9 +201,11 @@ __global__ __launch_bounds__(256, 3) void qk_log2_attn_kernel(const QkArgs a) {
     // (a half with nothing counted has sum 0, whatever its factor)
     const float tot = run_s * __builtin_amdgcn_exp2f(a.kappa * (float)(run_m - M)) +
                       os * __builtin_amdgcn_exp2f(a.kappa * (float)(om - M));
-    // -log2 p = kappa (M - s) + log2(tot); the code is that plus one half, truncated (ties go up:
-    // a tie has measure zero and lies inside the evaluation error anyway)
-    const float lsum05 = __builtin_amdgcn_logf(tot) + 0.5f;      // v_log_f32: base 2
+    // -log2 p = t = kappa (M - s) + log2(tot).  The weight 2^(qmax - c) has the fp16 exponent field
+    // 15 + qmax - c = round(15 + qmax - t) clamped to [15, 15 + qmax]: one fused multiply-add gives
+    // 15 + qmax - t, adding 1.5 * 2^23 rounds it to an integer (ties to even: a tie has measure
+    // zero and lies inside the evaluation error anyway) that sits in the low bits of the pattern.
+    const float c2 = (float)(15 + a.qmax) - __builtin_amdgcn_logf(tot) - a.kappa * (float)M;   // v_log_f32: base 2
 
     // ---- pass 2: codes, weights, product with V
     // four accumulators: block n holds the channels 4 c + n (c = column l & 31 < D / 4)
@@ -213,27 +215,22 @@ __global__ __launch_bounds__(256, 3) void qk_log2_attn_kernel(const QkArgs a) {
 #pragma unroll
         for (int r = 0; r < 16; ++r) acc_o[n][r] = 0.f;
     const int bslot = min(lane & 31, DQ - 1);
-    const uint32_t qmaxu = (uint32_t)a.qmax;
-    const float qmaxf = (float)a.qmax;
-    const uint32_t wtop = 15u + qmaxu;                           // exponent field of the weight of code 0
+    const uint32_t wtop = 15u + (uint32_t)a.qmax;                // exponent field of the weight of code 0
+    const float elo = AGQ_MAGIC + 15.0f, ehi = AGQ_MAGIC + (float)(15 + a.qmax);
 
     auto weights = [&](const agq_v16i &acc, int kb, const uint8_t *vbuf, int sub, auto masked_tag) {
         constexpr bool MASKED = decltype(masked_tag)::value;
-        uint32_t ex[16];                                         // exponent fields of the weights (0 = weight 0)
+        uint32_t ex[16];       // bit patterns whose low byte is the exponent field of the weight (0 = weight 0)
         uint32_t cw[4] = {0, 0, 0, 0};                           // codes of keys 8 q + 4 g + r, r = 0..3, as nibbles
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
-            const float tt = fmaf(a.kappa, (float)(M - acc[r]), lsum05);
-            uint32_t code = (uint32_t)__builtin_amdgcn_fmed3f(tt, 0.f, qmaxf);   // truncation of [0, qmax]
-            uint32_t e = wtop - code;
-            if (MASKED && kb + 8 * (r >> 2) + 4 * g + (r & 3) > row) {
-                e = 0;
-                code = qmaxu;
-            }
+            const float ef = __builtin_amdgcn_fmed3f(fmaf(a.kappa, (float)acc[r], c2) + AGQ_MAGIC, elo, ehi);
+            uint32_t e = __float_as_uint(ef);                    // 0x4B400000 + exponent field
+            if (MASKED && kb + 8 * (r >> 2) + 4 * g + (r & 3) > row) e = 0;
             ex[r] = e;
-            if (CODES) cw[r >> 2] |= code << (4 * (r & 3));
+            if (CODES) cw[r >> 2] |= ((e & 0xFFu) ? wtop - (e & 0xFFu) : (uint32_t)a.qmax) << (4 * (r & 3));
             // importance on the quantized map: the weight of the first key (always live)
-            if (r == 0 && a.score && kb == 0 && g == 0) atomicAdd(&a.score[row], 1 << (a.qmax - (int)code));
+            if (r == 0 && a.score && kb == 0 && g == 0) atomicAdd(&a.score[row], 1 << ((int)(e & 0xFFu) - 15));
         }
         if (CODES) {
 #pragma unroll
@@ -246,7 +243,8 @@ __global__ __launch_bounds__(256, 3) void qk_log2_attn_kernel(const QkArgs a) {
             // first operand: slots 8 g .. 8 g + 7 of step u = registers 8 u .. 8 u + 7, as fp16 bit patterns
             agq_u4 wq;
 #pragma unroll
-            for (int j = 0; j < 4; ++j) wq[j] = (ex[8 * u + 2 * j] << 10) | (ex[8 * u + 2 * j + 1] << 26);
+            for (int j = 0; j < 4; ++j)   // the shifts drop everything above the low byte's six bits
+                wq[j] = (ex[8 * u + 2 * j] << 10) | (ex[8 * u + 2 * j + 1] << 26);
             const agq_v8h af = __builtin_bit_cast(agq_v8h, wq);
             const int chunk = 4 * sub + 2 * u + g;
 #pragma unroll
