@@ -150,6 +150,19 @@ __global__ __launch_bounds__(256, 3) void qk_log2_attn_kernel(const QkArgs a) {
         return acc;
     };
 
+    // both sub-tiles of a tile at once: two independent accumulation chains
+    auto scores2 = [&](const uint8_t *kbuf, agq_v16i &acc0, agq_v16i &acc1) {
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc0[r] = acc1[r] = 0;
+#pragma unroll
+        for (int s = 0; s < DT; ++s) {
+            const agq_v4i k0f = *reinterpret_cast<const agq_v4i *>(kbuf + (lane & 31) * kKRow + 32 * s + 16 * g);
+            const agq_v4i k1f = *reinterpret_cast<const agq_v4i *>(kbuf + (32 + (lane & 31)) * kKRow + 32 * s + 16 * g);
+            acc0 = __builtin_amdgcn_mfma_i32_32x32x32_i8(k0f, qf[s], acc0, 0, 0, 0);
+            acc1 = __builtin_amdgcn_mfma_i32_32x32x32_i8(k1f, qf[s], acc1, 0, 0, 0);
+        }
+    };
+
     // ---- pass 1: per row the maximum score M (an integer) and sum_j 2^(kappa (s_j - M)).
     // Differences of scores are exact integers, so the only roundings are the product
     // with kappa and the exponential.
@@ -185,6 +198,24 @@ __global__ __launch_bounds__(256, 3) void qk_log2_attn_kernel(const QkArgs a) {
         __syncthreads();
         const int k0 = t * kKeys;
         if (k0 > wave_last) continue;                            // wave-uniform; the barrier above was joined
+        if (k0 + kKeys - 1 <= wave_lim) {
+            // whole tile live for every row of the wavefront: 32 scores per lane, one rescale
+            agq_v16i acc0, acc1;
+            scores2(kbuf, acc0, acc1);
+            int mx = max(acc0[0], acc1[0]);
+#pragma unroll
+            for (int r = 1; r < 16; ++r) mx = max(mx, max(acc0[r], acc1[r]));
+            const int nm = max(run_m, mx);
+            float add0 = 0.f, add1 = 0.f;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                add0 += __builtin_amdgcn_exp2f(a.kappa * (float)(acc0[r] - nm));
+                add1 += __builtin_amdgcn_exp2f(a.kappa * (float)(acc1[r] - nm));
+            }
+            run_s = run_s * __builtin_amdgcn_exp2f(a.kappa * (float)(run_m - nm)) + (add0 + add1);
+            run_m = nm;
+            continue;
+        }
 #pragma unroll
         for (int sub = 0; sub < 2; ++sub) {
             const int kb = k0 + 32 * sub;
@@ -270,6 +301,13 @@ __global__ __launch_bounds__(256, 3) void qk_log2_attn_kernel(const QkArgs a) {
         __syncthreads();
         const int k0 = t * kKeys;
         if (k0 > wave_last) continue;                            // wave-uniform; the barriers above were joined
+        if (k0 + kKeys - 1 <= wave_lim) {                        // whole tile live: both sub-tiles' scores first
+            agq_v16i acc0, acc1;
+            scores2(kt, acc0, acc1);
+            weights(acc0, k0, vbuf, 0, std::false_type{});
+            weights(acc1, k0 + 32, vbuf, 1, std::false_type{});
+            continue;
+        }
 #pragma unroll
         for (int sub = 0; sub < 2; ++sub) {
             const int kb = k0 + 32 * sub;
