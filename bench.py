@@ -37,7 +37,7 @@ PREFILL_M = 2048
 # HBM traffic per launch of the decode kernels from rocprofv3 --pmc (FETCH_SIZE x 2.0 KiB +
 # WRITE_SIZE x 1.0 KiB, the factors a 256 MiB copy gives); see profiles/.
 MEASURED_TRAFFIC_BYTES_PER_LAUNCH = 26.3e6
-MEASURED_ATTN_TRAFFIC_BYTES = 236.8e6   # log2_attn_kernel, one call of the bench's attention block
+MEASURED_ATTN_TRAFFIC_BYTES = 252.4e6   # log2_attn_kernel, one call of the bench's attention block
 
 
 def algorithmic_bytes(M, K, N):
