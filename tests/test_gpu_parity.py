@@ -889,3 +889,50 @@ def test_qk_attention_llama13b_full_size(agq, oracle):
         w = np.where(np.tril(np.ones((S, S), dtype=bool)), np.int64(1) << (qmax - c), 0).sum(axis=1).astype(np.float64)
         live = c.min(axis=1) < qmax                       # rows whose weights are not all clipped at 2^0
         assert (w[live] > 2.0 ** qmax / 1.5).all() and (w[live] < 2.0 ** qmax * 1.5 + S).all()
+
+
+def test_graph_replay_attention_and_trip(agq, oracle):
+    """The attention calls and the TRIP decode launch enqueue kernels only: captured into one HIP graph
+    after an eager warm-up, every replay must reproduce the eager results bit for bit."""
+    H, S, D, qmax = 3, 256, 128, 15
+    p, _ = synth.make_attention(H, S, D, seed=501)
+    qq, kq, vq = synth.make_qkv_int8(H, S, D, seed=502)
+    pd, qd, kd, vd = dev(p), dev(qq), dev(kq), dev(vq)
+    M, K, N = 4, 1024, 144
+    x, wq, sw = make_case(M, K, N, 503, 10)
+    e = oracle.trip_base_exp(x, 8, 4)
+    alpha = oracle.trip_search(x, 8, e, 0, 4)
+    packed, n_extra = agq.pack_w4_trip(dev(wq), alpha)
+    xd, swd = dev(x), dev(sw)
+    L = agq.lib()
+    st = lambda: torch.cuda.current_stream().cuda_stream
+    o1 = torch.zeros((S, H * D), dtype=torch.float16, device="cuda")
+    o2 = torch.zeros_like(o1)
+    score1 = torch.zeros(S, dtype=torch.int32, device="cuda")
+    score2 = torch.zeros(S, dtype=torch.int32, device="cuda")
+    y = torch.zeros((M, N), dtype=torch.float16, device="cuda")
+
+    def run_all():
+        assert L.agq_log2_quant_softmax(pd.data_ptr(), H, S, D, 1, qmax, vd.data_ptr(), -4, o1.data_ptr(), None,
+                                        score1.data_ptr(), st()) == 0
+        score2.zero_()                                             # the call accumulates (a fill kernel, not a memset node)
+        assert L.agq_qk_log2_softmax(qd.data_ptr(), kd.data_ptr(), H, S, D, 1, qmax, -5, -5, vd.data_ptr(), -4,
+                                     o2.data_ptr(), None, score2.data_ptr(), st()) == 0
+        assert L.agq_gemm_w4a8_trip(xd.data_ptr(), M, K, K, e, 0, packed.data_ptr(), n_extra, swd.data_ptr(), N,
+                                    y.data_ptr(), N, None, None, 0, st()) == 0
+
+    outs = (o1, o2, score1, score2, y)
+    run_all()
+    eager = [host(t).copy() for t in outs]
+    assert_f16_close(eager[4], oracle.linear_w4_trip(x, 8, e, 0, alpha, wq, sw)[1], "trip eager")
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        run_all()
+    for rep in range(3):
+        for t in outs:
+            t.fill_(rep + 1)                                       # eager work between replays; proves the replay writes
+        torch.cuda.synchronize()
+        graph.replay()
+        for t, want in zip(outs, eager):
+            got = host(t)
+            assert np.array_equal(got.view(np.uint8), want.view(np.uint8)), "replay differs from eager"
