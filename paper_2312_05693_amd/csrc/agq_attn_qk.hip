@@ -206,11 +206,14 @@ __global__ __launch_bounds__(256, 3) void qk_log2_attn_kernel(const QkArgs a) {
 #pragma unroll
             for (int r = 1; r < 16; ++r) mx = max(mx, max(acc0[r], acc1[r]));
             const int nm = max(run_m, mx);
+            // kappa s - kappa M with one rounding of the product (|kappa s| stays far below 2^10,
+            // so the difference is good to ~1e-5: enough for a sum of 2^x)
+            const float nmf = -a.kappa * (float)nm;
             float add0 = 0.f, add1 = 0.f;
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
-                add0 += __builtin_amdgcn_exp2f(a.kappa * (float)(acc0[r] - nm));
-                add1 += __builtin_amdgcn_exp2f(a.kappa * (float)(acc1[r] - nm));
+                add0 += __builtin_amdgcn_exp2f(fmaf(a.kappa, (float)acc0[r], nmf));
+                add1 += __builtin_amdgcn_exp2f(fmaf(a.kappa, (float)acc1[r], nmf));
             }
             run_s = run_s * __builtin_amdgcn_exp2f(a.kappa * (float)(run_m - nm)) + (add0 + add1);
             run_m = nm;
