@@ -3,7 +3,7 @@
 #include <stddef.h>
 #include <stdint.h>
 
-// geometry of the packed weight blob (see agq_pack.hip)
+// geometry of the packed weight blob (see the packer in agq_quant.hip)
 static inline int64_t agq_n_tiles_padded(int64_t N) { return ((N + 255) / 256) * 16; }  // 16-row tiles, padded to 256 rows
 static inline int64_t agq_k_tiles(int64_t K) { return K / 128; }
 // The blob ends with one int32 per (padded) output channel: the sum of its weights, which the
