@@ -277,8 +277,8 @@ __global__ __launch_bounds__(256, 3) void qk_log2_attn_kernel(const QkArgs a) {
             // first operand: slots 8 g .. 8 g + 7 of step u = registers 8 u .. 8 u + 7, as fp16 bit patterns
             agq_u4 wq;
 #pragma unroll
-            for (int j = 0; j < 4; ++j)   // the shifts drop everything above the low byte's six bits
-                wq[j] = (ex[8 * u + 2 * j] << 10) | (ex[8 * u + 2 * j + 1] << 26);
+            for (int j = 0; j < 4; ++j)   // the shifts drop everything above the low byte's five bits
+                wq[j] = ((ex[8 * u + 2 * j + 1] << 16) | ex[8 * u + 2 * j]) << 10;
             const agq_v8h af = __builtin_bit_cast(agq_v8h, wq);
             const int chunk = 4 * sub + 2 * u + g;
 #pragma unroll
