@@ -124,3 +124,50 @@ def test_binding_refuses_missing_library(monkeypatch):
     monkeypatch.setattr(binding, "LIB_PATH", "/nonexistent/libagq.so")
     with pytest.raises(RuntimeError):
         binding.lib()
+
+
+def test_trip_and_fused_attention_host_checks(lib):
+    """Sizes, factor validation and argument errors of the TRIP and attention-from-Q-and-K entry points
+    (all decided on the host)."""
+    import numpy as np
+    EINVAL = -1
+    K = 1024
+    alpha = np.zeros(K, dtype=np.int8)
+    assert lib.agq_trip_extra_chunks(alpha.ctypes.data, K) == 0
+    alpha[[3, 500]] = 4
+    alpha[7] = 1
+    assert lib.agq_trip_extra_chunks(alpha.ctypes.data, K) == 2            # one chunk per factor in use
+    alpha[:129] = 2
+    assert lib.agq_trip_extra_chunks(alpha.ctypes.data, K) == 3            # 129 channels of factor 2 need two chunks
+    alpha[0] = 5
+    assert lib.agq_trip_extra_chunks(alpha.ctypes.data, K) == EINVAL
+    alpha[0] = -1
+    assert lib.agq_trip_extra_chunks(alpha.ctypes.data, K) == EINVAL
+    assert lib.agq_trip_extra_chunks(None, K) == EINVAL
+    assert lib.agq_trip_extra_chunks(alpha.ctypes.data, 100) == EINVAL
+    # blob: nibbles of K/128 + E chunks per 16-row tile (rows padded to 256), weight sums, 32 + 128 E table
+    # entries, the factors
+    npad = 256
+    assert lib.agq_pack_w4_trip_bytes(100, K, 2) == (npad // 16) * (K // 128 + 2) * 1024 + npad * 4 + 128 + 2 * 512 + K
+    assert lib.agq_pack_w4_trip_bytes(100, K, 0) == lib.agq_pack_w4_bytes(100, K) + 128 + K
+    assert lib.agq_pack_w4_trip_bytes(100, K, 17) == 0 and lib.agq_pack_w4_trip_bytes(100, 65536, 1) == 0
+    assert lib.agq_gemm_trip_workspace_bytes(16, 64, K, 2) == 0
+    assert lib.agq_gemm_trip_workspace_bytes(130, 64, K, 2) == 256 * (K + 256)
+    p = ctypes.c_void_p(4096)
+    odd = ctypes.c_void_p(4100)
+    trip = lambda **kw: lib.agq_gemm_w4a8_trip(kw.get("x", p), kw.get("M", 4), kw.get("K", K), kw.get("ldx", K),
+                                               kw.get("e", 0), kw.get("zp", 0), kw.get("w", p), kw.get("E", 1), p, 64, p,
+                                               kw.get("ldy", 64), None, kw.get("ws", None), 0, None)
+    for bad in (dict(M=-1), dict(K=1000), dict(K=65536), dict(ldx=K - 8), dict(ldx=K + 4), dict(e=50), dict(zp=-1),
+                dict(zp=256), dict(E=-1), dict(E=17), dict(ldy=32), dict(x=None), dict(x=odd), dict(w=odd),
+                dict(M=200)):                                                # M = 200 needs a workspace
+        assert trip(**bad) == EINVAL, bad
+    assert trip(M=0) == 0
+    assert lib.agq_trip_search(p, 4, K, K, 8, 0, 0, 5, p, None) == EINVAL
+    assert lib.agq_trip_search(p, 4, K, K, 8, 0, 0, 4, None, None) == EINVAL
+    assert lib.agq_trip_search(p, 4, K, K, 3, 0, 0, 4, p, None) == EINVAL
+    qk = lambda **kw: lib.agq_qk_log2_softmax(kw.get("q", p), p, kw.get("H", 2), kw.get("S", 256), kw.get("D", 128), 1,
+                                              kw.get("qmax", 15), kw.get("e_q", 0), 0, p, 0, kw.get("o", p), None, None, None)
+    for bad in (dict(H=0), dict(S=64), dict(S=200), dict(S=65536), dict(D=32), dict(D=256), dict(qmax=4), dict(e_q=99),
+                dict(q=None), dict(q=odd), dict(o=None)):
+        assert qk(**bad) == EINVAL, bad
