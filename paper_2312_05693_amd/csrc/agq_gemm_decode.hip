@@ -95,7 +95,8 @@ __device__ __forceinline__ int find_proj(const DecodeArgs &a, int tile, int &nt)
 
 // ONE: fp16 with a single token row; Z: fp16 on the unsigned grid (a zero point is added to every code)
 // T: fp16 with a TRIP blob (Section 4.4): one more wavefront multiplies the extra chunks
-enum { XK_F16 = 0, XK_I8 = 1, XK_I4 = 2, XK_F16_ONE = 3, XK_F16_Z = 4, XK_F16_ONE_Z = 5, XK_F16_T = 6 };
+enum { XK_F16 = 0, XK_I8 = 1, XK_I4 = 2, XK_F16_ONE = 3, XK_F16_Z = 4, XK_F16_ONE_Z = 5,
+       XK_F16_T = 6, XK_F16_ONE_T = 7, XK_F16_TZ = 8 };
 
 typedef unsigned int agq_u4 __attribute__((ext_vector_type(4)));
 typedef unsigned int agq_u2 __attribute__((ext_vector_type(2)));
@@ -127,10 +128,10 @@ __global__ __launch_bounds__(1024) void gemm_decode_kernel(const DecodeArgs a) {
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int nwaves = a.waves;
-    constexpr bool TRIP = XK == XK_F16_T;
+    constexpr bool TRIP = XK == XK_F16_T || XK == XK_F16_ONE_T || XK == XK_F16_TZ;
     constexpr bool F16 = XK == XK_F16 || XK == XK_F16_ONE || XK == XK_F16_Z || XK == XK_F16_ONE_Z || TRIP;
-    constexpr bool ONE = XK == XK_F16_ONE || XK == XK_F16_ONE_Z;   // one row: a lane's 16 bytes are its own chunk's, four chunks per load
-    constexpr bool ZP = XK == XK_F16_Z || XK == XK_F16_ONE_Z || TRIP;   // fp16 input, zero point added (0 on the signed grid with TRIP)
+    constexpr bool ONE = XK == XK_F16_ONE || XK == XK_F16_ONE_Z || XK == XK_F16_ONE_T;   // one row: a lane's 16 bytes are its own chunk's, four chunks per load
+    constexpr bool ZP = XK == XK_F16_Z || XK == XK_F16_ONE_Z || XK == XK_F16_TZ;         // fp16 input on the unsigned grid
     // Everything the first vector loads depend on is requested in one round of
     // scalar loads; the weight pointer, scale pointer and width of this workgroup's
     // projection are picked by scalar selects instead of a second, dependent round
@@ -631,6 +632,12 @@ int agq_launch_gemm_decode(const void *x, int x_kind, int bits, int64_t M, int64
     // rows on and more than one tile per CU; below that the per-tile prologue,
     // which overlaps better with the weight stream, is faster).
     if (trip) {
+        if (zp) {
+            if (M <= 4) return launch_xk<XK_F16_TZ, 1>(a, kpw, grid, waves, lds, st);
+            if (M <= 8) return launch_xk<XK_F16_TZ, 2>(a, kpw, grid, waves, lds, st);
+            return launch_xk<XK_F16_TZ, 4>(a, kpw, grid, waves, lds, st);
+        }
+        if (M == 1) return launch_xk<XK_F16_ONE_T, 1>(a, kpw, grid, waves, lds, st);
         if (M <= 4) return launch_xk<XK_F16_T, 1>(a, kpw, grid, waves, lds, st);
         if (M <= 8) return launch_xk<XK_F16_T, 2>(a, kpw, grid, waves, lds, st);
         return launch_xk<XK_F16_T, 4>(a, kpw, grid, waves, lds, st);
