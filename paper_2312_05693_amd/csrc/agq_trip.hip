@@ -22,50 +22,56 @@
 namespace {
 
 constexpr int kThreads = 256;
+constexpr int kSearchThreads = 64;   // channels per workgroup of the factor search (one wavefront per factor)
 inline int64_t blocks_for(int64_t n) { return (n + kThreads - 1) / kThreads; }
 
 // ------------------------------------------------------------------ Eq.8
 //
-// One thread per channel walks the tokens in order and keeps, for every factor
-// 0..kmax, the squared error of quantizing (Eq.5, clip included) and
-// dequantizing its channel, in float64: every residual is exact, each square
-// and each addition rounds once, so the sums (and with them the argmin) are the
-// same on any machine that adds in token order.  Equal errors keep the smaller
-// factor.
-__global__ __launch_bounds__(kThreads) void trip_search_kernel(const __half *__restrict__ x, int64_t M, int64_t K,
-                                                                int64_t ldx, int e, double lo, double hi, int kmax,
-                                                                int8_t *__restrict__ alpha) {
+// One thread per (channel, factor): wavefront a of a workgroup handles factor a for
+// 64 channels, walks the tokens in order and keeps the squared error of quantizing
+// (Eq.5, clip included) and dequantizing its channel with that factor, in float64:
+// every residual is exact, each square and each addition rounds once, so the sums
+// (and with them the argmin) are the same on any machine that adds in token
+// order.  Equal errors keep the smaller factor.
+__global__ __launch_bounds__(kSearchThreads * 5) void trip_search_kernel(const __half *__restrict__ x, int64_t M,
+                                                                          int64_t K, int64_t ldx, int e, double lo,
+                                                                          double hi, int kmax,
+                                                                          int8_t *__restrict__ alpha) {
 #pragma clang fp contract(off)
-    const int64_t c = (int64_t)blockIdx.x * kThreads + threadIdx.x;
-    if (c >= K) return;
-    double err[5] = {0.0, 0.0, 0.0, 0.0, 0.0};
-    double inv[5], step[5];
+    __shared__ double errs[5][kSearchThreads];
+    const int a = threadIdx.y;                                   // factor of this wavefront (blockDim.y = kmax + 1)
+    const int64_t c = min((int64_t)blockIdx.x * kSearchThreads + threadIdx.x, K - 1);
+    const double inv = ldexp(1.0, -(e + a)), step = ldexp(1.0, e + a);
+    double err = 0.0;
+    // tokens are fetched sixteen at a time (the loads do not depend on the sum), and added in order
+    constexpr int kAhead = 16;
+    for (int64_t m0 = 0; m0 < M; m0 += kAhead) {
+        __half xv[kAhead];
 #pragma unroll
-    for (int a = 0; a < 5; ++a) {
-        inv[a] = ldexp(1.0, -(e + a));
-        step[a] = ldexp(1.0, e + a);
-    }
-    for (int64_t m = 0; m < M; ++m) {
-        const double v = (double)__half2float(x[m * ldx + c]);
+        for (int i = 0; i < kAhead; ++i) xv[i] = x[min(m0 + i, M - 1) * ldx + c];
 #pragma unroll
-        for (int a = 0; a < 5; ++a) {
-            if (a > kmax) break;
+        for (int i = 0; i < kAhead; ++i) {
+            if (m0 + i >= M) break;
+            const double v = (double)__half2float(xv[i]);
             // lo, hi are the grid bounds minus the zero point: CLIP(round + zp) - zp
-            const double q = fmin(fmax(rint(v * inv[a]), lo), hi);
-            const double r = v - q * step[a];
+            const double q = fmin(fmax(rint(v * inv), lo), hi);
+            const double r = v - q * step;
             const double sq = r * r;
-            err[a] = err[a] + sq;
+            err = err + sq;
         }
     }
-    int best = 0;
-    double best_err = err[0];
-#pragma unroll
-    for (int a = 1; a < 5; ++a)
-        if (a <= kmax && err[a] < best_err) {
-            best = a;
-            best_err = err[a];
-        }
-    alpha[c] = (int8_t)best;
+    errs[a][threadIdx.x] = err;
+    __syncthreads();
+    if (a == 0 && (int64_t)blockIdx.x * kSearchThreads + threadIdx.x < K) {
+        int best = 0;
+        double best_err = errs[0][threadIdx.x];
+        for (int b = 1; b <= kmax; ++b)
+            if (errs[b][threadIdx.x] < best_err) {
+                best = b;
+                best_err = errs[b][threadIdx.x];
+            }
+        alpha[c] = (int8_t)best;
+    }
 }
 
 // ------------------------------------------------------------------ blob
@@ -200,7 +206,8 @@ AgqQuant agq_make_quant_signed(int bits, int e, int zp);
 int agq_launch_trip_search(const void *x, int64_t M, int64_t K, int64_t ldx, int bits, int e, int zp, int kmax,
                            int8_t *alpha, void *stream) {
     const int lo = zp ? 0 : -(1 << (bits - 1)), hi = zp ? (1 << bits) - 1 : (1 << (bits - 1)) - 1;
-    trip_search_kernel<<<(unsigned)blocks_for(K), kThreads, 0, (hipStream_t)stream>>>(
+    trip_search_kernel<<<(unsigned)((K + kSearchThreads - 1) / kSearchThreads), dim3(kSearchThreads, kmax + 1), 0,
+                         (hipStream_t)stream>>>(
         (const __half *)x, M, K, ldx, e, (double)(lo - zp), (double)(hi - zp), kmax, alpha);
     return (int)hipGetLastError();
 }
