@@ -13,8 +13,10 @@ bytes of those calls (4-bit weights + fp16 scales + fp16 activation in and out)
 per second.
 
 The same line also carries the prefill regime (M = 2048, the seven shapes of
-one block, W4A8 and W4A4) as int8 TOP/s, the roofline of the dominant kernel,
-and the CPU oracle timed on the host cores.
+one block, W4A8 and W4A4) as int8 TOP/s, the TRIP layer on the same shapes
+beside the plain one, the attention block at LLaMA-13B size (from fp16
+probabilities, and from int8 Q and K in one kernel) with pruning, the roofline of
+the dominant kernel, and the CPU oracle timed on the host cores.
 """
 from __future__ import annotations
 
