@@ -93,6 +93,31 @@ def make_qkv_int8(H: int, S: int, D: int, seed: int):
     return to8(q), to8(k), to8(v)
 
 
+def rope_tables(P: int, D: int, base: float = 10000.0):
+    """(cos, sin) float32 [P, D/2]: the angle of position p and pair i is p * base^(-2i/D)."""
+    inv = base ** (-np.arange(0, D, 2, dtype=np.float64) / D)
+    ang = np.arange(P, dtype=np.float64)[:, None] * inv[None, :]
+    return np.cos(ang).astype(np.float32), np.sin(ang).astype(np.float32)
+
+
+def make_block_weights(d: int, H: int, F: int, seed: int) -> dict:
+    """Weights of one LLaMA-shaped block: 4-bit `w_<name>` int8 [N,K] with fp16 scales
+    `s_<name>` for q, k, v, o (d -> d), gate, up (d -> F), down (F -> d), and the two
+    normalisation gains (1 + N(0, 0.1), fp16).  The projections are drawn as in
+    `make_weight_q4` with a standard deviation of 1/sqrt(K), which keeps the residual
+    stream of a random block at unit scale."""
+    rng = np.random.default_rng([seed, 0xB10C])
+    w = {}
+    shapes = dict(q=(d, d), k=(d, d), v=(d, d), o=(d, d), gate=(F, d), up=(F, d), down=(d, F))
+    for i, (name, (N, K)) in enumerate(shapes.items()):
+        wq, sw = make_weight_q4(N, K, seed * 16 + i)
+        w["w_" + name] = wq
+        w["s_" + name] = (sw.astype(np.float64) / (0.02 * np.sqrt(K))).astype(np.float16)
+    w["g_attn"] = (1.0 + 0.1 * rng.standard_normal(d)).astype(np.float16)
+    w["g_mlp"] = (1.0 + 0.1 * rng.standard_normal(d)).astype(np.float16)
+    return w
+
+
 def n_outlier_channels(K: int, frac: float = 0.01) -> int:
     """About 1 % outlier channels, rounded up (prefill configurations)."""
     return int(np.ceil(frac * K))

@@ -1,0 +1,273 @@
+"""Pins for the block oracle (the fp16 non-linear operators between the quantized
+products, the cascade schedule of Eq.9, the wiring of one block): exact rational
+arithmetic, complex-number rotation, closed forms, library routines the oracle
+does not call, and wiring special cases.  No GPU is used here."""
+from __future__ import annotations
+
+import cmath
+from fractions import Fraction
+
+import numpy as np
+import pytest
+import torch
+
+from paper_2312_05693_amd import synth
+from test_oracle_pins import f16_fraction, fraction_to_f16
+
+
+@pytest.fixture(scope="module")
+def blk(oracle):
+    from oracle import agq_block_oracle
+    return agq_block_oracle
+
+
+def _rand16(shape, seed, scale=1.0):
+    rng = np.random.default_rng([seed, 0x51])
+    return (rng.standard_normal(shape) * scale).astype(np.float16)
+
+
+# ---------------------------------------------------------------- RMSNorm
+
+def test_rmsnorm_closed_forms(blk):
+    d = 96
+    g = np.ones(d, dtype=np.float16)
+    # a constant row has rms = |c|: output sign(c) exactly (eps = 0)
+    for c in (0.5, -3.0, 7.25):
+        y = blk.rmsnorm(np.full((1, d), c, dtype=np.float16), g, 0.0)
+        assert np.all(y == np.float16(np.sign(c)))
+    # one non-zero element v in a row of d: rms = |v|/sqrt(d), output sqrt(d)*sign(v)
+    x = np.zeros((1, 64), dtype=np.float16)
+    x[0, 5] = -2.0
+    y = blk.rmsnorm(x, np.ones(64, dtype=np.float16), 0.0)
+    assert y[0, 5] == np.float16(-8.0) and np.count_nonzero(y) == 1
+    # scaling the row by a power of two changes nothing when eps = 0
+    x = _rand16((7, d), 1)
+    g = _rand16(d, 2)
+    assert np.array_equal(blk.rmsnorm(x, g, 0.0), blk.rmsnorm((x.astype(np.float32) * 4).astype(np.float16), g, 0.0))
+    # a zero row stays zero with eps > 0
+    assert np.all(blk.rmsnorm(np.zeros((2, d), dtype=np.float16), g, 1e-6) == 0)
+    # eps enters under the root: row of ones, eps = 3 -> 1/sqrt(4)
+    y = blk.rmsnorm(np.ones((1, d), dtype=np.float16), np.ones(d, dtype=np.float16), 3.0)
+    assert np.all(y == np.float16(0.5))
+
+
+def test_rmsnorm_against_rationals_and_library(blk):
+    x = _rand16((5, 40), 3, 2.0)
+    g = _rand16(40, 4)
+    eps = 1e-5
+    y = blk.rmsnorm(x, g, eps)
+    # y^2 (ms + eps) == (x g)^2 up to the final fp16 rounding: ms as an exact rational
+    for t in range(5):
+        ms = sum(f16_fraction(v) ** 2 for v in x[t]) / 40 + Fraction(eps)
+        for c in range(40):
+            exact2 = (f16_fraction(x[t, c]) * f16_fraction(g[c])) ** 2 / ms
+            got = f16_fraction(y[t, c])
+            # neighbours of got bracket the exact value: |got| within half an ulp (2^-11 relative)
+            assert abs(got * got - exact2) <= exact2 * Fraction(1, 1000) + Fraction(1, 10 ** 12)
+            assert (got >= 0) == (f16_fraction(x[t, c]) * f16_fraction(g[c]) >= 0) or got == 0
+    # the library's routine (not used by the oracle), float64, rounded once
+    xt, gt = torch.from_numpy(x.astype(np.float64)), torch.from_numpy(g.astype(np.float64))
+    ref = torch.nn.functional.rms_norm(xt, (40,), gt, eps).numpy().astype(np.float16)
+    assert np.array_equal(ref, y)
+    # rows are normalised one by one (a column-wise mean would differ)
+    big = _rand16((64, 256), 5, 3.0)
+    gb = _rand16(256, 6)
+    ref = torch.nn.functional.rms_norm(torch.from_numpy(big.astype(np.float64)), (256,),
+                                       torch.from_numpy(gb.astype(np.float64)), eps).numpy().astype(np.float16)
+    assert np.array_equal(ref, blk.rmsnorm(big, gb, eps))
+
+
+# ---------------------------------------------------------------- rotary embedding
+
+def test_rope_special_angles(blk):
+    S, H, D = 6, 3, 8
+    x = _rand16((S, H * D), 7)
+    pos = np.arange(S, dtype=np.int32)
+    one, zero = np.ones((S, D // 2), np.float32), np.zeros((S, D // 2), np.float32)
+    assert np.array_equal(blk.rope(x, pos, one, zero, H), x)                      # angle 0
+    y = blk.rope(x, pos, zero, one, H).reshape(S, H, D)                          # quarter turn
+    xh = x.reshape(S, H, D)
+    assert np.array_equal(y[:, :, : D // 2], -xh[:, :, D // 2:])
+    assert np.array_equal(y[:, :, D // 2:], xh[:, :, : D // 2])
+    y = blk.rope(x, pos, -one, zero, H)                                          # half turn
+    assert np.array_equal(y, -x)
+    # the table row is chosen by pos[t], not by t
+    cos, sin = synth.rope_tables(32, D)
+    p2 = np.array([5, 0, 31, 7, 7, 2], dtype=np.int32)
+    y = blk.rope(x, p2, cos, sin, H)
+    for t in range(S):
+        yt = blk.rope(x[t:t + 1], np.array([0], dtype=np.int32), cos[p2[t]:p2[t] + 1], sin[p2[t]:p2[t] + 1], H)
+        assert np.array_equal(y[t:t + 1], yt)
+
+
+def test_rope_is_a_complex_rotation(blk):
+    S, H, D = 5, 2, 16
+    x = _rand16((S, H * D), 8, 3.0)
+    cos, sin = synth.rope_tables(64, D)
+    pos = np.array([0, 3, 17, 40, 63], dtype=np.int32)
+    y = blk.rope(x, pos, cos, sin, H)
+    for t in range(S):
+        for h in range(H):
+            for i in range(D // 2):
+                z = complex(float(x[t, h * D + i]), float(x[t, h * D + i + D // 2]))
+                w = z * complex(float(cos[pos[t], i]), float(sin[pos[t], i]))
+                assert abs(float(y[t, h * D + i]) - w.real) <= abs(w.real) * 2 ** -11 + 2 ** -25
+                assert abs(float(y[t, h * D + i + D // 2]) - w.imag) <= abs(w.imag) * 2 ** -11 + 2 ** -25
+    # exact rationals on a few elements: cos, sin and x are all dyadic rationals
+    for (t, h, i) in [(1, 0, 0), (2, 1, 3), (4, 1, 7)]:
+        a, b = f16_fraction(x[t, h * D + i]), f16_fraction(x[t, h * D + i + D // 2])
+        c, s = Fraction(float(cos[pos[t], i])), Fraction(float(sin[pos[t], i]))
+        assert float(y[t, h * D + i]) == fraction_to_f16(a * c - b * s)
+        assert float(y[t, h * D + i + D // 2]) == fraction_to_f16(b * c + a * s)
+
+
+def test_rope_relative_position_property(blk):
+    # <rope(q, m), rope(k, n)> depends on m - n only (textbook property of the embedding)
+    H, D = 1, 32
+    q, k = _rand16((1, D), 9), _rand16((1, D), 10)
+    cos, sin = synth.rope_tables(128, D)
+    def dot(m, n):
+        a = blk.rope(q, np.array([m]), cos, sin, H).astype(np.float64)
+        b = blk.rope(k, np.array([n]), cos, sin, H).astype(np.float64)
+        return float((a * b).sum())
+    ref = dot(5, 0)
+    for m, n in [(6, 1), (50, 45), (127, 122)]:
+        assert abs(dot(m, n) - ref) < 0.05
+    # and the textbook "rotate half" formulation, written with torch in float64
+    x = _rand16((9, 2 * D), 11)
+    pos = np.arange(9, dtype=np.int32) * 3
+    xt = torch.from_numpy(x.astype(np.float64)).reshape(9, 2, D)
+    cf = torch.from_numpy(np.concatenate([cos[pos], cos[pos]], axis=1).astype(np.float64))[:, None, :]
+    sf = torch.from_numpy(np.concatenate([sin[pos], sin[pos]], axis=1).astype(np.float64))[:, None, :]
+    rot = torch.cat([-xt[..., D // 2:], xt[..., : D // 2]], dim=-1)
+    ref = (xt * cf + rot * sf).reshape(9, 2 * D).numpy().astype(np.float16)
+    assert np.array_equal(ref, blk.rope(x, pos, cos, sin, 2))
+
+
+# ---------------------------------------------------------------- SwiGLU, residual
+
+def test_swiglu(blk):
+    f = lambda z, u=1.0: float(blk.swiglu(np.array([z], dtype=np.float16), np.array([u], dtype=np.float16))[0])
+    assert f(0.0) == 0.0
+    assert f(20.0) == 20.0 and -1e-7 < f(-20.0) <= 0.0                           # the two limits
+    assert f(1.0) == float(np.float16(1.0 / (1.0 + np.e ** -1.0)))
+    assert f(1.0, -4.0) == float(np.float16(-4.0 / (1.0 + np.e ** -1.0)))      # `up` multiplies
+    # silu(z) - silu(-z) = z
+    for z in (0.25, 1.5, 3.0, 7.0):
+        assert abs(f(z) - f(-z) - z) <= 2 ** -9 * z
+    # the largest fp16 magnitudes neither overflow the exponential into NaN nor lose the sign
+    assert f(-65504.0) == 0.0 and f(65504.0) == 65504.0
+    g, u = _rand16((33, 70), 12, 3.0), _rand16((33, 70), 13, 2.0)
+    ref = (torch.nn.functional.silu(torch.from_numpy(g.astype(np.float64)))
+           * torch.from_numpy(u.astype(np.float64))).numpy().astype(np.float16)
+    got = blk.swiglu(g, u)
+    assert np.array_equal(ref, got)
+    # rational bracket on a few elements: a (1 + e^-g) = g u up to fp16 rounding of a
+    for (i, j) in [(0, 0), (5, 9), (32, 69)]:
+        lhs = float(got[i, j]) * (1.0 + np.exp(-float(g[i, j])))
+        assert abs(lhs - float(g[i, j]) * float(u[i, j])) <= abs(lhs) * 2 ** -10 + 1e-7
+
+
+def test_residual_add_exact_rational(blk):
+    a, b = _rand16(300, 14, 5.0), _rand16(300, 15, 0.01)
+    a[:4] = [65504.0, -65504.0, 6e-8, 1024.0]
+    b[:4] = [65504.0, 32.0, 6e-8, 0.5]               # overflow, near overflow, subnormals, a tie
+    y = blk.residual_add(a, b)
+    for i in range(300):
+        assert float(y[i]) == fraction_to_f16(f16_fraction(a[i]) + f16_fraction(b[i]))
+    assert np.isinf(y[0]) and y[3] == np.float16(1024.0)      # 1024.5 ties to the even 1024
+
+
+def test_heads_int8_layout(oracle, blk):
+    S, H, D = 10, 3, 16
+    x = _rand16((S, H * D), 16, 2.0)
+    q = blk.heads_int8(x, H, -4, 128)
+    assert q.shape == (H, 128, D) and q.dtype == np.int8
+    ref = oracle.quantize_act(x, 8, -4, 0)
+    for h in range(H):
+        for s in range(S):
+            assert np.array_equal(q[h, s], ref[s, h * D:(h + 1) * D])
+    assert not q[:, S:].any()
+
+
+# ---------------------------------------------------------------- Eq.9 schedule
+
+def test_cascade_keep_eq9(blk):
+    assert blk.cascade_keep(2048, 0.75, 2) == [1024, 512]          # gamma = 1 - sqrt(1/4) = 1/2
+    assert blk.cascade_keep(2048, 0.5, 1) == [1024]
+    assert blk.cascade_keep(1000, 0.0, 3) == [1000, 1000, 1000]
+    for S, beta, m in [(2048, 0.3, 4), (777, 0.6, 5), (4096, 0.1, 8)]:
+        k = blk.cascade_keep(S, beta, m)
+        assert len(k) == m and all(a >= b for a, b in zip([S] + k, k))
+        # (1 - gamma)^m = 1 - beta: the last stage leaves S (1 - beta) tokens, up to one per stage
+        assert 0 <= k[-1] - S * (1 - beta) <= m
+        gamma = 1 - (1 - beta) ** (1 / m)
+        assert k[0] == S - int(S * gamma)
+
+
+# ---------------------------------------------------------------- the block's wiring
+
+def _block_inputs(S, d, H, F, seed):
+    x = synth.make_activation(S, d, 4, seed)
+    pos = np.arange(S, dtype=np.int32)
+    cos, sin = synth.rope_tables(S + 8, d // H)
+    return x, pos, cos, sin, synth.make_block_weights(d, H, F, seed)
+
+
+def test_block_wiring_special_cases(oracle, blk):
+    S, d, H, F = 72, 128, 2, 256
+    x, pos, cos, sin, w = _block_inputs(S, d, H, F, 21)
+    pos = pos + 3
+    r = blk.block_forward(x, pos, cos, sin, w, H, 15, 1e-5, 40)
+    # given exponents == calibrated exponents
+    r2 = blk.block_forward(x, pos, cos, sin, w, H, 15, 1e-5, 40, exps=r["exps"])
+    assert np.array_equal(r["x_out"], r2["x_out"]) and set(r["exps"]) == set(blk.EXP_NAMES)
+    # pruning: indices ascending, token 0 kept (it attends to itself only: the largest score)
+    idx = r["idx"]
+    assert len(idx) == 40 and np.all(np.diff(idx) > 0) and idx[0] == 0
+    assert r["score"][0] == H << 15 and r["score"].max() == r["score"][0]
+    assert np.array_equal(r["pos_out"], pos[idx])
+    assert np.array_equal(idx, oracle.prune_select(r["score"], 40))
+    # both residual branches silenced: the block hands the surviving rows through
+    w0 = dict(w)
+    w0["w_o"] = np.zeros_like(w["w_o"])
+    w0["w_down"] = np.zeros_like(w["w_down"])
+    r0 = blk.block_forward(x, pos, cos, sin, w0, H, 15, 1e-5, 40)
+    assert np.array_equal(r0["x_out"], x[r0["idx"]])
+    # only the MLP branch silenced: x_out = x[idx] + attention branch
+    w1 = dict(w)
+    w1["w_down"] = np.zeros_like(w["w_down"])
+    r1 = blk.block_forward(x, pos, cos, sin, w1, H, 15, 1e-5, 40)
+    assert np.array_equal(r1["x_out"], r1["x1"]) and np.array_equal(r1["idx"], idx)
+    assert np.array_equal(r1["x1"], blk.residual_add(x[idx], r1["attn_out"]))
+    # no pruning: every token survives in order
+    r3 = blk.block_forward(x, pos, cos, sin, w, H, 15, 1e-5, S)
+    assert np.array_equal(r3["idx"], np.arange(S)) and r3["x_out"].shape == (S, d)
+    # causality: the first t tokens do not see the later ones
+    t = 33
+    r4 = blk.block_forward(x[:t], pos[:t], cos, sin, w, H, 15, 1e-5, t, exps=r["exps"])
+    r5 = blk.block_forward(x, pos, cos, sin, w, H, 15, 1e-5, S, exps=r["exps"])
+    assert np.array_equal(r4["x_out"], r5["x_out"][:t])
+
+
+def test_block_stages_are_the_pinned_functions(oracle, blk):
+    # every tensor of the block is the pinned single function applied to the tensors before it
+    S, d, H, F = 40, 128, 2, 256
+    x, pos, cos, sin, w = _block_inputs(S, d, H, F, 22)
+    r = blk.block_forward(x, pos, cos, sin, w, H, 7, 1e-5, 25, bits_attn_out=8)
+    e = r["exps"]
+    assert np.array_equal(r["h1"], blk.rmsnorm(x, w["g_attn"], 1e-5))
+    assert e["e_attn_in"] == oracle.calibrate_act_exp(r["h1"], 8)
+    assert np.array_equal(r["k"], oracle.linear_w4(r["h1"], 8, e["e_attn_in"], 0, w["w_k"], w["s_k"])[1])
+    assert np.array_equal(r["k_rot"], blk.rope(r["k"], pos, cos, sin, H))
+    assert np.array_equal(r["v_q"], blk.heads_int8(r["v"], H, e["e_v"], 128))
+    codes, _ = oracle.qk_log2_codes(r["q_q"], r["k_q"], e["e_q"], e["e_k"], 7, True)
+    assert np.array_equal(codes[:, :S, :S], r["codes"]) and codes.max() <= 7
+    assert np.array_equal(r["o"], oracle.attn_v_from_codes(codes, r["v_q"], e["e_v"], 7, True)[1][:S])
+    assert e["e_attn_out"] == oracle.calibrate_act_exp(r["o"][r["idx"]], 8)
+    assert np.array_equal(r["attn_out"],
+                          oracle.linear_w4(r["o"][r["idx"]], 8, e["e_attn_out"], 0, w["w_o"], w["s_o"])[1])
+    assert np.array_equal(r["h2"], blk.rmsnorm(r["x1"], w["g_mlp"], 1e-5))
+    assert np.array_equal(r["act"], blk.swiglu(r["gate"], r["up"]))
+    assert np.array_equal(r["down"], oracle.linear_w4(r["act"], 8, e["e_mlp_act"], 0, w["w_down"], w["s_down"])[1])
+    assert np.array_equal(r["x_out"], blk.residual_add(r["x1"], r["down"]))
