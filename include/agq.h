@@ -256,6 +256,107 @@ int agq_prune_tokens(const int32_t *score, int64_t S, int64_t n_keep,
                      const void *x_f16, int64_t d, int32_t *idx_out,
                      void *x_out_f16, void *stream);
 
+/* One block of the quantized model: the activation quantization pipeline of
+ * Section 4.2 (Figure 3: every matrix product takes quantized operands, the
+ * non-linear operators in between stay in fp16) with the activation-aware token
+ * pruning of Section 4.3 right after attention, for a LLaMA block (RMSNorm,
+ * rotary embedding, SwiGLU).  With x fp16 [S,d], positions pos[S]:
+ *   h1        = RMSNorm(x; g_attn)
+ *   q,k,v     = W4A8(h1)        one Eq.2 pass (step 2^e_attn_in) serves all three
+ *   Q,K,V     = Eq.2 to int8 of rope(q), rope(k), v   (steps 2^e_q, 2^e_k, 2^e_v)
+ *   o, score  = agq_qk_log2_softmax(Q, K, V), causal
+ *   idx       = the n_keep tokens with the largest score (agq_prune_tokens' rule)
+ *   x1        = x[idx] + W4A8-or-W4A4(o[idx])           (step 2^e_attn_out;
+ *               Section 4.2 allows 4-bit activations after self-attention)
+ *   h2        = RMSNorm(x1; g_mlp)
+ *   a         = silu(gate) * up,  gate, up = W4A8(h2)   (one Eq.2 pass, 2^e_mlp_in)
+ *   x_out     = x1 + W4A8(a)                            (step 2^e_mlp_act)
+ * RMSNorm: y = x g / sqrt(mean(x^2) + rms_eps).  rope: inside a head of width D the
+ * pair (i, i + D/2) is rotated by the angle whose cosine and sine are
+ * rope_cos[pos, i], rope_sin[pos, i].  Every fp16 operator computes in float64 and
+ * rounds once to fp16.  All activation grids are signed (zp = 0).
+ *
+ * d = H*D with D = 64 or 128; d % 128 == 0, F % 128 == 0; 1 <= S <= 8192;
+ * 1 <= n_keep <= S (n_keep == S: nothing is pruned).  Eq.9's cascade is a sequence
+ * of such calls whose n_keep follow agq_cascade_keep.
+ * All pointers are device pointers, 16-byte aligned; weights are agq_pack_w4 blobs
+ * ([d,d] for q, k, v, o; [F,d] for gate, up; [d,F] for down) with fp16 scales.   */
+typedef struct agq_block {
+    int64_t d, H, F;
+    int qmax;               /* 15 or 7, as for agq_qk_log2_softmax                */
+    int bits_attn_out;      /* 4 or 8: activation grid of the projection after attention */
+    double rms_eps;
+    const void *g_attn_f16, *g_mlp_f16;                /* fp16 [d]               */
+    const void *w_q, *w_k, *w_v, *w_o, *w_gate, *w_up, *w_down;
+    const void *s_q, *s_k, *s_v, *s_o, *s_gate, *s_up, *s_down;
+    /* static exponents of the seven quantizers (post-training calibration)       */
+    int e_attn_in, e_q, e_k, e_v, e_attn_out, e_mlp_in, e_mlp_act;
+} agq_block;
+
+/* Where every intermediate tensor of a call lives inside the workspace (byte
+ * offsets; fp16 unless noted).  Shapes: h1, q, k, v [S,d]; q_q, k_q, v_q int8
+ * [H,S_pad,D] (rows from S on are zero); o [S_pad,d]; score int32 [S_pad]; idx int32
+ * [n_keep]; o_kept, attn_out, x1, h2, down [n_keep,d] (o_kept == o when nothing is
+ * pruned); gate, up, act [n_keep,F]; q_rot, k_rot [S,d] (written by
+ * agq_block_calibrate only).  total = the workspace size a call needs.           */
+typedef struct agq_block_layout {
+    int64_t S_pad;          /* S rounded up to a multiple of 128                   */
+    size_t h1, q, k, v, q_q, k_q, v_q, o, score, idx, o_kept, attn_out, x1, h2, gate, up, act, down, q_rot, k_rot,
+        gemm_ws, total;
+} agq_block_layout;
+int agq_block_layout_of(const agq_block *blk, int64_t S, int64_t n_keep, agq_block_layout *out);
+
+/* The fp16 operators of the block as calls of their own (Section 4.2 keeps them in
+ * fp16; other block shapes can be wired from these and the products above).  Each
+ * computes in float64 and rounds once to fp16.  fp16 tensors are contiguous
+ * (leading dimension = row width) and 16-byte aligned.
+ *
+ * agq_rmsnorm: y[r,:] = t[r,:] * g / sqrt(mean(t[r,:]^2) + eps).  res_f16 == NULL:
+ * t = x.  Otherwise t[r,:] = fp16(res[idx[r],:] + x[r,:]) (idx == NULL: row r
+ * itself), also written to sum_out_f16 [rows,d]: the residual addition, and the row
+ * gather after pruning, fused into the normalisation that follows them.
+ * d % 8 == 0, d <= 65536; idx values must be valid rows of res.
+ *
+ * agq_rope_quantize: rotary embedding of q and k (pairs (i, i + D/2) of every head,
+ * angle tables float32 [P, D/2] read at row pos[t], positions clamped into the
+ * table), then Eq.2 to int8 (signed grid, steps 2^e_q, 2^e_k, 2^e_v) of the rotated
+ * q, k and of v, written per head: int8 [H, S_pad, D] with zero rows from S on
+ * (S_pad >= S; agq_qk_log2_softmax wants a multiple of 128).  q, k, v: fp16
+ * [S, H*D]; D % 16 == 0.
+ *
+ * agq_swiglu: out = silu(gate) * up, silu(z) = z / (1 + exp(-z)); n elements,
+ * n % 8 == 0.   agq_residual_add: out = fp16(a + b); n % 8 == 0.                  */
+int agq_rmsnorm(const void *x_f16, const void *res_f16, const int32_t *idx, const void *g_f16,
+                int64_t rows, int64_t d, double eps, void *sum_out_f16, void *y_f16, void *stream);
+int agq_rope_quantize(const void *q_f16, const void *k_f16, const void *v_f16, int64_t S, int64_t H,
+                      int64_t D, const int32_t *pos, const float *rope_cos, const float *rope_sin,
+                      int64_t P, int e_q, int e_k, int e_v, int64_t S_pad, int8_t *q_q, int8_t *k_q,
+                      int8_t *v_q, void *stream);
+int agq_swiglu(const void *gate_f16, const void *up_f16, void *out_f16, int64_t n, void *stream);
+int agq_residual_add(const void *a_f16, const void *b_f16, void *out_f16, int64_t n, void *stream);
+
+/* x_f16 [S,d]; pos int32 [S], every value in [0, P); rope_cos, rope_sin float32
+ * [P, D/2] (a position outside the table is clamped into it).  x_out_f16
+ * [n_keep,d]; pos_out int32 [n_keep] = pos[idx] (may be NULL).  workspace: `total`
+ * bytes of agq_block_layout_of, 256-byte aligned.  Enqueues kernels only.        */
+int agq_block_forward(const agq_block *blk, const void *x_f16, const int32_t *pos, const float *rope_cos,
+                      const float *rope_sin, int64_t P, int64_t S, int64_t n_keep, void *x_out_f16,
+                      int32_t *pos_out, void *workspace, size_t workspace_bytes, void *stream);
+
+/* The same pass with every exponent derived on the way from this input
+ * (agq_calibrate_act_exp on the tensor each quantizer reads) and written back to
+ * *blk: the post-training calibration step.  Waits for `stream` several times; not
+ * capturable.                                                                     */
+int agq_block_calibrate(agq_block *blk, const void *x_f16, const int32_t *pos, const float *rope_cos,
+                        const float *rope_sin, int64_t P, int64_t S, int64_t n_keep, void *x_out_f16,
+                        int32_t *pos_out, void *workspace, size_t workspace_bytes, void *stream);
+
+/* Section 5.2, Eq.9: m pruning stages share the progressive ratio
+ * gamma = 1 - (1 - beta)^(1/m), so that a fraction beta is gone after the last one;
+ * a stage that receives S tokens keeps S - floor(S * gamma).  keep_out (HOST int64
+ * [m]) receives the tokens left after each stage.  0 <= beta < 1, 1 <= m <= 1024.  */
+int agq_cascade_keep(int64_t S, double beta, int m, int64_t *keep_out);
+
 #ifdef __cplusplus
 }
 #endif

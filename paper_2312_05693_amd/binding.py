@@ -43,6 +43,15 @@ SIGNATURES = {
     "agq_log2_quant_softmax": (_int, [_vp, _i64, _i64, _i64, _int, _int, _vp, _int, _vp, _vp, _vp, _vp]),
     "agq_qk_log2_softmax": (_int, [_vp, _vp, _i64, _i64, _i64, _int, _int, _int, _int, _vp, _int, _vp, _vp, _vp, _vp]),
     "agq_prune_tokens": (_int, [_vp, _i64, _i64, _vp, _i64, _vp, _vp, _vp]),
+    "agq_rmsnorm": (_int, [_vp, _vp, _vp, _vp, _i64, _i64, ctypes.c_double, _vp, _vp, _vp]),
+    "agq_rope_quantize": (_int, [_vp, _vp, _vp, _i64, _i64, _i64, _vp, _vp, _vp, _i64, _int, _int, _int, _i64, _vp, _vp,
+                                 _vp, _vp]),
+    "agq_swiglu": (_int, [_vp, _vp, _vp, _i64, _vp]),
+    "agq_residual_add": (_int, [_vp, _vp, _vp, _i64, _vp]),
+    "agq_block_layout_of": (_int, [_vp, _i64, _i64, _vp]),
+    "agq_block_forward": (_int, [_vp, _vp, _vp, _vp, _vp, _i64, _i64, _i64, _vp, _vp, _vp, _sz, _vp]),
+    "agq_block_calibrate": (_int, [_vp, _vp, _vp, _vp, _vp, _i64, _i64, _i64, _vp, _vp, _vp, _sz, _vp]),
+    "agq_cascade_keep": (_int, [_i64, ctypes.c_double, _int, _vp]),
 }
 
 AGQ_MAX_PROJ = 4
@@ -52,6 +61,25 @@ class AgqProj(ctypes.Structure):
     """struct agq_proj of include/agq.h"""
     _fields_ = [("w_packed", _vp), ("w_scale_f16", _vp), ("N", _i64), ("y_f16", _vp), ("ldy", _i64),
                 ("acc_out", _vp)]
+
+
+BLOCK_PROJ = ("q", "k", "v", "o", "gate", "up", "down")
+BLOCK_EXPS = ("e_attn_in", "e_q", "e_k", "e_v", "e_attn_out", "e_mlp_in", "e_mlp_act")
+BLOCK_TENSORS = ("h1", "q", "k", "v", "q_q", "k_q", "v_q", "o", "score", "idx", "o_kept", "attn_out", "x1", "h2",
+                 "gate", "up", "act", "down", "q_rot", "k_rot")
+
+
+class AgqBlock(ctypes.Structure):
+    """struct agq_block of include/agq.h"""
+    _fields_ = ([("d", _i64), ("H", _i64), ("F", _i64), ("qmax", _int), ("bits_attn_out", _int),
+                 ("rms_eps", ctypes.c_double), ("g_attn_f16", _vp), ("g_mlp_f16", _vp)]
+                + [("w_" + n, _vp) for n in BLOCK_PROJ] + [("s_" + n, _vp) for n in BLOCK_PROJ]
+                + [(n, _int) for n in BLOCK_EXPS])
+
+
+class AgqBlockLayout(ctypes.Structure):
+    """struct agq_block_layout of include/agq.h"""
+    _fields_ = [("S_pad", _i64)] + [(n, _sz) for n in BLOCK_TENSORS] + [("gemm_ws", _sz), ("total", _sz)]
 
 
 _lib = None
@@ -281,3 +309,101 @@ def prune_tokens(score, n_keep, x):
     out = torch.empty((n_keep, d), dtype=torch.float16, device=x.device)
     _ok(lib().agq_prune_tokens(_ptr(score), S, n_keep, _ptr(x), d, _ptr(idx), _ptr(out), _stream()), "agq_prune_tokens")
     return idx, out
+
+
+def rmsnorm(x, g, eps, res=None, idx=None):
+    """y = RMSNorm(x; g), or with res: (t, y) with t = res[idx] + x and y = RMSNorm(t; g)."""
+    rows, d = x.shape
+    y = torch.empty_like(x)
+    t = torch.empty_like(x) if res is not None else None
+    _ok(lib().agq_rmsnorm(_ptr(x), _ptr(res), _ptr(idx), _ptr(g), rows, d, eps, _ptr(t), _ptr(y), _stream()),
+        "agq_rmsnorm")
+    return y if res is None else (t, y)
+
+
+def rope_quantize(q, k, v, H, pos, rope_cos, rope_sin, e_q, e_k, e_v, S_pad=None):
+    """fp16 [S, H*D] each -> int8 [H, S_pad, D] each (q and k rotated, all three on Eq.2's grid)."""
+    S, d = q.shape
+    D = d // H
+    S_pad = -(-S // 128) * 128 if S_pad is None else S_pad
+    outs = [torch.empty((H, S_pad, D), dtype=torch.int8, device=q.device) for _ in range(3)]
+    _ok(lib().agq_rope_quantize(_ptr(q), _ptr(k), _ptr(v), S, H, D, _ptr(pos), _ptr(rope_cos), _ptr(rope_sin),
+                                rope_cos.shape[0], e_q, e_k, e_v, S_pad, _ptr(outs[0]), _ptr(outs[1]), _ptr(outs[2]),
+                                _stream()), "agq_rope_quantize")
+    return outs
+
+
+def swiglu(gate, up):
+    out = torch.empty_like(gate)
+    _ok(lib().agq_swiglu(_ptr(gate), _ptr(up), _ptr(out), gate.numel(), _stream()), "agq_swiglu")
+    return out
+
+
+def residual_add(a, b):
+    out = torch.empty_like(a)
+    _ok(lib().agq_residual_add(_ptr(a), _ptr(b), _ptr(out), a.numel(), _stream()), "agq_residual_add")
+    return out
+
+
+def make_block(d, H, F, weights: dict, qmax=15, bits_attn_out=4, rms_eps=1e-5, exps: dict | None = None) -> AgqBlock:
+    """weights: device tensors g_attn, g_mlp (fp16 [d]) and, for every projection in BLOCK_PROJ, the agq_pack_w4
+    blob `w_<name>` and the fp16 scales `s_<name>`.  The struct keeps the tensors alive."""
+    blk = AgqBlock(d=d, H=H, F=F, qmax=qmax, bits_attn_out=bits_attn_out, rms_eps=rms_eps,
+                   g_attn_f16=_ptr(weights["g_attn"]), g_mlp_f16=_ptr(weights["g_mlp"]))
+    for n in BLOCK_PROJ:
+        setattr(blk, "w_" + n, _ptr(weights["w_" + n]))
+        setattr(blk, "s_" + n, _ptr(weights["s_" + n]))
+    for n in BLOCK_EXPS:
+        setattr(blk, n, 0 if exps is None else int(exps[n]))
+    blk._keepalive = dict(weights)
+    return blk
+
+
+def block_exps(blk: AgqBlock) -> dict:
+    return {n: int(getattr(blk, n)) for n in BLOCK_EXPS}
+
+
+def block_layout(blk: AgqBlock, S: int, n_keep: int) -> AgqBlockLayout:
+    L = AgqBlockLayout()
+    _ok(lib().agq_block_layout_of(ctypes.byref(blk), S, n_keep, ctypes.byref(L)), "agq_block_layout_of")
+    return L
+
+
+def block_forward(blk: AgqBlock, x, pos, rope_cos, rope_sin, n_keep=None, workspace=None, calibrate=False):
+    """One block (Section 4.2's pipeline with pruning after attention).  x fp16 [S,d], pos int32 [S], rope tables
+    float32 [P, D/2].  calibrate=True derives the exponents from this input and stores them in blk.
+    Returns (x_out [n_keep,d], pos_out [n_keep], workspace, layout)."""
+    S, d = x.shape
+    n_keep = S if n_keep is None else n_keep
+    L = block_layout(blk, S, n_keep)
+    if workspace is None:
+        workspace = torch.empty(L.total, dtype=torch.uint8, device=x.device)
+    x_out = torch.empty((n_keep, d), dtype=torch.float16, device=x.device)
+    pos_out = torch.empty(n_keep, dtype=torch.int32, device=x.device)
+    fn = lib().agq_block_calibrate if calibrate else lib().agq_block_forward
+    _ok(fn(ctypes.byref(blk), _ptr(x), _ptr(pos), _ptr(rope_cos), _ptr(rope_sin), rope_cos.shape[0], S, n_keep,
+           _ptr(x_out), _ptr(pos_out), _ptr(workspace), workspace.numel(), _stream()),
+        "agq_block_calibrate" if calibrate else "agq_block_forward")
+    return x_out, pos_out, workspace, L
+
+
+def block_tensor(blk: AgqBlock, L: AgqBlockLayout, workspace, name: str, S: int, n_keep: int):
+    """View of one intermediate tensor of the last call inside its workspace."""
+    d, H, F, sp = blk.d, blk.H, blk.F, L.S_pad
+    shapes = dict(h1=(S, d), q=(S, d), k=(S, d), v=(S, d), q_rot=(S, d), k_rot=(S, d), o=(sp, d),
+                  o_kept=(n_keep, d), attn_out=(n_keep, d), x1=(n_keep, d), h2=(n_keep, d), down=(n_keep, d),
+                  gate=(n_keep, F), up=(n_keep, F), act=(n_keep, F))
+    off = getattr(L, name)
+    if name in ("q_q", "k_q", "v_q"):
+        return workspace[off:off + sp * d].view(torch.int8).view(H, sp, d // H)
+    if name in ("score", "idx"):
+        n = sp if name == "score" else n_keep
+        return workspace[off:off + 4 * n].view(torch.int32)
+    r, c = shapes[name]
+    return workspace[off:off + 2 * r * c].view(torch.float16).view(r, c)
+
+
+def cascade_keep(S: int, beta: float, m: int) -> list:
+    out = (ctypes.c_int64 * m)()
+    _ok(lib().agq_cascade_keep(S, beta, m, ctypes.cast(out, _vp)), "agq_cascade_keep")
+    return list(out)

@@ -171,3 +171,67 @@ def test_trip_and_fused_attention_host_checks(lib):
     for bad in (dict(H=0), dict(S=64), dict(S=200), dict(S=65536), dict(D=32), dict(D=256), dict(qmax=4), dict(e_q=99),
                 dict(q=None), dict(q=odd), dict(o=None)):
         assert qk(**bad) == EINVAL, bad
+
+
+def _fake_block(binding, **kw):
+    p = 4096
+    blk = binding.AgqBlock(d=512, H=4, F=1408, qmax=15, bits_attn_out=4, rms_eps=1e-5, g_attn_f16=p, g_mlp_f16=p)
+    for n in binding.BLOCK_PROJ:
+        setattr(blk, "w_" + n, p)
+        setattr(blk, "s_" + n, p)
+    for k, v in kw.items():
+        setattr(blk, k, v)
+    return blk
+
+
+def test_block_layout_and_host_checks(lib):
+    from paper_2312_05693_amd import binding
+    EINVAL, ESIZE = -1, -2
+    L = binding.AgqBlockLayout()
+    lay = lambda blk, S, keep: lib.agq_block_layout_of(ctypes.byref(blk), S, keep, ctypes.byref(L))
+    blk = _fake_block(binding)
+    assert lay(blk, 200, 150) == 0
+    assert L.S_pad == 256 and L.h1 == 0 and L.q == 200 * 512 * 2 and L.total % 256 == 0
+    offs = [getattr(L, n) for n in binding.BLOCK_TENSORS] + [L.gemm_ws, L.total]
+    assert offs == sorted(offs) and all(o % 256 == 0 for o in offs)
+    assert L.o_kept - L.idx == 768                       # 150 int32 indices, padded to 256 bytes
+    assert L.gate - L.h2 == 150 * 512 * 2 and L.up - L.gate == 150 * 1408 * 2
+    assert lay(blk, 200, 200) == 0 and L.o_kept == L.o   # nothing pruned: no gathered copy
+    for bad in (dict(d=500), dict(H=3), dict(H=16), dict(F=1400), dict(qmax=8), dict(bits_attn_out=6),
+                dict(rms_eps=-1.0), dict(H=0), dict(d=0)):
+        assert lay(_fake_block(binding, **bad), 200, 150) == EINVAL, bad
+    assert lay(blk, 0, 0) == EINVAL and lay(blk, 200, 0) == EINVAL and lay(blk, 200, 201) == EINVAL
+    assert lay(blk, 8193, 100) == EINVAL
+
+    p, odd = ctypes.c_void_p(4096), ctypes.c_void_p(4100)
+    ok = dict(blk=blk, x=p, pos=p, cos=p, sin=p, P=256, S=200, keep=150, out=p, pos_out=p, ws=p, wsb=1 << 40, st=None)
+
+    def call(fn=lib.agq_block_forward, **kw):
+        a = dict(ok, **kw)
+        return fn(ctypes.byref(a["blk"]), a["x"], a["pos"], a["cos"], a["sin"], a["P"], a["S"], a["keep"], a["out"],
+                  a["pos_out"], a["ws"], a["wsb"], a["st"])
+
+    for name in ("x", "pos", "cos", "sin", "out", "ws"):
+        assert call(**{name: None}) == EINVAL, name
+    assert call(x=odd) == EINVAL and call(ws=ctypes.c_void_p(4096 + 16)) == EINVAL
+    assert call(P=0) == EINVAL and call(S=0) == EINVAL and call(keep=201) == EINVAL
+    assert call(wsb=1000) == ESIZE
+    assert call(blk=_fake_block(binding, e_q=41)) == EINVAL
+    assert call(blk=_fake_block(binding, w_down=None)) == EINVAL
+    assert call(blk=_fake_block(binding, s_gate=4100)) == EINVAL
+    assert call(fn=lib.agq_block_calibrate, wsb=1000) == ESIZE
+    assert lib.agq_block_forward(None, p, p, p, p, 256, 200, 150, p, p, p, 1 << 40, None) == EINVAL
+
+
+def test_cascade_keep_matches_the_oracle(lib, oracle):
+    from oracle import agq_block_oracle
+    from paper_2312_05693_amd import binding
+    for S, beta, m in [(2048, 0.75, 2), (2048, 0.5, 1), (2048, 0.3, 4), (777, 0.6, 5), (4096, 0.1, 8), (5, 0.9, 3),
+                       (0, 0.5, 2), (2048, 0.0, 3)]:
+        assert binding.cascade_keep(S, beta, m) == agq_block_oracle.cascade_keep(S, beta, m)
+    out = (ctypes.c_int64 * 4)()
+    assert lib.agq_cascade_keep(100, 1.0, 2, ctypes.cast(out, ctypes.c_void_p)) == -1
+    assert lib.agq_cascade_keep(100, -0.1, 2, ctypes.cast(out, ctypes.c_void_p)) == -1
+    assert lib.agq_cascade_keep(100, 0.5, 0, ctypes.cast(out, ctypes.c_void_p)) == -1
+    assert lib.agq_cascade_keep(100, float("nan"), 2, ctypes.cast(out, ctypes.c_void_p)) == -1
+    assert lib.agq_cascade_keep(100, 0.5, 2, None) == -1

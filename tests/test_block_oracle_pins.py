@@ -4,7 +4,6 @@ arithmetic, complex-number rotation, closed forms, library routines the oracle
 does not call, and wiring special cases.  No GPU is used here."""
 from __future__ import annotations
 
-import cmath
 from fractions import Fraction
 
 import numpy as np
