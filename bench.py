@@ -56,6 +56,7 @@ def main():
     ap.add_argument("--no-prefill", action="store_true")
     ap.add_argument("--no-attention", action="store_true")
     ap.add_argument("--no-trip", action="store_true")
+    ap.add_argument("--no-block", action="store_true")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also run a 256 MiB device copy: the known traffic that scales the FETCH_SIZE / WRITE_SIZE counters")
     ap.add_argument("--per-projection", action="store_true", help="seven single calls per block instead of four")
@@ -322,6 +323,19 @@ def main():
             del blobs_t, blobs_p, xcal
         result["trip"] = trip
 
+    def time_plain(f, reps=12):
+        """ms per call, eager launches on the current stream (events recorded on that stream)"""
+        for _ in range(3):
+            f()
+        torch.cuda.synchronize()
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        for _ in range(reps):
+            f()
+        b.record()
+        torch.cuda.synchronize()
+        return a.elapsed_time(b) / reps
+
     # ---- attention side path at LLaMA-13B size: log2-quantized softmax x V with the start-token score,
     #      then Eq.4 pruning to half the tokens (HBM bound: the probabilities are read once)
     if not args.no_attention:
@@ -342,18 +356,6 @@ def main():
         def attn():
             turn[0] += 1
             return agq.log2_quant_softmax(probs[turn[0] % 3], vq, -5)
-
-        def time_plain(f, reps=12):
-            for _ in range(3):
-                f()
-            torch.cuda.synchronize()
-            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            a.record()
-            for _ in range(reps):
-                f()
-            b.record()
-            torch.cuda.synchronize()
-            return a.elapsed_time(b) / reps
 
         us_attn = time_plain(attn) * 1e3
         o_a, _, score_a = attn()
@@ -406,6 +408,42 @@ def main():
                          "frac": round(ideal_us / us_qk, 4), "traffic": None, "kernel": "qk_log2_attn_kernel",
                          "note": "algorithmic ops: one int8 Q K^T and one fp16 P V over the causal pairs; peak = "
                                  "those ops at 5.0 POP/s and 2.5 PFLOP/s; the kernel computes Q K^T twice (two passes)"}}
+
+    # ---- one whole block of the pipeline (Section 4.2, Figure 3): RMSNorm, q/k/v, rotary embedding + Eq.2,
+    #      attention from int8 Q and K, pruning (Section 4.3), 4-bit projection after attention, residual,
+    #      RMSNorm, gate/up, SwiGLU, down, residual; 2048 tokens in, all of them or half of them out
+    if not args.no_block:
+        def unit_packed(N, K):
+            w = torch.randn((N, K), generator=gen, device=dev, dtype=torch.float32)
+            sw = w.abs().amax(dim=1) / 7.0
+            wq = torch.clamp(torch.round(w / sw[:, None]), -8, 7).to(torch.int8)
+            return agq.pack_w4(wq), (sw / K ** 0.5).to(torch.float16)      # unit-scale residual stream
+
+        blocks = []
+        for (model, d, H, F) in (("llama13b", 5120, 40, 13824), ("llama7b", 4096, 32, 11008)):
+            S = PREFILL_M
+            wts = {"g_attn": torch.ones(d, dtype=torch.float16, device=dev), "g_mlp": torch.ones(d, dtype=torch.float16, device=dev)}
+            for n, (N, K) in dict(q=(d, d), k=(d, d), v=(d, d), o=(d, d), gate=(F, d), up=(F, d), down=(d, F)).items():
+                wts["w_" + n], wts["s_" + n] = unit_packed(N, K)
+            xb = torch.from_numpy(synth.make_activation(S, d, synth.n_outlier_channels(d), seed=5)).to(dev)
+            posb = torch.arange(S, dtype=torch.int32, device=dev)
+            cs, sn = synth.rope_tables(S, d // H)
+            cs, sn = torch.from_numpy(cs).to(dev), torch.from_numpy(sn).to(dev)
+            entry = {"model": model, "d": d, "H": H, "F": F, "S": S}
+            for keep in (S, S // 2):
+                blk = agq.make_block(d, H, F, wts, qmax=15, bits_attn_out=4, rms_eps=1e-5)
+                _, _, wsb, _ = agq.block_forward(blk, xb, posb, cs, sn, n_keep=keep, calibrate=True)
+                ms = time_plain(lambda: agq.block_forward(blk, xb, posb, cs, sn, n_keep=keep, workspace=wsb), reps=10)
+                pairs = H * S * (S + 1) // 2
+                ops = 2.0 * S * d * 3 * d + 4.0 * pairs * (d // H) + 2.0 * keep * d * d + 6.0 * keep * d * F
+                entry["keep_%d" % keep] = {"ms": round(ms, 4), "tokens_in/s": round(S / ms * 1e3, 0),
+                                           "products_TOP/s": round(ops / ms / 1e9, 1), "exps": agq.block_exps(blk)}
+                del wsb
+            blocks.append(entry)
+            del wts, xb
+        result["block"] = {"workload": "one LLaMA block of the quantized pipeline, 2048 tokens, W4A8 with 4-bit activations "
+                                       "after attention, without pruning and pruning to half after attention",
+                           "blocks": blocks}
 
     # ---- CPU baseline: the oracle as it stands, on a bounded sample of the decode workload
     if not args.no_cpu_baseline:

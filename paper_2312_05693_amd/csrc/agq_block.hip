@@ -143,6 +143,7 @@ struct RopeArgs {
     const int32_t *pos;
     const float *cos_t, *sin_t;   // float32 [P, D/2]
     int S, S_pad, H, D, P;
+    int32_t *zero;            // optional int32 [S_pad] cleared on the way (the importance score accumulates)
 };
 
 // blockIdx.x = token row (0 .. S_pad-1), blockIdx.y = tensor (0 q, 1 k, 2 v).  A work
@@ -155,6 +156,7 @@ __global__ __launch_bounds__(256) void rope_kernel(const RopeArgs a) {
     const int D = a.D, Dh = D >> 1, per_head = D >> 4;
     const int items = a.H * per_head;
     const bool pad = row >= a.S;
+    if (QUANT && a.zero && t == 0 && threadIdx.x == 0) a.zero[row] = 0;
     const int p = pad ? 0 : min(max(a.pos[row], 0), a.P - 1);   // a position outside the table is clamped into it
     // selects instead of indexing with t: the argument record stays in scalar registers
     const uint16_t *src = (t == 0 ? a.src[0] : t == 1 ? a.src[1] : a.src[2]) + (size_t)row * a.H * D;
@@ -223,11 +225,6 @@ __global__ __launch_bounds__(256) void add_kernel(const uint16_t *__restrict__ a
     store8(out + c * 8, o);
 }
 
-__global__ void fill_i32_kernel(int32_t *p, int n, int v) {
-    const int i = blockIdx.x * 256 + threadIdx.x;
-    if (i < n) p[i] = v;
-}
-
 }  // namespace
 
 int agq_launch_rmsnorm(const void *x, const void *res, const int32_t *idx, const void *g, void *x1_out, void *y, int64_t rows,
@@ -247,7 +244,7 @@ int agq_launch_rmsnorm(const void *x, const void *res, const int32_t *idx, const
 
 int agq_launch_rope(const void *q, const void *k, const void *v, int64_t S, int64_t S_pad, int64_t H, int64_t D,
                     const int32_t *pos, const float *cos_t, const float *sin_t, int64_t P, int e_q, int e_k, int e_v,
-                    int8_t *q_q, int8_t *k_q, int8_t *v_q, void *q_rot, void *k_rot, void *stream) {
+                    int8_t *q_q, int8_t *k_q, int8_t *v_q, void *q_rot, void *k_rot, int32_t *zero, void *stream) {
     if (S == 0) return 0;
     RopeArgs a;
     a.src[0] = (const uint16_t *)q; a.src[1] = (const uint16_t *)k; a.src[2] = (const uint16_t *)v;
@@ -256,6 +253,7 @@ int agq_launch_rope(const void *q, const void *k, const void *v, int64_t S, int6
     a.inv[0] = ldexpf(1.0f, -e_q); a.inv[1] = ldexpf(1.0f, -e_k); a.inv[2] = ldexpf(1.0f, -e_v);
     a.pos = pos; a.cos_t = cos_t; a.sin_t = sin_t;
     a.S = (int)S; a.S_pad = (int)S_pad; a.H = (int)H; a.D = (int)D; a.P = (int)P;
+    a.zero = zero;
     hipStream_t st = (hipStream_t)stream;
     if (q_q)
         rope_kernel<true><<<dim3((unsigned)S_pad, 3), 256, 0, st>>>(a);
@@ -277,12 +275,6 @@ int agq_launch_add(const void *a, const void *b, void *out, int64_t n, void *str
     const size_t nchunk = (size_t)n / 8;
     add_kernel<<<(unsigned)((nchunk + 255) / 256), 256, 0, (hipStream_t)stream>>>((const uint16_t *)a, (const uint16_t *)b,
                                                                                 (uint16_t *)out, nchunk);
-    return (int)hipGetLastError();
-}
-
-int agq_launch_fill_i32(int32_t *p, int64_t n, int v, void *stream) {
-    if (n == 0) return 0;
-    fill_i32_kernel<<<(unsigned)((n + 255) / 256), 256, 0, (hipStream_t)stream>>>(p, (int)n, v);
     return (int)hipGetLastError();
 }
 

@@ -116,17 +116,16 @@ int run(const agq_block *b, int *exps, bool calibrate, const void *x, const int3
     AGQ_TRY(agq_gemm_w4a8_multi(at(L.h1), AGQ_X_F16, S, d, d, exps[E_ATTN_IN], 0, qkv, 3, gws, gws_bytes, stream));
     if (calibrate) {
         AGQ_TRY_HIP(agq_launch_rope(at(L.q), at(L.k), at(L.v), S, L.S_pad, H, D, pos, cos_t, sin_t, P, 0, 0, 0, nullptr,
-                                    nullptr, nullptr, at(L.q_rot), at(L.k_rot), stream));
+                                    nullptr, nullptr, at(L.q_rot), at(L.k_rot), nullptr, stream));
         AGQ_TRY(exp_for(E_Q, at(L.q_rot), S, d, 8));
         AGQ_TRY(exp_for(E_K, at(L.k_rot), S, d, 8));
         AGQ_TRY(exp_for(E_V, at(L.v), S, d, 8));
     }
     int8_t *q_q = static_cast<int8_t *>(at(L.q_q)), *k_q = static_cast<int8_t *>(at(L.k_q)),
            *v_q = static_cast<int8_t *>(at(L.v_q));
+    int32_t *score = static_cast<int32_t *>(at(L.score));   // accumulated by the attention call: cleared by the kernel before it
     AGQ_TRY_HIP(agq_launch_rope(at(L.q), at(L.k), at(L.v), S, L.S_pad, H, D, pos, cos_t, sin_t, P, exps[E_Q], exps[E_K],
-                                exps[E_V], q_q, k_q, v_q, nullptr, nullptr, stream));
-    int32_t *score = static_cast<int32_t *>(at(L.score));
-    AGQ_TRY_HIP(agq_launch_fill_i32(score, L.S_pad, 0, stream));
+                                exps[E_V], q_q, k_q, v_q, nullptr, nullptr, score, stream));
     AGQ_TRY(agq_qk_log2_softmax(q_q, k_q, H, L.S_pad, D, 1, b->qmax, exps[E_Q], exps[E_K], v_q, exps[E_V], at(L.o), nullptr,
                                 score, stream));
 
@@ -187,7 +186,7 @@ int agq_rope_quantize(const void *q_f16, const void *k_f16, const void *v_f16, i
         if (!p || !aligned16(p)) return AGQ_EINVAL;
     if (!pos) return AGQ_EINVAL;
     return agq_launch_rope(q_f16, k_f16, v_f16, S, S_pad, H, D, pos, rope_cos, rope_sin, P, e_q, e_k, e_v, q_q, k_q, v_q,
-                           nullptr, nullptr, stream) ? AGQ_EHIP : AGQ_OK;
+                           nullptr, nullptr, nullptr, stream) ? AGQ_EHIP : AGQ_OK;
 }
 
 static int elementwise_ok(const void *a, const void *b, const void *out, int64_t n) {

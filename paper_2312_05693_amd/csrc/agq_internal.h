@@ -85,11 +85,11 @@ int agq_launch_prune(const int32_t *score, int64_t S, int64_t n_keep, const void
 // (optional) receive pos[...] and the source row of every output row
 int agq_launch_rmsnorm(const void *x, const void *res, const int32_t *idx, const void *g, void *x1_out, void *y, int64_t rows,
                        int64_t d, double eps, const int32_t *pos, int32_t *pos_out, int32_t *idx_out, void *stream);
-// q_q != NULL: rotate q and k, Eq.2 on q, k, v, int8 [H,S_pad,D] out; q_q == NULL: rotated fp16 q, k to q_rot, k_rot
+// q_q != NULL: rotate q and k, Eq.2 on q, k, v, int8 [H,S_pad,D] out (and zero[0..S_pad) = 0 when given);
+// q_q == NULL: rotated fp16 q, k to q_rot, k_rot
 int agq_launch_rope(const void *q, const void *k, const void *v, int64_t S, int64_t S_pad, int64_t H, int64_t D,
                     const int32_t *pos, const float *cos_t, const float *sin_t, int64_t P, int e_q, int e_k, int e_v,
-                    int8_t *q_q, int8_t *k_q, int8_t *v_q, void *q_rot, void *k_rot, void *stream);
+                    int8_t *q_q, int8_t *k_q, int8_t *v_q, void *q_rot, void *k_rot, int32_t *zero, void *stream);
 int agq_launch_swiglu(const void *gate, const void *up, void *out, int64_t n, void *stream);
 int agq_launch_add(const void *a, const void *b, void *out, int64_t n, void *stream);
-int agq_launch_fill_i32(int32_t *p, int64_t n, int v, void *stream);
 int agq_read_i32(const int32_t *dev, int32_t *host, int n, void *stream);
