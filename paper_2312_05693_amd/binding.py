@@ -369,17 +369,19 @@ def block_layout(blk: AgqBlock, S: int, n_keep: int) -> AgqBlockLayout:
     return L
 
 
-def block_forward(blk: AgqBlock, x, pos, rope_cos, rope_sin, n_keep=None, workspace=None, calibrate=False):
+def block_forward(blk: AgqBlock, x, pos, rope_cos, rope_sin, n_keep=None, workspace=None, calibrate=False, out=None):
     """One block (Section 4.2's pipeline with pruning after attention).  x fp16 [S,d], pos int32 [S], rope tables
     float32 [P, D/2].  calibrate=True derives the exponents from this input and stores them in blk.
-    Returns (x_out [n_keep,d], pos_out [n_keep], workspace, layout)."""
+    out: optional (x_out, pos_out) to write into.  Returns (x_out [n_keep,d], pos_out [n_keep], workspace, layout)."""
     S, d = x.shape
     n_keep = S if n_keep is None else n_keep
     L = block_layout(blk, S, n_keep)
     if workspace is None:
         workspace = torch.empty(L.total, dtype=torch.uint8, device=x.device)
-    x_out = torch.empty((n_keep, d), dtype=torch.float16, device=x.device)
-    pos_out = torch.empty(n_keep, dtype=torch.int32, device=x.device)
+    if out is None:
+        out = (torch.empty((n_keep, d), dtype=torch.float16, device=x.device),
+               torch.empty(n_keep, dtype=torch.int32, device=x.device))
+    x_out, pos_out = out
     fn = lib().agq_block_calibrate if calibrate else lib().agq_block_forward
     _ok(fn(ctypes.byref(blk), _ptr(x), _ptr(pos), _ptr(rope_cos), _ptr(rope_sin), rope_cos.shape[0], S, n_keep,
            _ptr(x_out), _ptr(pos_out), _ptr(workspace), workspace.numel(), _stream()),

@@ -181,6 +181,28 @@ def test_cascade_of_blocks(agq, oracle, blk_oracle):
     assert xg.shape == (keeps[-1], d) and host(pg)[0] == 0
 
 
+def test_block_graph_replay(agq, oracle, blk_oracle):
+    """agq_block_forward enqueues kernels only (no memset nodes, no allocation): captured into a HIP graph after an
+    eager call, every replay reproduces the eager result bit for bit, with eager work in between."""
+    S, d, H, F, keep = 200, 256, 2, 640, 120
+    x, pos, cos, sin, w = make_inputs(S, d, H, F, seed=31)
+    blk = agq.make_block(d, H, F, upload_weights(agq, w), rms_eps=EPS)
+    xd, pd, cd, sd = dev(x), dev(pos), dev(cos), dev(sin)
+    x_out, pos_out, ws, L = agq.block_forward(blk, xd, pd, cd, sd, n_keep=keep, calibrate=True)
+    agq.block_forward(blk, xd, pd, cd, sd, n_keep=keep, workspace=ws, out=(x_out, pos_out))
+    eager_x, eager_p = host(x_out).copy(), host(pos_out).copy()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        agq.block_forward(blk, xd, pd, cd, sd, n_keep=keep, workspace=ws, out=(x_out, pos_out))
+    for rep in range(3):
+        x_out.fill_(rep + 1)
+        pos_out.fill_(-1)
+        ws.fill_(0x5A if rep else 0)          # the call may not depend on what the workspace held
+        torch.cuda.synchronize()
+        graph.replay()
+        assert same(host(x_out), eager_x) and np.array_equal(host(pos_out), eager_p), rep
+
+
 SPECIAL = np.array([0.0, -0.0, 6e-8, -6e-8, 6.1e-5, -6.1e-5, 65504.0, -65504.0, 1024.0, 0.5, 2048.0, 1.0, 0.333, 12.0,
                     -12.0, 20.0, -20.0, 1e-3, -1e-3, 3.0, -7.0, 0.25, 1e4, -1e4], dtype=np.float16)
 
