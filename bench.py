@@ -12,11 +12,13 @@ Cache), resident in HBM before the timed region.  The metric is the algorithmic
 bytes of those calls (4-bit weights + fp16 scales + fp16 activation in and out)
 per second.
 
-The same line also carries the prefill regime (M = 2048, the seven shapes of
-one block, W4A8 and W4A4) as int8 TOP/s, the TRIP layer on the same shapes
-beside the plain one, the attention block at LLaMA-13B size (from fp16
-probabilities, and from int8 Q and K in one kernel) with pruning, the roofline of
-the dominant kernel, and the CPU oracle timed on the host cores.
+The same line also carries the same sweep with 4-bit activations (W4A4), the
+prefill regime (M = 2048, the seven shapes of one block, W4A8 and W4A4) as int8
+TOP/s, the TRIP layer on the same shapes beside the plain one, the attention
+block at LLaMA-13B size (from fp16 probabilities, and from int8 Q and K in one
+kernel) with pruning, one whole block of the pipeline (RMSNorm, projections,
+rotary embedding, attention, pruning, MLP) at LLaMA-13B and 7B shapes, the
+roofline of the dominant kernel, and the CPU oracle timed on the host cores.
 """
 from __future__ import annotations
 
@@ -116,25 +118,28 @@ def main():
             ys[(M, name)] = torch.empty((M, 11008), dtype=torch.float16, device=dev)
     NAMES = ("q", "k", "v", "o", "gate", "up", "down")
 
-    def single(M, layer, idx):
+    def single(M, layer, idx, bits=8):
         K, N, packed, sw = layer[idx]
-        agq.gemm_w4a8(xs[(M, K)], es[(M, K)], packed, sw, N, K, y=ys[(M, NAMES[idx])])
+        fn = agq.gemm_w4a8 if bits == 8 else agq.gemm_w4a4
+        fn(xs[(M, K)], es[(M, K)] + (8 - bits), packed, sw, N, K, y=ys[(M, NAMES[idx])])
 
-    def multi(M, layer, idxs):
+    def multi(M, layer, idxs, bits=8):
         K = layer[idxs[0]][0]
         projs = [(layer[i][2], layer[i][3], layer[i][1], ys[(M, NAMES[i])], None) for i in idxs]
-        agq.gemm_w4a8_multi(xs[(M, K)], es[(M, K)], projs, K)
+        fn = agq.gemm_w4a8_multi if bits == 8 else agq.gemm_w4a4_multi
+        fn(xs[(M, K)], es[(M, K)] + (8 - bits), projs, K)
 
-    def decode_pass(M):
+    def decode_pass(M, bits=8):
+        # the 4-bit activation grid takes the 8-bit exponent plus four: the same range in sixteen steps
         for layer in layers:
             if args.per_projection:
                 for idx in range(7):
-                    single(M, layer, idx)
+                    single(M, layer, idx, bits)
             else:
-                multi(M, layer, (0, 1, 2))
-                single(M, layer, 3)
-                multi(M, layer, (4, 5))
-                single(M, layer, 6)
+                multi(M, layer, (0, 1, 2), bits)
+                single(M, layer, 3, bits)
+                multi(M, layer, (4, 5), bits)
+                single(M, layer, 6, bits)
 
     def decode_step():
         for M in DECODE_M:
@@ -179,6 +184,17 @@ def main():
         per_m["M%d" % M] = {"ms_per_sweep": round(ms, 4), "GB/s": round(by / (ms * 1e-3) / 1e9, 1),
                             "frac_hbm": round(by / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
 
+    # the same sweep with 4-bit activations (W4A4: Eq.2 with b = 4 in the prologue, same kernels and weights)
+    per_m_a4 = {}
+    for M in DECODE_M:
+        def one4():
+            decode_pass(M, 4)
+        reps = max(3, args.steps // 3)
+        ms = timed(one4, 1, reps) / reps
+        by = sum(algorithmic_bytes(M, K, N) for layer in layers for (K, N, _, _) in layer)
+        per_m_a4["M%d" % M] = {"ms_per_sweep": round(ms, 4), "GB/s": round(by / (ms * 1e-3) / 1e9, 1),
+                               "frac_hbm": round(by / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
+
     result = {
         "metric": "W4A8 GEMM HBM GB/s, LLaMA-7B decode sweep (224 projections x M in {1,4,16})",
         "value": round(gbs, 1),
@@ -202,6 +218,7 @@ def main():
                                "every launch of a step", "avg_launch_us": round(avg_launch_us, 3),
                      "algorithmic_bytes_per_launch": int(bytes_per_step / launches_per_step)},
         "decode_by_M": per_m,
+        "decode_w4a4_by_M": per_m_a4,
         "launch": "one HIP graph per step, replayed; per block: qkv (one multi call), o, gate+up (one multi call), down"
                   if not args.per_projection else "one HIP graph per step, replayed; seven single calls per block",
     }
