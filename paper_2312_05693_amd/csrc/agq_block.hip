@@ -245,7 +245,7 @@ int agq_launch_rmsnorm(const void *x, const void *res, const int32_t *idx, const
 int agq_launch_rope(const void *q, const void *k, const void *v, int64_t S, int64_t S_pad, int64_t H, int64_t D,
                     const int32_t *pos, const float *cos_t, const float *sin_t, int64_t P, int e_q, int e_k, int e_v,
                     int8_t *q_q, int8_t *k_q, int8_t *v_q, void *q_rot, void *k_rot, int32_t *zero, void *stream) {
-    if (S == 0) return 0;
+    if (q_q ? S_pad == 0 : S == 0) return 0;   // with S == 0 the padding rows are still cleared
     RopeArgs a;
     a.src[0] = (const uint16_t *)q; a.src[1] = (const uint16_t *)k; a.src[2] = (const uint16_t *)v;
     a.dst_q[0] = q_q; a.dst_q[1] = k_q; a.dst_q[2] = v_q;

@@ -266,6 +266,13 @@ def test_rope_quantize_operator(agq, blk_oracle, S, H, D, S_pad):
                 blk_oracle.heads_int8(v, H, e_v, S_pad)]
         for gt, wt, n in zip(got, want, "qkv"):
             assert same(host(gt), wt), (n, e_q, e_k, e_v)
+    # no tokens at all: the padding rows are still cleared
+    junk = [torch.full((H, 128, D), 77, dtype=torch.int8, device="cuda") for _ in range(3)]
+    t = dev(q)
+    assert agq.lib().agq_rope_quantize(t.data_ptr(), t.data_ptr(), t.data_ptr(), 0, H, D, dev(pos).data_ptr(),
+                                       dev(cos).data_ptr(), dev(sin).data_ptr(), P, 0, 0, 0, 128, junk[0].data_ptr(),
+                                       junk[1].data_ptr(), junk[2].data_ptr(), None) == agq.AGQ_OK
+    assert all(not host(j).any() for j in junk)
 
 
 def test_block_llama13b_full_size_sampled(agq, oracle, blk_oracle):
