@@ -364,12 +364,12 @@ def log2_codes_packed(p, qmax: int, causal: bool = True) -> np.ndarray:
 
 def qk_scores(qq, kq) -> np.ndarray:
     """Section 4.2 lists QK among the quantized matrix products: s[h,i,j] =
-    sum_d qq[h,i,d] * kq[h,j,d] on the integer codes of Eq.2 (int8 [H,S,D] each).
-    int64, asserted to fit int32."""
+    sum_d qq[h,i,d] * kq[h,j,d] on the integer codes of Eq.2 (int8: qq [H,S,D],
+    kq [H,T,D]; T = S in the attention block).  int64, asserted to fit int32."""
     qq = np.asarray(qq, dtype=np.int64)
     kq = np.asarray(kq, dtype=np.int64)
-    if qq.shape != kq.shape or qq.ndim != 3:
-        raise ValueError("qq and kq are [H, S, D]")
+    if qq.ndim != 3 or kq.ndim != 3 or qq.shape[0] != kq.shape[0] or qq.shape[2] != kq.shape[2]:
+        raise ValueError("qq is [H, S, D], kq [H, T, D]")
     s = np.einsum("hid,hjd->hij", qq, kq)
     if s.size and max(int(s.max()), -int(s.min())) > INT32_MAX:
         raise OverflowError("score leaves int32")
@@ -390,7 +390,9 @@ def qk_log2_codes(qq, kq, e_q: int, e_k: int, qmax: int, causal: bool = True):
     t in lower precision may differ from c only where margin is below its error.
     Masked entries (j > i, causal) carry code qmax and margin +Inf."""
     s = qk_scores(qq, kq).astype(np.float64)
-    H, S, _ = s.shape
+    H, S, T = s.shape
+    if causal and S != T:
+        raise ValueError("the causal mask needs as many queries as keys")
     D = np.asarray(qq).shape[2]
     z2 = s * (2.0 ** (int(e_q) + int(e_k)) / np.sqrt(float(D)) * np.log2(np.e))   # logits in base-2 units
     if causal:

@@ -936,3 +936,68 @@ def test_graph_replay_attention_and_trip(agq, oracle):
         for t, want in zip(outs, eager):
             got = host(t)
             assert np.array_equal(got.view(np.uint8), want.view(np.uint8)), "replay differs from eager"
+
+
+# ------------------------------------------------------------------ maximum sizes
+
+@pytest.mark.parametrize("bits", [8, 4])
+def test_gemm_longest_reduction(agq, oracle, bits):
+    """K = 65536, the longest reduction the calls accept, with every operand at its extreme: the accumulator
+    reaches 128 * 8 * K = 2^26 (8 * 8 * K for 4-bit codes), and 2^30 inside the kernels with their extra factors."""
+    K, N = 65536, 32
+    lo = -(1 << (bits - 1))
+    wq = np.full((N, K), -8, np.int8)
+    wq[1::2] = 7
+    sw = np.full(N, 2.0 ** -14, np.float16)
+    for M in (3, 40):
+        x = np.full((M, K), float(lo), np.float16)
+        run_linear(agq, oracle, x, wq, sw, bits, e=0)
+    x, wq2, sw2 = make_case(5, K, N, seed=61, n_out=7)
+    run_linear(agq, oracle, x, wq2, sw2, bits)
+    assert agq.lib().agq_pack_w4_bytes(N, 2 * K) == 0
+
+
+def test_log2_attn_longest_sequence(agq, oracle):
+    """S = 32768, the longest sequence agq_log2_quant_softmax accepts (one head, 2 GiB of probabilities made on
+    the GPU); the oracle checks sampled rows, among them the first, the last and both sides of tile borders."""
+    S, D, qmax, e_v = 32768, 16, 15, -3
+    g = torch.Generator(device="cuda")
+    g.manual_seed(77)
+    p = torch.empty((1, S, S), dtype=torch.float16, device="cuda")
+    for r0 in range(0, S, 2048):
+        u = torch.rand((2048, S), generator=g, device="cuda") ** 24          # a few large entries per row
+        u[:, 0] += 0.05                                                       # attention to the first token
+        rows = torch.arange(r0, r0 + 2048, device="cuda")[:, None]
+        u = torch.where(torch.arange(S, device="cuda")[None, :] <= rows, u, torch.zeros_like(u))
+        p[0, r0:r0 + 2048] = (u / u.sum(dim=1, keepdim=True)).to(torch.float16)
+        del u
+    vq = np.random.default_rng(78).integers(-127, 128, size=(1, S, D)).astype(np.int8)
+    o, _, score = agq.log2_quant_softmax(p, dev(vq), e_v, qmax=qmax, causal=True)
+    rows = np.array([0, 1, 63, 64, 127, 128, 129, 4095, 4096, 20000, 32639, 32640, 32767])
+    p_rows = p[0, torch.from_numpy(rows).cuda()].cpu().numpy()
+    A = oracle.attn_v_rows(p_rows, rows + 1, vq[0], qmax)
+    want = np.ldexp(A.astype(np.float64), e_v - qmax).astype(np.float16)
+    assert np.array_equal(host(o)[rows].view(np.uint16), want.view(np.uint16))
+    col0 = p[:, :, 0].cpu().numpy()
+    assert np.array_equal(host(score).astype(np.int64), oracle.start_token_score(col0[:, :, None]))
+
+
+def test_qk_attention_longest_sequence(agq, oracle):
+    """S = 32768 for agq_qk_log2_softmax (one head, D = 64): the oracle evaluates sampled rows, each as the
+    non-causal attention of that query over the keys up to it."""
+    H, S, D, qmax, e_q, e_k, e_v = 1, 32768, 64, 15, -5, -5, -4
+    qq, kq, vq = synth.make_qkv_int8(H, S, D, seed=79)
+    o, codes, score = agq.qk_log2_softmax(dev(qq), dev(kq), dev(vq), e_q, e_k, e_v, qmax=qmax, causal=True,
+                                          want_codes=True, want_score=True)
+    o_h, score_h = host(o), host(score)
+    rows = [0, 1, 31, 32, 127, 128, 4095, 4096, 17000, 32639, 32640, 32767]
+    for i in rows:
+        got_c = unpack_codes(codes[0, i].cpu().numpy()[None, None], S)          # [1, 1, S]
+        assert (got_c[0, 0, i + 1:] == qmax).all()
+        want_c, margin = oracle.qk_log2_codes(qq[:, i:i + 1], kq[:, :i + 1], e_q, e_k, qmax, causal=False)
+        sure = margin > CODE_MARGIN
+        live = got_c[:, :, :i + 1]
+        assert np.array_equal(live[sure], want_c[sure]) and np.abs(live - want_c).max() <= 1
+        _, want_o = oracle.attn_v_from_codes(live, vq[:, :i + 1], e_v, qmax, causal=False)
+        assert np.array_equal(o_h[i:i + 1].view(np.uint16), want_o.view(np.uint16)), i
+        assert score_h[i] == 1 << (qmax - int(live[0, 0, 0]))
