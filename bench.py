@@ -223,6 +223,16 @@ def main():
                   if not args.per_projection else "one HIP graph per step, replayed; seven single calls per block",
     }
 
+    # ---- the small correctness configuration (one OPT-125M-sized layer, 128 tokens): launch-latency bound, time only
+    x0 = torch.from_numpy(synth.make_activation(128, 768, 4, seed=0)).to(dev)
+    p0w, s0w = make_packed(768, 768)
+    e0 = int(agq.calibrate_act_exp(x0, 8).item())
+    y0 = torch.empty((128, 768), dtype=torch.float16, device=dev)
+    ws0 = torch.empty(max(agq.gemm_workspace_bytes(128, 768, 768), 16), dtype=torch.uint8, device=dev)
+    ms0 = timed(lambda: agq.gemm_w4a8(x0, e0, p0w, s0w, 768, 768, y=y0, workspace=ws0), 2, 20) / 20
+    result["config0_opt125m_w4a8"] = {"M": 128, "K": 768, "N": 768, "us": round(ms0 * 1e3, 2),
+                                      "note": "151 Mop and 0.7 MB: two launches (quantize + layout, GEMM), latency bound"}
+
     # ---- prefill: one block's seven shapes at M = 2048, W4A8 and W4A4 (int8 MFMA bound)
     if not args.no_prefill:
         prefill = {}
