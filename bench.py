@@ -467,6 +467,29 @@ def main():
                 entry["keep_%d" % keep] = {"ms": round(ms, 4), "tokens_in/s": round(S / ms * 1e3, 0),
                                            "products_TOP/s": round(ops / ms / 1e9, 1), "exps": agq.block_exps(blk)}
                 del wsb
+            if model == "llama13b":
+                # TRIP (Section 4.3) at the two normalised activations (q/k/v and gate/up inputs, where the outlier
+                # channels sit): factors by Eq.8 on the tensors of the calibration pass, base step per Eq.6
+                S_, keep = S, S
+                blk = agq.make_block(d, H, F, wts, qmax=15, bits_attn_out=4, rms_eps=1e-5)
+                xo, po, wsb, Lb = agq.block_forward(blk, xb, posb, cs, sn, n_keep=keep, calibrate=True)
+                exps_t, trip_n, wts_t, kmax = agq.block_exps(blk), {}, dict(wts), 4
+                for site, src, names in (("attn_in", "h1", ("q", "k", "v")), ("mlp_in", "h2", ("gate", "up"))):
+                    t_site = agq.block_tensor(blk, Lb, wsb, src, S_, keep)
+                    exps_t["e_" + site] -= kmax
+                    alpha = agq.trip_search(t_site, 8, exps_t["e_" + site], kmax).cpu().numpy()
+                    for n in names:
+                        N, K = (d, d) if site == "attn_in" else (F, d)
+                        wq_n = agq.unpack_w4(wts["w_" + n], N, K)
+                        wts_t["w_" + n], trip_n[site] = agq.pack_w4_trip(wq_n, alpha)
+                        del wq_n
+                    entry["trip_" + site] = {"channels_with_factor": int((alpha > 0).sum()), "extra_chunks": trip_n[site]}
+                del wsb
+                blk_t = agq.make_block(d, H, F, wts_t, qmax=15, bits_attn_out=4, rms_eps=1e-5, exps=exps_t, trip=trip_n)
+                xo, po, wsb, _ = agq.block_forward(blk_t, xb, posb, cs, sn, n_keep=keep)
+                ms = timed(lambda: agq.block_forward(blk_t, xb, posb, cs, sn, n_keep=keep, workspace=wsb, out=(xo, po)), 2, 10) / 10
+                entry["keep_%d_trip" % keep] = {"ms": round(ms, 4), "tokens_in/s": round(S / ms * 1e3, 0)}
+                del wsb, wts_t
             blocks.append(entry)
             del wts, xb
         result["block"] = {"workload": "one LLaMA block of the quantized pipeline, 2048 tokens, W4A8 with 4-bit activations "

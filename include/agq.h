@@ -291,6 +291,14 @@ typedef struct agq_block {
     const void *s_q, *s_k, *s_v, *s_o, *s_gate, *s_up, *s_down;
     /* static exponents of the seven quantizers (post-training calibration)       */
     int e_attn_in, e_q, e_k, e_v, e_attn_out, e_mlp_in, e_mlp_act;
+    /* TRIP (Section 4.3) at the four activations that feed projections: -1 = the
+     * projections of that activation are agq_pack_w4 blobs and Eq.2 is used; n >= 0 =
+     * they are agq_pack_w4_trip blobs, all packed with the same factors, n =
+     * agq_trip_extra_chunks of those factors, and the site's exponent is Eq.6's base
+     * step.  (attn_in: q, k, v; attn_out: o; mlp_in: gate, up; mlp_act: down.)
+     * Needs d, F <= 32768.  Factors come from agq_trip_search on the site's tensor of
+     * a calibration pass (h1, o_kept, h2, act in the workspace).                  */
+    int trip_attn_in, trip_attn_out, trip_mlp_in, trip_mlp_act;
 } agq_block;
 
 /* Where every intermediate tensor of a call lives inside the workspace (byte
@@ -346,7 +354,7 @@ int agq_block_forward(const agq_block *blk, const void *x_f16, const int32_t *po
 /* The same pass with every exponent derived on the way from this input
  * (agq_calibrate_act_exp on the tensor each quantizer reads) and written back to
  * *blk: the post-training calibration step.  Waits for `stream` several times; not
- * capturable.                                                                     */
+ * capturable.  All four trip_* fields must be -1 (plain blobs).                   */
 int agq_block_calibrate(agq_block *blk, const void *x_f16, const int32_t *pos, const float *rope_cos,
                         const float *rope_sin, int64_t P, int64_t S, int64_t n_keep, void *x_out_f16,
                         int32_t *pos_out, void *workspace, size_t workspace_bytes, void *stream);

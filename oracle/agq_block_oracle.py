@@ -117,12 +117,20 @@ def cascade_keep(S: int, beta: float, m: int) -> list[int]:
 EXP_NAMES = ("e_attn_in", "e_q", "e_k", "e_v", "e_attn_out", "e_mlp_in", "e_mlp_act")
 
 
+SITES = ("attn_in", "attn_out", "mlp_in", "mlp_act")      # the four activations that feed projections
+
+
 def block_forward(x, pos, cos, sin, w: dict, H: int, qmax: int, eps: float, keep: int,
-                  bits_attn_out: int = 4, exps: dict | None = None) -> dict:
+                  bits_attn_out: int = 4, exps: dict | None = None, alphas: dict | None = None,
+                  trip_kmax: int | None = None) -> dict:
     """One block of the pipeline of Section 4.2 on fp16 x [S,d] with positions pos [S].
     w holds g_attn, g_mlp (fp16 [d]) and for each of q, k, v, o, gate, up, down
     the 4-bit weights `w_<name>` (int8 [N,K]) with their scales `s_<name>`.
     exps: the static exponents (EXP_NAMES); None calibrates them on this input.
+    alphas: TRIP factors (Section 4.3, Eq.5) per site of SITES, int [K] each, for the
+    activations that feed projections; a site without an entry uses Eq.2.  With a site's
+    factors its exponent is Eq.6's base step.  trip_kmax (only with exps None): derive
+    base step and factors of every site on the way (Eq.6, Eq.8 with K = trip_kmax).
     keep: tokens that survive the pruning after attention (== S: none pruned).
     Returns every intermediate tensor by name, `x_out` [keep,d], `pos_out`, `idx`
     and the exponents used."""
@@ -132,16 +140,27 @@ def block_forward(x, pos, cos, sin, w: dict, H: int, qmax: int, eps: float, keep
     S_pad = -(-S // 128) * 128
     e = dict(exps) if exps is not None else {}
 
-    def exp_of(name, t, bits):
+    al = dict(alphas) if alphas is not None else {}
+
+    def exp_of(name, t, bits, site=None):
         if exps is None:
-            e[name] = O.calibrate_act_exp(t, bits)
+            if site is not None and trip_kmax is not None:
+                e[name] = O.trip_base_exp(t, bits, trip_kmax)
+                al[site] = O.trip_search(t, bits, e[name], 0, trip_kmax)
+            else:
+                e[name] = O.calibrate_act_exp(t, bits)
         return e[name]
+
+    def linear(t, bits, ee, site, name):
+        if al.get(site) is not None:
+            return O.linear_w4_trip(t, bits, ee, 0, al[site], w["w_" + name], w["s_" + name])[1]
+        return O.linear_w4(t, bits, ee, 0, w["w_" + name], w["s_" + name])[1]
 
     r = {}
     r["h1"] = rmsnorm(x, w["g_attn"], eps)
-    ea = exp_of("e_attn_in", r["h1"], 8)
+    ea = exp_of("e_attn_in", r["h1"], 8, "attn_in")
     for n in ("q", "k", "v"):
-        _, r[n] = O.linear_w4(r["h1"], 8, ea, 0, w["w_" + n], w["s_" + n])
+        r[n] = linear(r["h1"], 8, ea, "attn_in", n)
     r["q_rot"] = rope(r["q"], pos, cos, sin, H)
     r["k_rot"] = rope(r["k"], pos, cos, sin, H)
     eq, ek, ev = exp_of("e_q", r["q_rot"], 8), exp_of("e_k", r["k_rot"], 8), exp_of("e_v", r["v"], 8)
@@ -156,17 +175,18 @@ def block_forward(x, pos, cos, sin, w: dict, H: int, qmax: int, eps: float, keep
     idx = O.prune_select(r["score"], keep)
     r["idx"] = idx
     r["o_kept"] = r["o"][idx]
-    eo = exp_of("e_attn_out", r["o_kept"], bits_attn_out)
-    _, r["attn_out"] = O.linear_w4(r["o_kept"], bits_attn_out, eo, 0, w["w_o"], w["s_o"])
+    eo = exp_of("e_attn_out", r["o_kept"], bits_attn_out, "attn_out")
+    r["attn_out"] = linear(r["o_kept"], bits_attn_out, eo, "attn_out", "o")
     r["x1"] = residual_add(x[idx], r["attn_out"])
     r["pos_out"] = np.asarray(pos, dtype=np.int32)[idx]
     r["h2"] = rmsnorm(r["x1"], w["g_mlp"], eps)
-    em = exp_of("e_mlp_in", r["h2"], 8)
-    _, r["gate"] = O.linear_w4(r["h2"], 8, em, 0, w["w_gate"], w["s_gate"])
-    _, r["up"] = O.linear_w4(r["h2"], 8, em, 0, w["w_up"], w["s_up"])
+    em = exp_of("e_mlp_in", r["h2"], 8, "mlp_in")
+    r["gate"] = linear(r["h2"], 8, em, "mlp_in", "gate")
+    r["up"] = linear(r["h2"], 8, em, "mlp_in", "up")
     r["act"] = swiglu(r["gate"], r["up"])
-    ed = exp_of("e_mlp_act", r["act"], 8)
-    _, r["down"] = O.linear_w4(r["act"], 8, ed, 0, w["w_down"], w["s_down"])
+    ed = exp_of("e_mlp_act", r["act"], 8, "mlp_act")
+    r["down"] = linear(r["act"], 8, ed, "mlp_act", "down")
     r["x_out"] = residual_add(r["x1"], r["down"])
+    r["alphas"] = al
     r["exps"] = e
     return r

@@ -65,6 +65,7 @@ class AgqProj(ctypes.Structure):
 
 BLOCK_PROJ = ("q", "k", "v", "o", "gate", "up", "down")
 BLOCK_EXPS = ("e_attn_in", "e_q", "e_k", "e_v", "e_attn_out", "e_mlp_in", "e_mlp_act")
+BLOCK_SITES = ("attn_in", "attn_out", "mlp_in", "mlp_act")
 BLOCK_TENSORS = ("h1", "q", "k", "v", "q_q", "k_q", "v_q", "o", "score", "idx", "o_kept", "attn_out", "x1", "h2",
                  "gate", "up", "act", "down", "q_rot", "k_rot")
 
@@ -74,7 +75,7 @@ class AgqBlock(ctypes.Structure):
     _fields_ = ([("d", _i64), ("H", _i64), ("F", _i64), ("qmax", _int), ("bits_attn_out", _int),
                  ("rms_eps", ctypes.c_double), ("g_attn_f16", _vp), ("g_mlp_f16", _vp)]
                 + [("w_" + n, _vp) for n in BLOCK_PROJ] + [("s_" + n, _vp) for n in BLOCK_PROJ]
-                + [(n, _int) for n in BLOCK_EXPS])
+                + [(n, _int) for n in BLOCK_EXPS] + [("trip_" + n, _int) for n in BLOCK_SITES])
 
 
 class AgqBlockLayout(ctypes.Structure):
@@ -345,9 +346,11 @@ def residual_add(a, b):
     return out
 
 
-def make_block(d, H, F, weights: dict, qmax=15, bits_attn_out=4, rms_eps=1e-5, exps: dict | None = None) -> AgqBlock:
+def make_block(d, H, F, weights: dict, qmax=15, bits_attn_out=4, rms_eps=1e-5, exps: dict | None = None,
+               trip: dict | None = None) -> AgqBlock:
     """weights: device tensors g_attn, g_mlp (fp16 [d]) and, for every projection in BLOCK_PROJ, the agq_pack_w4
-    blob `w_<name>` and the fp16 scales `s_<name>`.  The struct keeps the tensors alive."""
+    blob `w_<name>` and the fp16 scales `s_<name>`.  trip: for the sites of BLOCK_SITES whose projections are
+    agq_pack_w4_trip blobs, the number of extra chunks of their factors.  The struct keeps the tensors alive."""
     blk = AgqBlock(d=d, H=H, F=F, qmax=qmax, bits_attn_out=bits_attn_out, rms_eps=rms_eps,
                    g_attn_f16=_ptr(weights["g_attn"]), g_mlp_f16=_ptr(weights["g_mlp"]))
     for n in BLOCK_PROJ:
@@ -355,6 +358,8 @@ def make_block(d, H, F, weights: dict, qmax=15, bits_attn_out=4, rms_eps=1e-5, e
         setattr(blk, "s_" + n, _ptr(weights["s_" + n]))
     for n in BLOCK_EXPS:
         setattr(blk, n, 0 if exps is None else int(exps[n]))
+    for n in BLOCK_SITES:
+        setattr(blk, "trip_" + n, -1 if trip is None or trip.get(n) is None else int(trip[n]))
     blk._keepalive = dict(weights)
     return blk
 

@@ -12,6 +12,7 @@ inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 
 inline size_t up256(size_t v) { return (v + 255) & ~(size_t)255; }
 constexpr int64_t kMaxTokens = 8192;   // agq_prune_tokens' limit
 constexpr int64_t kMaxWidth = 65536;   // the GEMMs' limit on K
+constexpr int64_t kMaxTripWidth = 32768;   // and with TRIP blobs
 
 bool dims_ok(const agq_block *b) {
     if (!b || b->H < 1 || b->d < 128 || b->d > kMaxWidth || b->F < 128 || b->F > kMaxWidth) return false;
@@ -21,7 +22,17 @@ bool dims_ok(const agq_block *b) {
     if (b->H > 127) return false;   // the importance score sums H terms of 2^qmax in int32 with room to spare
     if (b->qmax != 15 && b->qmax != 7) return false;
     if (b->bits_attn_out != 4 && b->bits_attn_out != 8) return false;
+    const int trips[4] = {b->trip_attn_in, b->trip_attn_out, b->trip_mlp_in, b->trip_mlp_act};
+    for (int t : trips) {
+        if (t < -1 || t > AGQ_TRIP_MAX_EXTRA) return false;
+        if (t >= 0 && (b->d > kMaxTripWidth || b->F > kMaxTripWidth)) return false;
+    }
     return b->rms_eps >= 0.0 && b->rms_eps == b->rms_eps;
+}
+
+// scratch of the projections that read an activation [M,K] (plain or TRIP blobs)
+size_t site_ws(int64_t M, int64_t N, int64_t K, int n_extra) {
+    return n_extra >= 0 ? agq_gemm_trip_workspace_bytes(M, N, K, n_extra) : agq_gemm_workspace_bytes(M, N, K);
 }
 
 int layout_of(const agq_block *b, int64_t S, int64_t n_keep, agq_block_layout *L) {
@@ -51,10 +62,10 @@ int layout_of(const agq_block *b, int64_t S, int64_t n_keep, agq_block_layout *L
     L->down = take(k * d * 2);
     L->q_rot = take(s * d * 2);
     L->k_rot = take(s * d * 2);
-    size_t ws = agq_gemm_workspace_bytes(S, b->d, b->d);
-    const size_t w2 = agq_gemm_workspace_bytes(n_keep, b->F, b->d), w3 = agq_gemm_workspace_bytes(n_keep, b->d, b->F);
-    ws = ws > w2 ? ws : w2;
-    ws = ws > w3 ? ws : w3;
+    const size_t need[4] = {site_ws(S, b->d, b->d, b->trip_attn_in), site_ws(n_keep, b->d, b->d, b->trip_attn_out),
+                            site_ws(n_keep, b->F, b->d, b->trip_mlp_in), site_ws(n_keep, b->d, b->F, b->trip_mlp_act)};
+    size_t ws = 0;
+    for (size_t n : need) ws = ws > n ? ws : n;
     L->gemm_ws = take(ws + 16);   // a few words behind the GEMM scratch hold calibration results
     L->total = off;
     return AGQ_OK;
@@ -69,6 +80,30 @@ int layout_of(const agq_block *b, int64_t S, int64_t n_keep, agq_block_layout *L
     do {                                 \
         if ((call) != 0) return AGQ_EHIP; \
     } while (0)
+
+// The projections `projs` of one activation x [M,K] (fp16, contiguous): plain blobs go through the multi-projection
+// call (Eq.2 once); TRIP blobs, all packed with the same factors, share one gathered pre-pass (its tables are the
+// same in every blob) when the tiled kernel runs, and are single launches in the weight-streaming regime.
+int site_gemm(int bits, const void *x, int64_t M, int64_t K, int e, int n_extra, const agq_proj *projs, int count, void *gws,
+              size_t gws_bytes, void *stream) {
+    if (n_extra < 0)
+        return bits == 8 ? agq_gemm_w4a8_multi(x, AGQ_X_F16, M, K, K, e, 0, projs, count, gws, gws_bytes, stream)
+                         : agq_gemm_w4a4_multi(x, AGQ_X_F16, M, K, K, e, 0, projs, count, gws, gws_bytes, stream);
+    if (M <= AGQ_DECODE_MAX_M) {
+        for (int p = 0; p < count; ++p) {
+            const agq_proj &pr = projs[p];
+            AGQ_TRY((bits == 8 ? agq_gemm_w4a8_trip : agq_gemm_w4a4_trip)(x, M, K, K, e, 0, pr.w_packed, n_extra, pr.w_scale_f16,
+                                                                       pr.N, pr.y_f16, pr.ldy, nullptr, nullptr, 0, stream));
+        }
+        return AGQ_OK;
+    }
+    if (gws_bytes < agq_gemm_trip_workspace_bytes(M, projs[0].N, K, n_extra)) return AGQ_ESIZE;
+    AGQ_TRY_HIP(agq_launch_prepack_trip(x, bits, M, K, K, e, 0, projs[0].w_packed, projs[0].N, n_extra, gws, stream));
+    for (int p = 0; p < count; ++p)
+        AGQ_TRY_HIP(agq_launch_gemm_tiled(gws, M, K, e, 0, projs[p].w_packed, projs[p].w_scale_f16, projs[p].N, projs[p].y_f16,
+                                          projs[p].ldy, nullptr, n_extra, stream));
+    return AGQ_OK;
+}
 
 // exps: the exponents to use, updated in place when `calibrate` is set
 int run(const agq_block *b, int *exps, bool calibrate, const void *x, const int32_t *pos, const float *cos_t,
@@ -87,6 +122,8 @@ int run(const agq_block *b, int *exps, bool calibrate, const void *x, const int3
     if (!calibrate)
         for (int i = 0; i < 7; ++i)
             if (exps[i] < AGQ_E_MIN || exps[i] > AGQ_E_MAX) return AGQ_EINVAL;
+    if (calibrate && (b->trip_attn_in >= 0 || b->trip_attn_out >= 0 || b->trip_mlp_in >= 0 || b->trip_mlp_act >= 0))
+        return AGQ_EINVAL;   // the calibration pass runs on plain blobs; factors are searched on its tensors afterwards
     if (workspace_bytes < L.total) return AGQ_ESIZE;
 
     char *ws = static_cast<char *>(workspace);
@@ -113,7 +150,7 @@ int run(const agq_block *b, int *exps, bool calibrate, const void *x, const int3
     const agq_proj qkv[3] = {{b->w_q, b->s_q, d, at(L.q), d, nullptr},
                              {b->w_k, b->s_k, d, at(L.k), d, nullptr},
                              {b->w_v, b->s_v, d, at(L.v), d, nullptr}};
-    AGQ_TRY(agq_gemm_w4a8_multi(at(L.h1), AGQ_X_F16, S, d, d, exps[E_ATTN_IN], 0, qkv, 3, gws, gws_bytes, stream));
+    AGQ_TRY(site_gemm(8, at(L.h1), S, d, exps[E_ATTN_IN], b->trip_attn_in, qkv, 3, gws, gws_bytes, stream));
     if (calibrate) {
         AGQ_TRY_HIP(agq_launch_rope(at(L.q), at(L.k), at(L.v), S, L.S_pad, H, D, pos, cos_t, sin_t, P, 0, 0, 0, nullptr,
                                     nullptr, nullptr, at(L.q_rot), at(L.k_rot), nullptr, stream));
@@ -134,23 +171,20 @@ int run(const agq_block *b, int *exps, bool calibrate, const void *x, const int3
     const bool pruned = n_keep < S;
     if (pruned) AGQ_TRY(agq_prune_tokens(score, S, n_keep, at(L.o), d, idx, at(L.o_kept), stream));
     AGQ_TRY(exp_for(E_ATTN_OUT, at(L.o_kept), n_keep, d, b->bits_attn_out));
-    if (b->bits_attn_out == 4)
-        AGQ_TRY(agq_gemm_w4a4(at(L.o_kept), AGQ_X_F16, n_keep, d, d, exps[E_ATTN_OUT], 0, b->w_o, b->s_o, d, at(L.attn_out), d,
-                              nullptr, gws, gws_bytes, stream));
-    else
-        AGQ_TRY(agq_gemm_w4a8(at(L.o_kept), AGQ_X_F16, n_keep, d, d, exps[E_ATTN_OUT], 0, b->w_o, b->s_o, d, at(L.attn_out), d,
-                              nullptr, gws, gws_bytes, stream));
+    const agq_proj op = {b->w_o, b->s_o, d, at(L.attn_out), d, nullptr};
+    AGQ_TRY(site_gemm(b->bits_attn_out, at(L.o_kept), n_keep, d, exps[E_ATTN_OUT], b->trip_attn_out, &op, 1, gws, gws_bytes,
+                      stream));
 
     // MLP half: x1 = x[idx] + attn_out, h2 = RMSNorm(x1)
     AGQ_TRY_HIP(agq_launch_rmsnorm(at(L.attn_out), x, pruned ? idx : nullptr, b->g_mlp_f16, at(L.x1), at(L.h2), n_keep, d,
                                    b->rms_eps, pos, pos_out, pruned ? nullptr : idx, stream));
     AGQ_TRY(exp_for(E_MLP_IN, at(L.h2), n_keep, d, 8));
     const agq_proj gu[2] = {{b->w_gate, b->s_gate, F, at(L.gate), F, nullptr}, {b->w_up, b->s_up, F, at(L.up), F, nullptr}};
-    AGQ_TRY(agq_gemm_w4a8_multi(at(L.h2), AGQ_X_F16, n_keep, d, d, exps[E_MLP_IN], 0, gu, 2, gws, gws_bytes, stream));
+    AGQ_TRY(site_gemm(8, at(L.h2), n_keep, d, exps[E_MLP_IN], b->trip_mlp_in, gu, 2, gws, gws_bytes, stream));
     AGQ_TRY_HIP(agq_launch_swiglu(at(L.gate), at(L.up), at(L.act), n_keep * F, stream));
     AGQ_TRY(exp_for(E_MLP_ACT, at(L.act), n_keep, F, 8));
-    AGQ_TRY(agq_gemm_w4a8(at(L.act), AGQ_X_F16, n_keep, F, F, exps[E_MLP_ACT], 0, b->w_down, b->s_down, d, at(L.down), d,
-                          nullptr, gws, gws_bytes, stream));
+    const agq_proj dp = {b->w_down, b->s_down, d, at(L.down), d, nullptr};
+    AGQ_TRY(site_gemm(8, at(L.act), n_keep, F, exps[E_MLP_ACT], b->trip_mlp_act, &dp, 1, gws, gws_bytes, stream));
     AGQ_TRY_HIP(agq_launch_add(at(L.x1), at(L.down), x_out, n_keep * d, stream));
     return AGQ_OK;
 }

@@ -179,6 +179,8 @@ def _fake_block(binding, **kw):
     for n in binding.BLOCK_PROJ:
         setattr(blk, "w_" + n, p)
         setattr(blk, "s_" + n, p)
+    for n in binding.BLOCK_SITES:
+        setattr(blk, "trip_" + n, -1)
     for k, v in kw.items():
         setattr(blk, k, v)
     return blk
@@ -220,6 +222,12 @@ def test_block_layout_and_host_checks(lib):
     assert call(blk=_fake_block(binding, w_down=None)) == EINVAL
     assert call(blk=_fake_block(binding, s_gate=4100)) == EINVAL
     assert call(fn=lib.agq_block_calibrate, wsb=1000) == ESIZE
+    # TRIP sites: the count of extra chunks is checked, the workspace grows with it, calibration wants plain blobs
+    assert call(blk=_fake_block(binding, trip_mlp_in=17)) == EINVAL and call(blk=_fake_block(binding, trip_attn_in=-2)) == EINVAL
+    assert call(fn=lib.agq_block_calibrate, blk=_fake_block(binding, trip_attn_out=0)) == EINVAL
+    L2 = binding.AgqBlockLayout()
+    assert lib.agq_block_layout_of(ctypes.byref(_fake_block(binding, trip_mlp_act=3)), 200, 150, ctypes.byref(L2)) == 0
+    assert lay(blk, 200, 150) == 0 and L2.total - L2.gemm_ws >= 256 * (1408 + 3 * 128) > L.total - L.gemm_ws - 512
     assert lib.agq_block_forward(None, p, p, p, p, 256, 200, 150, p, p, p, 1 << 40, None) == EINVAL
 
 

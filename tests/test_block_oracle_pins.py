@@ -270,3 +270,33 @@ def test_block_stages_are_the_pinned_functions(oracle, blk):
     assert np.array_equal(r["act"], blk.swiglu(r["gate"], r["up"]))
     assert np.array_equal(r["down"], oracle.linear_w4(r["act"], 8, e["e_mlp_act"], 0, w["w_down"], w["s_down"])[1])
     assert np.array_equal(r["x_out"], blk.residual_add(r["x1"], r["down"]))
+
+
+def test_block_trip_sites(oracle, blk):
+    # factors at the activations that feed projections (Eq.5-8): all-zero factors are the plain block; otherwise
+    # the site's projections are the pinned TRIP layer on the tensor before them
+    S, d, H, F = 48, 128, 2, 256
+    x, pos, cos, sin, w = _block_inputs(S, d, H, F, 23)
+    plain = blk.block_forward(x, pos, cos, sin, w, H, 15, 1e-5, 30)
+    zeros = {s: np.zeros(F if s == "mlp_act" else d, dtype=np.int8) for s in blk.SITES}
+    same = blk.block_forward(x, pos, cos, sin, w, H, 15, 1e-5, 30, exps=plain["exps"], alphas=zeros)
+    assert np.array_equal(same["x_out"], plain["x_out"]) and np.array_equal(same["idx"], plain["idx"])
+    r = blk.block_forward(x, pos, cos, sin, w, H, 15, 1e-5, 30, trip_kmax=3)
+    e, al = r["exps"], r["alphas"]
+    assert set(al) == set(blk.SITES)
+    assert e["e_attn_in"] == oracle.trip_base_exp(r["h1"], 8, 3) == oracle.calibrate_act_exp(r["h1"], 8) - 3
+    assert np.array_equal(al["attn_in"], oracle.trip_search(r["h1"], 8, e["e_attn_in"], 0, 3))
+    assert np.array_equal(al["attn_out"], oracle.trip_search(r["o_kept"], 4, e["e_attn_out"], 0, 3))
+    assert np.array_equal(al["mlp_act"], oracle.trip_search(r["act"], 8, e["e_mlp_act"], 0, 3))
+    for name, src, site, bits in (("k", "h1", "attn_in", 8), ("o", "o_kept", "attn_out", 4), ("up", "h2", "mlp_in", 8),
+                                  ("down", "act", "mlp_act", 8)):
+        out = "attn_out" if name == "o" else name
+        want = oracle.linear_w4_trip(r[src], bits, e["e_" + site], 0, al[site], w["w_" + name], w["s_" + name])[1]
+        assert np.array_equal(r[out], want), name
+    # the outlier channels of the input (scaled by 20 in the recipe) are the ones that get the large factors after
+    # the first normalisation
+    big = np.argsort(np.abs(x.astype(np.float64)).mean(axis=0))[-4:]
+    assert set(np.flatnonzero(al["attn_in"] >= 2)) <= set(big) and (al["attn_in"][big] >= 1).all()
+    # given factors and exponents reproduce the derived run
+    again = blk.block_forward(x, pos, cos, sin, w, H, 15, 1e-5, 30, exps=e, alphas=al)
+    assert np.array_equal(again["x_out"], r["x_out"])

@@ -52,12 +52,22 @@ def make_inputs(S, d, H, F, seed, pos=None, P=None):
     return x, pos, cos, sin, synth.make_block_weights(d, H, F, seed)
 
 
-def upload_weights(agq, w):
+SITE_OF = dict(q="attn_in", k="attn_in", v="attn_in", o="attn_out", gate="mlp_in", up="mlp_in", down="mlp_act")
+
+
+def upload_weights(agq, w, alphas=None):
+    """Device weights; with `alphas` (site -> factors) the projections of those sites become TRIP blobs.
+    Returns the dict for make_block and, per site with factors, the number of extra chunks."""
     out = {"g_attn": dev(w["g_attn"]), "g_mlp": dev(w["g_mlp"])}
+    trip = {}
     for n in agq.BLOCK_PROJ:
-        out["w_" + n] = agq.pack_w4(dev(w["w_" + n]))
+        alpha = (alphas or {}).get(SITE_OF[n])
+        if alpha is None:
+            out["w_" + n] = agq.pack_w4(dev(w["w_" + n]))
+        else:
+            out["w_" + n], trip[SITE_OF[n]] = agq.pack_w4_trip(dev(w["w_" + n]), alpha)
         out["s_" + n] = dev(w["s_" + n])
-    return out
+    return (out, trip) if alphas is not None else out
 
 
 def gpu_tensors(agq, blk, L, ws, S, keep, names=None):
@@ -66,11 +76,16 @@ def gpu_tensors(agq, blk, L, ws, S, keep, names=None):
             if n not in ("q_rot", "k_rot")}
 
 
-def check_stages(agq, oracle, B, w, H, qmax, bits_o, x, pos, cos, sin, keep, exps, g, x_out, pos_out):
+def check_stages(agq, oracle, B, w, H, qmax, bits_o, x, pos, cos, sin, keep, exps, g, x_out, pos_out, alphas=None):
     """g: the GPU's intermediates.  Returns True when the GPU's attention codes equal the oracle's."""
     S, d = x.shape
     D, sp = d // H, g["o"].shape[0]
-    lin = lambda t, bits, e, n: oracle.linear_w4(t, bits, e, 0, w["w_" + n], w["s_" + n])[1]
+
+    def lin(t, bits, e, n):
+        alpha = (alphas or {}).get(SITE_OF[n])
+        if alpha is not None:
+            return oracle.linear_w4_trip(t, bits, e, 0, alpha, w["w_" + n], w["s_" + n])[1]
+        return oracle.linear_w4(t, bits, e, 0, w["w_" + n], w["s_" + n])[1]
     assert same(g["h1"], B.rmsnorm(x, w["g_attn"], EPS)), "h1"
     for n in ("q", "k", "v"):
         assert same(g[n], lin(g["h1"], 8, exps["e_attn_in"], n)), n
@@ -135,6 +150,36 @@ def test_block_stage_by_stage(agq, oracle, blk_oracle, S, d, H, F, keep, qmax, b
     # the same call again into the same workspace gives the same bits (no state, no uninitialised reads)
     x_out2, _, _, _ = agq.block_forward(blk, dev(x), dev(pos), dev(cos), dev(sin), n_keep=keep, workspace=ws)
     assert same(host(x_out2), host(x_out))
+
+
+@pytest.mark.parametrize("S,keep,sites,kmax", [(200, 150, ("attn_in", "mlp_in"), 4), (12, 7, ("attn_in", "mlp_in"), 4),
+                                               (160, 160, ("attn_in", "attn_out", "mlp_in", "mlp_act"), 1),
+                                               (40, 30, ("mlp_act",), 2)])
+def test_block_with_trip_sites(agq, oracle, blk_oracle, S, keep, sites, kmax):
+    """TRIP (Eq.5-8) at chosen activations of the block: their projections are TRIP blobs, the exponent is Eq.6's
+    base step; q, k, v (and gate, up) share the gathered pre-pass.  Checked stage by stage like the plain block."""
+    d, H, F = 512, 4, 1408
+    x, pos, cos, sin, w = make_inputs(S, d, H, F, seed=300 + S)
+    full = blk_oracle.block_forward(x, pos, cos, sin, w, H, 15, EPS, keep, trip_kmax=kmax)     # factors at every site
+    alphas = {s_: full["alphas"][s_] for s_ in sites}
+    # exponents: base step at the chosen sites, the plain calibration elsewhere
+    ref = blk_oracle.block_forward(x, pos, cos, sin, w, H, 15, EPS, keep)
+    exps = dict(ref["exps"])
+    for s_ in sites:
+        exps["e_" + s_] = full["exps"]["e_" + s_]
+    ref = blk_oracle.block_forward(x, pos, cos, sin, w, H, 15, EPS, keep, exps=exps, alphas=alphas)
+    wd, trip = upload_weights(agq, w, alphas)
+    assert set(trip) == set(sites)          # a site whose factors are all zero is a TRIP blob without extra chunks
+    blk = agq.make_block(d, H, F, wd, rms_eps=EPS, exps=exps, trip=trip)
+    x_out, pos_out, ws, L = agq.block_forward(blk, dev(x), dev(pos), dev(cos), dev(sin), n_keep=keep)
+    g = gpu_tensors(agq, blk, L, ws, S, keep)
+    same_codes = check_stages(agq, oracle, blk_oracle, w, H, 15, 4, x, pos, cos, sin, keep, exps, g, host(x_out),
+                              host(pos_out), alphas=alphas)
+    if same_codes:
+        assert same(host(x_out), ref["x_out"])
+    # the calibration pass wants plain blobs
+    with pytest.raises(agq.AgqError):
+        agq.block_forward(blk, dev(x), dev(pos), dev(cos), dev(sin), n_keep=keep, calibrate=True)
 
 
 def test_block_calibrate_finds_the_oracle_exponents(agq, oracle, blk_oracle):
