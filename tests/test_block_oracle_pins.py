@@ -300,3 +300,48 @@ def test_block_trip_sites(oracle, blk):
     # given factors and exponents reproduce the derived run
     again = blk.block_forward(x, pos, cos, sin, w, H, 15, 1e-5, 30, exps=e, alphas=al)
     assert np.array_equal(again["x_out"], r["x_out"])
+
+
+def test_block_approximates_the_unquantized_block(blk):
+    # the quantized block against the same block in float64 with the dequantized weights, written with torch's own
+    # operators (rms_norm, softmax attention, silu): every stage within the error its quantizer allows (the
+    # layer-wise 8-bit step is coarse here because of the outlier channels; a probability rounded to a power of two
+    # is within a factor sqrt(2)) - a mis-wired block is far outside - and with the TRIP factors of Section 4.3
+    # the projections of the activations with outlier channels come an order of magnitude closer
+    S, d, H, F = 96, 256, 4, 512
+    D = d // H
+    x, pos, cos, sin, w = _block_inputs(S, d, H, F, 24)
+    T = lambda a: torch.from_numpy(np.asarray(a, dtype=np.float64))
+    W = {n: T(w["w_" + n]) * T(w["s_" + n])[:, None] for n in ("q", "k", "v", "o", "gate", "up", "down")}
+    F_ = torch.nn.functional
+
+    def rot(t):
+        t = t.reshape(S, H, D)
+        c = T(np.concatenate([cos[pos], cos[pos]], axis=1))[:, None, :]
+        s_ = T(np.concatenate([sin[pos], sin[pos]], axis=1))[:, None, :]
+        return t * c + torch.cat([-t[..., D // 2:], t[..., : D // 2]], dim=-1) * s_
+
+    def mlp_of(x1):
+        h2 = F_.rms_norm(x1, (d,), T(w["g_mlp"]), 1e-5)
+        return (F_.silu(h2 @ W["gate"].T) * (h2 @ W["up"].T)) @ W["down"].T
+
+    xt = T(x)
+    h1 = F_.rms_norm(xt, (d,), T(w["g_attn"]), 1e-5)
+    q, k, v = rot(h1 @ W["q"].T), rot(h1 @ W["k"].T), (h1 @ W["v"].T).reshape(S, H, D)
+    att = F_.scaled_dot_product_attention(q.transpose(0, 1), k.transpose(0, 1), v.transpose(0, 1), is_causal=True)
+    attn_out = att.transpose(0, 1).reshape(S, d) @ W["o"].T
+    x1 = xt + attn_out
+    rel = lambda a, b: float(np.linalg.norm(np.asarray(a, dtype=np.float64) - b.numpy()) / np.linalg.norm(b.numpy()))
+
+    def errors(r):
+        x1o = T(r["x1"])               # the MLP branch on the oracle's own x1: the attention error does not leak in
+        return dict(h1=rel(r["h1"], h1), q=rel(r["q"], h1 @ W["q"].T), q_rot=rel(r["q_rot"], q.reshape(S, d)),
+                    attn=rel(r["attn_out"], attn_out), down=rel(r["down"], mlp_of(x1o)),
+                    out_mlp=rel(r["x_out"], x1o + mlp_of(x1o)), out=rel(r["x_out"], x1 + mlp_of(x1)))
+
+    plain = errors(blk.block_forward(x, pos, cos, sin, w, H, 15, 1e-5, S, bits_attn_out=8))
+    assert plain["h1"] < 1e-3 and plain["q"] < 0.1 and abs(plain["q_rot"] - plain["q"]) < 1e-3
+    assert plain["attn"] < 0.25 and plain["down"] < 0.12 and plain["out_mlp"] < 0.03 and plain["out"] < 0.06
+    trip = errors(blk.block_forward(x, pos, cos, sin, w, H, 15, 1e-5, S, bits_attn_out=8, trip_kmax=4))
+    assert trip["q"] < 0.01 and trip["q"] < plain["q"] / 5
+    assert trip["down"] < 0.03 and trip["down"] < plain["down"] / 2 and trip["out"] < plain["out"]
