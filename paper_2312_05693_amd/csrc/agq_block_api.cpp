@@ -10,7 +10,8 @@ namespace {
 
 inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; }
 inline size_t up256(size_t v) { return (v + 255) & ~(size_t)255; }
-constexpr int64_t kMaxTokens = 8192;   // agq_prune_tokens' limit
+constexpr int64_t kMaxTokens = 8192;        // agq_prune_tokens' limit (calls that prune)
+constexpr int64_t kMaxAttnTokens = 32768;   // the attention call's limit (calls that keep every token)
 constexpr int64_t kMaxWidth = 65536;   // the GEMMs' limit on K
 constexpr int64_t kMaxTripWidth = 32768;   // and with TRIP blobs
 
@@ -36,7 +37,8 @@ size_t site_ws(int64_t M, int64_t N, int64_t K, int n_extra) {
 }
 
 int layout_of(const agq_block *b, int64_t S, int64_t n_keep, agq_block_layout *L) {
-    if (!dims_ok(b) || !L || S < 1 || S > kMaxTokens || n_keep < 1 || n_keep > S) return AGQ_EINVAL;
+    if (!dims_ok(b) || !L || S < 1 || n_keep < 1 || n_keep > S) return AGQ_EINVAL;
+    if (S > (n_keep < S ? kMaxTokens : kMaxAttnTokens)) return AGQ_EINVAL;
     const size_t d = (size_t)b->d, F = (size_t)b->F, s = (size_t)S, k = (size_t)n_keep;
     const size_t sp = (s + 127) / 128 * 128;
     L->S_pad = (int64_t)sp;

@@ -203,7 +203,8 @@ def test_block_layout_and_host_checks(lib):
                 dict(rms_eps=-1.0), dict(H=0), dict(d=0)):
         assert lay(_fake_block(binding, **bad), 200, 150) == EINVAL, bad
     assert lay(blk, 0, 0) == EINVAL and lay(blk, 200, 0) == EINVAL and lay(blk, 200, 201) == EINVAL
-    assert lay(blk, 8193, 100) == EINVAL
+    assert lay(blk, 8193, 100) == EINVAL and lay(blk, 8193, 8193) == 0 and lay(blk, 32768, 32768) == 0
+    assert lay(blk, 32769, 32769) == EINVAL
 
     p, odd = ctypes.c_void_p(4096), ctypes.c_void_p(4100)
     ok = dict(blk=blk, x=p, pos=p, cos=p, sin=p, P=256, S=200, keep=150, out=p, pos_out=p, ws=p, wsb=1 << 40, st=None)

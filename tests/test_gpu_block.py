@@ -320,12 +320,11 @@ def test_rope_quantize_operator(agq, blk_oracle, S, H, D, S_pad):
     assert all(not host(j).any() for j in junk)
 
 
-def test_block_llama13b_full_size_sampled(agq, oracle, blk_oracle):
-    """The benchmark's block (d = 5120, H = 40, F = 13824, S = 2048, half of the tokens pruned): rows sampled for
-    the oracle at every stage, the pruning indices and the attention relations in full."""
-    S, d, H, F, keep, qmax = 2048, 5120, 40, 13824, 1024, 15
-    B = blk_oracle
-    x, pos, cos, sin, w = make_inputs(S, d, H, F, seed=13)
+def check_block_sampled(agq, oracle, B, S, d, H, F, keep, seed):
+    """A calibration pass and a forward pass at a size the oracle cannot do whole: rows sampled for the oracle at
+    every stage, the pruning indices, the element-wise operators and the attention relations in full."""
+    qmax = 15
+    x, pos, cos, sin, w = make_inputs(S, d, H, F, seed=seed)
     wd = upload_weights(agq, w)
     blk = agq.make_block(d, H, F, wd, qmax=qmax, bits_attn_out=4, rms_eps=EPS)
     x_out, pos_out, ws, L = agq.block_forward(blk, dev(x), dev(pos), dev(cos), dev(sin), n_keep=keep, calibrate=True)
@@ -334,7 +333,7 @@ def test_block_llama13b_full_size_sampled(agq, oracle, blk_oracle):
     assert same(host(x_fwd), host(x_out))
     g = gpu_tensors(agq, blk, L, ws, S, keep)
     x_out, pos_out = host(x_out), host(pos_out)
-    rows = np.array([0, 1, 777, 1300, 2047])
+    rows = np.array(sorted({0, 1, S // 3 + 94, (5 * S) // 8 + 20, S - 1}))
     lin = lambda t, bits, e, n: oracle.linear_w4(t, bits, e, 0, w["w_" + n], w["s_" + n])[1]
     assert same(g["h1"][rows], B.rmsnorm(x[rows], w["g_attn"], EPS))
     assert exps["e_attn_in"] == oracle.calibrate_act_exp(g["h1"], 8)
@@ -344,14 +343,15 @@ def test_block_llama13b_full_size_sampled(agq, oracle, blk_oracle):
         rot = B.rope(g[n][rows], pos[rows], cos, sin, H)
         assert same(g[n + "_q"][:, rows], B.heads_int8(rot, H, exps["e_" + n])), n
     assert same(g["v_q"][:, rows], B.heads_int8(g["v"][rows], H, exps["e_v"]))
+    assert not g["q_q"][:, S:].any() and not g["k_q"][:, S:].any() and not g["v_q"][:, S:].any()
     o2, _, score2 = agq.qk_log2_softmax(dev(g["q_q"]), dev(g["k_q"]), dev(g["v_q"]), exps["e_q"], exps["e_k"],
                                         exps["e_v"], qmax=qmax, causal=True, want_codes=False, want_score=True)
     assert same(g["o"], host(o2)) and same(g["score"], host(score2))
-    idx = oracle.prune_select(g["score"][:S], keep)
+    idx = oracle.prune_select(g["score"][:S], keep) if keep < S else np.arange(S, dtype=np.int32)
     assert np.array_equal(g["idx"], idx) and idx[0] == 0 and np.array_equal(pos_out, pos[idx])
-    assert same(g["o_kept"], g["o"][idx])
-    kr = np.array([0, 1, 500, 1023])
-    assert exps["e_attn_out"] == oracle.calibrate_act_exp(g["o_kept"], 4)
+    assert same(g["o_kept"][:keep], g["o"][idx])
+    kr = np.array(sorted({0, 1, keep // 2 - 12, keep - 1}))
+    assert exps["e_attn_out"] == oracle.calibrate_act_exp(g["o_kept"][:keep], 4)
     assert same(g["attn_out"][kr], lin(g["o_kept"][kr], 4, exps["e_attn_out"], "o"))
     assert same(g["x1"], B.residual_add(x[idx], g["attn_out"]))
     assert same(g["h2"][kr], B.rmsnorm(g["x1"][kr], w["g_mlp"], EPS))
@@ -361,3 +361,15 @@ def test_block_llama13b_full_size_sampled(agq, oracle, blk_oracle):
     assert exps["e_mlp_act"] == oracle.calibrate_act_exp(g["act"], 8)
     assert same(g["down"][kr], lin(g["act"][kr], 8, exps["e_mlp_act"], "down"))
     assert same(x_out, B.residual_add(g["x1"], g["down"]))
+
+
+def test_block_llama13b_full_size_sampled(agq, oracle, blk_oracle):
+    """The benchmark's block (d = 5120, H = 40, F = 13824, S = 2048, half of the tokens pruned)."""
+    check_block_sampled(agq, oracle, blk_oracle, 2048, 5120, 40, 13824, 1024, seed=13)
+
+
+def test_block_longest_sequences(agq, oracle, blk_oracle):
+    """The largest token counts a call accepts: 8192 with pruning (the selection's limit), and beyond it without
+    (here 8200, padded to 8320 for the attention call), on a narrow block."""
+    check_block_sampled(agq, oracle, blk_oracle, 8192, 128, 2, 128, 5000, seed=14)
+    check_block_sampled(agq, oracle, blk_oracle, 8200, 128, 2, 128, 8200, seed=15)
