@@ -42,6 +42,7 @@ PREFILL_M = 2048
 # WRITE_SIZE x 1.0 KiB, the factors a 256 MiB copy gives); see profiles/.
 MEASURED_TRAFFIC_BYTES_PER_LAUNCH = 26.3e6
 MEASURED_ATTN_TRAFFIC_BYTES = 252.4e6   # log2_attn_kernel, one call of the bench's attention block
+MEASURED_TILED_TRAFFIC_BYTES = 113.4e6  # gemm_tiled_kernel, mean per launch over the shapes of a default run
 
 
 def algorithmic_bytes(M, K, N):
@@ -275,8 +276,8 @@ def main():
             tops = tot_ops / (tot_ms * 1e-3) / 1e12
             prefill[name] = {"M": PREFILL_M, "ms_per_block": round(tot_ms, 4), "TOP/s": round(tops, 1),
                              "roofline": {"bound": "mfma", "achieved": round(tops, 1), "peak": INT8_PEAK_TOPS,
-                                          "unit": "TOP/s", "frac": round(tops / INT8_PEAK_TOPS, 4), "traffic": None,
-                                          "kernel": "gemm_tiled_kernel",
+                                          "unit": "TOP/s", "frac": round(tops / INT8_PEAK_TOPS, 4),
+                                          "traffic": MEASURED_TILED_TRAFFIC_BYTES, "kernel": "gemm_tiled_kernel",
                                           "note": "fp16 input: time includes the 4 quantize/layout pre-passes of a block"},
                              "single_calls": shapes}
         result["prefill"] = prefill
