@@ -103,6 +103,11 @@ int agq_unpack_w4(const void *packed, int64_t N, int64_t K, int8_t *wq_out,
  *            NULL when that is 0.  Holds the quantized activation when M is
  *            large enough for the tiled kernel; contents are scratch.
  * K % 128 == 0, K <= 65536 (keeps every partial sum inside int32), M >= 0.
+ * Which kernel runs is the library's choice and does not change a result: up to 16
+ * rows the weight-streaming kernel; 17..256 rows of fp16 input the same kernel with
+ * sixteen rows per workgroup while re-reading the weights per row group is cheaper
+ * than the tiled path (a measured rule on the sizes); else the layout pre-pass and
+ * the tiled kernel.
  * Graph capture: the calls enqueue kernels only and may be captured, with one
  * exception: the first call in a process that needs the kernel with the
  * activation kept in LDS (9 <= M <= 16, more than 4096 output channels in the

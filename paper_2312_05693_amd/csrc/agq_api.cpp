@@ -22,11 +22,12 @@ int gemm_w4_multi(int bits, const void *x, int x_kind, int64_t M, int64_t K, int
     if (x_kind == AGQ_X_F16 && (ldx % 8) != 0) return AGQ_EINVAL;
     if (x_kind == AGQ_X_Q && (ldx % (bits == 8 ? 16 : 32)) != 0) return AGQ_EINVAL;
     if (!projs || count < 1 || count > AGQ_MAX_PROJ) return AGQ_EINVAL;
-    int64_t tiles = 0;
+    int64_t tiles = 0, n_sum = 0;
     for (int p = 0; p < count; ++p) {
         if (projs[p].N < 1 || projs[p].N > kMaxDim || projs[p].ldy < projs[p].N || projs[p].ldy > kMaxDim)
             return AGQ_EINVAL;
         tiles += (projs[p].N + 15) / 16;
+        n_sum += projs[p].N;
     }
     if (tiles > kMaxDim) return AGQ_EINVAL;
     if (M == 0) return AGQ_OK;
@@ -41,7 +42,7 @@ int gemm_w4_multi(int bits, const void *x, int x_kind, int64_t M, int64_t K, int
         if (!workspace || !aligned16(workspace)) return AGQ_EINVAL;
         if (workspace_bytes < need) return AGQ_ESIZE;
     }
-    if (M <= AGQ_DECODE_MAX_M)
+    if (M <= AGQ_DECODE_MAX_M || agq_decode_row_groups(x_kind, M, K, n_sum))
         return hip_status(agq_launch_gemm_decode(x, x_kind, bits, M, K, ldx, e, zp, projs, count, -1, stream));
 
     // many tokens: lay the codes out in MFMA operand order once (quantizing on the

@@ -122,12 +122,16 @@ __device__ __forceinline__ agq_u2 quant8v(const agq_u4 &h, const AgqQuant &q) {
 
 // XK: what x holds; KPW: weight chunks per wavefront and pass over K;
 // MP: passes of four token rows the Eq.2 prologue makes (M <= 4 MP).
-template <int XK, int KPW, int MP>
+template <int XK, int KPW, int MP, bool RG = false>
 __global__ __launch_bounds__(1024) void gemm_decode_kernel(const DecodeArgs a) {
     extern __shared__ __align__(16) unsigned char smem[];
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int nwaves = a.waves;
+    // RG: more than sixteen token rows, sixteen per workgroup; blockIdx.y picks the group
+    const int row0 = RG ? 16 * (int)blockIdx.y : 0;
+    const int Mloc = RG ? min(16, a.M - row0) : a.M;
+    const void *const xbase = RG ? static_cast<const void *>(reinterpret_cast<const __half *>(a.x) + (int64_t)row0 * a.ldx) : a.x;
     constexpr bool TRIP = XK == XK_F16_T || XK == XK_F16_ONE_T || XK == XK_F16_TZ;
     constexpr bool F16 = XK == XK_F16 || XK == XK_F16_ONE || XK == XK_F16_Z || XK == XK_F16_ONE_Z || TRIP;
     constexpr bool ONE = XK == XK_F16_ONE || XK == XK_F16_ONE_Z || XK == XK_F16_ONE_T;   // one row: a lane's 16 bytes are its own chunk's, four chunks per load
@@ -171,7 +175,7 @@ __global__ __launch_bounds__(1024) void gemm_decode_kernel(const DecodeArgs a) {
     constexpr int NX = ONE ? (HB + 3) / 4 : HB;                       // activation loads per batch and row pass
     constexpr int kRegion = 8 * R;                                     // 16-byte pieces per chunk
     agq_u4 *stage = reinterpret_cast<agq_u4 *>(smem) + wave * (HB * kRegion);
-    const int arow = min(lane & 15, a.M - 1);   // operand row of this lane, clamped into the tensor
+    const int arow = min(lane & 15, Mloc - 1);   // operand row of this lane, clamped into the tensor
     const int ag = lane >> 4;
     const int srow = (lane & 15) & (R - 1);     // staged row this lane's operand comes from
     uint32_t sw_bits = 0;                       // raw fp16 scale of this thread's output channel
@@ -191,14 +195,14 @@ __global__ __launch_bounds__(1024) void gemm_decode_kernel(const DecodeArgs a) {
             for (int i = 0; i < NX; ++i) {
                 if (ONE) {   // lane = (chunk 4 i + rr of the batch, eight k): one row only
                     const int64_t kc = min(kb + i0 + 4 * i + rr, KT - 1);
-                    xv[i][0] = *reinterpret_cast<const agq_u4 *>(reinterpret_cast<const __half *>(a.x) + kc * 128 + c16 * 8);
+                    xv[i][0] = *reinterpret_cast<const agq_u4 *>(reinterpret_cast<const __half *>(xbase) + kc * 128 + c16 * 8);
                     continue;
                 }
                 const int64_t kc = min(kb + i0 + i, KT - 1);
-                const __half *xh = reinterpret_cast<const __half *>(a.x) + kc * 128 + c16 * 8;
+                const __half *xh = reinterpret_cast<const __half *>(xbase) + kc * 128 + c16 * 8;
 #pragma unroll
                 for (int it = 0; it < MP; ++it)
-                    xv[i][it] = *reinterpret_cast<const agq_u4 *>(xh + (int64_t)min(it * 4 + rr, a.M - 1) * a.ldx);
+                    xv[i][it] = *reinterpret_cast<const agq_u4 *>(xh + (int64_t)min(it * 4 + rr, Mloc - 1) * a.ldx);
             }
         };
         if (F16) {
@@ -208,12 +212,12 @@ __global__ __launch_bounds__(1024) void gemm_decode_kernel(const DecodeArgs a) {
             for (int i = 0; i < KPW; ++i) {
                 const int64_t kc = min(kb + i, KT - 1);
                 if (XK == XK_I8) {
-                    const int8_t *xq = reinterpret_cast<const int8_t *>(a.x) + (int64_t)arow * a.ldx + ag * 16 + kc * 128;
+                    const int8_t *xq = reinterpret_cast<const int8_t *>(xbase) + (int64_t)arow * a.ldx + ag * 16 + kc * 128;
                     fa0[i] = __builtin_bit_cast(agq_v4i, *reinterpret_cast<const agq_u4 *>(xq) ^ a.flip);
                     fa1[i] = __builtin_bit_cast(agq_v4i, *reinterpret_cast<const agq_u4 *>(xq + 64) ^ a.flip);
                 } else {
                     // nibble codes, low nibble = even k: widen to 16 * code in k order
-                    const uint8_t *xq = reinterpret_cast<const uint8_t *>(a.x) + (int64_t)arow * (a.ldx >> 1) + ag * 8 + kc * 64;
+                    const uint8_t *xq = reinterpret_cast<const uint8_t *>(xbase) + (int64_t)arow * (a.ldx >> 1) + ag * 8 + kc * 64;
                     const agq_u2 p0 = *reinterpret_cast<const agq_u2 *>(xq);
                     const agq_u2 p1 = *reinterpret_cast<const agq_u2 *>(xq + 32);
                     const uint32_t pw[4] = {p0.x ^ a.flip, p0.y ^ a.flip, p1.x ^ a.flip, p1.y ^ a.flip};
@@ -257,7 +261,7 @@ __global__ __launch_bounds__(1024) void gemm_decode_kernel(const DecodeArgs a) {
                             if (ch < HB) reinterpret_cast<agq_u2 *>(stage + ch * kRegion + (s * 4 + g) * R)[hf] = codes;
                         } else {
                             const int m = it * 4 + rr;
-                            if (m < a.M) reinterpret_cast<agq_u2 *>(stage + i * kRegion + (s * 4 + g) * R + m)[hf] = codes;
+                            if (m < Mloc) reinterpret_cast<agq_u2 *>(stage + i * kRegion + (s * 4 + g) * R + m)[hf] = codes;
                         }
                     }
                 // the same wavefront wrote and now reads: LDS keeps program order per wave
@@ -296,7 +300,7 @@ __global__ __launch_bounds__(1024) void gemm_decode_kernel(const DecodeArgs a) {
         const int32_t *meta = blob_wsum(pblob, pN, KTall) + ((pN + 255) / 256) * 256;
         const int32_t *idx = meta + 32;
         const agq_u4 *wx = reinterpret_cast<const agq_u4 *>(pblob) + ((int64_t)nt * KTall) * 64 + lane;
-        const __half *xh = reinterpret_cast<const __half *>(a.x);
+        const __half *xh = reinterpret_cast<const __half *>(xbase);
         const int c16 = lane & 15, rr = lane >> 4;
         const int s = c16 >> 3, g = (c16 & 7) >> 1, hf = c16 & 1;
         const int metav = meta[c16];                    // the factors of all (at most 16) chunks
@@ -318,7 +322,7 @@ __global__ __launch_bounds__(1024) void gemm_decode_kernel(const DecodeArgs a) {
                                    ia[u][1].x, ia[u][1].y, ia[u][1].z, ia[u][1].w};
 #pragma unroll
                 for (int it = 0; it < MP; ++it) {
-                    const __half *xr = xh + (int64_t)min(it * 4 + rr, a.M - 1) * a.ldx;
+                    const __half *xr = xh + (int64_t)min(it * 4 + rr, Mloc - 1) * a.ldx;
 #pragma unroll
                     for (int j = 0; j < 8; ++j) xg[u][it][j] = xr[max(kk[j], 0)];   // an unused slot (-1) meets zero weights
                 }
@@ -336,7 +340,7 @@ __global__ __launch_bounds__(1024) void gemm_decode_kernel(const DecodeArgs a) {
                     for (int j = 0; j < 8; ++j) b[j] = agq_quant1(__half2float(xg[u][it][j]), qe) + (uint32_t)qe.zp;
                     const agq_u2 codes = {agq_pack4(b[0], b[1], b[2], b[3]), agq_pack4(b[4], b[5], b[6], b[7])};
                     const int m = it * 4 + rr;
-                    if (m < a.M) reinterpret_cast<agq_u2 *>(stage + (s * 4 + g) * R + m)[hf] = codes;
+                    if (m < Mloc) reinterpret_cast<agq_u2 *>(stage + (s * 4 + g) * R + m)[hf] = codes;
                 }
                 __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
                 __builtin_amdgcn_wave_barrier();
@@ -369,14 +373,14 @@ __global__ __launch_bounds__(1024) void gemm_decode_kernel(const DecodeArgs a) {
         const int l = o & 63, r = o >> 6;
         const int m = 4 * (l >> 4) + r;
         const int n = nt * 16 + (l & 15);
-        if (m < a.M && n < pN) {
+        if (m < Mloc && n < pN) {
             int sum = 0;
             for (int w = 0; w < nwaves; ++w) sum += red[(w * 4 + r) * 64 + l];
             int v = sum >> shift;   // exact: every term carries the factor
             if (a.corr) v += a.corr * blob_wsum(pblob, pN, KTall)[n];
-            if (pacc) pacc[(int64_t)m * pN + n] = v;
+            if (pacc) pacc[(int64_t)(row0 + m) * pN + n] = v;
             const uint32_t sb = nmain >= 4 ? sw_bits : (uint32_t) reinterpret_cast<const uint16_t *>(psw)[n];
-            py[(int64_t)m * pldy + n] = agq_dequant(v, a.scale_e * __half2float(__ushort_as_half((unsigned short)sb)));
+            py[(int64_t)(row0 + m) * pldy + n] = agq_dequant(v, a.scale_e * __half2float(__ushort_as_half((unsigned short)sb)));
         }
     }
 }
@@ -548,6 +552,19 @@ int launch_shared(const DecodeArgs &a, int kpw, int tiles, unsigned grid, int wp
     }
 }
 
+// more than sixteen rows: sixteen per workgroup, grid.y row groups (fp16 input, four passes of four rows)
+template <int XK>
+int launch_rg(const DecodeArgs &a, int kpw, unsigned grid, unsigned groups, int waves, size_t lds, hipStream_t st) {
+    const dim3 g(grid, groups);
+    switch (kpw) {
+        case 1: gemm_decode_kernel<XK, 1, 4, true><<<g, waves * 64, lds, st>>>(a); break;
+        case 2: gemm_decode_kernel<XK, 2, 4, true><<<g, waves * 64, lds, st>>>(a); break;
+        case 4: gemm_decode_kernel<XK, 4, 4, true><<<g, waves * 64, lds, st>>>(a); break;
+        default: gemm_decode_kernel<XK, 8, 4, true><<<g, waves * 64, lds, st>>>(a); break;
+    }
+    return (int)hipGetLastError();
+}
+
 template <int XK, int MP>
 int launch_xk(const DecodeArgs &a, int kpw, unsigned grid, int waves, size_t lds, hipStream_t st) {
     switch (kpw) {
@@ -631,6 +648,11 @@ int agq_launch_gemm_decode(const void *x, int x_kind, int bits, int64_t M, int64
     // channel tiles and the activation is large (measured at K = 4096: from nine
     // rows on and more than one tile per CU; below that the per-tile prologue,
     // which overlaps better with the weight stream, is faster).
+    if (M > AGQ_DECODE_MAX_M) {   // row groups (the caller has checked: fp16 input, plain blobs)
+        const unsigned groups = (unsigned)((M + 15) / 16);
+        if (zp) return launch_rg<XK_F16_Z>(a, kpw, grid, groups, waves, lds, st);
+        return launch_rg<XK_F16>(a, kpw, grid, groups, waves, lds, st);
+    }
     if (trip) {
         if (zp) {
             if (M <= 4) return launch_xk<XK_F16_TZ, 1>(a, kpw, grid, waves, lds, st);

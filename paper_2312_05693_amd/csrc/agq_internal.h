@@ -46,6 +46,16 @@ static inline AgqTripLayout agq_trip_layout(int64_t N, int64_t K, int E) {
 
 // tokens up to which the weight-streaming kernel is used
 #define AGQ_DECODE_MAX_M 16
+// ... and beyond that, sixteen rows per workgroup (grid.y row groups): every row group reads the weights again
+// (from L2 after the first), so this pays while those reads stay small.  Measured on MI355X against the pre-pass
+// plus the tiled kernel, which needs hundreds of 128 x 128 tiles to fill the chip and walks K serially: the
+// row-group launch takes about 3.5 us + 0.36 us per MB read, the other path about 6.6 us + 3.7 us per 1000 of K
+// (768 x 768 at 128 rows: 4.5 against 9.7 us; 4096 x 4096 at 64 rows: 16.7 against 22.2 us).
+#define AGQ_ROW_GROUP_MAX_M 256
+static inline bool agq_decode_row_groups(int x_kind, int64_t M, int64_t K, int64_t n_sum) {
+    return x_kind == 0 && M > AGQ_DECODE_MAX_M && M <= AGQ_ROW_GROUP_MAX_M &&
+           ((M + 15) / 16) * (K * n_sum / 2) <= 6000000 + 10200 * K;
+}
 
 int agq_launch_calibrate(const void *x, int64_t M, int64_t K, int64_t ldx, int bits, int32_t *e_dev, void *stream);
 int agq_launch_quantize(const void *x, int64_t M, int64_t K, int64_t ldx, int bits, int e, int zp,

@@ -170,11 +170,62 @@ def test_decode_variants(agq, oracle, bits, x_kind, M, K, N):
     run_linear(agq, oracle, x, wq, sw, bits, x_kind)
 
 
-@pytest.mark.parametrize("M", [17, 64, 128, 129, 200, 333])
+@pytest.mark.parametrize("M", [17, 64, 128, 129, 200, 257, 300, 333, 400])
 @pytest.mark.parametrize("K,N", [(128, 16), (384, 272), (768, 768), (1024, 500)])
 def test_tiled_small(agq, oracle, M, K, N):
+    # up to 256 rows of fp16 input these small layers run as row groups of the weight-streaming kernel,
+    # beyond that through the pre-pass and the tiled kernel (ragged last tiles in both directions)
     x, wq, sw = make_case(M, K, N, seed=200 + M + K + N)
     run_linear(agq, oracle, x, wq, sw, 8)
+
+
+@pytest.mark.parametrize("M,K,N,bits,zp", [(17, 4096, 4096, 8, 0), (64, 4096, 4096, 8, 0), (80, 4096, 4096, 8, 0),
+                                             (32, 4096, 11008, 8, 0), (48, 4096, 11008, 8, 0), (64, 11008, 4096, 8, 0),
+                                             (250, 2048, 512, 4, 0), (256, 768, 768, 8, 131), (100, 1408, 272, 4, 9),
+                                             (31, 13824, 48, 8, 0)])
+def test_row_groups_and_the_switch_to_tiles(agq, oracle, M, K, N, bits, zp):
+    """17..256 rows: sixteen rows per workgroup of the weight-streaming kernel while the weights re-read per row
+    group stay cheap, else the tiled path; shapes on both sides of the switch, both grids, ragged last groups.
+    The accumulators are compared on sampled rows where the full product would take the oracle too long."""
+    x, wq, sw = make_case(M, K, N, seed=400 + M + N, n_out=6)
+    e = oracle.calibrate_act_exp(x, bits) + (1 if zp else 0)
+    acc = torch.full((M, N), -3, dtype=torch.int32, device="cuda")
+    fn = agq.gemm_w4a8 if bits == 8 else agq.gemm_w4a4
+    y = fn(dev(x), e, agq.pack_w4(dev(wq)), dev(sw), N, K, acc_out=acc, zp=zp)
+    rows = sorted({0, 1, 15, 16, min(17, M - 1), M // 2, M - 2, M - 1})
+    acc_w, y_w = oracle.linear_w4(x[rows], bits, e, zp, wq, sw)
+    assert np.array_equal(host(acc)[rows].astype(np.int64), acc_w)
+    assert_f16_close(host(y)[rows], y_w, "y")
+    # every row was written, and row groups do not leak into each other: a second activation that differs in one
+    # row changes that row only
+    x2 = x.copy()
+    x2[M // 2] = x[0]
+    acc2 = torch.full((M, N), -3, dtype=torch.int32, device="cuda")
+    fn(dev(x2), e, agq.pack_w4(dev(wq)), dev(sw), N, K, acc_out=acc2, zp=zp)
+    a1, a2 = host(acc), host(acc2)
+    assert np.array_equal(np.delete(a1, M // 2, axis=0), np.delete(a2, M // 2, axis=0))
+    assert np.array_equal(a2[M // 2], a1[0])
+
+
+def test_row_groups_strided_multi(agq, oracle):
+    # strided input and output, several projections, the 4-bit grid: 100 rows in seven groups (the last with four)
+    M, K, Ns, bits = 100, 512, [64, 272, 100], 4
+    xs = np.zeros((M, K + 64), dtype=np.float16)
+    xs[:, :K] = synth.make_activation(M, K, 3, seed=77)
+    xd = dev(xs)[:, :K]
+    e = oracle.calibrate_act_exp(xs[:, :K], bits)
+    projs, wants, outs = [], [], []
+    for i, N in enumerate(Ns):
+        wq, sw = synth.make_weight_q4(N, K, seed=80 + i)
+        ybuf = torch.full((M, N + 24), 7.0, dtype=torch.float16, device="cuda")
+        outs.append(ybuf)
+        projs.append((agq.pack_w4(dev(wq)), dev(sw), N, ybuf[:, :N], None))
+        wants.append(oracle.linear_w4(xs[:, :K], bits, e, 0, wq, sw)[1])
+    agq.gemm_w4a4_multi(xd, e, projs, K)
+    for ybuf, want, N in zip(outs, wants, Ns):
+        got = host(ybuf)
+        assert_f16_close(got[:, :N], want, "y")
+        assert (got[:, N:] == 7.0).all()          # nothing written past a row's N columns
 
 
 @pytest.mark.parametrize("bits,x_kind", [(8, "q"), (4, "f16"), (4, "q")])
