@@ -48,13 +48,7 @@ int gemm_w4_multi(int bits, const void *x, int x_kind, int64_t M, int64_t K, int
     // many tokens: lay the codes out in MFMA operand order once (quantizing on the
     // way when x is fp16), then run the tiled kernel per projection on that copy
     if (agq_launch_prepack_act(x, x_kind, bits, M, K, ldx, e, zp, workspace, stream)) return AGQ_EHIP;
-    for (int p = 0; p < count; ++p) {
-        if (agq_launch_gemm_tiled(workspace, M, K, e, agq_zp_corr(bits, zp), projs[p].w_packed, projs[p].w_scale_f16,
-                                  projs[p].N,
-                                  projs[p].y_f16, projs[p].ldy, projs[p].acc_out, -1, stream))
-            return AGQ_EHIP;
-    }
-    return AGQ_OK;
+    return hip_status(agq_launch_gemm_tiled(workspace, M, K, e, agq_zp_corr(bits, zp), projs, count, -1, stream));
 }
 
 int gemm_w4(int bits, const void *x, int x_kind, int64_t M, int64_t K, int64_t ldx, int e, int zp,
@@ -90,8 +84,8 @@ int gemm_w4_trip(int bits, const void *x, int64_t M, int64_t K, int64_t ldx, int
         return hip_status(agq_launch_gemm_decode(x, AGQ_X_F16, bits, M, K, ldx, e, zp, &one, 1, n_extra, stream));
     }
     if (agq_launch_prepack_trip(x, bits, M, K, ldx, e, zp, w_packed, N, n_extra, workspace, stream)) return AGQ_EHIP;
-    return hip_status(agq_launch_gemm_tiled(workspace, M, K, e, agq_zp_corr(bits, zp), w_packed, sw, N, y, ldy, acc_out,
-                                            n_extra, stream));
+    const agq_proj one = {w_packed, sw, N, y, ldy, acc_out};
+    return hip_status(agq_launch_gemm_tiled(workspace, M, K, e, agq_zp_corr(bits, zp), &one, 1, n_extra, stream));
 }
 
 }  // namespace

@@ -101,9 +101,7 @@ int site_gemm(int bits, const void *x, int64_t M, int64_t K, int e, int n_extra,
     }
     if (gws_bytes < agq_gemm_trip_workspace_bytes(M, projs[0].N, K, n_extra)) return AGQ_ESIZE;
     AGQ_TRY_HIP(agq_launch_prepack_trip(x, bits, M, K, K, e, 0, projs[0].w_packed, projs[0].N, n_extra, gws, stream));
-    for (int p = 0; p < count; ++p)
-        AGQ_TRY_HIP(agq_launch_gemm_tiled(gws, M, K, e, 0, projs[p].w_packed, projs[p].w_scale_f16, projs[p].N, projs[p].y_f16,
-                                          projs[p].ldy, nullptr, n_extra, stream));
+    AGQ_TRY_HIP(agq_launch_gemm_tiled(gws, M, K, e, 0, projs, count, n_extra, stream));
     return AGQ_OK;
 }
 

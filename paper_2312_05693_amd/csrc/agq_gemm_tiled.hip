@@ -30,6 +30,7 @@
 // a lane then holds four consecutive output channels of one token.  The
 // epilogue dequantizes in registers, transposes through LDS (free by then) and
 // stores whole 128-byte rows, 16 bytes per lane.
+#include "../../include/agq.h"
 #include "agq_device.h"
 #include "agq_internal.h"
 
@@ -49,18 +50,26 @@ constexpr int kStages = 3;
 constexpr int kCopies = (kAChunks + kBChunks) * 64 / kThreads;   // 6 copies per wavefront and step
 constexpr int kOutStride = 144;           // bytes per row of a wavefront's 64 x 64 fp16 output tile in LDS
 
+constexpr int kMaxProj = 4;   // == AGQ_MAX_PROJ of the public header
+
+// Up to four projections of the same activation share a launch (q/k/v, gate/up): one
+// grid covers the tiles of all of them, which fills the chip where a single projection
+// has too few tiles and saves the gaps between launches.
 struct TiledArgs {
     const agq_u4 *xt;    // activation codes in operand order (pre-pass output)
-    int M, N, K, KT;
-    int tiles_m, tiles_n;
-    const agq_u4 *blob;
-    const __half *sw;
-    __half *y;
-    int64_t ldy;
-    int32_t *acc_out;
+    int M, K, KT;
+    int tiles_m;
+    int tile_start[kMaxProj + 1];   // first workgroup of every projection; [count..] = the grid size
+    int N4[kMaxProj];
+    int tiles_n4[kMaxProj];
+    const agq_u4 *blob4[kMaxProj];
+    const __half *sw4[kMaxProj];
+    __half *y4[kMaxProj];
+    int64_t ldy4[kMaxProj];
+    int32_t *acc4[kMaxProj];
+    const int32_t *wsum4[kMaxProj];   // per-channel weight sums (end of every blob)
     float scale_e;
     int corr;               // unsigned activation grid: acc += corr * wsum[n]; 0 on the signed grid
-    const int32_t *wsum;    // per-channel weight sums (end of the blob)
     // TRIP blob: the first n_extra steps are the extra chunks of the channels with a factor;
     // trip_shift[kt] (device) is the left shift of the running accumulators after step kt
     int n_extra;
@@ -88,9 +97,22 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_tiled_kernel(const TiledArgs
     const int nblk = gridDim.x;
     int bid = blockIdx.x;
     if ((nblk & 7) == 0) bid = (bid & 7) * (nblk >> 3) + (bid >> 3);
-    const int band = bid / (kBand * a.tiles_n);
+    // which projection this workgroup serves: scalar compares and selects (an index into the
+    // argument record would move it to memory)
+    const int pj = (bid >= a.tile_start[1]) + (bid >= a.tile_start[2]) + (bid >= a.tile_start[3]);
+    auto pick = [pj](auto v0, auto v1, auto v2, auto v3) { return pj == 0 ? v0 : (pj == 1 ? v1 : (pj == 2 ? v2 : v3)); };
+    bid -= pick(0, a.tile_start[1], a.tile_start[2], a.tile_start[3]);
+    const int pN = pick(a.N4[0], a.N4[1], a.N4[2], a.N4[3]);
+    const int ptiles_n = pick(a.tiles_n4[0], a.tiles_n4[1], a.tiles_n4[2], a.tiles_n4[3]);
+    const agq_u4 *const pblob = pick(a.blob4[0], a.blob4[1], a.blob4[2], a.blob4[3]);
+    const __half *const psw = pick(a.sw4[0], a.sw4[1], a.sw4[2], a.sw4[3]);
+    __half *const py = pick(a.y4[0], a.y4[1], a.y4[2], a.y4[3]);
+    const int64_t pldy = pick(a.ldy4[0], a.ldy4[1], a.ldy4[2], a.ldy4[3]);
+    int32_t *const pacc = pick(a.acc4[0], a.acc4[1], a.acc4[2], a.acc4[3]);
+    const int32_t *const pwsum = pick(a.wsum4[0], a.wsum4[1], a.wsum4[2], a.wsum4[3]);
+    const int band = bid / (kBand * ptiles_n);
     const int rows = min(kBand, a.tiles_m - band * kBand);
-    const int within = bid - band * kBand * a.tiles_n;
+    const int within = bid - band * kBand * ptiles_n;
     const int tn = within / rows, tm = band * kBand + within - tn * rows;
     const int m0 = tm * BM, n0 = tn * BN;
     const int KT = a.KT;
@@ -107,7 +129,7 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_tiled_kernel(const TiledArgs
     for (int p = 0; p < 2; ++p) {
         const int c = wave * 2 + p, grp = c >> 2, j = (c >> 1) & 1, t = c & 1;
         const int chunk_row = n0 / 16 + grp * 4 + j * 2 + ((lane & 31) >> 4);
-        bsrc[p] = a.blob + ((int64_t)chunk_row * KT) * 64 + (2 * t + (lane >> 5)) * 16 + (lane & 15);
+        bsrc[p] = pblob + ((int64_t)chunk_row * KT) * 64 + (2 * t + (lane >> 5)) * 16 + (lane & 15);
     }
     // LDS byte address (wave-uniform, kept in a scalar register) of this
     // wavefront's first activation chunk in stage 0
@@ -134,12 +156,12 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_tiled_kernel(const TiledArgs
         for (int q = 0; q < 4; ++q) {
             const int n = ncol + j * 32 + q * 8;
             // channels past N are never stored: clamp their addresses into the array
-            const uint16_t *sp = reinterpret_cast<const uint16_t *>(a.sw);
-            if ((a.N & 3) == 0) {
-                swp[j][q] = *reinterpret_cast<const uint2 *>(sp + min(n, a.N - 4));   // 8-byte aligned: n % 4 == 0
+            const uint16_t *sp = reinterpret_cast<const uint16_t *>(psw);
+            if ((pN & 3) == 0) {
+                swp[j][q] = *reinterpret_cast<const uint2 *>(sp + min(n, pN - 4));   // 8-byte aligned: n % 4 == 0
             } else {
                 uint32_t h[4];
-                for (int r = 0; r < 4; ++r) h[r] = sp[min(n + r, a.N - 1)];
+                for (int r = 0; r < 4; ++r) h[r] = sp[min(n + r, pN - 1)];
                 swp[j][q] = make_uint2(h[0] | (h[1] << 16), h[2] | (h[3] << 16));
             }
         }
@@ -260,7 +282,7 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_tiled_kernel(const TiledArgs
         for (int j = 0; j < 2; ++j)
 #pragma unroll
             for (int q = 0; q < 4; ++q) {
-                const int4 ws = *reinterpret_cast<const int4 *>(a.wsum + ncol + j * 32 + q * 8);   // padded to 256 channels
+                const int4 ws = *reinterpret_cast<const int4 *>(pwsum + ncol + j * 32 + q * 8);   // padded to 256 channels
                 const int t[4] = {ws.x, ws.y, ws.z, ws.w};
 #pragma unroll
                 for (int r = 0; r < 4; ++r) {
@@ -270,7 +292,7 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_tiled_kernel(const TiledArgs
                 }
             }
     }
-    if (a.acc_out) {   // exact accumulators for parity checks (plain stores)
+    if (pacc) {   // exact accumulators for parity checks (plain stores)
 #pragma unroll
         for (int i = 0; i < 2; ++i)
 #pragma unroll
@@ -278,7 +300,7 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_tiled_kernel(const TiledArgs
 #pragma unroll
                 for (int r = 0; r < 16; ++r) {
                     const int m = mrow + i * 32, n = ncol + j * 32 + (r >> 2) * 8 + (r & 3);
-                    if (m < a.M && n < a.N) a.acc_out[(int64_t)m * a.N + n] = acc[i][j][r] >> AGQ_W_SHIFT;
+                    if (m < a.M && n < pN) pacc[(int64_t)m * pN + n] = acc[i][j][r] >> AGQ_W_SHIFT;
                 }
     }
     unsigned char *obuf = lds + wave * (64 * kOutStride);   // 9 KiB per wavefront, 36 KiB in all
@@ -306,19 +328,19 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_tiled_kernel(const TiledArgs
     __builtin_amdgcn_wave_barrier();
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
     const int nbase = n0 + wn * 64 + (lane & 7) * 8;          // eight channels per lane
-    const bool vec_ok = (a.ldy & 7) == 0 && nbase + 7 < a.N;
+    const bool vec_ok = (pldy & 7) == 0 && nbase + 7 < pN;
 #pragma unroll
     for (int it = 0; it < 8; ++it) {
         const int row = it * 8 + (lane >> 3);
         const int m = m0 + wm * 64 + row;
-        if (m >= a.M || nbase >= a.N) continue;
+        if (m >= a.M || nbase >= pN) continue;
         const uint4 v = *reinterpret_cast<const uint4 *>(obuf + row * kOutStride + (lane & 7) * 16);
-        __half *yp = a.y + (int64_t)m * a.ldy + nbase;
+        __half *yp = py + (int64_t)m * pldy + nbase;
         if (vec_ok) {
             *reinterpret_cast<uint4 *>(yp) = v;
         } else {
             const uint32_t w[4] = {v.x, v.y, v.z, v.w};
-            for (int c = 0; c < 8 && nbase + c < a.N; ++c)
+            for (int c = 0; c < 8 && nbase + c < pN; ++c)
                 yp[c] = __ushort_as_half((unsigned short)(w[c >> 1] >> (16 * (c & 1))));
         }
     }
@@ -326,35 +348,41 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_tiled_kernel(const TiledArgs
 
 }  // namespace
 
-int agq_launch_gemm_tiled(const void *x_tiles, int64_t M, int64_t K, int e, int corr, const void *w_packed,
-                          const void *sw, int64_t N, void *y, int64_t ldy, int32_t *acc_out, int n_extra,
-                          void *stream) {
-    TiledArgs a;
+int agq_launch_gemm_tiled(const void *x_tiles, int64_t M, int64_t K, int e, int corr, const struct agq_proj *projs, int count,
+                          int n_extra, void *stream) {
+    TiledArgs a = {};
     a.xt = (const agq_u4 *)x_tiles;
     a.M = (int)M;
-    a.N = (int)N;
     a.K = (int)K;
     a.KT = (int)agq_k_tiles(K);
     a.tiles_m = (int)((M + BM - 1) / BM);
-    a.tiles_n = (int)((N + BN - 1) / BN);
-    a.blob = (const agq_u4 *)w_packed;
-    a.sw = (const __half *)sw;
-    a.y = (__half *)y;
-    a.ldy = ldy;
-    a.acc_out = acc_out;
     a.scale_e = ldexpf(1.0f, e);
     a.corr = corr;
-    a.wsum = agq_blob_wsum(w_packed, N, K);
     a.n_extra = 0;
     a.trip_shift = nullptr;
-    const unsigned grid = (unsigned)(a.tiles_m * a.tiles_n);
+    int tiles = 0;
+    for (int p = 0; p < kMaxProj; ++p) {
+        const agq_proj &pr = projs[p < count ? p : count - 1];
+        a.tile_start[p] = tiles;
+        a.N4[p] = (int)pr.N;
+        a.tiles_n4[p] = (int)((pr.N + BN - 1) / BN);
+        if (p < count) tiles += a.tiles_m * a.tiles_n4[p];
+        a.blob4[p] = (const agq_u4 *)pr.w_packed;
+        a.sw4[p] = (const __half *)pr.w_scale_f16;
+        a.y4[p] = (__half *)pr.y_f16;
+        a.ldy4[p] = pr.ldy;
+        a.acc4[p] = pr.acc_out;
+        a.wsum4[p] = n_extra >= 0 ? (const int32_t *)((const char *)pr.w_packed + agq_trip_layout(pr.N, K, n_extra).wsum_off)
+                                  : agq_blob_wsum(pr.w_packed, pr.N, K);
+    }
+    for (int p = count; p <= kMaxProj; ++p) a.tile_start[p] = tiles;
+    const unsigned grid = (unsigned)tiles;
     if (n_extra >= 0) {
-        const AgqTripLayout L = agq_trip_layout(N, K, n_extra);
-        const char *base = (const char *)w_packed;
+        // every blob of the call was packed with the same factors: the shift table of the first serves all
+        const AgqTripLayout L = agq_trip_layout(projs[0].N, K, n_extra);
         a.KT = (int)L.KTall;
-        a.wsum = (const int32_t *)(base + L.wsum_off);
         a.n_extra = n_extra;
-        a.trip_shift = (const int32_t *)(base + L.meta_off) + 16;
+        a.trip_shift = (const int32_t *)((const char *)projs[0].w_packed + L.meta_off) + 16;
         gemm_tiled_kernel<true><<<grid, kThreads, 0, (hipStream_t)stream>>>(a);
     } else {
         gemm_tiled_kernel<false><<<grid, kThreads, 0, (hipStream_t)stream>>>(a);

@@ -68,10 +68,10 @@ struct agq_proj;
 // n_extra >= 0 with a TRIP blob (one projection, fp16 input); -1 for plain blobs
 int agq_launch_gemm_decode(const void *x, int x_kind, int bits, int64_t M, int64_t K, int64_t ldx, int e, int zp,
                            const struct agq_proj *projs, int count, int n_extra, void *stream);
-// K counts the main chunks only; with a TRIP blob x_tiles and the blob hold n_extra more steps in front
-int agq_launch_gemm_tiled(const void *x_tiles, int64_t M, int64_t K, int e, int corr,
-                          const void *w_packed, const void *sw, int64_t N, void *y, int64_t ldy,
-                          int32_t *acc_out, int n_extra, void *stream);
+// K counts the main chunks only; with TRIP blobs (all packed with the same factors) x_tiles and the blobs hold
+// n_extra more steps in front.  The `count` projections of the activation run as one launch.
+int agq_launch_gemm_tiled(const void *x_tiles, int64_t M, int64_t K, int e, int corr, const struct agq_proj *projs, int count,
+                          int n_extra, void *stream);
 int agq_launch_trip_search(const void *x, int64_t M, int64_t K, int64_t ldx, int bits, int e, int zp, int kmax,
                            int8_t *alpha, void *stream);
 int agq_trip_count_extra(const int8_t *alpha_host, int64_t K);   // number of extra chunks, -1 = bad factors or too many

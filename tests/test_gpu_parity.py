@@ -234,7 +234,7 @@ def test_tiled_variants(agq, oracle, bits, x_kind):
     run_linear(agq, oracle, x, wq, sw, bits, x_kind)
 
 
-@pytest.mark.parametrize("M,bits", [(1, 8), (4, 8), (16, 8), (3, 4), (40, 8), (150, 4)])
+@pytest.mark.parametrize("M,bits", [(1, 8), (4, 8), (16, 8), (3, 4), (40, 8), (150, 4), (300, 8), (700, 4)])
 def test_multi_projection_equals_single_calls(agq, oracle, M, bits):
     # q/k/v-style: several weight matrices on one activation, one call
     K = 512
