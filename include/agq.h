@@ -126,9 +126,9 @@ int agq_gemm_w4a4(const void *x, int x_kind, int64_t M, int64_t K, int64_t ldx,
 /* Several projections of the same activation in one call (q/k/v, gate/up of a
  * transformer block; Section 4.2's pipeline quantizes such an activation once).
  * Same computation as `count` calls of agq_gemm_w4a8 / agq_gemm_w4a4 with the
- * same x, M, K, e: Eq.2 (or the layout pre-pass) runs once, and for M <= 16 all
- * projections run as one kernel launch, which is what a launch-bound decode
- * step needs.  projs: HOST array of `count` descriptors (1 <= count <=
+ * same x, M, K, e: Eq.2 (or the layout pre-pass) runs once, and all projections
+ * run as one kernel launch: what a launch-bound decode step needs, and for many
+ * rows one grid over the tiles of all projections fills the chip better.  projs: HOST array of `count` descriptors (1 <= count <=
  * AGQ_MAX_PROJ), read before the call returns.  workspace:
  * agq_gemm_workspace_bytes(M, N, K) for any N.  Other arguments and errors as
  * for the single calls.                                                       */
