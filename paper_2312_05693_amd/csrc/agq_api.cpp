@@ -30,6 +30,8 @@ int gemm_w4_multi(int bits, const void *x, int x_kind, int64_t M, int64_t K, int
         n_sum += projs[p].N;
     }
     if (tiles > kMaxDim) return AGQ_EINVAL;
+    // the tiled kernel's grid: 128 x 128 tiles of all projections
+    if (((M + 127) / 128) * ((n_sum + 127) / 128 + count) > kMaxDim) return AGQ_EINVAL;
     if (M == 0) return AGQ_OK;
     if (!x || !aligned16(x)) return AGQ_EINVAL;
     for (int p = 0; p < count; ++p) {

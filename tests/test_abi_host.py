@@ -76,6 +76,7 @@ def test_argument_errors_need_no_gpu(lib):
     assert call(fn=lib.agq_gemm_w4a4, kind=1, ldx=272) == EINVAL
     assert call(M=64, ws=None) == EINVAL             # tiled kernel needs the workspace
     assert call(M=64, ws=p, wsb=100) == ESIZE
+    assert call(M=1 << 30, N=1 << 30, ldy=1 << 30, ws=p, wsb=1 << 62) == EINVAL   # more tiles than a grid holds
     assert call(M=0, x=None, y=None) == 0            # empty batch is a no-op
 
     from paper_2312_05693_amd.binding import AgqProj
