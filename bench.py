@@ -17,7 +17,8 @@ prefill regime (M = 2048, the seven shapes of one block, W4A8 and W4A4) as int8
 TOP/s, the TRIP layer on the same shapes beside the plain one, the attention
 block at LLaMA-13B size (from fp16 probabilities, and from int8 Q and K in one
 kernel) with pruning, one whole block of the pipeline (RMSNorm, projections,
-rotary embedding, attention, pruning, MLP) at LLaMA-13B and 7B shapes, the
+rotary embedding, attention, pruning, MLP) at LLaMA-13B and 7B shapes, a stack of
+four such blocks with the cascade schedule of Eq.9, the
 roofline of the dominant kernel, and the CPU oracle timed on the host cores.
 """
 from __future__ import annotations
@@ -498,6 +499,33 @@ def main():
                 del wsb, wts_t
             blocks.append(entry)
             del wts, xb
+        # a stack of four LLaMA-13B-shaped blocks (distinct weights) in one call: without pruning, and with Eq.9's
+        # cascade (beta = 0.5 over two stages, applied in blocks 1 and 3)
+        d, H, F, S, nb = 5120, 40, 13824, PREFILL_M, 4
+        xb = torch.from_numpy(synth.make_activation(S, d, synth.n_outlier_channels(d), seed=5)).to(dev)
+        posb = torch.arange(S, dtype=torch.int32, device=dev)
+        cs, sn = synth.rope_tables(S, d // H)
+        cs, sn = torch.from_numpy(cs).to(dev), torch.from_numpy(sn).to(dev)
+        stack_w = []
+        for _ in range(nb):
+            wts = {"g_attn": torch.ones(d, dtype=torch.float16, device=dev), "g_mlp": torch.ones(d, dtype=torch.float16, device=dev)}
+            for n, (N, K) in dict(q=(d, d), k=(d, d), v=(d, d), o=(d, d), gate=(F, d), up=(F, d), down=(d, F)).items():
+                wts["w_" + n], wts["s_" + n] = unit_packed(N, K)
+            stack_w.append(wts)
+        stages = agq.cascade_keep(S, 0.5, 2)
+        stack = {"model": "llama13b", "blocks": nb, "S": S}
+        for name, keep in (("dense", [S] * nb), ("cascade", [S, stages[0], stages[0], stages[1]])):
+            blks, xg, pg = [], xb, posb
+            for l in range(nb):                   # calibrate every block on the tokens it receives
+                blk = agq.make_block(d, H, F, stack_w[l], qmax=15, bits_attn_out=4, rms_eps=1e-5)
+                xg, pg, _, _ = agq.block_forward(blk, xg, pg, cs, sn, n_keep=keep[l], calibrate=True)
+                blks.append(blk)
+            xo, po, wss = agq.stack_forward(blks, keep, xb, posb, cs, sn)
+            ms = timed(lambda: agq.stack_forward(blks, keep, xb, posb, cs, sn, workspace=wss, out=(xo, po)), 5, 10) / 10
+            stack[name] = {"keep": keep, "ms": round(ms, 4), "tokens_in/s": round(S / ms * 1e3, 0)}
+            del wss, blks
+        del stack_w, xb
+        result["block_stack"] = stack
         result["block"] = {"workload": "one LLaMA block of the quantized pipeline, 2048 tokens, W4A8 with 4-bit activations "
                                        "after attention, without pruning and pruning to half after attention",
                            "blocks": blocks}

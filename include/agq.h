@@ -364,6 +364,21 @@ int agq_block_calibrate(agq_block *blk, const void *x_f16, const int32_t *pos, c
                         const float *rope_sin, int64_t P, int64_t S, int64_t n_keep, void *x_out_f16,
                         int32_t *pos_out, void *workspace, size_t workspace_bytes, void *stream);
 
+/* A stack of blocks with the cascade pruning of Section 5.2: block l receives the
+ * tokens block l-1 kept and keeps keep[l] of them (keep[l] equal to what it
+ * receives: that block prunes nothing); Eq.9's schedule prunes in m of the blocks
+ * with the counts of agq_cascade_keep.  blocks: HOST array of n_blocks descriptors
+ * with the same d (read before the call returns); keep: HOST int64 [n_blocks],
+ * non-increasing, keep[0] <= S.  x_out_f16 [keep[n_blocks-1], d]; pos_out as for a
+ * block.  workspace: agq_stack_workspace_bytes (0 = invalid arguments), 256-byte
+ * aligned; after the call it holds the intermediates of the last block only.
+ * Enqueues kernels only.  Same result as n_blocks calls of agq_block_forward.    */
+size_t agq_stack_workspace_bytes(const agq_block *blocks, int n_blocks, int64_t S, const int64_t *keep);
+int agq_stack_forward(const agq_block *blocks, int n_blocks, const int64_t *keep, const void *x_f16,
+                      const int32_t *pos, const float *rope_cos, const float *rope_sin, int64_t P,
+                      int64_t S, void *x_out_f16, int32_t *pos_out, void *workspace,
+                      size_t workspace_bytes, void *stream);
+
 /* Section 5.2, Eq.9: m pruning stages share the progressive ratio
  * gamma = 1 - (1 - beta)^(1/m), so that a fraction beta is gone after the last one;
  * a stage that receives S tokens keeps S - floor(S * gamma).  keep_out (HOST int64

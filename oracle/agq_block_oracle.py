@@ -190,3 +190,17 @@ def block_forward(x, pos, cos, sin, w: dict, H: int, qmax: int, eps: float, keep
     r["alphas"] = al
     r["exps"] = e
     return r
+
+
+def stack_forward(x, pos, cos, sin, weights: list, H: int, qmax: int, eps: float, keep: list,
+                  bits_attn_out: int = 4, exps: list | None = None) -> list:
+    """A stack of blocks with the cascade pruning of Section 5.2: block l receives what block l-1
+    kept (tokens and positions) and keeps keep[l] of them.  weights, keep and exps are per block.
+    Returns the per-block results of `block_forward`; the last one's x_out / pos_out are the stack's."""
+    out = []
+    for l, (w, k) in enumerate(zip(weights, keep)):
+        r = block_forward(x, pos, cos, sin, w, H, qmax, eps, int(k), bits_attn_out,
+                          None if exps is None else exps[l])
+        out.append(r)
+        x, pos = r["x_out"], r["pos_out"]
+    return out

@@ -52,6 +52,8 @@ SIGNATURES = {
     "agq_block_forward": (_int, [_vp, _vp, _vp, _vp, _vp, _i64, _i64, _i64, _vp, _vp, _vp, _sz, _vp]),
     "agq_block_calibrate": (_int, [_vp, _vp, _vp, _vp, _vp, _i64, _i64, _i64, _vp, _vp, _vp, _sz, _vp]),
     "agq_cascade_keep": (_int, [_i64, ctypes.c_double, _int, _vp]),
+    "agq_stack_workspace_bytes": (_sz, [_vp, _int, _i64, _vp]),
+    "agq_stack_forward": (_int, [_vp, _int, _vp, _vp, _vp, _vp, _vp, _i64, _i64, _vp, _vp, _vp, _sz, _vp]),
 }
 
 AGQ_MAX_PROJ = 4
@@ -408,6 +410,27 @@ def block_tensor(blk: AgqBlock, L: AgqBlockLayout, workspace, name: str, S: int,
         return workspace[off:off + 4 * n].view(torch.int32)
     r, c = shapes[name]
     return workspace[off:off + 2 * r * c].view(torch.float16).view(r, c)
+
+
+def stack_forward(blocks, keep, x, pos, rope_cos, rope_sin, workspace=None, out=None):
+    """A stack of blocks with cascade pruning: block l keeps keep[l] of the tokens it receives.
+    Returns (x_out [keep[-1], d], pos_out, workspace)."""
+    n = len(blocks)
+    arr = (AgqBlock * n)(*blocks)
+    kp = (ctypes.c_int64 * n)(*[int(k) for k in keep])
+    S, d = x.shape
+    need = lib().agq_stack_workspace_bytes(ctypes.cast(arr, _vp), n, S, ctypes.cast(kp, _vp))
+    if need == 0:
+        raise AgqError(AGQ_EINVAL, "agq_stack_workspace_bytes")
+    if workspace is None:
+        workspace = torch.empty(need, dtype=torch.uint8, device=x.device)
+    if out is None:
+        out = (torch.empty((int(keep[-1]), d), dtype=torch.float16, device=x.device),
+               torch.empty(int(keep[-1]), dtype=torch.int32, device=x.device))
+    _ok(lib().agq_stack_forward(ctypes.cast(arr, _vp), n, ctypes.cast(kp, _vp), _ptr(x), _ptr(pos), _ptr(rope_cos),
+                                _ptr(rope_sin), rope_cos.shape[0], S, _ptr(out[0]), _ptr(out[1]), _ptr(workspace),
+                                workspace.numel(), _stream()), "agq_stack_forward")
+    return out[0], out[1], workspace
 
 
 def cascade_keep(S: int, beta: float, m: int) -> list:

@@ -266,6 +266,86 @@ int agq_block_calibrate(agq_block *blk, const void *x_f16, const int32_t *pos, c
     return AGQ_OK;
 }
 
+namespace {
+
+// layout of a stack's workspace: two token buffers and two position buffers (ping-pong between blocks), then
+// the largest block workspace
+struct StackLayout {
+    size_t xa, xb, pa, pb, blk, total;
+};
+
+int stack_layout(const agq_block *blocks, int n_blocks, int64_t S, const int64_t *keep, StackLayout *out) {
+    if (!blocks || !keep || !out || n_blocks < 1 || n_blocks > 4096 || S < 1) return AGQ_EINVAL;
+    size_t blk_max = 0;
+    int64_t in = S;
+    for (int l = 0; l < n_blocks; ++l) {
+        if (blocks[l].d != blocks[0].d) return AGQ_EINVAL;
+        agq_block_layout L;
+        AGQ_TRY(layout_of(&blocks[l], in, keep[l], &L));   // checks 1 <= keep[l] <= in and the block itself
+        blk_max = blk_max > L.total ? blk_max : L.total;
+        in = keep[l];
+    }
+    const size_t xbytes = up256((size_t)keep[0] * (size_t)blocks[0].d * 2), pbytes = up256((size_t)keep[0] * 4);
+    out->xa = 0;
+    out->xb = xbytes;
+    out->pa = 2 * xbytes;
+    out->pb = 2 * xbytes + pbytes;
+    out->blk = 2 * xbytes + 2 * pbytes;
+    out->total = out->blk + blk_max;
+    return AGQ_OK;
+}
+
+}  // namespace
+
+size_t agq_stack_workspace_bytes(const agq_block *blocks, int n_blocks, int64_t S, const int64_t *keep) {
+    StackLayout L;
+    return stack_layout(blocks, n_blocks, S, keep, &L) == AGQ_OK ? L.total : 0;
+}
+
+int agq_stack_forward(const agq_block *blocks, int n_blocks, const int64_t *keep, const void *x_f16, const int32_t *pos,
+                      const float *rope_cos, const float *rope_sin, int64_t P, int64_t S, void *x_out_f16,
+                      int32_t *pos_out, void *workspace, size_t workspace_bytes, void *stream) {
+    StackLayout L;
+    AGQ_TRY(stack_layout(blocks, n_blocks, S, keep, &L));
+    if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255) != 0) return AGQ_EINVAL;
+    if (workspace_bytes < L.total) return AGQ_ESIZE;
+    char *ws = static_cast<char *>(workspace);
+    // every block is validated before the first launch: a bad descriptor must not leave half a stack enqueued
+    {
+        int64_t in = S;
+        for (int l = 0; l < n_blocks; ++l) {
+            const agq_block &b = blocks[l];
+            const void *ptrs[] = {b.g_attn_f16, b.g_mlp_f16, b.w_q, b.w_k, b.w_v, b.w_o, b.w_gate, b.w_up, b.w_down,
+                                  b.s_q, b.s_k, b.s_v, b.s_o, b.s_gate, b.s_up, b.s_down};
+            for (const void *p : ptrs)
+                if (!p || !aligned16(p)) return AGQ_EINVAL;
+            const int es[7] = {b.e_attn_in, b.e_q, b.e_k, b.e_v, b.e_attn_out, b.e_mlp_in, b.e_mlp_act};
+            for (int e : es)
+                if (e < AGQ_E_MIN || e > AGQ_E_MAX) return AGQ_EINVAL;
+            in = keep[l];
+        }
+        (void)in;
+        if (!x_f16 || !pos || !rope_cos || !rope_sin || !x_out_f16 || P < 1 || P > ((int64_t)1 << 30)) return AGQ_EINVAL;
+        if (!aligned16(x_f16) || !aligned16(rope_cos) || !aligned16(rope_sin) || !aligned16(x_out_f16)) return AGQ_EINVAL;
+    }
+    const void *xin = x_f16;
+    const int32_t *pin = pos;
+    int64_t in = S;
+    for (int l = 0; l < n_blocks; ++l) {
+        const bool last = l == n_blocks - 1;
+        void *xo = last ? x_out_f16 : static_cast<void *>(ws + ((l & 1) ? L.xb : L.xa));
+        int32_t *po = last ? pos_out : reinterpret_cast<int32_t *>(ws + ((l & 1) ? L.pb : L.pa));
+        int exps[7] = {blocks[l].e_attn_in, blocks[l].e_q, blocks[l].e_k, blocks[l].e_v, blocks[l].e_attn_out,
+                       blocks[l].e_mlp_in, blocks[l].e_mlp_act};
+        AGQ_TRY(run(&blocks[l], exps, false, xin, pin, rope_cos, rope_sin, P, in, keep[l], xo, po, ws + L.blk,
+                    L.total - L.blk, stream));
+        xin = xo;
+        pin = po;
+        in = keep[l];
+    }
+    return AGQ_OK;
+}
+
 int agq_cascade_keep(int64_t S, double beta, int m, int64_t *keep_out) {
     if (S < 0 || S > ((int64_t)1 << 40) || !(beta >= 0.0) || !(beta < 1.0) || m < 1 || m > 1024 || !keep_out)
         return AGQ_EINVAL;

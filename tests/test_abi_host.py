@@ -233,6 +233,28 @@ def test_block_layout_and_host_checks(lib):
     assert lib.agq_block_forward(None, p, p, p, p, 256, 200, 150, p, p, p, 1 << 40, None) == EINVAL
 
 
+def test_stack_host_checks(lib):
+    from paper_2312_05693_amd import binding
+    n = 3
+    arr = (binding.AgqBlock * n)(*[_fake_block(binding) for _ in range(n)])
+    keep = lambda *v: ctypes.cast((ctypes.c_int64 * n)(*v), ctypes.c_void_p)
+    size = lambda S, k: lib.agq_stack_workspace_bytes(ctypes.cast(arr, ctypes.c_void_p), n, S, k)
+    L = binding.AgqBlockLayout()
+    assert lib.agq_block_layout_of(ctypes.byref(arr[0]), 200, 200, ctypes.byref(L)) == 0
+    full = size(200, keep(200, 200, 200))
+    assert full == L.total + 2 * 200 * 512 * 2 + 2 * 1024          # two token buffers, two position buffers, one block
+    assert size(200, keep(200, 150, 100)) == full                   # the first block is the largest
+    assert size(200, keep(150, 160, 100)) == 0 and size(200, keep(201, 100, 100)) == 0 and size(0, keep(1, 1, 1)) == 0
+    p = ctypes.c_void_p(4096)
+    call = lambda k, ws=p, wsb=1 << 40, x=p: lib.agq_stack_forward(ctypes.cast(arr, ctypes.c_void_p), n, k, x, p, p, p, 256,
+                                                                  200, p, p, ws, wsb, None)
+    assert call(keep(200, 150, 160)) == -1 and call(keep(200, 150, 100), wsb=1000) == -2
+    assert call(keep(200, 150, 100), ws=None) == -1 and call(keep(200, 150, 100), x=None) == -1
+    bad = (binding.AgqBlock * n)(_fake_block(binding), _fake_block(binding, e_k=99), _fake_block(binding))
+    assert lib.agq_stack_forward(ctypes.cast(bad, ctypes.c_void_p), n, keep(200, 150, 100), p, p, p, p, 256, 200, p, p, p,
+                                 1 << 40, None) == -1               # found before anything is launched
+
+
 def test_cascade_keep_matches_the_oracle(lib, oracle):
     from oracle import agq_block_oracle
     from paper_2312_05693_amd import binding

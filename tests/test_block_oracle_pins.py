@@ -345,3 +345,32 @@ def test_block_approximates_the_unquantized_block(blk):
     trip = errors(blk.block_forward(x, pos, cos, sin, w, H, 15, 1e-5, S, bits_attn_out=8, trip_kmax=4))
     assert trip["q"] < 0.01 and trip["q"] < plain["q"] / 5
     assert trip["down"] < 0.03 and trip["down"] < plain["down"] / 2 and trip["out"] < plain["out"]
+
+
+def test_stack_with_cascade(blk):
+    # three blocks, Eq.9's counts for two stages in blocks 0 and 2: every block sees what the one before kept; with
+    # both branches of every block silenced the stack hands through the rows the selections compose to
+    S, d, H, F = 64, 128, 2, 256
+    x, pos, cos, sin, _ = _block_inputs(S, d, H, F, 25)
+    pos = pos + 5
+    stages = blk.cascade_keep(S, 0.5, 2)
+    keep = [stages[0], stages[0], stages[1]]
+    ws = []
+    for l in range(3):
+        w = synth.make_block_weights(d, H, F, 30 + l)
+        w["w_o"] = np.zeros_like(w["w_o"])
+        w["w_down"] = np.zeros_like(w["w_down"])
+        ws.append(w)
+    rs = blk.stack_forward(x, pos, cos, sin, ws, H, 15, 1e-5, keep)
+    assert [r["x_out"].shape[0] for r in rs] == keep and keep == [46, 46, 33]   # 64 - floor(64 g), 46 - floor(46 g), g = 1 - sqrt(1/2)
+    composed = np.arange(S)
+    for r in rs:
+        composed = composed[r["idx"]]
+    assert np.array_equal(rs[-1]["x_out"], x[composed]) and np.array_equal(rs[-1]["pos_out"], pos[composed])
+    assert composed[0] == 0 and np.all(np.diff(composed) > 0)
+    assert np.array_equal(rs[1]["idx"], np.arange(keep[0]))          # the middle block prunes nothing
+    # each block ran on the previous block's output, with its own calibration
+    again = blk.block_forward(rs[0]["x_out"], rs[0]["pos_out"], cos, sin, ws[1], H, 15, 1e-5, keep[1])
+    assert np.array_equal(again["x_out"], rs[1]["x_out"]) and again["exps"] == rs[1]["exps"]
+    given = blk.stack_forward(x, pos, cos, sin, ws, H, 15, 1e-5, keep, exps=[r["exps"] for r in rs])
+    assert np.array_equal(given[-1]["x_out"], rs[-1]["x_out"])

@@ -226,6 +226,43 @@ def test_cascade_of_blocks(agq, oracle, blk_oracle):
     assert xg.shape == (keeps[-1], d) and host(pg)[0] == 0
 
 
+def test_stack_with_cascade_equals_block_by_block(agq, oracle, blk_oracle):
+    """agq_stack_forward: five blocks, Eq.9's schedule (two pruning stages, beta = 0.6) applied in blocks 1 and 3; the
+    call equals the same blocks run one by one (each of which is checked stage by stage above), bit for bit."""
+    S, d, H, F, n = 300, 256, 2, 640, 5
+    stages = agq.cascade_keep(S, 0.6, 2)
+    keep = [S, stages[0], stages[0], stages[1], stages[1]]
+    x, pos, cos, sin, _ = make_inputs(S, d, H, F, seed=41)
+    xd, pd, cd, sd = dev(x), dev(pos), dev(cos), dev(sin)
+    blocks, xg, pg, s_in = [], xd, pd, S
+    for layer in range(n):                      # calibrate every block on the tokens it will receive
+        w = synth.make_block_weights(d, H, F, 60 + layer)
+        blk = agq.make_block(d, H, F, upload_weights(agq, w), rms_eps=EPS)
+        agq.block_forward(blk, xg, pg, cd, sd, n_keep=keep[layer], calibrate=True)
+        xg, pg, _, _ = agq.block_forward(blk, xg, pg, cd, sd, n_keep=keep[layer])
+        blocks.append(blk)
+    x_seq, p_seq = host(xg).copy(), host(pg).copy()
+    x_st, p_st, ws = agq.stack_forward(blocks, keep, xd, pd, cd, sd)
+    assert x_st.shape == (keep[-1], d) and same(host(x_st), x_seq) and np.array_equal(host(p_st), p_seq)
+    assert host(p_st)[0] == 0 and np.all(np.diff(host(p_st)) > 0)
+    # captured into a graph and replayed into a dirty workspace
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        agq.stack_forward(blocks, keep, xd, pd, cd, sd, workspace=ws, out=(x_st, p_st))
+    for rep in range(2):
+        x_st.fill_(3.0)
+        ws.fill_(0xA5)
+        torch.cuda.synchronize()
+        graph.replay()
+        assert same(host(x_st), x_seq) and np.array_equal(host(p_st), p_seq)
+    # argument errors: a count that grows, a block of another width
+    with pytest.raises(agq.AgqError):
+        agq.stack_forward(blocks, [S, 200, 210, 100, 100], xd, pd, cd, sd)
+    other = agq.make_block(512, 4, 640, blocks[0]._keepalive, rms_eps=EPS)
+    with pytest.raises(agq.AgqError):
+        agq.stack_forward(blocks[:1] + [other], keep[:2], xd, pd, cd, sd)
+
+
 def test_block_graph_replay(agq, oracle, blk_oracle):
     """agq_block_forward enqueues kernels only (no memset nodes, no allocation): captured into a HIP graph after an
     eager call, every replay reproduces the eager result bit for bit, with eager work in between."""
