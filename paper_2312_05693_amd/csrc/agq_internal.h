@@ -65,7 +65,7 @@ int agq_launch_prepack_act(const void *x, int x_kind, int bits, int64_t M, int64
 int agq_launch_pack(const int8_t *wq, int64_t N, int64_t K, void *packed, int32_t *bad, void *stream);
 int agq_launch_unpack(const void *packed, int64_t N, int64_t K, int8_t *wq, void *stream);
 struct agq_proj;
-// n_extra >= 0 with a TRIP blob (one projection, fp16 input); -1 for plain blobs
+// n_extra >= 0 with TRIP blobs (all packed with the same factors, fp16 input); -1 for plain blobs
 int agq_launch_gemm_decode(const void *x, int x_kind, int bits, int64_t M, int64_t K, int64_t ldx, int e, int zp,
                            const struct agq_proj *projs, int count, int n_extra, void *stream);
 // K counts the main chunks only; with TRIP blobs (all packed with the same factors) x_tiles and the blobs hold
