@@ -203,6 +203,17 @@ int agq_gemm_w4a4_trip(const void *x_f16, int64_t M, int64_t K, int64_t ldx, int
                        const void *w_packed, int n_extra, const void *w_scale_f16,
                        int64_t N, void *y_f16, int64_t ldy, int32_t *acc_out,
                        void *workspace, size_t workspace_bytes, void *stream);
+/* Several projections of one activation with TRIP (the factors belong to the
+ * activation, so q/k/v or gate/up share them): every blob packed with the same
+ * factors, n_extra theirs.  One quantize-and-gather pass, one launch.  projs as for
+ * agq_gemm_w4a8_multi; workspace: agq_gemm_trip_workspace_bytes(M, N, K, n_extra)
+ * for any N.                                                                     */
+int agq_gemm_w4a8_trip_multi(const void *x_f16, int64_t M, int64_t K, int64_t ldx, int e, int zp,
+                             const agq_proj *projs, int count, int n_extra, void *workspace,
+                             size_t workspace_bytes, void *stream);
+int agq_gemm_w4a4_trip_multi(const void *x_f16, int64_t M, int64_t K, int64_t ldx, int e, int zp,
+                             const agq_proj *projs, int count, int n_extra, void *workspace,
+                             size_t workspace_bytes, void *stream);
 
 /* Log2 quantizer on softmax probabilities (Section 4.1 Eq.3 with max|X| = 1,
  * used for the softmax output per Section 5.1) fused with the product with the

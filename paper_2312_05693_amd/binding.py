@@ -40,6 +40,8 @@ SIGNATURES = {
     "agq_gemm_trip_workspace_bytes": (_sz, [_i64, _i64, _i64, _int]),
     "agq_gemm_w4a8_trip": (_int, _TRIP_GEMM_ARGS),
     "agq_gemm_w4a4_trip": (_int, _TRIP_GEMM_ARGS),
+    "agq_gemm_w4a8_trip_multi": (_int, [_vp, _i64, _i64, _i64, _int, _int, _vp, _int, _int, _vp, _sz, _vp]),
+    "agq_gemm_w4a4_trip_multi": (_int, [_vp, _i64, _i64, _i64, _int, _int, _vp, _int, _int, _vp, _sz, _vp]),
     "agq_log2_quant_softmax": (_int, [_vp, _i64, _i64, _i64, _int, _int, _vp, _int, _vp, _vp, _vp, _vp]),
     "agq_qk_log2_softmax": (_int, [_vp, _vp, _i64, _i64, _i64, _int, _int, _int, _int, _vp, _int, _vp, _vp, _vp, _vp]),
     "agq_prune_tokens": (_int, [_vp, _i64, _i64, _vp, _i64, _vp, _vp, _vp]),
@@ -280,6 +282,25 @@ def gemm_trip(x, bits, e, w_packed, n_extra, w_scale, N, K, y=None, acc_out=None
            y.stride(0) if M else N, _ptr(acc_out), _ptr(workspace), workspace.numel() if workspace is not None else 0,
            _stream()), "agq_gemm_w4a%d_trip" % bits)
     return y
+
+
+def gemm_trip_multi(x, bits, e, projs, n_extra, K, workspace=None, zp=0):
+    """The TRIP layer for several projections of one activation: projs = [(blob, w_scale, N, y|None, acc_out|None), ...],
+    every blob packed with the same factors.  Returns the list of y."""
+    M = x.shape[0]
+    ys, arr = [], (AgqProj * len(projs))()
+    for i, (packed, scale, N, y, acc) in enumerate(projs):
+        if y is None:
+            y = torch.empty((M, N), dtype=torch.float16, device=x.device)
+        ys.append(y)
+        arr[i] = AgqProj(_ptr(packed), _ptr(scale), N, _ptr(y), y.stride(0) if M else N, _ptr(acc))
+    need = lib().agq_gemm_trip_workspace_bytes(M, projs[0][2], K, n_extra)
+    if workspace is None and need:
+        workspace = torch.empty(need, dtype=torch.uint8, device=x.device)
+    fn = lib().agq_gemm_w4a8_trip_multi if bits == 8 else lib().agq_gemm_w4a4_trip_multi
+    _ok(fn(_ptr(x), M, K, x.stride(0) if M else K, e, zp, ctypes.cast(arr, _vp), len(projs), n_extra, _ptr(workspace),
+           workspace.numel() if workspace is not None else 0, _stream()), "agq_gemm_w4a%d_trip_multi" % bits)
+    return ys
 
 
 def log2_quant_softmax(p, v_q, e_v, qmax=15, causal=True, want_codes=False, want_score=True):

@@ -67,27 +67,43 @@ inline bool trip_dims_ok(int64_t N, int64_t K, int n_extra) {
            n_extra <= AGQ_TRIP_MAX_EXTRA;
 }
 
-int gemm_w4_trip(int bits, const void *x, int64_t M, int64_t K, int64_t ldx, int e, int zp, const void *w_packed,
-                 int n_extra, const void *sw, int64_t N, void *y, int64_t ldy, int32_t *acc_out, void *workspace,
-                 size_t workspace_bytes, void *stream) {
-    if (M < 0 || M > kMaxDim || !trip_dims_ok(N, K, n_extra)) return AGQ_EINVAL;
+// The TRIP layer for `count` projections of one activation (their blobs packed with the same factors): one
+// gathered pre-pass and one launch.
+int gemm_w4_trip_multi(int bits, const void *x, int64_t M, int64_t K, int64_t ldx, int e, int zp, const agq_proj *projs,
+                       int count, int n_extra, void *workspace, size_t workspace_bytes, void *stream) {
+    if (!projs || count < 1 || count > AGQ_MAX_PROJ) return AGQ_EINVAL;
+    int64_t n_sum = 0;
+    for (int p = 0; p < count; ++p) {
+        if (M < 0 || M > kMaxDim || !trip_dims_ok(projs[p].N, K, n_extra)) return AGQ_EINVAL;
+        if (projs[p].ldy < projs[p].N || projs[p].ldy > kMaxDim) return AGQ_EINVAL;
+        n_sum += projs[p].N;
+    }
     if (!e_ok(e) || zp < 0 || zp > (1 << bits) - 1 || ldx < K || (ldx % 8) != 0) return AGQ_EINVAL;
-    if (ldy < N || ldy > kMaxDim) return AGQ_EINVAL;
+    if (((M + 127) / 128) * ((n_sum + 127) / 128 + count) > kMaxDim) return AGQ_EINVAL;
     if (M == 0) return AGQ_OK;
-    if (!x || !w_packed || !sw || !y) return AGQ_EINVAL;
-    if (!aligned16(x) || !aligned16(w_packed) || !aligned16(sw) || !aligned16(y)) return AGQ_EINVAL;
-    const size_t need = agq_gemm_trip_workspace_bytes(M, N, K, n_extra);
+    if (!x || !aligned16(x)) return AGQ_EINVAL;
+    for (int p = 0; p < count; ++p) {
+        if (!projs[p].w_packed || !projs[p].w_scale_f16 || !projs[p].y_f16) return AGQ_EINVAL;
+        if (!aligned16(projs[p].w_packed) || !aligned16(projs[p].w_scale_f16) || !aligned16(projs[p].y_f16))
+            return AGQ_EINVAL;
+    }
+    const size_t need = agq_gemm_trip_workspace_bytes(M, projs[0].N, K, n_extra);
     if (need > 0) {
         if (!workspace || !aligned16(workspace)) return AGQ_EINVAL;
         if (workspace_bytes < need) return AGQ_ESIZE;
     }
-    if (M <= AGQ_DECODE_MAX_M) {
-        const agq_proj one = {w_packed, sw, N, y, ldy, acc_out};
-        return hip_status(agq_launch_gemm_decode(x, AGQ_X_F16, bits, M, K, ldx, e, zp, &one, 1, n_extra, stream));
-    }
-    if (agq_launch_prepack_trip(x, bits, M, K, ldx, e, zp, w_packed, N, n_extra, workspace, stream)) return AGQ_EHIP;
+    if (M <= AGQ_DECODE_MAX_M)
+        return hip_status(agq_launch_gemm_decode(x, AGQ_X_F16, bits, M, K, ldx, e, zp, projs, count, n_extra, stream));
+    if (agq_launch_prepack_trip(x, bits, M, K, ldx, e, zp, projs[0].w_packed, projs[0].N, n_extra, workspace, stream))
+        return AGQ_EHIP;
+    return hip_status(agq_launch_gemm_tiled(workspace, M, K, e, agq_zp_corr(bits, zp), projs, count, n_extra, stream));
+}
+
+int gemm_w4_trip(int bits, const void *x, int64_t M, int64_t K, int64_t ldx, int e, int zp, const void *w_packed,
+                 int n_extra, const void *sw, int64_t N, void *y, int64_t ldy, int32_t *acc_out, void *workspace,
+                 size_t workspace_bytes, void *stream) {
     const agq_proj one = {w_packed, sw, N, y, ldy, acc_out};
-    return hip_status(agq_launch_gemm_tiled(workspace, M, K, e, agq_zp_corr(bits, zp), &one, 1, n_extra, stream));
+    return gemm_w4_trip_multi(bits, x, M, K, ldx, e, zp, &one, 1, n_extra, workspace, workspace_bytes, stream);
 }
 
 }  // namespace
@@ -193,6 +209,16 @@ int agq_gemm_w4a8_trip(const void *x_f16, int64_t M, int64_t K, int64_t ldx, int
                        void *workspace, size_t workspace_bytes, void *stream) {
     return gemm_w4_trip(8, x_f16, M, K, ldx, e, zp, w_packed, n_extra, w_scale_f16, N, y_f16, ldy, acc_out, workspace,
                         workspace_bytes, stream);
+}
+
+int agq_gemm_w4a8_trip_multi(const void *x_f16, int64_t M, int64_t K, int64_t ldx, int e, int zp, const agq_proj *projs,
+                             int count, int n_extra, void *workspace, size_t workspace_bytes, void *stream) {
+    return gemm_w4_trip_multi(8, x_f16, M, K, ldx, e, zp, projs, count, n_extra, workspace, workspace_bytes, stream);
+}
+
+int agq_gemm_w4a4_trip_multi(const void *x_f16, int64_t M, int64_t K, int64_t ldx, int e, int zp, const agq_proj *projs,
+                             int count, int n_extra, void *workspace, size_t workspace_bytes, void *stream) {
+    return gemm_w4_trip_multi(4, x_f16, M, K, ldx, e, zp, projs, count, n_extra, workspace, workspace_bytes, stream);
 }
 
 int agq_gemm_w4a4_trip(const void *x_f16, int64_t M, int64_t K, int64_t ldx, int e, int zp, const void *w_packed,

@@ -83,23 +83,15 @@ int layout_of(const agq_block *b, int64_t S, int64_t n_keep, agq_block_layout *L
         if ((call) != 0) return AGQ_EHIP; \
     } while (0)
 
-// The projections `projs` of one activation x [M,K] (fp16, contiguous): plain blobs go through the multi-projection
-// call (Eq.2 once); TRIP blobs, all packed with the same factors, share one gathered pre-pass (its tables are the
-// same in every blob) when the tiled kernel runs; in the weight-streaming regime they are one launch too.
+// The projections `projs` of one activation x [M,K] (fp16, contiguous) through the multi-projection calls: one
+// quantizer pass and one launch, with plain blobs or with TRIP blobs packed with the same factors.
 int site_gemm(int bits, const void *x, int64_t M, int64_t K, int e, int n_extra, const agq_proj *projs, int count, void *gws,
               size_t gws_bytes, void *stream) {
     if (n_extra < 0)
         return bits == 8 ? agq_gemm_w4a8_multi(x, AGQ_X_F16, M, K, K, e, 0, projs, count, gws, gws_bytes, stream)
                          : agq_gemm_w4a4_multi(x, AGQ_X_F16, M, K, K, e, 0, projs, count, gws, gws_bytes, stream);
-    if (M <= AGQ_DECODE_MAX_M) {
-        // the weight-streaming kernel picks each workgroup's blob, and with it that blob's tables: one launch
-        AGQ_TRY_HIP(agq_launch_gemm_decode(x, AGQ_X_F16, bits, M, K, K, e, 0, projs, count, n_extra, stream));
-        return AGQ_OK;
-    }
-    if (gws_bytes < agq_gemm_trip_workspace_bytes(M, projs[0].N, K, n_extra)) return AGQ_ESIZE;
-    AGQ_TRY_HIP(agq_launch_prepack_trip(x, bits, M, K, K, e, 0, projs[0].w_packed, projs[0].N, n_extra, gws, stream));
-    AGQ_TRY_HIP(agq_launch_gemm_tiled(gws, M, K, e, 0, projs, count, n_extra, stream));
-    return AGQ_OK;
+    return bits == 8 ? agq_gemm_w4a8_trip_multi(x, M, K, K, e, 0, projs, count, n_extra, gws, gws_bytes, stream)
+                     : agq_gemm_w4a4_trip_multi(x, M, K, K, e, 0, projs, count, n_extra, gws, gws_bytes, stream);
 }
 
 // exps: the exponents to use, updated in place when `calibrate` is set

@@ -767,6 +767,30 @@ def test_trip_linear_tiled(agq, oracle, M, K, N, bits):
     run_trip_linear(agq, oracle, x, wq, sw, bits, e, random_alpha(rng, K, (0, 0, 0, 1)))
 
 
+@pytest.mark.parametrize("M,bits,zp", [(1, 8, 0), (9, 8, 0), (16, 4, 0), (40, 8, 0), (300, 8, 131), (130, 4, 0)])
+def test_trip_multi_projection(agq, oracle, M, bits, zp):
+    """The factors belong to the activation: three projections packed with the same factors, one call."""
+    K, Ns = 1024, [272, 64, 1000]
+    x = synth.make_activation(M if M > 40 else 64, K, 10, seed=600 + M)
+    e = oracle.trip_base_exp(x, bits, 4) + (1 if zp else 0)
+    alpha = oracle.trip_search(x, bits, e, zp, 4)
+    x = x[:M]
+    projs, wants, n_extra = [], [], None
+    for i, N in enumerate(Ns):
+        wq, sw = synth.make_weight_q4(N, K, seed=610 + i)
+        blob, n_extra = agq.pack_w4_trip(dev(wq), alpha)
+        acc = torch.full((M, N), -5, dtype=torch.int32, device="cuda")
+        projs.append((blob, dev(sw), N, None, acc))
+        wants.append(oracle.linear_w4_trip(x, bits, e, zp, alpha, wq, sw))
+    assert n_extra >= 1
+    ys = agq.gemm_trip_multi(dev(x), bits, e, projs, n_extra, K, zp=zp)
+    for (acc_w, y_w), (_, _, _, _, acc), y in zip(wants, projs, ys):
+        assert np.array_equal(host(acc).astype(np.int64), acc_w)
+        assert_f16_close(host(y), y_w, "trip multi")
+    L = agq.lib()
+    assert L.agq_gemm_w4a8_trip_multi(dev(x).data_ptr(), M, K, K, e, 0, None, 3, n_extra, None, 0, None) == agq.AGQ_EINVAL
+
+
 @pytest.mark.parametrize("M", [4, 16, 200])
 def test_trip_linear_no_factors_equals_plain(agq, oracle, M):
     """All factors zero: the TRIP layer is the plain layer (no extra chunks)."""
