@@ -293,8 +293,9 @@ int agq_prune_tokens(const int32_t *score, int64_t S, int64_t n_keep,
  * rounds once to fp16.  All activation grids are signed (zp = 0).
  *
  * d = H*D with D = 64 or 128; d % 128 == 0, F % 128 == 0; 1 <= n_keep <= S
- * (n_keep == S: nothing is pruned); S <= 8192 when tokens are pruned, else S <= 32768.  Eq.9's cascade is a sequence
- * of such calls whose n_keep follow agq_cascade_keep.
+ * (n_keep == S: nothing is pruned); S <= 8192 when tokens are pruned, else
+ * S <= 32768.  Eq.9's cascade is a sequence of such calls whose n_keep follow
+ * agq_cascade_keep (agq_stack_forward runs such a sequence in one call).
  * All pointers are device pointers, 16-byte aligned; weights are agq_pack_w4 blobs
  * ([d,d] for q, k, v, o; [F,d] for gate, up; [d,F] for down) with fp16 scales.   */
 typedef struct agq_block {
