@@ -286,6 +286,27 @@ def main():
                                           "traffic": MEASURED_TILED_TRAFFIC_BYTES, "kernel": "gemm_tiled_kernel",
                                           "note": "fp16 input: time includes the 4 quantize/layout pre-passes of a block"},
                              "single_calls": shapes}
+        # Between the two regimes (W4A8, fp16 input, single calls over eight distinct weight matrices per shape in a
+        # replayed graph): row groups of the weight-streaming kernel, then the tiled kernel with K split over
+        # workgroups while it has few tiles
+        by_m = []
+        for i in (0, 4, 6):
+            pname, K, N = synth.LLAMA7B_PROJ[i]
+            row = {"proj": pname, "K": K, "N": N}
+            e8 = int(agq.calibrate_act_exp(xk[K], 8).item())
+            for M in (32, 64, 128, 256, 512, 1024):
+                xm = xk[K][:M].contiguous()
+                ym = torch.empty((M, N), dtype=torch.float16, device=dev)
+                wsm = torch.empty(max(16, agq.gemm_workspace_bytes(M, N, K)), dtype=torch.uint8, device=dev)
+
+                def calls():
+                    for layer in layers[:8]:
+                        agq.gemm_w4a8(xm, e8, layer[i][2], layer[i][3], N, K, y=ym, workspace=wsm)
+
+                us = timed(calls, 3, 10) / 10 / 8 * 1e3
+                row["M%d" % M] = {"us": round(us, 2), "TOP/s": round(2.0 * M * N * K / us / 1e6, 1)}
+            by_m.append(row)
+        prefill["w4a8_by_M"] = by_m
         result["prefill"] = prefill
 
     # ---- TRIP (Section 4.3 / 4.4): the same three shapes with per-channel factors found by Eq.8 on a

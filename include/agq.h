@@ -101,13 +101,19 @@ int agq_unpack_w4(const void *packed, int64_t N, int64_t K, int8_t *wq_out,
  *            copy of the accumulators (NULL to skip).
  * workspace: agq_gemm_workspace_bytes(M,N,K) bytes, 16-byte aligned, may be
  *            NULL when that is 0.  Holds the quantized activation when M is
- *            large enough for the tiled kernel; contents are scratch.
+ *            large enough for the tiled kernel, and behind it, when the call
+ *            has few output tiles and a long K, the int32 partial tiles of a
+ *            split of K over workgroups; contents are scratch.  A workspace of
+ *            agq_gemm_workspace_bytes(M,0,K) bytes (the activation only) is
+ *            accepted too: K is then not split, which costs time where it
+ *            applies and changes no result; a smaller one is AGQ_ESIZE.
  * K % 128 == 0, K <= 65536 (keeps every partial sum inside int32), M >= 0.
  * Which kernel runs is the library's choice and does not change a result: up to 16
  * rows the weight-streaming kernel; 17..256 rows of fp16 input the same kernel with
  * sixteen rows per workgroup while re-reading the weights per row group is cheaper
  * than the tiled path (a measured rule on the sizes); else the layout pre-pass and
- * the tiled kernel.
+ * the tiled kernel, with K split over workgroups when the call has fewer than 256
+ * tiles of 128 x 128 and the workspace has the room.
  * Graph capture: the calls enqueue kernels only and may be captured, with one
  * exception: the first call in a process that needs the kernel with the
  * activation kept in LDS (9 <= M <= 16, more than 4096 output channels in the
@@ -130,7 +136,8 @@ int agq_gemm_w4a4(const void *x, int x_kind, int64_t M, int64_t K, int64_t ldx,
  * run as one kernel launch: what a launch-bound decode step needs, and for many
  * rows one grid over the tiles of all projections fills the chip better.  projs: HOST array of `count` descriptors (1 <= count <=
  * AGQ_MAX_PROJ), read before the call returns.  workspace:
- * agq_gemm_workspace_bytes(M, N, K) for any N.  Other arguments and errors as
+ * agq_gemm_workspace_bytes(M, N, K) with N = the widths of the projections added
+ * up (any smaller N down to 0 is accepted, see above).  Other arguments and errors as
  * for the single calls.                                                       */
 #define AGQ_MAX_PROJ 4
 typedef struct agq_proj {

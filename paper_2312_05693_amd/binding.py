@@ -203,7 +203,7 @@ def _gemm_multi(fn_name, x, x_kind, M, K, ldx, e, zp, projs, workspace):
             y = torch.empty((M, N), dtype=torch.float16, device=dev)
         ys.append(y)
         arr[i] = AgqProj(_ptr(packed), _ptr(scale), N, _ptr(y), y.stride(0) if M else N, _ptr(acc))
-    need = gemm_workspace_bytes(M, projs[0][2], K)
+    need = gemm_workspace_bytes(M, sum(p[2] for p in projs), K)
     if workspace is None and need:
         workspace = torch.empty(need, dtype=torch.uint8, device=dev)
     ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()

@@ -14,6 +14,9 @@ inline int hip_status(int err) { return err == 0 ? AGQ_OK : AGQ_EHIP; }
 constexpr int64_t kMaxDim = (int64_t)1 << 30;
 constexpr int64_t kMaxAttnS = 32768;   // one head of P stays below 4 GiB: 32-bit offsets inside the kernel
 
+// int8 codes in operand order, tokens padded to the 128-row tile (a multiple of 16 KiB)
+inline size_t codes_bytes(int64_t M, int64_t K) { return (size_t)((M + 127) / 128) * 128 * (size_t)K; }
+
 int gemm_w4_multi(int bits, const void *x, int x_kind, int64_t M, int64_t K, int64_t ldx, int e, int zp,
                   const agq_proj *projs, int count, void *workspace, size_t workspace_bytes, void *stream) {
     if (M < 0 || M > kMaxDim || K < 128 || K > 65536 || (K % 128) != 0) return AGQ_EINVAL;
@@ -39,18 +42,26 @@ int gemm_w4_multi(int bits, const void *x, int x_kind, int64_t M, int64_t K, int
         if (!aligned16(projs[p].w_packed) || !aligned16(projs[p].w_scale_f16) || !aligned16(projs[p].y_f16))
             return AGQ_EINVAL;
     }
-    const size_t need = agq_gemm_workspace_bytes(M, projs[0].N, K);
+    const size_t need = M <= AGQ_DECODE_MAX_M ? 0 : codes_bytes(M, K);
     if (need > 0) {
         if (!workspace || !aligned16(workspace)) return AGQ_EINVAL;
         if (workspace_bytes < need) return AGQ_ESIZE;
     }
-    if (M <= AGQ_DECODE_MAX_M || agq_decode_row_groups(x_kind, M, K, n_sum))
+    // With few tiles and a long K the tiled kernel splits the tiles' K steps over workgroups, if the
+    // caller's workspace has the room for the partial tiles behind the codes.
+    int64_t tiles_n = 0;
+    for (int p = 0; p < count; ++p) tiles_n += (projs[p].N + 127) / 128;
+    AgqSplitPlan plan = agq_tiled_split_plan(M, tiles_n, K / 128, true);
+    if (workspace_bytes < need + plan.bytes) plan = agq_tiled_split_plan(M, tiles_n, K / 128, false);
+    if (M <= AGQ_DECODE_MAX_M || agq_decode_row_groups(x_kind, M, K, n_sum, plan.cost_ns))
         return hip_status(agq_launch_gemm_decode(x, x_kind, bits, M, K, ldx, e, zp, projs, count, -1, stream));
 
     // many tokens: lay the codes out in MFMA operand order once (quantizing on the
-    // way when x is fp16), then run the tiled kernel per projection on that copy
+    // way when x is fp16), then run the tiled kernel for all projections on that copy
+    void *const split_ws = plan.splits > 1 ? static_cast<char *>(workspace) + codes_bytes(M, K) : nullptr;
     if (agq_launch_prepack_act(x, x_kind, bits, M, K, ldx, e, zp, workspace, stream)) return AGQ_EHIP;
-    return hip_status(agq_launch_gemm_tiled(workspace, M, K, e, agq_zp_corr(bits, zp), projs, count, -1, stream));
+    return hip_status(
+        agq_launch_gemm_tiled(workspace, M, K, e, agq_zp_corr(bits, zp), projs, count, -1, split_ws, stream));
 }
 
 int gemm_w4(int bits, const void *x, int x_kind, int64_t M, int64_t K, int64_t ldx, int e, int zp,
@@ -96,7 +107,8 @@ int gemm_w4_trip_multi(int bits, const void *x, int64_t M, int64_t K, int64_t ld
         return hip_status(agq_launch_gemm_decode(x, AGQ_X_F16, bits, M, K, ldx, e, zp, projs, count, n_extra, stream));
     if (agq_launch_prepack_trip(x, bits, M, K, ldx, e, zp, projs[0].w_packed, projs[0].N, n_extra, workspace, stream))
         return AGQ_EHIP;
-    return hip_status(agq_launch_gemm_tiled(workspace, M, K, e, agq_zp_corr(bits, zp), projs, count, n_extra, stream));
+    return hip_status(
+        agq_launch_gemm_tiled(workspace, M, K, e, agq_zp_corr(bits, zp), projs, count, n_extra, nullptr, stream));
 }
 
 int gemm_w4_trip(int bits, const void *x, int64_t M, int64_t K, int64_t ldx, int e, int zp, const void *w_packed,
@@ -159,9 +171,16 @@ int agq_unpack_w4(const void *packed, int64_t N, int64_t K, int8_t *wq_out, void
 }
 
 size_t agq_gemm_workspace_bytes(int64_t M, int64_t N, int64_t K) {
-    (void)N;
     if (M <= AGQ_DECODE_MAX_M || K < 1) return 0;
-    return (size_t)((M + 127) / 128) * 128 * (size_t)K;   // int8 codes, tokens padded to the 128-row tile
+    // the codes, plus the partial tiles of a K split when the call has few tiles (+ 3: a call with up to
+    // four projections whose widths add up to N has at most three more column tiles than one of width N)
+    const int64_t tiles_n = N > 0 ? (N + 127) / 128 : 0;
+    size_t split = 0;
+    for (int64_t t = tiles_n; t <= tiles_n + 3 && t > 0; ++t) {
+        const AgqSplitPlan plan = agq_tiled_split_plan(M, t, K / 128, true);
+        if (plan.bytes > split) split = plan.bytes;
+    }
+    return codes_bytes(M, K) + split;
 }
 
 int agq_trip_search(const void *x_f16, int64_t M, int64_t K, int64_t ldx, int bits, int e, int zp, int kmax,

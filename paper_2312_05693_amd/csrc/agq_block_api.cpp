@@ -64,8 +64,9 @@ int layout_of(const agq_block *b, int64_t S, int64_t n_keep, agq_block_layout *L
     L->down = take(k * d * 2);
     L->q_rot = take(s * d * 2);
     L->k_rot = take(s * d * 2);
-    const size_t need[4] = {site_ws(S, b->d, b->d, b->trip_attn_in), site_ws(n_keep, b->d, b->d, b->trip_attn_out),
-                            site_ws(n_keep, b->F, b->d, b->trip_mlp_in), site_ws(n_keep, b->d, b->F, b->trip_mlp_act)};
+    // N: the widths of the projections of one call added up (q, k, v; gate, up)
+    const size_t need[4] = {site_ws(S, 3 * b->d, b->d, b->trip_attn_in), site_ws(n_keep, b->d, b->d, b->trip_attn_out),
+                            site_ws(n_keep, 2 * b->F, b->d, b->trip_mlp_in), site_ws(n_keep, b->d, b->F, b->trip_mlp_act)};
     size_t ws = 0;
     for (size_t n : need) ws = ws > n ? ws : n;
     L->gemm_ws = take(ws + 16);   // a few words behind the GEMM scratch hold calibration results

@@ -74,13 +74,27 @@ struct TiledArgs {
     // trip_shift[kt] (device) is the left shift of the running accumulators after step kt
     int n_extra;
     const int32_t *trip_shift;
+    // K split over `splits` workgroups per tile (few tiles, long K), steps_per_split K steps each: they
+    // leave int32 partial tiles in `part`, which a second kernel adds up and dequantizes
+    int splits, steps_per_split, tiles_all;
+    int32_t *part;       // [tile][split][16][256 threads][4]
 };
 
 // TRIP: the blob and the activation stages carry extra steps in front, ordered by
 // descending factor; after the last step of a factor the accumulators are shifted
 // left by the difference to the next factor (Horner), so that at the end every
 // extra step has been multiplied by 2^factor (Section 4.4) - exact in int32.
-template <bool TRIP>
+//
+// SPLIT: with fewer tiles than the chip has workgroup slots and a long K, a tile's K steps are shared
+// out over several workgroups.  Each stores its int32 accumulators as a partial tile and is done;
+// split_reduce_kernel, launched behind it, adds the partial tiles up and runs the epilogue.  (One
+// kernel in which the last workgroup to arrive at a tile adds the others' partial tiles was measured
+// slower than no split at all: it has to read them in dependent rounds through device-scope loads,
+// or with cache-wide write-backs and invalidations around them.  A lone workgroup on a CU is not
+// short of copies in flight either: six stages instead of three changed nothing, its sixteen
+// 64-cycle MFMAs per wavefront and step are the step time.)  An int32 sum does not depend on
+// its order, so the result is the unsplit kernel's bit for bit.
+template <bool TRIP, bool SPLIT>
 __global__ __launch_bounds__(kThreads, 2) void gemm_tiled_kernel(const TiledArgs a) {
     // Three pipeline stages of 24 KiB; the epilogue reuses the first 36 KiB.
     __shared__ __align__(16) unsigned char lds[kStages * kStageBytes];
@@ -97,6 +111,10 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_tiled_kernel(const TiledArgs
     const int nblk = gridDim.x;
     int bid = blockIdx.x;
     if ((nblk & 7) == 0) bid = (bid & 7) * (nblk >> 3) + (bid >> 3);
+    // SPLIT: workgroups with the same K slice are neighbours (they share activation stages)
+    const int split = SPLIT ? bid / a.tiles_all : 0;
+    if (SPLIT) bid -= split * a.tiles_all;
+    const int tile_id = bid;
     // which projection this workgroup serves: scalar compares and selects (an index into the
     // argument record would move it to memory)
     const int pj = (bid >= a.tile_start[1]) + (bid >= a.tile_start[2]) + (bid >= a.tile_start[3]);
@@ -115,7 +133,9 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_tiled_kernel(const TiledArgs
     const int within = bid - band * kBand * ptiles_n;
     const int tn = within / rows, tm = band * kBand + within - tn * rows;
     const int m0 = tm * BM, n0 = tn * BN;
-    const int KT = a.KT;
+    const int KTfull = a.KT;
+    const int kbeg = SPLIT ? split * a.steps_per_split : 0;
+    const int KT = SPLIT ? min(a.steps_per_split, KTfull - kbeg) : KTfull;   // steps of this workgroup
 
     // Copies of this wavefront per step: activation chunks 4 wave .. 4 wave + 3 of
     // the 16 KiB stage, and weight chunks 2 wave, 2 wave + 1.  Weight chunk c
@@ -123,13 +143,13 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_tiled_kernel(const TiledArgs
     // k-blocks t = c & 1 (low nibbles) and t + 2 (high nibbles): channel l & 31
     // of the tile lives in the blob's 16-row chunk (l & 31) >> 4 at blob lane
     // (2 t + (l >> 5)) * 16 + (l & 15).
-    const agq_u4 *asrc = a.xt + ((int64_t)tm * KT * 16 + wave * 4) * 64 + lane;
+    const agq_u4 *asrc = a.xt + (((int64_t)tm * KTfull + kbeg) * 16 + wave * 4) * 64 + lane;
     const agq_u4 *bsrc[2];
 #pragma unroll
     for (int p = 0; p < 2; ++p) {
         const int c = wave * 2 + p, grp = c >> 2, j = (c >> 1) & 1, t = c & 1;
         const int chunk_row = n0 / 16 + grp * 4 + j * 2 + ((lane & 31) >> 4);
-        bsrc[p] = pblob + ((int64_t)chunk_row * KT) * 64 + (2 * t + (lane >> 5)) * 16 + (lane & 15);
+        bsrc[p] = pblob + ((int64_t)chunk_row * KTfull + kbeg) * 64 + (2 * t + (lane >> 5)) * 16 + (lane & 15);
     }
     // LDS byte address (wave-uniform, kept in a scalar register) of this
     // wavefront's first activation chunk in stage 0
@@ -270,6 +290,22 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_tiled_kernel(const TiledArgs
 #undef AGQ_STEP
     __syncthreads();                                   // every wavefront is done with the stages
 
+    if (SPLIT) {
+        // accumulator piece c = (i * 2 + j) * 4 + q of thread t at [c][t]: 16 bytes per lane, contiguous
+        int4 *const mine = reinterpret_cast<int4 *>(a.part) + ((int64_t)tile_id * a.splits + split) * (16 * kThreads) + threadIdx.x;
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+            if (m0 + wm * 64 + i * 32 >= a.M) continue;   // no token in these 32 rows: nobody reads them (uniform)
+#pragma unroll
+            for (int j = 0; j < 2; ++j)
+#pragma unroll
+                for (int q = 0; q < 4; ++q)
+                    mine[((i * 2 + j) * 4 + q) * kThreads] =
+                        make_int4(acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]);
+        }
+        return;
+    }
+
     // Fused epilogue.  Drop the factor 16 of the widened weights, dequantize with
     // 2^e * sw[n] in registers, then transpose through LDS: a lane holds four
     // consecutive channels of one token (8 bytes), the store wants eight lanes
@@ -346,10 +382,64 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_tiled_kernel(const TiledArgs
     }
 }
 
+// Second kernel of a K split: workgroup (tile, piece c) adds the `splits` partial copies of accumulator piece c of
+// every thread of the tile's workgroups (same thread numbering, same tile walk as above) and runs the same
+// epilogue arithmetic on the sums; a thread owns four consecutive channels of one token.
+__global__ __launch_bounds__(kThreads) void split_reduce_kernel(const TiledArgs a) {
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int wm = wave >> 1, wn = wave & 1;
+    const int tile_id = blockIdx.x >> 4, c = blockIdx.x & 15;
+    const int i = c >> 3, j = (c >> 2) & 1, q = c & 3;
+    int bid = tile_id;
+    const int pj = (bid >= a.tile_start[1]) + (bid >= a.tile_start[2]) + (bid >= a.tile_start[3]);
+    auto pick = [pj](auto v0, auto v1, auto v2, auto v3) { return pj == 0 ? v0 : (pj == 1 ? v1 : (pj == 2 ? v2 : v3)); };
+    bid -= pick(0, a.tile_start[1], a.tile_start[2], a.tile_start[3]);
+    const int pN = pick(a.N4[0], a.N4[1], a.N4[2], a.N4[3]);
+    const int ptiles_n = pick(a.tiles_n4[0], a.tiles_n4[1], a.tiles_n4[2], a.tiles_n4[3]);
+    const uint16_t *const psw = reinterpret_cast<const uint16_t *>(pick(a.sw4[0], a.sw4[1], a.sw4[2], a.sw4[3]));
+    __half *const py = pick(a.y4[0], a.y4[1], a.y4[2], a.y4[3]);
+    const int64_t pldy = pick(a.ldy4[0], a.ldy4[1], a.ldy4[2], a.ldy4[3]);
+    int32_t *const pacc = pick(a.acc4[0], a.acc4[1], a.acc4[2], a.acc4[3]);
+    const int32_t *const pwsum = pick(a.wsum4[0], a.wsum4[1], a.wsum4[2], a.wsum4[3]);
+    const int band = bid / (kBand * ptiles_n);
+    const int rows = min(kBand, a.tiles_m - band * kBand);
+    const int within = bid - band * kBand * ptiles_n;
+    const int tn = within / rows, tm = band * kBand + within - tn * rows;
+    const int m = tm * BM + wm * 64 + i * 32 + (lane & 31);
+    const int n = tn * BN + wn * 64 + j * 32 + q * 8 + (lane >> 5) * 4;
+
+    if (m >= a.M || n >= pN) return;
+    const int4 *src = reinterpret_cast<const int4 *>(a.part) + ((int64_t)tile_id * a.splits * 16 + c) * kThreads + threadIdx.x;
+    int sum[4] = {0, 0, 0, 0};
+#pragma unroll 4
+    for (int s = 0; s < a.splits; ++s) {
+        const int4 v = src[(int64_t)s * (16 * kThreads)];
+        sum[0] += v.x;
+        sum[1] += v.y;
+        sum[2] += v.z;
+        sum[3] += v.w;
+    }
+    uint32_t h[4];
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+        const int nn = min(n + r, pN - 1);   // channels past N are not stored
+        if (a.corr) sum[r] += (a.corr * pwsum[nn]) << AGQ_W_SHIFT;
+        const int v = sum[r] >> AGQ_W_SHIFT;
+        if (pacc && n + r < pN) pacc[(int64_t)m * pN + n + r] = v;
+        h[r] = __half_as_ushort(agq_dequant(v, a.scale_e * __half2float(__ushort_as_half((unsigned short)psw[nn]))));
+    }
+    __half *yp = py + (int64_t)m * pldy + n;
+    if ((pldy & 3) == 0 && n + 3 < pN) {
+        *reinterpret_cast<uint2 *>(yp) = make_uint2(h[0] | (h[1] << 16), h[2] | (h[3] << 16));
+    } else {
+        for (int r = 0; r < 4 && n + r < pN; ++r) yp[r] = __ushort_as_half((unsigned short)h[r]);
+    }
+}
+
 }  // namespace
 
 int agq_launch_gemm_tiled(const void *x_tiles, int64_t M, int64_t K, int e, int corr, const struct agq_proj *projs, int count,
-                          int n_extra, void *stream) {
+                          int n_extra, void *split_ws, void *stream) {
     TiledArgs a = {};
     a.xt = (const agq_u4 *)x_tiles;
     a.M = (int)M;
@@ -377,15 +467,27 @@ int agq_launch_gemm_tiled(const void *x_tiles, int64_t M, int64_t K, int e, int 
     }
     for (int p = count; p <= kMaxProj; ++p) a.tile_start[p] = tiles;
     const unsigned grid = (unsigned)tiles;
+    if (split_ws && n_extra < 0) {
+        const AgqSplitPlan plan = agq_tiled_split_plan(M, tiles / a.tiles_m, a.KT, true);
+        if (plan.splits > 1) {
+            a.splits = plan.splits;
+            a.steps_per_split = plan.steps;
+            a.tiles_all = tiles;
+            a.part = (int32_t *)split_ws;
+            gemm_tiled_kernel<false, true><<<grid * (unsigned)plan.splits, kThreads, 0, (hipStream_t)stream>>>(a);
+            split_reduce_kernel<<<grid * 16, kThreads, 0, (hipStream_t)stream>>>(a);
+            return (int)hipGetLastError();
+        }
+    }
     if (n_extra >= 0) {
         // every blob of the call was packed with the same factors: the shift table of the first serves all
         const AgqTripLayout L = agq_trip_layout(projs[0].N, K, n_extra);
         a.KT = (int)L.KTall;
         a.n_extra = n_extra;
         a.trip_shift = (const int32_t *)((const char *)projs[0].w_packed + L.meta_off) + 16;
-        gemm_tiled_kernel<true><<<grid, kThreads, 0, (hipStream_t)stream>>>(a);
+        gemm_tiled_kernel<true, false><<<grid, kThreads, 0, (hipStream_t)stream>>>(a);
     } else {
-        gemm_tiled_kernel<false><<<grid, kThreads, 0, (hipStream_t)stream>>>(a);
+        gemm_tiled_kernel<false, false><<<grid, kThreads, 0, (hipStream_t)stream>>>(a);
     }
     return (int)hipGetLastError();
 }

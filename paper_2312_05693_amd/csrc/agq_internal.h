@@ -46,15 +46,47 @@ static inline AgqTripLayout agq_trip_layout(int64_t N, int64_t K, int E) {
 
 // tokens up to which the weight-streaming kernel is used
 #define AGQ_DECODE_MAX_M 16
-// ... and beyond that, sixteen rows per workgroup (grid.y row groups): every row group reads the weights again
-// (from L2 after the first), so this pays while those reads stay small.  Measured on MI355X against the pre-pass
-// plus the tiled kernel, which needs hundreds of 128 x 128 tiles to fill the chip and walks K serially: the
-// row-group launch takes about 3.5 us + 0.36 us per MB read, the other path about 6.6 us + 3.7 us per 1000 of K
-// (768 x 768 at 128 rows: 4.5 against 9.7 us; 4096 x 4096 at 64 rows: 16.7 against 22.2 us).
+// K split of the tiled kernel.  A workgroup that has its CU (or its half of one) to itself takes about 470 ns per
+// K step (sixteen 64-cycle MFMAs per wavefront), however few workgroups the launch has: with few 128 x 128 tiles and
+// a long K most CUs idle while a few walk K.  Then `splits` workgroups share a tile's K steps (at least four each,
+// at most one workgroup per CU in all) and leave int32 partial tiles behind the activation codes in the workspace,
+// which a second kernel adds up.  That costs about 2 us for the launch and 0.45 us per MB of partial tiles
+// (written, read back); the plan is the split count with the smallest sum under this model (all measured on
+// MI355X).  M tokens, tiles_n = 128-wide column tiles of all projections of the call, KT = K steps.
+// splits == 1: no split, bytes == 0.
+struct AgqSplitPlan {
+    int splits, steps;
+    size_t bytes;
+    int64_t cost_ns;   // the model's time for the chosen plan (GEMM launches only)
+};
+static inline AgqSplitPlan agq_tiled_split_plan(int64_t M, int64_t tiles_n, int64_t KT, bool may_split) {
+    const int64_t tiles = ((M + 127) / 128) * tiles_n;
+    AgqSplitPlan p = {1, (int)KT, 0, KT * 470 * (tiles > 256 ? (tiles + 255) / 256 : 1)};
+    if (!may_split || tiles < 1 || tiles * 2 > 256 || KT < 8) return p;
+    const int64_t part_bytes = ((M + 31) / 32) * 32 * tiles_n * 512;   // per split: rows that hold tokens x columns x 4
+    for (int64_t s = 2; s <= KT / 4 && s * tiles <= 256; ++s) {
+        const int64_t steps = (KT + s - 1) / s;
+        if ((KT + steps - 1) / steps != s) continue;                   // the same steps with fewer workgroups exist
+        const int64_t cost = steps * 470 + 2000 + part_bytes * s * 450 / 1000000;
+        if (cost < p.cost_ns) {
+            p.cost_ns = cost;
+            p.splits = (int)s;
+            p.steps = (int)steps;
+        }
+    }
+    if (p.splits > 1) p.bytes = (size_t)tiles * p.splits * (128 * 128 * 4);
+    return p;
+}
+
+// Between 17 and 256 rows of fp16 input the weight-streaming kernel can run with sixteen rows per workgroup
+// (grid.y row groups): every row group reads the weights again (from L2 after the first), about 3.5 us +
+// 0.36 us per MB read in all.  The other path is the layout pre-pass plus the tiled kernel: about 8 us around
+// the plan's time above (768 x 768 at 128 rows: 4.5 against 9.7 us; 4096 x 4096 at 32 rows: 9.5 against 13.3 us,
+// at 64 rows 16.2 against 14.6 us).  tiled_ns: the cost of the plan the call would run.
 #define AGQ_ROW_GROUP_MAX_M 256
-static inline bool agq_decode_row_groups(int x_kind, int64_t M, int64_t K, int64_t n_sum) {
+static inline bool agq_decode_row_groups(int x_kind, int64_t M, int64_t K, int64_t n_sum, int64_t tiled_ns) {
     return x_kind == 0 && M > AGQ_DECODE_MAX_M && M <= AGQ_ROW_GROUP_MAX_M &&
-           ((M + 15) / 16) * (K * n_sum / 2) <= 6000000 + 10200 * K;
+           3500 + ((M + 15) / 16) * (K * n_sum / 2) * 360 / 1000000 <= 8000 + tiled_ns;
 }
 
 int agq_launch_calibrate(const void *x, int64_t M, int64_t K, int64_t ldx, int bits, int32_t *e_dev, void *stream);
@@ -70,8 +102,9 @@ int agq_launch_gemm_decode(const void *x, int x_kind, int bits, int64_t M, int64
                            const struct agq_proj *projs, int count, int n_extra, void *stream);
 // K counts the main chunks only; with TRIP blobs (all packed with the same factors) x_tiles and the blobs hold
 // n_extra more steps in front.  The `count` projections of the activation run as one launch.
+// split_ws != NULL (plain blobs only): room for the partial tiles agq_tiled_split_plan describes for this call's tiles.
 int agq_launch_gemm_tiled(const void *x_tiles, int64_t M, int64_t K, int e, int corr, const struct agq_proj *projs, int count,
-                          int n_extra, void *stream);
+                          int n_extra, void *split_ws, void *stream);
 int agq_launch_trip_search(const void *x, int64_t M, int64_t K, int64_t ldx, int bits, int e, int zp, int kmax,
                            int8_t *alpha, void *stream);
 int agq_trip_count_extra(const int8_t *alpha_host, int64_t K);   // number of extra chunks, -1 = bad factors or too many

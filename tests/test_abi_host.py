@@ -46,6 +46,14 @@ def test_sizes(lib):
     assert lib.agq_pack_w4_bytes(0, 128) == 0
     assert lib.agq_gemm_workspace_bytes(16, 4096, 4096) == 0
     assert lib.agq_gemm_workspace_bytes(2048, 4096, 4096) == 2048 * 4096
+    # few tiles and a long K: room for the int32 partial tiles of a K split behind the codes (whole 64 KiB
+    # tiles); N = 0 asks for the codes alone
+    codes = 128 * 4096
+    assert lib.agq_gemm_workspace_bytes(128, 0, 4096) == codes
+    extra = lib.agq_gemm_workspace_bytes(128, 4096, 4096) - codes
+    assert extra > 0 and extra % (128 * 128 * 4) == 0 and extra <= 256 * 128 * 128 * 4
+    assert lib.agq_gemm_workspace_bytes(100, 11008, 4096) > lib.agq_gemm_workspace_bytes(100, 0, 4096)
+    assert lib.agq_gemm_workspace_bytes(128, 768, 768) == 128 * 768           # short K: no split
 
 
 def test_argument_errors_need_no_gpu(lib):
@@ -229,7 +237,7 @@ def test_block_layout_and_host_checks(lib):
     assert call(fn=lib.agq_block_calibrate, blk=_fake_block(binding, trip_attn_out=0)) == EINVAL
     L2 = binding.AgqBlockLayout()
     assert lib.agq_block_layout_of(ctypes.byref(_fake_block(binding, trip_mlp_act=3)), 200, 150, ctypes.byref(L2)) == 0
-    assert lay(blk, 200, 150) == 0 and L2.total - L2.gemm_ws >= 256 * (1408 + 3 * 128) > L.total - L.gemm_ws - 512
+    assert lay(blk, 200, 150) == 0 and L2.total - L2.gemm_ws >= 256 * (1408 + 3 * 128) > 256 * 1408
     assert lib.agq_block_forward(None, p, p, p, p, 256, 200, 150, p, p, p, 1 << 40, None) == EINVAL
 
 
@@ -243,7 +251,12 @@ def test_stack_host_checks(lib):
     assert lib.agq_block_layout_of(ctypes.byref(arr[0]), 200, 200, ctypes.byref(L)) == 0
     full = size(200, keep(200, 200, 200))
     assert full == L.total + 2 * 200 * 512 * 2 + 2 * 1024          # two token buffers, two position buffers, one block
-    assert size(200, keep(200, 150, 100)) == full                   # the first block is the largest
+    # the largest block decides (not always the first: fewer tokens can mean more room for split-K partial tiles)
+    totals = []
+    for S_in, k in ((200, 200), (200, 150), (150, 100)):
+        assert lib.agq_block_layout_of(ctypes.byref(arr[0]), S_in, k, ctypes.byref(L)) == 0
+        totals.append(L.total)
+    assert size(200, keep(200, 150, 100)) == max(totals) + 2 * 200 * 512 * 2 + 2 * 1024
     assert size(200, keep(150, 160, 100)) == 0 and size(200, keep(201, 100, 100)) == 0 and size(0, keep(1, 1, 1)) == 0
     p = ctypes.c_void_p(4096)
     call = lambda k, ws=p, wsb=1 << 40, x=p: lib.agq_stack_forward(ctypes.cast(arr, ctypes.c_void_p), n, k, x, p, p, p, 256,

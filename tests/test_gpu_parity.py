@@ -207,6 +207,74 @@ def test_row_groups_and_the_switch_to_tiles(agq, oracle, M, K, N, bits, zp):
     assert np.array_equal(a2[M // 2], a1[0])
 
 
+@pytest.mark.parametrize("M,K,N,bits,zp,x_kind", [(300, 2048, 384, 8, 0, "f16"), (290, 2048, 500, 4, 0, "f16"),
+                                                    (700, 2816, 272, 8, 131, "f16"), (260, 2560, 130, 8, 0, "q"),
+                                                    (128, 4096, 4096, 8, 0, "f16"), (257, 4096, 4096, 4, 9, "f16"),
+                                                    (400, 11008, 4096, 8, 0, "f16"), (300, 13824, 640, 8, 0, "q")])
+def test_tiled_split_k(agq, oracle, M, K, N, bits, zp, x_kind):
+    """Few 128 x 128 tiles and a long K: the K steps of a tile are shared out over several workgroups, whose int32
+    partial tiles a second kernel adds up.  Against the oracle (sampled rows at the large sizes), against the
+    same call with a workspace that only has room for the activation (no split), and call after call into the same
+    workspace."""
+    x, wq, sw = make_case(M, K, N, seed=900 + M + N, n_out=6)
+    e = oracle.calibrate_act_exp(x, bits) + (1 if zp else 0)
+    full, small = agq.gemm_workspace_bytes(M, N, K), agq.gemm_workspace_bytes(M, 0, K)
+    assert full > small == -(-M // 128) * 128 * K       # these shapes are split
+    fn = agq.gemm_w4a8 if bits == 8 else agq.gemm_w4a4
+    if x_kind == "f16":
+        xin, kind = dev(x), agq.AGQ_X_F16
+    else:
+        xin, kind = agq.quantize_act(dev(x), bits, e, zp), agq.AGQ_X_Q
+    packed, swd = agq.pack_w4(dev(wq)), dev(sw)
+    ws = torch.empty(full, dtype=torch.uint8, device="cuda")
+    ws.fill_(0xA5)                                       # nothing relies on what the workspace held
+    outs = []
+    for rep in range(3):
+        acc = torch.full((M, N), -3, dtype=torch.int32, device="cuda")
+        y = fn(xin, e, packed, swd, N, K, x_kind=kind, acc_out=acc, zp=zp, workspace=ws)
+        outs.append((host(acc), host(y)))
+    acc1 = torch.full((M, N), -3, dtype=torch.int32, device="cuda")
+    y1 = fn(xin, e, packed, swd, N, K, x_kind=kind, acc_out=acc1, zp=zp, workspace=ws[:small])
+    for a, yy in outs:
+        assert np.array_equal(a, host(acc1)) and np.array_equal(yy.view(np.int16), host(y1).view(np.int16))
+    rows = list(range(M)) if M * K * N <= 3e8 else sorted({0, 1, 31, 32, 127, M // 2, M - 2, M - 1} & set(range(M)))
+    acc_w, y_w = oracle.linear_w4(x[rows], bits, e, zp, wq, sw)
+    assert np.array_equal(outs[0][0][rows].astype(np.int64), acc_w)
+    assert_f16_close(outs[0][1][rows], y_w, "y")
+
+
+def test_tiled_split_k_multi_and_graph(agq, oracle):
+    # q/k/v-style call whose tiles together are still few: one split launch over all projections; replayed as a graph
+    M, K, Ns, bits = 300, 2048, [256, 100, 384], 8
+    x = synth.make_activation(M, K, 4, seed=910)
+    e = oracle.calibrate_act_exp(x, bits)
+    xd = dev(x)
+    projs, wants = [], []
+    for i, N in enumerate(Ns):
+        wq, sw = synth.make_weight_q4(N, K, seed=920 + i)
+        projs.append((agq.pack_w4(dev(wq)), dev(sw), N, torch.empty((M, N), dtype=torch.float16, device="cuda"),
+                      torch.empty((M, N), dtype=torch.int32, device="cuda")))
+        wants.append(oracle.linear_w4(x, bits, e, 0, wq, sw))
+    full = agq.gemm_workspace_bytes(M, sum(Ns), K)
+    assert full > agq.gemm_workspace_bytes(M, 0, K)
+    ws = torch.empty(full, dtype=torch.uint8, device="cuda")
+    agq.gemm_w4a8_multi(xd, e, projs, K, workspace=ws)
+    for (acc_w, y_w), p in zip(wants, projs):
+        assert np.array_equal(host(p[4]).astype(np.int64), acc_w)
+        assert_f16_close(host(p[3]), y_w, "multi split")
+    eager = [host(p[3]).copy() for p in projs]
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        agq.gemm_w4a8_multi(xd, e, projs, K, workspace=ws)
+    for rep in range(3):
+        for p in projs:
+            p[3].zero_()
+        g.replay()
+        torch.cuda.synchronize()
+        for want, p in zip(eager, projs):
+            assert np.array_equal(host(p[3]).view(np.int16), want.view(np.int16))
+
+
 def test_row_groups_strided_multi(agq, oracle):
     # strided input and output, several projections, the 4-bit grid: 100 rows in seven groups (the last with four)
     M, K, Ns, bits = 100, 512, [64, 272, 100], 4
