@@ -189,7 +189,8 @@ int agq_gemm_w4a4_multi(const void *x, int x_kind, int64_t M, int64_t K, int64_t
  * agq_gemm_w4a8_trip / agq_gemm_w4a4_trip: the layer above with b = 8 / 4.
  * x_f16 is fp16 [M,K] (ldx % 8 == 0, 16-byte aligned): the quantizer runs inside
  * the call.  n_extra: as returned by agq_trip_extra_chunks for the factors the
- * blob was packed with.  workspace: agq_gemm_trip_workspace_bytes(M,N,K,n_extra).
+ * blob was packed with.  workspace: agq_gemm_trip_workspace_bytes(M,N,K,n_extra)
+ * (with N = 0: the activation alone, accepted too, as for agq_gemm_w4a8).
  * Other arguments, alignment and errors as for agq_gemm_w4a8.                 */
 #define AGQ_TRIP_MAX_FACTOR 4
 #define AGQ_TRIP_MAX_EXTRA 16
@@ -214,7 +215,7 @@ int agq_gemm_w4a4_trip(const void *x_f16, int64_t M, int64_t K, int64_t ldx, int
  * activation, so q/k/v or gate/up share them): every blob packed with the same
  * factors, n_extra theirs.  One quantize-and-gather pass, one launch.  projs as for
  * agq_gemm_w4a8_multi; workspace: agq_gemm_trip_workspace_bytes(M, N, K, n_extra)
- * for any N.                                                                     */
+ * with N = the widths added up.                                                  */
 int agq_gemm_w4a8_trip_multi(const void *x_f16, int64_t M, int64_t K, int64_t ldx, int e, int zp,
                              const agq_proj *projs, int count, int n_extra, void *workspace,
                              size_t workspace_bytes, void *stream);

@@ -294,7 +294,7 @@ def gemm_trip_multi(x, bits, e, projs, n_extra, K, workspace=None, zp=0):
             y = torch.empty((M, N), dtype=torch.float16, device=x.device)
         ys.append(y)
         arr[i] = AgqProj(_ptr(packed), _ptr(scale), N, _ptr(y), y.stride(0) if M else N, _ptr(acc))
-    need = lib().agq_gemm_trip_workspace_bytes(M, projs[0][2], K, n_extra)
+    need = lib().agq_gemm_trip_workspace_bytes(M, sum(p[2] for p in projs), K, n_extra)
     if workspace is None and need:
         workspace = torch.empty(need, dtype=torch.uint8, device=x.device)
     fn = lib().agq_gemm_w4a8_trip_multi if bits == 8 else lib().agq_gemm_w4a4_trip_multi

@@ -98,7 +98,7 @@ int gemm_w4_trip_multi(int bits, const void *x, int64_t M, int64_t K, int64_t ld
         if (!aligned16(projs[p].w_packed) || !aligned16(projs[p].w_scale_f16) || !aligned16(projs[p].y_f16))
             return AGQ_EINVAL;
     }
-    const size_t need = agq_gemm_trip_workspace_bytes(M, projs[0].N, K, n_extra);
+    const size_t need = M <= AGQ_DECODE_MAX_M ? 0 : codes_bytes(M, K + 128 * (int64_t)n_extra);
     if (need > 0) {
         if (!workspace || !aligned16(workspace)) return AGQ_EINVAL;
         if (workspace_bytes < need) return AGQ_ESIZE;
@@ -107,8 +107,14 @@ int gemm_w4_trip_multi(int bits, const void *x, int64_t M, int64_t K, int64_t ld
         return hip_status(agq_launch_gemm_decode(x, AGQ_X_F16, bits, M, K, ldx, e, zp, projs, count, n_extra, stream));
     if (agq_launch_prepack_trip(x, bits, M, K, ldx, e, zp, projs[0].w_packed, projs[0].N, n_extra, workspace, stream))
         return AGQ_EHIP;
+    // few tiles and a long K: K split over workgroups when the workspace has the room (as for plain blobs)
+    int64_t tiles_n = 0;
+    for (int p = 0; p < count; ++p) tiles_n += (projs[p].N + 127) / 128;
+    const AgqSplitPlan plan = agq_tiled_split_plan(M, tiles_n, K / 128 + n_extra, true, n_extra);
+    void *const split_ws =
+        plan.splits > 1 && workspace_bytes >= need + plan.bytes ? static_cast<char *>(workspace) + need : nullptr;
     return hip_status(
-        agq_launch_gemm_tiled(workspace, M, K, e, agq_zp_corr(bits, zp), projs, count, n_extra, nullptr, stream));
+        agq_launch_gemm_tiled(workspace, M, K, e, agq_zp_corr(bits, zp), projs, count, n_extra, split_ws, stream));
 }
 
 int gemm_w4_trip(int bits, const void *x, int64_t M, int64_t K, int64_t ldx, int e, int zp, const void *w_packed,
@@ -218,9 +224,14 @@ int agq_unpack_w4_trip(const void *packed, int64_t N, int64_t K, int n_extra, in
 }
 
 size_t agq_gemm_trip_workspace_bytes(int64_t M, int64_t N, int64_t K, int n_extra) {
-    (void)N;
     if (M <= AGQ_DECODE_MAX_M || K < 1 || n_extra < 0) return 0;
-    return (size_t)((M + 127) / 128) * 128 * (size_t)(K + 128 * (int64_t)n_extra);
+    const int64_t tiles_n = N > 0 ? (N + 127) / 128 : 0;
+    size_t split = 0;
+    for (int64_t t = tiles_n; t <= tiles_n + 3 && t > 0; ++t) {
+        const AgqSplitPlan plan = agq_tiled_split_plan(M, t, K / 128 + n_extra, true, n_extra);
+        if (plan.bytes > split) split = plan.bytes;
+    }
+    return codes_bytes(M, K + 128 * (int64_t)n_extra) + split;
 }
 
 int agq_gemm_w4a8_trip(const void *x_f16, int64_t M, int64_t K, int64_t ldx, int e, int zp, const void *w_packed,

@@ -277,7 +277,7 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_tiled_kernel(const TiledArgs
             asm volatile("s_waitcnt vmcnt(0)" ::: "memory");                 \
         __syncthreads();                                                     \
         step((KT_), NXT, FILL, XC, BC, XN, BN);                              \
-        if (TRIP && (KT_) < a.n_extra) shift_acc(a.trip_shift[(KT_)]);       \
+        if (TRIP && split == 0 && (KT_) < a.n_extra) shift_acc(a.trip_shift[(KT_)]); \
     }
     for (int kt = 0; kt < KT; kt += 6) {      // stage of step kt is kt % 3, register set kt % 2
         AGQ_STEP(kt, stage1, stage0, xa0, b0, xa1, b1)
@@ -467,27 +467,33 @@ int agq_launch_gemm_tiled(const void *x_tiles, int64_t M, int64_t K, int e, int 
     }
     for (int p = count; p <= kMaxProj; ++p) a.tile_start[p] = tiles;
     const unsigned grid = (unsigned)tiles;
-    if (split_ws && n_extra < 0) {
-        const AgqSplitPlan plan = agq_tiled_split_plan(M, tiles / a.tiles_m, a.KT, true);
-        if (plan.splits > 1) {
-            a.splits = plan.splits;
-            a.steps_per_split = plan.steps;
-            a.tiles_all = tiles;
-            a.part = (int32_t *)split_ws;
-            gemm_tiled_kernel<false, true><<<grid * (unsigned)plan.splits, kThreads, 0, (hipStream_t)stream>>>(a);
-            split_reduce_kernel<<<grid * 16, kThreads, 0, (hipStream_t)stream>>>(a);
-            return (int)hipGetLastError();
-        }
-    }
+    hipStream_t st = (hipStream_t)stream;
     if (n_extra >= 0) {
         // every blob of the call was packed with the same factors: the shift table of the first serves all
         const AgqTripLayout L = agq_trip_layout(projs[0].N, K, n_extra);
         a.KT = (int)L.KTall;
         a.n_extra = n_extra;
         a.trip_shift = (const int32_t *)((const char *)projs[0].w_packed + L.meta_off) + 16;
-        gemm_tiled_kernel<true, false><<<grid, kThreads, 0, (hipStream_t)stream>>>(a);
-    } else {
-        gemm_tiled_kernel<false, false><<<grid, kThreads, 0, (hipStream_t)stream>>>(a);
     }
+    if (split_ws) {
+        // the extra steps and their shifts stay together in the first slice
+        const AgqSplitPlan plan = agq_tiled_split_plan(M, tiles / a.tiles_m, a.KT, true, n_extra >= 0 ? n_extra : 0);
+        if (plan.splits > 1) {
+            a.splits = plan.splits;
+            a.steps_per_split = plan.steps;
+            a.tiles_all = tiles;
+            a.part = (int32_t *)split_ws;
+            if (n_extra >= 0)
+                gemm_tiled_kernel<true, true><<<grid * (unsigned)plan.splits, kThreads, 0, st>>>(a);
+            else
+                gemm_tiled_kernel<false, true><<<grid * (unsigned)plan.splits, kThreads, 0, st>>>(a);
+            split_reduce_kernel<<<grid * 16, kThreads, 0, st>>>(a);
+            return (int)hipGetLastError();
+        }
+    }
+    if (n_extra >= 0)
+        gemm_tiled_kernel<true, false><<<grid, kThreads, 0, st>>>(a);
+    else
+        gemm_tiled_kernel<false, false><<<grid, kThreads, 0, st>>>(a);
     return (int)hipGetLastError();
 }

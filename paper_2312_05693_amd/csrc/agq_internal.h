@@ -47,26 +47,27 @@ static inline AgqTripLayout agq_trip_layout(int64_t N, int64_t K, int E) {
 // tokens up to which the weight-streaming kernel is used
 #define AGQ_DECODE_MAX_M 16
 // K split of the tiled kernel.  A workgroup that has its CU (or its half of one) to itself takes about 470 ns per
-// K step (sixteen 64-cycle MFMAs per wavefront), however few workgroups the launch has: with few 128 x 128 tiles and
-// a long K most CUs idle while a few walk K.  Then `splits` workgroups share a tile's K steps (at least four each,
+// K step (twice the time of its MFMAs: a single wavefront per SIMD cannot cover its own waits), however few
+// workgroups the launch has: with few 128 x 128 tiles and a long K most CUs idle while a few walk K.  Then `splits` workgroups share a tile's K steps (at least four each,
 // at most one workgroup per CU in all) and leave int32 partial tiles behind the activation codes in the workspace,
 // which a second kernel adds up.  That costs about 2 us for the launch and 0.45 us per MB of partial tiles
 // (written, read back); the plan is the split count with the smallest sum under this model (all measured on
-// MI355X).  M tokens, tiles_n = 128-wide column tiles of all projections of the call, KT = K steps.
+// MI355X).  M tokens, tiles_n = 128-wide column tiles of all projections of the call, KT = K steps (TRIP
+// blobs: the extra steps in front included, all of which stay in the first slice: min_steps of them).
 // splits == 1: no split, bytes == 0.
 struct AgqSplitPlan {
     int splits, steps;
     size_t bytes;
     int64_t cost_ns;   // the model's time for the chosen plan (GEMM launches only)
 };
-static inline AgqSplitPlan agq_tiled_split_plan(int64_t M, int64_t tiles_n, int64_t KT, bool may_split) {
+static inline AgqSplitPlan agq_tiled_split_plan(int64_t M, int64_t tiles_n, int64_t KT, bool may_split, int min_steps = 0) {
     const int64_t tiles = ((M + 127) / 128) * tiles_n;
     AgqSplitPlan p = {1, (int)KT, 0, KT * 470 * (tiles > 256 ? (tiles + 255) / 256 : 1)};
     if (!may_split || tiles < 1 || tiles * 2 > 256 || KT < 8) return p;
     const int64_t part_bytes = ((M + 31) / 32) * 32 * tiles_n * 512;   // per split: rows that hold tokens x columns x 4
     for (int64_t s = 2; s <= KT / 4 && s * tiles <= 256; ++s) {
         const int64_t steps = (KT + s - 1) / s;
-        if ((KT + steps - 1) / steps != s) continue;                   // the same steps with fewer workgroups exist
+        if ((KT + steps - 1) / steps != s || steps < min_steps) continue;   // the same steps with fewer workgroups exist
         const int64_t cost = steps * 470 + 2000 + part_bytes * s * 450 / 1000000;
         if (cost < p.cost_ns) {
             p.cost_ns = cost;
@@ -102,7 +103,7 @@ int agq_launch_gemm_decode(const void *x, int x_kind, int bits, int64_t M, int64
                            const struct agq_proj *projs, int count, int n_extra, void *stream);
 // K counts the main chunks only; with TRIP blobs (all packed with the same factors) x_tiles and the blobs hold
 // n_extra more steps in front.  The `count` projections of the activation run as one launch.
-// split_ws != NULL (plain blobs only): room for the partial tiles agq_tiled_split_plan describes for this call's tiles.
+// split_ws != NULL: room for the partial tiles agq_tiled_split_plan describes for this call's tiles.
 int agq_launch_gemm_tiled(const void *x_tiles, int64_t M, int64_t K, int e, int corr, const struct agq_proj *projs, int count,
                           int n_extra, void *split_ws, void *stream);
 int agq_launch_trip_search(const void *x, int64_t M, int64_t K, int64_t ldx, int bits, int e, int zp, int kmax,

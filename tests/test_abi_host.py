@@ -161,7 +161,9 @@ def test_trip_and_fused_attention_host_checks(lib):
     assert lib.agq_pack_w4_trip_bytes(100, K, 0) == lib.agq_pack_w4_bytes(100, K) + 128 + K
     assert lib.agq_pack_w4_trip_bytes(100, K, 17) == 0 and lib.agq_pack_w4_trip_bytes(100, 65536, 1) == 0
     assert lib.agq_gemm_trip_workspace_bytes(16, 64, K, 2) == 0
-    assert lib.agq_gemm_trip_workspace_bytes(130, 64, K, 2) == 256 * (K + 256)
+    assert lib.agq_gemm_trip_workspace_bytes(130, 0, K, 2) == 256 * (K + 256)          # the codes alone
+    split_room = lib.agq_gemm_trip_workspace_bytes(130, 64, K, 2) - 256 * (K + 256)  # + partial tiles of a K split
+    assert split_room > 0 and split_room % (128 * 128 * 4) == 0
     p = ctypes.c_void_p(4096)
     odd = ctypes.c_void_p(4100)
     trip = lambda **kw: lib.agq_gemm_w4a8_trip(kw.get("x", p), kw.get("M", 4), kw.get("K", K), kw.get("ldx", K),

@@ -835,6 +835,34 @@ def test_trip_linear_tiled(agq, oracle, M, K, N, bits):
     run_trip_linear(agq, oracle, x, wq, sw, bits, e, random_alpha(rng, K, (0, 0, 0, 1)))
 
 
+@pytest.mark.parametrize("M,K,N,bits,zp", [(300, 4096, 300, 8, 0), (140, 8192, 700, 4, 9)])
+def test_trip_tiled_split_k(agq, oracle, M, K, N, bits, zp):
+    """TRIP blobs with few tiles and a long K: the K split keeps the extra steps and their shifts in the first slice.
+    Against the oracle and, bit for bit, against the call with a workspace too small for a split."""
+    rng = np.random.default_rng(43)
+    kmax = 4 if bits == 8 else 3
+    x, wq, sw, e = trip_case(M, K, N, 70 + M, K // 100, kmax, bits, oracle)
+    e += 1 if zp else 0
+    alpha = random_alpha(rng, K, (140, 3, 0, 20)[:kmax] + (0,) * (4 - kmax))
+    packed, n_extra = agq.pack_w4_trip(dev(wq), alpha)
+    assert n_extra >= 3
+    full = agq.lib().agq_gemm_trip_workspace_bytes(M, N, K, n_extra)
+    small = agq.lib().agq_gemm_trip_workspace_bytes(M, 0, K, n_extra)
+    assert full > small == -(-M // 128) * 128 * (K + 128 * n_extra)
+    res = []
+    for nbytes in (full, small, full):
+        ws = torch.empty(nbytes, dtype=torch.uint8, device="cuda").fill_(0x5A)
+        acc = torch.empty((M, N), dtype=torch.int32, device="cuda")
+        y = agq.gemm_trip(dev(x), bits, e, packed, n_extra, dev(sw), N, K, acc_out=acc, zp=zp, workspace=ws)
+        res.append((host(acc), host(y)))
+    for a, yy in res[1:]:
+        assert np.array_equal(a, res[0][0]) and np.array_equal(yy.view(np.int16), res[0][1].view(np.int16))
+    rows = sorted({0, 1, 31, 32, 127, 128, M // 2, M - 1})
+    want_acc, want_y = oracle.linear_w4_trip(x[rows], bits, e, zp, alpha, wq, sw)
+    assert np.array_equal(res[0][0][rows].astype(np.int64), want_acc)
+    assert_f16_close(res[0][1][rows], want_y, "trip split")
+
+
 @pytest.mark.parametrize("M,bits,zp", [(1, 8, 0), (9, 8, 0), (16, 4, 0), (40, 8, 0), (300, 8, 131), (130, 4, 0)])
 def test_trip_multi_projection(agq, oracle, M, bits, zp):
     """The factors belong to the activation: three projections packed with the same factors, one call."""
