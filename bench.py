@@ -61,6 +61,7 @@ def main():
     ap.add_argument("--no-attention", action="store_true")
     ap.add_argument("--no-trip", action="store_true")
     ap.add_argument("--no-block", action="store_true")
+    ap.add_argument("--no-by-m", action="store_true", help="skip the sweep over 32..1024 rows in the prefill section")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also run a 256 MiB device copy: the known traffic that scales the FETCH_SIZE / WRITE_SIZE counters")
     ap.add_argument("--per-projection", action="store_true", help="seven single calls per block instead of four")
@@ -290,7 +291,7 @@ def main():
         # replayed graph): row groups of the weight-streaming kernel, then the tiled kernel with K split over
         # workgroups while it has few tiles
         by_m = []
-        for i in (0, 4, 6):
+        for i in (() if args.no_by_m else (0, 4, 6)):
             pname, K, N = synth.LLAMA7B_PROJ[i]
             row = {"proj": pname, "K": K, "N": N}
             e8 = int(agq.calibrate_act_exp(xk[K], 8).item())
@@ -306,7 +307,8 @@ def main():
                 us = timed(calls, 3, 10) / 10 / 8 * 1e3
                 row["M%d" % M] = {"us": round(us, 2), "TOP/s": round(2.0 * M * N * K / us / 1e6, 1)}
             by_m.append(row)
-        prefill["w4a8_by_M"] = by_m
+        if by_m:
+            prefill["w4a8_by_M"] = by_m
         result["prefill"] = prefill
 
     # ---- TRIP (Section 4.3 / 4.4): the same three shapes with per-channel factors found by Eq.8 on a
