@@ -42,8 +42,8 @@ PREFILL_M = 2048
 # HBM traffic per launch of the decode kernels from rocprofv3 --pmc (FETCH_SIZE x 2.0 KiB +
 # WRITE_SIZE x 1.0 KiB, the factors a 256 MiB copy gives); see profiles/.
 MEASURED_TRAFFIC_BYTES_PER_LAUNCH = 26.3e6
-MEASURED_ATTN_TRAFFIC_BYTES = 252.4e6   # log2_attn_kernel, one call of the bench's attention block
-MEASURED_TILED_TRAFFIC_BYTES = 163.0e6  # gemm_tiled_kernel, mean per launch of a default run (up to three projections each)
+MEASURED_ATTN_TRAFFIC_BYTES = 252.3e6   # log2_attn_kernel, one call of the bench's attention block
+MEASURED_TILED_TRAFFIC_BYTES = 165.2e6  # gemm_tiled_kernel, mean per launch of a run without the by-M sweep (up to three projections each)
 
 
 def algorithmic_bytes(M, K, N):
