@@ -405,6 +405,13 @@ def test_block_llama13b_full_size_sampled(agq, oracle, blk_oracle):
     check_block_sampled(agq, oracle, blk_oracle, 2048, 5120, 40, 13824, 1024, seed=13)
 
 
+def test_block_with_few_tokens_on_wide_layers(agq, oracle, blk_oracle):
+    """Few tokens on wide layers: the projections after the pruning have few output tiles and a long K, so the
+    tiled kernel splits K over workgroups (partial tiles in the block's GEMM scratch)."""
+    check_block_sampled(agq, oracle, blk_oracle, 300, 2048, 16, 4096, 200, seed=16)
+    check_block_sampled(agq, oracle, blk_oracle, 520, 1024, 8, 8192, 130, seed=17)
+
+
 def test_block_longest_sequences(agq, oracle, blk_oracle):
     """The largest token counts a call accepts: 8192 with pruning (the selection's limit), and beyond it without
     (here 8200, padded to 8320 for the attention call), on a narrow block."""
