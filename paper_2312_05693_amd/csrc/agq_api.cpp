@@ -53,15 +53,17 @@ int gemm_w4_multi(int bits, const void *x, int x_kind, int64_t M, int64_t K, int
     for (int p = 0; p < count; ++p) tiles_n += (projs[p].N + 127) / 128;
     AgqSplitPlan plan = agq_tiled_split_plan(M, tiles_n, K / 128, true);
     if (workspace_bytes < need + plan.bytes) plan = agq_tiled_split_plan(M, tiles_n, K / 128, false);
-    if (M <= AGQ_DECODE_MAX_M || agq_decode_row_groups(x_kind, M, K, n_sum, plan.cost_ns))
+    const bool half_tiles = agq_tiled_half_tiles(M, tiles_n, K / 128, plan.cost_ns);
+    const int64_t tiled_ns = half_tiles ? K / 128 * 370 : plan.cost_ns;
+    if (M <= AGQ_DECODE_MAX_M || agq_decode_row_groups(x_kind, M, K, n_sum, tiled_ns))
         return hip_status(agq_launch_gemm_decode(x, x_kind, bits, M, K, ldx, e, zp, projs, count, -1, stream));
 
     // many tokens: lay the codes out in MFMA operand order once (quantizing on the
     // way when x is fp16), then run the tiled kernel for all projections on that copy
-    void *const split_ws = plan.splits > 1 ? static_cast<char *>(workspace) + codes_bytes(M, K) : nullptr;
+    void *const split_ws = plan.splits > 1 && !half_tiles ? static_cast<char *>(workspace) + codes_bytes(M, K) : nullptr;
     if (agq_launch_prepack_act(x, x_kind, bits, M, K, ldx, e, zp, workspace, stream)) return AGQ_EHIP;
     return hip_status(
-        agq_launch_gemm_tiled(workspace, M, K, e, agq_zp_corr(bits, zp), projs, count, -1, split_ws, stream));
+        agq_launch_gemm_tiled(workspace, M, K, e, agq_zp_corr(bits, zp), projs, count, -1, split_ws, half_tiles, stream));
 }
 
 int gemm_w4(int bits, const void *x, int x_kind, int64_t M, int64_t K, int64_t ldx, int e, int zp,
@@ -110,11 +112,12 @@ int gemm_w4_trip_multi(int bits, const void *x, int64_t M, int64_t K, int64_t ld
     // few tiles and a long K: K split over workgroups when the workspace has the room (as for plain blobs)
     int64_t tiles_n = 0;
     for (int p = 0; p < count; ++p) tiles_n += (projs[p].N + 127) / 128;
-    const AgqSplitPlan plan = agq_tiled_split_plan(M, tiles_n, K / 128 + n_extra, true, n_extra);
-    void *const split_ws =
-        plan.splits > 1 && workspace_bytes >= need + plan.bytes ? static_cast<char *>(workspace) + need : nullptr;
-    return hip_status(
-        agq_launch_gemm_tiled(workspace, M, K, e, agq_zp_corr(bits, zp), projs, count, n_extra, split_ws, stream));
+    AgqSplitPlan plan = agq_tiled_split_plan(M, tiles_n, K / 128 + n_extra, true, n_extra);
+    if (workspace_bytes < need + plan.bytes) plan = agq_tiled_split_plan(M, tiles_n, K / 128 + n_extra, false);
+    const bool half_tiles = agq_tiled_half_tiles(M, tiles_n, K / 128 + n_extra, plan.cost_ns);
+    void *const split_ws = plan.splits > 1 && !half_tiles ? static_cast<char *>(workspace) + need : nullptr;
+    return hip_status(agq_launch_gemm_tiled(workspace, M, K, e, agq_zp_corr(bits, zp), projs, count, n_extra, split_ws,
+                                            half_tiles, stream));
 }
 
 int gemm_w4_trip(int bits, const void *x, int64_t M, int64_t K, int64_t ldx, int e, int zp, const void *w_packed,

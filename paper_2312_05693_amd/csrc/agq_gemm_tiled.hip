@@ -94,11 +94,22 @@ struct TiledArgs {
 // short of copies in flight either: six stages instead of three changed nothing, its sixteen
 // 64-cycle MFMAs per wavefront and step are the step time.)  An int32 sum does not depend on
 // its order, so the result is the unsplit kernel's bit for bit.
-template <bool TRIP, bool SPLIT>
+//
+// NI: 32-token MFMA tiles per wavefront.  2: the 128-token workgroup tile described above.  1: a 64-token
+// tile (each wavefront 32 x 64, half of the MFMAs per step for two thirds of the operand bytes), for grids
+// whose 128-token tiles would leave the last round of workgroups mostly empty.
+template <bool TRIP, bool SPLIT, int NI = 2>
 __global__ __launch_bounds__(kThreads, 2) void gemm_tiled_kernel(const TiledArgs a) {
-    // Three pipeline stages of 24 KiB; the epilogue reuses the first 36 KiB.
-    __shared__ __align__(16) unsigned char lds[kStages * kStageBytes];
-    unsigned char *const stage0 = lds, *const stage1 = lds + kStageBytes, *const stage2 = lds + 2 * kStageBytes;
+    static_assert(NI == 2 || (NI == 1 && !SPLIT), "the partial tiles of a K split are laid out for 128 tokens");
+    constexpr int BMT = NI * 64;                 // tokens per workgroup tile
+    constexpr int kAChunksT = NI * 8;            // activation chunks of 1 KiB per stage
+    constexpr int kABytesT = kAChunksT * 1024;
+    constexpr int kStageT = kABytesT + kBChunks * 1024;      // 24 KiB (16 KiB for NI == 1)
+    constexpr int kNA = NI * 2;                  // activation copies per wavefront and step
+    constexpr int kCopiesT = kNA + 2;
+    // Three pipeline stages; the epilogue reuses the first 36 KiB.
+    __shared__ __align__(16) unsigned char lds[kStages * kStageT];
+    unsigned char *const stage0 = lds, *const stage1 = lds + kStageT, *const stage2 = lds + 2 * kStageT;
     const int lane = threadIdx.x & 63;
     const int wave = threadIdx.x >> 6;
     const int wm = wave >> 1, wn = wave & 1;
@@ -132,7 +143,7 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_tiled_kernel(const TiledArgs
     const int rows = min(kBand, a.tiles_m - band * kBand);
     const int within = bid - band * kBand * ptiles_n;
     const int tn = within / rows, tm = band * kBand + within - tn * rows;
-    const int m0 = tm * BM, n0 = tn * BN;
+    const int m0 = tm * BMT, n0 = tn * BN;
     const int KTfull = a.KT;
     const int kbeg = SPLIT ? split * a.steps_per_split : 0;
     const int KT = SPLIT ? min(a.steps_per_split, KTfull - kbeg) : KTfull;   // steps of this workgroup
@@ -143,7 +154,9 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_tiled_kernel(const TiledArgs
     // k-blocks t = c & 1 (low nibbles) and t + 2 (high nibbles): channel l & 31
     // of the tile lives in the blob's 16-row chunk (l & 31) >> 4 at blob lane
     // (2 t + (l >> 5)) * 16 + (l & 15).
-    const agq_u4 *asrc = a.xt + (((int64_t)tm * KTfull + kbeg) * 16 + wave * 4) * 64 + lane;
+    // (NI == 1: the 64-token tile tm is half tm & 1 of the 128-token tile tm >> 1 of the pre-pass: eight
+    // consecutive chunks of every stage, two per wavefront)
+    const agq_u4 *asrc = a.xt + (((int64_t)(NI == 2 ? tm : tm >> 1) * KTfull + kbeg) * 16 + (NI == 2 ? 0 : (tm & 1) * 8) + wave * kNA) * 64 + lane;
     const agq_u4 *bsrc[2];
 #pragma unroll
     for (int p = 0; p < 2; ++p) {
@@ -160,10 +173,10 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_tiled_kernel(const TiledArgs
         if (kt >= KT) return;               // nothing to fetch past the last step (uniform)
         const int k = kt;
         const uint32_t dst = lds_base + (uint32_t)(st - lds);
-        if (p < 4)
-            lds_dma16(asrc + ((int64_t)k * 16 + p) * 64, dst + (wave_u * 4 + p) * 1024);
+        if (p < kNA)
+            lds_dma16(asrc + ((int64_t)k * 16 + p) * 64, dst + (wave_u * kNA + p) * 1024);
         else
-            lds_dma16(bsrc[p - 4] + (int64_t)k * 64, dst + kABytes + (wave_u * 2 + (p - 4)) * 1024);
+            lds_dma16(bsrc[p - kNA] + (int64_t)k * 64, dst + kABytesT + (wave_u * 2 + (p - kNA)) * 1024);
     };
 
     // per-channel scales of this lane's output columns, fetched early
@@ -186,9 +199,9 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_tiled_kernel(const TiledArgs
             }
         }
 
-    agq_v16i acc[2][2];
+    agq_v16i acc[NI][2];
 #pragma unroll
-    for (int i = 0; i < 2; ++i)
+    for (int i = 0; i < NI; ++i)
 #pragma unroll
         for (int j = 0; j < 2; ++j)
 #pragma unroll
@@ -199,15 +212,15 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_tiled_kernel(const TiledArgs
     // Two such sets alternate: while one is multiplied, the other is filled from
     // the next step's LDS stage, so no MFMA ever waits for an LDS read it issued
     // a few instructions earlier.
-    agq_u4 xa0[8], b0[4], xa1[8], b1[4];
+    agq_u4 xa0[NI * 4], b0[4], xa1[NI * 4], b1[4];
 
     // One K step, software-pipelined by hand.  A wavefront issues in order and an
     // MFMA blocks the next MFMA while the matrix core is busy, but LDS reads,
     // copies and bit operations slip in between: every pair of MFMAs is followed
     // by LDS reads for the next step (twelve per step), and the six copies of the
     // step three ahead are spread over the step.
-    auto step = [&](int kt, const unsigned char *nxt, unsigned char *fill, const agq_u4 (&xc)[8], const agq_u4 (&bc)[4],
-                    agq_u4 (&xn)[8], agq_u4 (&bn)[4]) {
+    auto step = [&](int kt, const unsigned char *nxt, unsigned char *fill, const agq_u4 (&xc)[NI * 4], const agq_u4 (&bc)[4],
+                    agq_u4 (&xn)[NI * 4], agq_u4 (&bn)[4]) {
         const agq_u4 *sn = reinterpret_cast<const agq_u4 *>(nxt) + lane;
 #pragma unroll
         for (int t = 0; t < 4; ++t) {
@@ -220,15 +233,15 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_tiled_kernel(const TiledArgs
             }
             __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-            for (int i = 0; i < 2; ++i) {
+            for (int i = 0; i < NI; ++i) {
                 const agq_v4i x = __builtin_bit_cast(agq_v4i, xc[i * 4 + t]);
                 acc[i][0] = __builtin_amdgcn_mfma_i32_32x32x32_i8(wb[0], x, acc[i][0], 0, 0, 0);
                 acc[i][1] = __builtin_amdgcn_mfma_i32_32x32x32_i8(wb[1], x, acc[i][1], 0, 0, 0);
                 __builtin_amdgcn_sched_barrier(0);
-                const int mi = wm * 2 + i;   // 32-token tile of the stage
+                const int mi = wm * NI + i;   // 32-token tile of the stage
                 xn[i * 4 + t] = sn[(mi * 4 + t) * 64];
-                if (i == 1) bn[t] = sn[(kAChunks + wn * 4 + t) * 64];
-                if (2 * t + i < kCopies) copy_piece(2 * t + i, kt + 3, fill);
+                if (i == NI - 1) bn[t] = sn[(kAChunksT + wn * 4 + t) * 64];
+                if (NI * t + i < kCopiesT) copy_piece(NI * t + i, kt + 3, fill);
                 __builtin_amdgcn_sched_barrier(0);
             }
         }
@@ -237,7 +250,7 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_tiled_kernel(const TiledArgs
     auto shift_acc = [&](int sh) {          // uniform
         if (sh == 0) return;
 #pragma unroll
-        for (int i = 0; i < 2; ++i)
+        for (int i = 0; i < NI; ++i)
 #pragma unroll
             for (int j = 0; j < 2; ++j)
 #pragma unroll
@@ -245,36 +258,41 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_tiled_kernel(const TiledArgs
     };
 
 #pragma unroll
-    for (int p = 0; p < kCopies; ++p) copy_piece(p, 0, stage0);
+    for (int p = 0; p < kCopiesT; ++p) copy_piece(p, 0, stage0);
 #pragma unroll
-    for (int p = 0; p < kCopies; ++p) copy_piece(p, 1, stage1);
+    for (int p = 0; p < kCopiesT; ++p) copy_piece(p, 1, stage1);
 #pragma unroll
-    for (int p = 0; p < kCopies; ++p) copy_piece(p, 2, stage2);
-    if (KT >= 3)
+    for (int p = 0; p < kCopiesT; ++p) copy_piece(p, 2, stage2);
+    static_assert(kCopiesT == 6 || kCopiesT == 4, "the vmcnt immediates below count the copies of one and two steps");
+    if (KT < 3)
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    else if (kCopiesT == 6)
         asm volatile("s_waitcnt vmcnt(12)" ::: "memory");   // step 0 has landed
     else
-        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
     __syncthreads();
     {
         const agq_u4 *s0 = reinterpret_cast<const agq_u4 *>(stage0) + lane;
 #pragma unroll
-        for (int i = 0; i < 2; ++i)
+        for (int i = 0; i < NI; ++i)
 #pragma unroll
-            for (int t = 0; t < 4; ++t) xa0[i * 4 + t] = s0[((wm * 2 + i) * 4 + t) * 64];
+            for (int t = 0; t < 4; ++t) xa0[i * 4 + t] = s0[((wm * NI + i) * 4 + t) * 64];
 #pragma unroll
-        for (int j = 0; j < 4; ++j) b0[j] = s0[(kAChunks + wn * 4 + j) * 64];
+        for (int j = 0; j < 4; ++j) b0[j] = s0[(kAChunksT + wn * 4 + j) * 64];
     }
     // Every step kt: wait until this wavefront's copies of step kt+1 have landed
-    // (loads return in order, each step issues six, so only the six of step
+    // (loads return in order, each step issues kCopiesT, so only those of step
     // kt+2, if there is one, may still fly), meet the others (everybody's copies of step kt+1 are
     // in LDS, and everybody has read step kt's fragments out of the stage that is
     // refilled next), then multiply step kt while copying step kt+3.
 #define AGQ_STEP(KT_, NXT, FILL, XC, BC, XN, BN)                             \
     if ((KT_) < KT) {                                                        \
-        if ((KT_) + 2 < KT)                                                  \
+        if ((KT_) + 2 >= KT)                                                 \
+            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");                 \
+        else if (kCopiesT == 6)                                              \
             asm volatile("s_waitcnt vmcnt(6)" ::: "memory");                 \
         else                                                                 \
-            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");                 \
+            asm volatile("s_waitcnt vmcnt(4)" ::: "memory");                 \
         __syncthreads();                                                     \
         step((KT_), NXT, FILL, XC, BC, XN, BN);                              \
         if (TRIP && split == 0 && (KT_) < a.n_extra) shift_acc(a.trip_shift[(KT_)]); \
@@ -294,7 +312,7 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_tiled_kernel(const TiledArgs
         // accumulator piece c = (i * 2 + j) * 4 + q of thread t at [c][t]: 16 bytes per lane, contiguous
         int4 *const mine = reinterpret_cast<int4 *>(a.part) + ((int64_t)tile_id * a.splits + split) * (16 * kThreads) + threadIdx.x;
 #pragma unroll
-        for (int i = 0; i < 2; ++i) {
+        for (int i = 0; i < NI; ++i) {
             if (m0 + wm * 64 + i * 32 >= a.M) continue;   // no token in these 32 rows: nobody reads them (uniform)
 #pragma unroll
             for (int j = 0; j < 2; ++j)
@@ -310,7 +328,7 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_tiled_kernel(const TiledArgs
     // 2^e * sw[n] in registers, then transpose through LDS: a lane holds four
     // consecutive channels of one token (8 bytes), the store wants eight lanes
     // per 128-byte row.  Each wavefront uses a private 64 x 144-byte region.
-    const int mrow = m0 + wm * 64 + (lane & 31);
+    const int mrow = m0 + wm * (NI * 32) + (lane & 31);
     if (a.corr) {
         // unsigned activation grid: add corr * sum_k w[n,k], times the 16 the
         // accumulators still carry (|16 acc| <= 16 * 255 * 8 * K < 2^31 for K <= 65536)
@@ -323,14 +341,14 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_tiled_kernel(const TiledArgs
 #pragma unroll
                 for (int r = 0; r < 4; ++r) {
                     const int add = (a.corr * t[r]) << AGQ_W_SHIFT;
-                    acc[0][j][4 * q + r] += add;
-                    acc[1][j][4 * q + r] += add;
+#pragma unroll
+                    for (int i = 0; i < NI; ++i) acc[i][j][4 * q + r] += add;
                 }
             }
     }
     if (pacc) {   // exact accumulators for parity checks (plain stores)
 #pragma unroll
-        for (int i = 0; i < 2; ++i)
+        for (int i = 0; i < NI; ++i)
 #pragma unroll
             for (int j = 0; j < 2; ++j)
 #pragma unroll
@@ -341,7 +359,7 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_tiled_kernel(const TiledArgs
     }
     unsigned char *obuf = lds + wave * (64 * kOutStride);   // 9 KiB per wavefront, 36 KiB in all
 #pragma unroll
-    for (int i = 0; i < 2; ++i)
+    for (int i = 0; i < NI; ++i)
 #pragma unroll
         for (int j = 0; j < 2; ++j)
 #pragma unroll
@@ -366,9 +384,9 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_tiled_kernel(const TiledArgs
     const int nbase = n0 + wn * 64 + (lane & 7) * 8;          // eight channels per lane
     const bool vec_ok = (pldy & 7) == 0 && nbase + 7 < pN;
 #pragma unroll
-    for (int it = 0; it < 8; ++it) {
+    for (int it = 0; it < NI * 4; ++it) {
         const int row = it * 8 + (lane >> 3);
-        const int m = m0 + wm * 64 + row;
+        const int m = m0 + wm * (NI * 32) + row;
         if (m >= a.M || nbase >= pN) continue;
         const uint4 v = *reinterpret_cast<const uint4 *>(obuf + row * kOutStride + (lane & 7) * 16);
         __half *yp = py + (int64_t)m * pldy + nbase;
@@ -439,13 +457,14 @@ __global__ __launch_bounds__(kThreads) void split_reduce_kernel(const TiledArgs 
 }  // namespace
 
 int agq_launch_gemm_tiled(const void *x_tiles, int64_t M, int64_t K, int e, int corr, const struct agq_proj *projs, int count,
-                          int n_extra, void *split_ws, void *stream) {
+                          int n_extra, void *split_ws, bool half_tiles, void *stream) {
     TiledArgs a = {};
     a.xt = (const agq_u4 *)x_tiles;
     a.M = (int)M;
     a.K = (int)K;
     a.KT = (int)agq_k_tiles(K);
     a.tiles_m = (int)((M + BM - 1) / BM);
+    if (half_tiles) a.tiles_m = (int)((M + 63) / 64);
     a.scale_e = ldexpf(1.0f, e);
     a.corr = corr;
     a.n_extra = 0;
@@ -475,7 +494,7 @@ int agq_launch_gemm_tiled(const void *x_tiles, int64_t M, int64_t K, int e, int 
         a.n_extra = n_extra;
         a.trip_shift = (const int32_t *)((const char *)projs[0].w_packed + L.meta_off) + 16;
     }
-    if (split_ws) {
+    if (split_ws && !half_tiles) {
         // the extra steps and their shifts stay together in the first slice
         const AgqSplitPlan plan = agq_tiled_split_plan(M, tiles / a.tiles_m, a.KT, true, n_extra >= 0 ? n_extra : 0);
         if (plan.splits > 1) {
@@ -491,9 +510,15 @@ int agq_launch_gemm_tiled(const void *x_tiles, int64_t M, int64_t K, int e, int 
             return (int)hipGetLastError();
         }
     }
-    if (n_extra >= 0)
+    if (half_tiles) {
+        if (n_extra >= 0)
+            gemm_tiled_kernel<true, false, 1><<<grid, kThreads, 0, st>>>(a);
+        else
+            gemm_tiled_kernel<false, false, 1><<<grid, kThreads, 0, st>>>(a);
+    } else if (n_extra >= 0) {
         gemm_tiled_kernel<true, false><<<grid, kThreads, 0, st>>>(a);
-    else
+    } else {
         gemm_tiled_kernel<false, false><<<grid, kThreads, 0, st>>>(a);
+    }
     return (int)hipGetLastError();
 }

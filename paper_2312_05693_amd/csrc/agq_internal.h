@@ -79,6 +79,15 @@ static inline AgqSplitPlan agq_tiled_split_plan(int64_t M, int64_t tiles_n, int6
     return p;
 }
 
+// 64-token tiles instead of 128-token ones in the tiled kernel: twice the workgroups, each with half of the MFMAs
+// per K step for two thirds of the operand bytes.  At full load that is 15-20 % slower (measured), but while the
+// 128-token tiles number 128 or fewer every workgroup still has a CU to itself, and its step takes about 370 ns
+// instead of 470: used when that beats the plan above (4096 x 4096 at 256..512 rows: 19.4..21.6 against
+// 23.0..25.2 us; with a long K the split wins: 11008 -> 4096 at 128 rows 22.7 against 43.1 us).
+static inline bool agq_tiled_half_tiles(int64_t M, int64_t tiles_n, int64_t KT, int64_t plan_cost_ns) {
+    return ((M + 127) / 128) * tiles_n <= 128 && KT * 370 < plan_cost_ns;
+}
+
 // Between 17 and 256 rows of fp16 input the weight-streaming kernel can run with sixteen rows per workgroup
 // (grid.y row groups): every row group reads the weights again (from L2 after the first), about 3.5 us +
 // 0.36 us per MB read in all.  The other path is the layout pre-pass plus the tiled kernel: about 8 us around
@@ -103,9 +112,10 @@ int agq_launch_gemm_decode(const void *x, int x_kind, int bits, int64_t M, int64
                            const struct agq_proj *projs, int count, int n_extra, void *stream);
 // K counts the main chunks only; with TRIP blobs (all packed with the same factors) x_tiles and the blobs hold
 // n_extra more steps in front.  The `count` projections of the activation run as one launch.
-// split_ws != NULL: room for the partial tiles agq_tiled_split_plan describes for this call's tiles.
+// split_ws != NULL: room for the partial tiles agq_tiled_split_plan describes for this call's tiles (the call
+// is split).  half_tiles: 64-token tiles (never together with split_ws).
 int agq_launch_gemm_tiled(const void *x_tiles, int64_t M, int64_t K, int e, int corr, const struct agq_proj *projs, int count,
-                          int n_extra, void *split_ws, void *stream);
+                          int n_extra, void *split_ws, bool half_tiles, void *stream);
 int agq_launch_trip_search(const void *x, int64_t M, int64_t K, int64_t ldx, int bits, int e, int zp, int kmax,
                            int8_t *alpha, void *stream);
 int agq_trip_count_extra(const int8_t *alpha_host, int64_t K);   // number of extra chunks, -1 = bad factors or too many

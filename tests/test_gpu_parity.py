@@ -243,6 +243,29 @@ def test_tiled_split_k(agq, oracle, M, K, N, bits, zp, x_kind):
     assert_f16_close(outs[0][1][rows], y_w, "y")
 
 
+@pytest.mark.parametrize("M,K,N,bits,zp,x_kind", [(448, 4096, 1000, 8, 0, "f16"), (300, 1024, 2100, 4, 9, "f16"),
+                                                    (512, 4096, 4096, 8, 0, "q"), (321, 512, 5000, 8, 131, "f16")])
+def test_tiled_64_token_tiles(agq, oracle, M, K, N, bits, zp, x_kind):
+    """At most 128 tiles of 128 x 128 and no K split that pays: the tiled kernel runs 64-token tiles (twice the
+    workgroups).  Token counts that end inside the first and inside the second half of a 128-token tile."""
+    x, wq, sw = make_case(M, K, N, seed=950 + M + N, n_out=6)
+    e = oracle.calibrate_act_exp(x, bits) + (1 if zp else 0)
+    fn = agq.gemm_w4a8 if bits == 8 else agq.gemm_w4a4
+    if x_kind == "f16":
+        xin, kind = dev(x), agq.AGQ_X_F16
+    else:
+        xin, kind = agq.quantize_act(dev(x), bits, e, zp), agq.AGQ_X_Q
+    acc = torch.full((M, N), -3, dtype=torch.int32, device="cuda")
+    ybuf = torch.full((M, N + 8), 5.0, dtype=torch.float16, device="cuda")
+    fn(xin, e, agq.pack_w4(dev(wq)), dev(sw), N, K, x_kind=kind, acc_out=acc, zp=zp, y=ybuf[:, :N])
+    rows = sorted({0, 1, 31, 32, 63, 64, 127, 128, 191, 192, M // 2, M - 2, M - 1})
+    acc_w, y_w = oracle.linear_w4(x[rows], bits, e, zp, wq, sw)
+    got = host(ybuf)
+    assert np.array_equal(host(acc)[rows].astype(np.int64), acc_w)
+    assert_f16_close(got[rows, :N], y_w, "y")
+    assert (got[:, N:] == 5.0).all() and not (host(acc) == -3).all(axis=1).any()     # every row written, nothing beyond
+
+
 def test_tiled_split_k_multi_and_graph(agq, oracle):
     # q/k/v-style call whose tiles together are still few: one split launch over all projections; replayed as a graph
     M, K, Ns, bits = 300, 2048, [256, 100, 384], 8
