@@ -112,8 +112,9 @@ int agq_unpack_w4(const void *packed, int64_t N, int64_t K, int8_t *wq_out,
  * rows the weight-streaming kernel; 17..256 rows of fp16 input the same kernel with
  * sixteen rows per workgroup while re-reading the weights per row group is cheaper
  * than the tiled path (a measured rule on the sizes); else the layout pre-pass and
- * the tiled kernel, with K split over workgroups when the call has fewer than 256
- * tiles of 128 x 128 and the workspace has the room.
+ * the tiled kernel; while the call has at most 128 tiles of 128 x 128 either with K
+ * split over workgroups (a long K, and the workspace has the room) or with 64-token
+ * tiles, whichever a measured cost model puts first.
  * Graph capture: the calls enqueue kernels only and may be captured, with one
  * exception: the first call in a process that needs the kernel with the
  * activation kept in LDS (9 <= M <= 16, more than 4096 output channels in the

@@ -8,6 +8,8 @@
 // per K step), a prologue or an epilogue stalls only one of the two wavefronts
 // that feed a matrix core.  The 32 x 32 x 32 form is used because back-to-back
 // 16 x 16 x 64 MFMAs of one wavefront keep the matrix core only 55 % busy.
+// Two variants serve calls with few tiles: 64-token tiles (NI == 1) and a split of
+// K over workgroups (SPLIT), both described at the kernel.
 //
 //   activation codes: int8, already laid out in MFMA operand order by the
 //     pre-pass (16 KiB per 128-token tile and K step, see agq_quant.hip), copied
