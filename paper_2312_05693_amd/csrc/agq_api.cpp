@@ -49,13 +49,16 @@ int gemm_w4_multi(int bits, const void *x, int x_kind, int64_t M, int64_t K, int
     }
     // With few tiles and a long K the tiled kernel splits the tiles' K steps over workgroups, if the
     // caller's workspace has the room for the partial tiles behind the codes.
-    int64_t tiles_n = 0;
-    for (int p = 0; p < count; ++p) tiles_n += (projs[p].N + 127) / 128;
+    int64_t tiles_n = 0, wg_pairs = 0;
+    for (int p = 0; p < count; ++p) {
+        tiles_n += (projs[p].N + 127) / 128;
+        wg_pairs += (projs[p].N + 31) / 32;
+    }
     AgqSplitPlan plan = agq_tiled_split_plan(M, tiles_n, K / 128, true);
     if (workspace_bytes < need + plan.bytes) plan = agq_tiled_split_plan(M, tiles_n, K / 128, false);
     const bool half_tiles = agq_tiled_half_tiles(M, tiles_n, K / 128, plan.cost_ns);
     const int64_t tiled_ns = half_tiles ? K / 128 * 370 : plan.cost_ns;
-    if (M <= AGQ_DECODE_MAX_M || agq_decode_row_groups(x_kind, M, K, n_sum, tiled_ns))
+    if (M <= AGQ_DECODE_MAX_M || agq_decode_row_groups(x_kind, M, K, n_sum, wg_pairs, tiled_ns))
         return hip_status(agq_launch_gemm_decode(x, x_kind, bits, M, K, ldx, e, zp, projs, count, -1, stream));
 
     // many tokens: lay the codes out in MFMA operand order once (quantizing on the

@@ -151,6 +151,9 @@ __global__ __launch_bounds__(1024) void gemm_decode_kernel(const DecodeArgs a) {
                  "s"(ZP ? a.q.h_zp2 : 0u), "s"(F16 ? 0u : a.flip), "s"(a.corr), "s"(TRIP ? a.n_extra : 0));
     int nt;
     const int pj = find_proj(a, blockIdx.x, nt);   // which projection this workgroup serves (uniform)
+    // RG: a workgroup serves two neighbouring channel tiles of its projection with the same quantized rows (the
+    // activation, which every workgroup reads in full, is most of such a launch's traffic); tile_start counts pairs
+    if (RG) nt *= 2;
     __half *const py = a.y4[pj];
     int32_t *const pacc = a.acc4[pj];
     const int pldy = a.ldy4[pj];
@@ -163,8 +166,11 @@ __global__ __launch_bounds__(1024) void gemm_decode_kernel(const DecodeArgs a) {
     const int KTall = KT + n_extra;
     const int nmain = TRIP ? nwaves - 1 : nwaves;
     const agq_u4 *wptr = reinterpret_cast<const agq_u4 *>(pblob) + ((int64_t)nt * KTall + n_extra) * 64 + lane;
+    const bool second = RG && (nt + 1) * 16 < pN;                     // the pair's second tile exists (uniform)
+    const agq_u4 *wptr2 = second ? wptr + (int64_t)KTall * 64 : wptr;
 
     agq_v4i acc0 = {0, 0, 0, 0}, acc1 = {0, 0, 0, 0};
+    agq_v4i acc2 = {0, 0, 0, 0}, acc3 = {0, 0, 0, 0};                 // second tile (RG)
     // Staging of the quantized activation: one region per chunk of a batch, in MFMA
     // operand order [k-half s][k-group g][row m] x 16 bytes with only the R = 4 MP
     // rows the prologue writes (operand rows beyond R alias lower rows; they never
@@ -234,11 +240,16 @@ __global__ __launch_bounds__(1024) void gemm_decode_kernel(const DecodeArgs a) {
             }
         }
         asm volatile("" ::: "memory");   // keep the activation loads ahead of the weight loads
-        agq_u4 w[KPW];
+        agq_u4 w[KPW], w2[RG ? KPW : 1];
 #pragma unroll
         for (int i = 0; i < KPW; ++i) w[i] = wptr[(int64_t)min(kb + i, KT - 1) * 64];
-        if (kb == wave * KPW && threadIdx.x < 256) {
-            const int n = min(nt * 16 + (lane & 15), pN - 1);
+        if (RG) {
+#pragma unroll
+            for (int i = 0; i < KPW; ++i) w2[i] = wptr2[(int64_t)min(kb + i, KT - 1) * 64];
+        }
+        if (kb == wave * KPW && threadIdx.x < (RG ? 512 : 256)) {
+            // the scale of the first output this thread will store (RG: threads 256.. store the second tile)
+            const int n = min((nt + (RG ? (int)(threadIdx.x >> 8) : 0)) * 16 + (lane & 15), pN - 1);
             sw_bits = reinterpret_cast<const uint16_t *>(psw)[n];
         }
         asm volatile("" ::: "memory");
@@ -285,6 +296,13 @@ __global__ __launch_bounds__(1024) void gemm_decode_kernel(const DecodeArgs a) {
                 const agq_v4i b1v = __builtin_bit_cast(agq_v4i, wv & 0xF0F0F0F0u);
                 acc0 = __builtin_amdgcn_mfma_i32_16x16x64_i8(a0, b0v, acc0, 0, 0, 0);
                 acc1 = __builtin_amdgcn_mfma_i32_16x16x64_i8(a1, b1v, acc1, 0, 0, 0);
+                if (RG) {
+                    const agq_u4 wv2 = valid ? w2[b0 + i] : agq_u4{0u, 0u, 0u, 0u};
+                    const agq_v4i b2v = __builtin_bit_cast(agq_v4i, (wv2 << 4) & 0xF0F0F0F0u);
+                    const agq_v4i b3v = __builtin_bit_cast(agq_v4i, wv2 & 0xF0F0F0F0u);
+                    acc2 = __builtin_amdgcn_mfma_i32_16x16x64_i8(a0, b2v, acc2, 0, 0, 0);
+                    acc3 = __builtin_amdgcn_mfma_i32_16x16x64_i8(a1, b3v, acc3, 0, 0, 0);
+                }
             }
         }
     }
@@ -367,19 +385,26 @@ __global__ __launch_bounds__(1024) void gemm_decode_kernel(const DecodeArgs a) {
     const agq_v4i acc = acc0 + acc1;
 #pragma unroll
     for (int r = 0; r < 4; ++r) red[(wave * 4 + r) * 64 + lane] = acc[r];
+    if (RG) {   // the second tile's sums behind the first's (a wavefront's staging region holds 2 KiB or more here)
+        const agq_v4i accb = acc2 + acc3;
+#pragma unroll
+        for (int r = 0; r < 4; ++r) red[((nwaves + wave) * 4 + r) * 64 + lane] = accb[r];
+    }
     __syncthreads();
     const int shift = AGQ_W_SHIFT + (XK == XK_I4 ? 4 : 0);
-    for (int o = threadIdx.x; o < 256; o += nwaves * 64) {
-        const int l = o & 63, r = o >> 6;
+    for (int o = threadIdx.x; o < (RG ? 512 : 256); o += nwaves * 64) {
+        const int tsel = RG ? o >> 8 : 0;            // which tile of the pair
+        const int l = o & 63, r = (o >> 6) & 3;
         const int m = 4 * (l >> 4) + r;
-        const int n = nt * 16 + (l & 15);
+        const int n = (nt + tsel) * 16 + (l & 15);
         if (m < Mloc && n < pN) {
             int sum = 0;
-            for (int w = 0; w < nwaves; ++w) sum += red[(w * 4 + r) * 64 + l];
+            for (int w = 0; w < nwaves; ++w) sum += red[((tsel * nwaves + w) * 4 + r) * 64 + l];
             int v = sum >> shift;   // exact: every term carries the factor
             if (a.corr) v += a.corr * blob_wsum(pblob, pN, KTall)[n];
             if (pacc) pacc[(int64_t)(row0 + m) * pN + n] = v;
-            const uint32_t sb = nmain >= 4 ? sw_bits : (uint32_t) reinterpret_cast<const uint16_t *>(psw)[n];
+            const bool have = RG ? o == (int)threadIdx.x : nmain >= 4;   // prefetched above
+            const uint32_t sb = have ? sw_bits : (uint32_t) reinterpret_cast<const uint16_t *>(psw)[n];
             py[(int64_t)(row0 + m) * pldy + n] = agq_dequant(v, a.scale_e * __half2float(__ushort_as_half((unsigned short)sb)));
         }
     }
@@ -597,7 +622,8 @@ int agq_launch_gemm_decode(const void *x, int x_kind, int bits, int64_t M, int64
     for (int p = 0; p < kMaxProj; ++p) {
         const agq_proj &pr = projs[p < count ? p : count - 1];
         a.tile_start[p] = tiles;
-        if (p < count) tiles += (int)((pr.N + 15) / 16);
+        // row groups (more than sixteen rows): a workgroup serves a pair of tiles
+        if (p < count) tiles += M > AGQ_DECODE_MAX_M ? (int)((pr.N + 31) / 32) : (int)((pr.N + 15) / 16);
         a.blob4[p] = (const uint4 *)pr.w_packed;
         a.sw4[p] = (const __half *)pr.w_scale_f16;
         a.N4[p] = (int)pr.N;
@@ -621,6 +647,12 @@ int agq_launch_gemm_decode(const void *x, int x_kind, int bits, int64_t M, int64
         // smaller workgroups win.
         kpw = 1;
         while (kpw < 4 && (a.KT + kpw - 1) / kpw > 16) kpw *= 2;
+        waves = (a.KT + kpw - 1) / kpw;
+        if (waves > 16) waves = 16;
+    }
+    if (M > AGQ_DECODE_MAX_M && kpw == 8) {
+        // row groups keep two tiles' weight chunks in registers: four chunks per wavefront at most
+        kpw = 4;
         waves = (a.KT + kpw - 1) / kpw;
         if (waves > 16) waves = 16;
     }

@@ -88,15 +88,22 @@ static inline bool agq_tiled_half_tiles(int64_t M, int64_t tiles_n, int64_t KT, 
     return ((M + 127) / 128) * tiles_n <= 128 && KT * 370 < plan_cost_ns;
 }
 
-// Between 17 and 256 rows of fp16 input the weight-streaming kernel can run with sixteen rows per workgroup
-// (grid.y row groups): every row group reads the weights again (from L2 after the first), about 3.5 us +
-// 0.36 us per MB read in all.  The other path is the layout pre-pass plus the tiled kernel: about 8 us around
-// the plan's time above (768 x 768 at 128 rows: 4.5 against 9.7 us; 4096 x 4096 at 32 rows: 9.5 against 13.3 us,
-// at 64 rows 16.2 against 14.6 us).  tiled_ns: the cost of the plan the call would run.
+// Between 17 and 256 rows of fp16 input the weight-streaming kernel can run with sixteen rows and two channel
+// tiles per workgroup (grid.y row groups): every row group reads the weights again (from L2 after the first),
+// about 3 us + 0.24 us per MB read in all, more when the workgroups fill the last round of 256 CUs badly.  The
+// other path is the layout pre-pass plus the tiled kernel: about 8 us around the plan's time above.  Measured
+// (row groups against tiles): 4096 x 4096 at 32 / 64 / 96 / 128 rows 6.4 / 11.0 / 15.6 / 19.6 against 13.4 /
+// 14.7 / 16.2 / 17.5 us; 4096 -> 11008 at 48 / 64 rows 18.3 / 21.7 against 19.8 / 19.9 us; 768 x 768 at 128
+// rows 4.1 against 8.2 us.  wg_pairs: tile pairs (32 channels) of all projections; tiled_ns: the cost of the
+// plan the call would run instead.
 #define AGQ_ROW_GROUP_MAX_M 256
-static inline bool agq_decode_row_groups(int x_kind, int64_t M, int64_t K, int64_t n_sum, int64_t tiled_ns) {
-    return x_kind == 0 && M > AGQ_DECODE_MAX_M && M <= AGQ_ROW_GROUP_MAX_M &&
-           3500 + ((M + 15) / 16) * (K * n_sum / 2) * 360 / 1000000 <= 8000 + tiled_ns;
+static inline bool agq_decode_row_groups(int x_kind, int64_t M, int64_t K, int64_t n_sum, int64_t wg_pairs,
+                                         int64_t tiled_ns) {
+    if (x_kind != 0 || M <= AGQ_DECODE_MAX_M || M > AGQ_ROW_GROUP_MAX_M) return false;
+    const int64_t groups = (M + 15) / 16, wgs = groups * wg_pairs;
+    int64_t read_ns = groups * (K * n_sum / 2) * 240 / 1000000;
+    if (wgs < 768) read_ns = read_ns * ((wgs + 255) / 256 * 256) / wgs;   // a short last round costs a whole one
+    return 3000 + read_ns <= 8000 + tiled_ns;
 }
 
 int agq_launch_calibrate(const void *x, int64_t M, int64_t K, int64_t ldx, int bits, int32_t *e_dev, void *stream);
