@@ -110,7 +110,7 @@ int agq_unpack_w4(const void *packed, int64_t N, int64_t K, int8_t *wq_out,
  * K % 128 == 0, K <= 65536 (keeps every partial sum inside int32), M >= 0.
  * Which kernel runs is the library's choice and does not change a result: up to 16
  * rows the weight-streaming kernel; 17..256 rows of fp16 input the same kernel with
- * sixteen rows per workgroup while re-reading the weights per row group is cheaper
+ * sixteen rows (and two channel tiles) per workgroup while re-reading the weights per row group is cheaper
  * than the tiled path (a measured rule on the sizes); else the layout pre-pass and
  * the tiled kernel; while the call has at most 128 tiles of 128 x 128 either with K
  * split over workgroups (a long K, and the workspace has the room) or with 64-token

@@ -95,7 +95,8 @@ static inline bool agq_tiled_half_tiles(int64_t M, int64_t tiles_n, int64_t KT, 
 // (row groups against tiles): 4096 x 4096 at 32 / 64 / 96 / 128 rows 6.4 / 11.0 / 15.6 / 19.6 against 13.4 /
 // 14.7 / 16.2 / 17.5 us; 4096 -> 11008 at 48 / 64 rows 18.3 / 21.7 against 19.8 / 19.9 us; 768 x 768 at 128
 // rows 4.1 against 8.2 us.  wg_pairs: tile pairs (32 channels) of all projections; tiled_ns: the cost of the
-// plan the call would run instead.
+// plan the call would run instead.  (Four tiles per workgroup instead of two were measured too: the same at best,
+// and 50 % slower on the widest layer, where the registers no longer hold the weight chunks.)
 #define AGQ_ROW_GROUP_MAX_M 256
 static inline bool agq_decode_row_groups(int x_kind, int64_t M, int64_t K, int64_t n_sum, int64_t wg_pairs,
                                          int64_t tiled_ns) {
