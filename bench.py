@@ -239,7 +239,7 @@ def main():
     ms0 = timed(cfg0_calls, 2, 20) / 20 / 16
     result["config0_opt125m_w4a8"] = {"M": 128, "K": 768, "N": 768, "us": round(ms0 * 1e3, 2),
                                       "note": "151 Mop and 0.7 MB, latency bound: one launch of the weight-streaming "
-                                              "kernel with eight row groups (the tiled path would take two launches)"}
+                                              "kernel with eight row groups of 24 tile pairs (the tiled path would take two launches)"}
 
     # ---- prefill: one block's seven shapes at M = 2048, W4A8 and W4A4 (int8 MFMA bound)
     if not args.no_prefill:
