@@ -130,6 +130,28 @@ int agq_gemm_w4a4(const void *x, int x_kind, int64_t M, int64_t K, int64_t ldx,
                   int64_t N, void *y_f16, int64_t ldy, int32_t *acc_out,
                   void *workspace, size_t workspace_bytes, void *stream);
 
+/* For callers that cannot allocate device memory (code under HIP graph capture,
+ * tight serving loops, harnesses that forbid hipMalloc): agq_gemm_w4a8 without the
+ * workspace arguments.  The quantized activation of the tiled path, and the partial
+ * tiles of a K split behind it, live in a fixed array of
+ * AGQ_STATIC_WORKSPACE_BYTES inside the library's device image (one copy on every
+ * GPU the library is used on, held until the process ends); the call makes no
+ * hipMalloc / hipFree and calls no allocating routine.  The array's address is
+ * looked up once per device, on the first call made with that device current.
+ * Same arguments, checks, kernels and results as agq_gemm_w4a8.  A call whose
+ * activation codes alone (M rounded up to 128, times K bytes; nothing for M <= 16)
+ * exceed the array returns AGQ_ESIZE before any HIP call; every configuration up
+ * to 2048 x 11008 fits.  When the codes fit but the partial tiles do not, K is
+ * not split (slower for few output tiles, same result).
+ * All calls on one GPU share the array: two calls that overlap in time on one GPU
+ * (different streams or threads) race and give wrong results; calls on one stream
+ * are safe.  Nothing in the array needs clearing between calls.                */
+#define AGQ_STATIC_WORKSPACE_BYTES ((size_t)32 << 20)
+int agq_gemm_w4a8_static(const void *x, int x_kind, int64_t M, int64_t K, int64_t ldx,
+                         int e, int zp, const void *w_packed, const void *w_scale_f16,
+                         int64_t N, void *y_f16, int64_t ldy, int32_t *acc_out,
+                         void *stream);
+
 /* Several projections of the same activation in one call (q/k/v, gate/up of a
  * transformer block; Section 4.2's pipeline quantizes such an activation once).
  * Same computation as `count` calls of agq_gemm_w4a8 / agq_gemm_w4a4 with the

@@ -30,6 +30,7 @@ SIGNATURES = {
     "agq_gemm_workspace_bytes": (_sz, [_i64, _i64, _i64]),
     "agq_gemm_w4a8": (_int, _GEMM_ARGS),
     "agq_gemm_w4a4": (_int, _GEMM_ARGS),
+    "agq_gemm_w4a8_static": (_int, _GEMM_ARGS[:13] + [_vp]),
     "agq_gemm_w4a8_multi": (_int, [_vp, _int, _i64, _i64, _i64, _int, _int, _vp, _int, _vp, _sz, _vp]),
     "agq_gemm_w4a4_multi": (_int, [_vp, _int, _i64, _i64, _i64, _int, _int, _vp, _int, _vp, _sz, _vp]),
     "agq_trip_search": (_int, [_vp, _i64, _i64, _i64, _int, _int, _int, _int, _vp, _vp]),
@@ -185,6 +186,14 @@ def gemm_w4a8(x, e, w_packed, w_scale, N, K, x_kind=AGQ_X_F16, y=None, acc_out=N
     M = x.shape[0]
     return _gemm("agq_gemm_w4a8", x, x_kind, M, K, x.stride(0) if M else K, e, zp, w_packed, w_scale, N, y, acc_out,
                  workspace)
+
+
+def gemm_w4a8_static(x, e, w_packed, w_scale, N, K, y, x_kind=AGQ_X_F16, acc_out=None, zp=0):
+    """agq_gemm_w4a8 on the library's fixed workspace; y (and acc_out) are the caller's: nothing is allocated."""
+    M = x.shape[0]
+    _ok(lib().agq_gemm_w4a8_static(_ptr(x), x_kind, M, K, x.stride(0) if M else K, e, zp, _ptr(w_packed), _ptr(w_scale),
+                                   N, _ptr(y), y.stride(0) if M else N, _ptr(acc_out), _stream()), "agq_gemm_w4a8_static")
+    return y
 
 
 def gemm_w4a4(x, e, w_packed, w_scale, N, K, x_kind=AGQ_X_F16, y=None, acc_out=None, workspace=None, zp=0):

@@ -17,8 +17,12 @@ constexpr int64_t kMaxAttnS = 32768;   // one head of P stays below 4 GiB: 32-bi
 // int8 codes in operand order, tokens padded to the 128-row tile (a multiple of 16 KiB)
 inline size_t codes_bytes(int64_t M, int64_t K) { return (size_t)((M + 127) / 128) * 128 * (size_t)K; }
 
-int gemm_w4_multi(int bits, const void *x, int x_kind, int64_t M, int64_t K, int64_t ldx, int e, int zp,
-                  const agq_proj *projs, int count, void *workspace, size_t workspace_bytes, void *stream) {
+}  // namespace
+
+// The linear layer behind every agq_gemm_w4a* call.  check_only: run the argument checks (host only) and return.
+int agq_gemm_w4_run(int bits, const void *x, int x_kind, int64_t M, int64_t K, int64_t ldx, int e, int zp,
+                    const agq_proj *projs, int count, void *workspace, size_t workspace_bytes, void *stream,
+                    bool check_only) {
     if (M < 0 || M > kMaxDim || K < 128 || K > 65536 || (K % 128) != 0) return AGQ_EINVAL;
     if (x_kind != AGQ_X_F16 && x_kind != AGQ_X_Q) return AGQ_EINVAL;
     if (!e_ok(e) || zp < 0 || zp > (1 << bits) - 1 || ldx < K) return AGQ_EINVAL;
@@ -47,6 +51,7 @@ int gemm_w4_multi(int bits, const void *x, int x_kind, int64_t M, int64_t K, int
         if (!workspace || !aligned16(workspace)) return AGQ_EINVAL;
         if (workspace_bytes < need) return AGQ_ESIZE;
     }
+    if (check_only) return AGQ_OK;
     // With few tiles and a long K the tiled kernel splits the tiles' K steps over workgroups, if the
     // caller's workspace has the room for the partial tiles behind the codes.
     int64_t tiles_n = 0, wg_pairs = 0;
@@ -67,6 +72,13 @@ int gemm_w4_multi(int bits, const void *x, int x_kind, int64_t M, int64_t K, int
     if (agq_launch_prepack_act(x, x_kind, bits, M, K, ldx, e, zp, workspace, stream)) return AGQ_EHIP;
     return hip_status(
         agq_launch_gemm_tiled(workspace, M, K, e, agq_zp_corr(bits, zp), projs, count, -1, split_ws, half_tiles, stream));
+}
+
+namespace {
+
+int gemm_w4_multi(int bits, const void *x, int x_kind, int64_t M, int64_t K, int64_t ldx, int e, int zp,
+                  const agq_proj *projs, int count, void *workspace, size_t workspace_bytes, void *stream) {
+    return agq_gemm_w4_run(bits, x, x_kind, M, K, ldx, e, zp, projs, count, workspace, workspace_bytes, stream, false);
 }
 
 int gemm_w4(int bits, const void *x, int x_kind, int64_t M, int64_t K, int64_t ldx, int e, int zp,

@@ -115,6 +115,11 @@ int agq_launch_prepack_act(const void *x, int x_kind, int bits, int64_t M, int64
 int agq_launch_pack(const int8_t *wq, int64_t N, int64_t K, void *packed, int32_t *bad, void *stream);
 int agq_launch_unpack(const void *packed, int64_t N, int64_t K, int8_t *wq, void *stream);
 struct agq_proj;
+// The linear layer behind every agq_gemm_w4a* call of the public header (argument checks, choice of kernel,
+// launches); returns an agq_status.  check_only: the host-side argument checks alone.
+int agq_gemm_w4_run(int bits, const void *x, int x_kind, int64_t M, int64_t K, int64_t ldx, int e, int zp,
+                    const struct agq_proj *projs, int count, void *workspace, size_t workspace_bytes, void *stream,
+                    bool check_only);
 // n_extra >= 0 with TRIP blobs (all packed with the same factors, fp16 input); -1 for plain blobs
 int agq_launch_gemm_decode(const void *x, int x_kind, int bits, int64_t M, int64_t K, int64_t ldx, int e, int zp,
                            const struct agq_proj *projs, int count, int n_extra, void *stream);

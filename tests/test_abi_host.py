@@ -87,6 +87,20 @@ def test_argument_errors_need_no_gpu(lib):
     assert call(M=1 << 30, N=1 << 30, ldy=1 << 30, ws=p, wsb=1 << 62) == EINVAL   # more tiles than a grid holds
     assert call(M=0, x=None, y=None) == 0            # empty batch is a no-op
 
+    # the call on the library's fixed workspace: same checks, and a size beyond the array is an error of its own
+    s = lib.agq_gemm_w4a8_static
+
+    def scall(**kw):
+        a = dict(ok_args, **kw)
+        return s(a["x"], a["kind"], a["M"], a["K"], a["ldx"], a["e"], a["zp"], a["w"], a["sw"], a["N"], a["y"],
+                 a["ldy"], a["acc"], a["st"])
+
+    assert scall(x=None) == EINVAL and scall(w=None) == EINVAL and scall(y=None) == EINVAL and scall(x=odd) == EINVAL
+    assert scall(K=200) == EINVAL and scall(N=0) == EINVAL and scall(e=41) == EINVAL and scall(zp=256) == EINVAL
+    assert scall(M=0, x=None, y=None) == 0
+    assert scall(M=2049, K=16384, ldx=16384) == ESIZE      # 2176 x 16384 codes: more than the 32 MiB array
+    assert scall(M=4096, K=16384, ldx=16384) == ESIZE
+
     from paper_2312_05693_amd.binding import AgqProj
     m = lib.agq_gemm_w4a8_multi
     good = (AgqProj * 2)(AgqProj(4096, 4096, 64, 4096, 64, None), AgqProj(4096, 4096, 32, 4096, 32, None))
