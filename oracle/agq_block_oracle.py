@@ -87,7 +87,8 @@ def residual_add(a, b) -> np.ndarray:
 
 def heads_int8(x, H: int, e: int, S_pad: int | None = None) -> np.ndarray:
     """Eq.2 (8 bit, signed grid, step 2^e) on fp16 [S, H*D], returned per head as
-    int8 [H, S_pad, D]; rows from S on are zero."""
+    int8 [H, S, D].  S_pad (a test aid for comparing against a padded buffer): [H, S_pad, D]
+    with zero rows from S on; the block itself never pads."""
     q = O.quantize_act(x, 8, e, 0)
     S, d = q.shape
     out = np.zeros((H, S_pad or S, d // H), dtype=np.int8)
@@ -137,7 +138,6 @@ def block_forward(x, pos, cos, sin, w: dict, H: int, qmax: int, eps: float, keep
     x = np.asarray(x)
     S, d = x.shape
     D = d // H
-    S_pad = -(-S // 128) * 128
     e = dict(exps) if exps is not None else {}
 
     al = dict(alphas) if alphas is not None else {}
@@ -164,14 +164,12 @@ def block_forward(x, pos, cos, sin, w: dict, H: int, qmax: int, eps: float, keep
     r["q_rot"] = rope(r["q"], pos, cos, sin, H)
     r["k_rot"] = rope(r["k"], pos, cos, sin, H)
     eq, ek, ev = exp_of("e_q", r["q_rot"], 8), exp_of("e_k", r["k_rot"], 8), exp_of("e_v", r["v"], 8)
-    r["q_q"] = heads_int8(r["q_rot"], H, eq, S_pad)
-    r["k_q"] = heads_int8(r["k_rot"], H, ek, S_pad)
-    r["v_q"] = heads_int8(r["v"], H, ev, S_pad)
-    codes, margin = O.qk_log2_codes(r["q_q"], r["k_q"], eq, ek, qmax, causal=True)
-    r["codes"], r["margin"] = codes[:, :S, :S], margin[:, :S, :S]
-    _, o = O.attn_v_from_codes(codes, r["v_q"], ev, qmax, causal=True)
-    r["o"] = o[:S]
-    r["score"] = O.start_token_score_codes(codes, qmax)[:S]
+    r["q_q"] = heads_int8(r["q_rot"], H, eq)
+    r["k_q"] = heads_int8(r["k_rot"], H, ek)
+    r["v_q"] = heads_int8(r["v"], H, ev)
+    r["codes"], r["margin"] = O.qk_log2_codes(r["q_q"], r["k_q"], eq, ek, qmax, causal=True)
+    _, r["o"] = O.attn_v_from_codes(r["codes"], r["v_q"], ev, qmax, causal=True)
+    r["score"] = O.start_token_score_codes(r["codes"], qmax)
     idx = O.prune_select(r["score"], keep)
     r["idx"] = idx
     r["o_kept"] = r["o"][idx]

@@ -259,10 +259,19 @@ def test_block_stages_are_the_pinned_functions(oracle, blk):
     assert e["e_attn_in"] == oracle.calibrate_act_exp(r["h1"], 8)
     assert np.array_equal(r["k"], oracle.linear_w4(r["h1"], 8, e["e_attn_in"], 0, w["w_k"], w["s_k"])[1])
     assert np.array_equal(r["k_rot"], blk.rope(r["k"], pos, cos, sin, H))
-    assert np.array_equal(r["v_q"], blk.heads_int8(r["v"], H, e["e_v"], 128))
+    assert np.array_equal(r["v_q"], blk.heads_int8(r["v"], H, e["e_v"]))
+    assert r["q_q"].shape == (H, S, d // H) and r["codes"].shape == (H, S, S) and r["o"].shape == (S, d)
     codes, _ = oracle.qk_log2_codes(r["q_q"], r["k_q"], e["e_q"], e["e_k"], 7, True)
-    assert np.array_equal(codes[:, :S, :S], r["codes"]) and codes.max() <= 7
-    assert np.array_equal(r["o"], oracle.attn_v_from_codes(codes, r["v_q"], e["e_v"], 7, True)[1][:S])
+    assert np.array_equal(codes, r["codes"]) and codes.max() <= 7
+    assert np.array_equal(r["o"], oracle.attn_v_from_codes(codes, r["v_q"], e["e_v"], 7, True)[1])
+    # zero rows appended behind the tokens (the library pads its per-head tensors to whole tiles) change nothing
+    # under the causal mask: the first S rows of everything are the unpadded result
+    def pad(t):
+        return np.concatenate([t, np.zeros((H, 128 - S, d // H), dtype=np.int8)], axis=1)
+    codes_p, margin_p = oracle.qk_log2_codes(pad(r["q_q"]), pad(r["k_q"]), e["e_q"], e["e_k"], 7, True)
+    assert np.array_equal(codes_p[:, :S, :S], r["codes"]) and np.array_equal(margin_p[:, :S, :S], r["margin"])
+    assert np.array_equal(oracle.attn_v_from_codes(codes_p, pad(r["v_q"]), e["e_v"], 7, True)[1][:S], r["o"])
+    assert np.array_equal(oracle.start_token_score_codes(codes_p, 7)[:S], r["score"])
     assert e["e_attn_out"] == oracle.calibrate_act_exp(r["o"][r["idx"]], 8)
     assert np.array_equal(r["attn_out"],
                           oracle.linear_w4(r["o"][r["idx"]], 8, e["e_attn_out"], 0, w["w_o"], w["s_o"])[1])
