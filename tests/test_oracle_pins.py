@@ -686,3 +686,47 @@ def test_attn_v_from_codes(oracle):
     # importance on the quantized map
     sc = oracle.start_token_score_codes(codes, qmax)
     assert sc.tolist() == [sum(1 << (qmax - int(codes[h, i, 0])) for h in range(H)) for i in range(S)]
+
+
+def test_start_token_score_codes_pins(oracle):
+    """Section 4.3: importance = attention paid to the first token, here read on the quantized map.
+    Pinned by a hand-worked map with literal scores (other columns, heads and rows carry different
+    codes, so a wrong column, axis or sign of the exponent changes the numbers), by probabilities that
+    are exact powers of two (the score must be the unquantized map's score, rescaled), and by the two
+    extreme heads."""
+    # codes[h, i, j]; column 0 is what counts.  qmax = 15:
+    #   token 0: heads give 2^15 + 2^15           = 65536
+    #   token 1: 2^(15-3) + 2^(15-1)              = 20480
+    #   token 2: 2^(15-15) + 2^(15-14)            = 3
+    codes = np.array([[[0, 9, 2], [3, 0, 9], [15, 1, 0]],
+                      [[0, 4, 4], [1, 7, 7], [14, 0, 3]]])
+    assert oracle.start_token_score_codes(codes, 15).tolist() == [65536, 20480, 3]
+    # qmax = 7 (Eq.3's signed 4-bit range): 2^7 + 2^7, 2^4 + 2^6, 2^0 + 2^1 with codes 7 and 6 in the last row
+    codes7 = np.array([[[0, 5], [3, 0], [7, 1]], [[0, 2], [1, 7], [6, 0]]])
+    assert oracle.start_token_score_codes(codes7, 7).tolist() == [256, 80, 3]
+    # one head only, one token only: shapes must not be confused
+    assert oracle.start_token_score_codes(np.array([[[2, 0, 0, 0]]]), 15).tolist() == [8192]
+    # probabilities that are powers of two no smaller than 2^-qmax quantize without error (Eq.3), so the
+    # score on the codes is the score on the probabilities, 2^24 p summed over heads, in units of 2^qmax
+    rng = np.random.default_rng(71)
+    for qmax in (15, 7):
+        H, S = 5, 12
+        c = rng.integers(0, qmax + 1, size=(H, S, S))
+        p = np.ldexp(1.0, -c).astype(np.float16)
+        assert np.array_equal(oracle.log2_quant(p, qmax), c)
+        got = oracle.start_token_score_codes(oracle.log2_quant(p, qmax), qmax)
+        assert np.array_equal(got << (24 - qmax), oracle.start_token_score(p))
+        # and both equal the plain column sum of the map
+        assert np.array_equal(got, (p[:, :, 0].astype(np.float64).sum(axis=0) * 2.0 ** qmax).astype(np.int64))
+    # every head looks only at the first token: H * 2^qmax; no head does (p = 0 -> code qmax): H
+    H, S = 4, 6
+    p = np.zeros((H, S, S), dtype=np.float16)
+    assert oracle.start_token_score_codes(oracle.log2_quant(p, 15), 15).tolist() == [H] * S
+    p[:, :, 0] = 1.0
+    assert oracle.start_token_score_codes(oracle.log2_quant(p, 15), 15).tolist() == [H << 15] * S
+    # monotone: lowering one head's code for a token raises that token's score and no other's
+    base = oracle.start_token_score_codes(codes, 15)
+    codes2 = codes.copy()
+    codes2[1, 1, 0] = 0
+    moved = oracle.start_token_score_codes(codes2, 15)
+    assert moved[1] == base[1] - (1 << 14) + (1 << 15) and moved[0] == base[0] and moved[2] == base[2]
