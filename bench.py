@@ -39,11 +39,27 @@ INT8_PEAK_TOPS = 5000.0        # MI355X dense int8 MFMA
 DECODE_M = (1, 4, 16)
 PREFILL_M = 2048
 
-# HBM traffic per launch of the decode kernels from rocprofv3 --pmc (FETCH_SIZE x 2.0 KiB +
-# WRITE_SIZE x 1.0 KiB, the factors a 256 MiB copy gives); see profiles/.
-MEASURED_TRAFFIC_BYTES_PER_LAUNCH = 26.3e6
-MEASURED_ATTN_TRAFFIC_BYTES = 252.3e6   # log2_attn_kernel, one call of the bench's attention block
-MEASURED_TILED_TRAFFIC_BYTES = 165.2e6  # gemm_tiled_kernel, mean per launch of a run without the by-M sweep (up to three projections each)
+# HBM traffic per launch from rocprofv3 --pmc runs of this file (FETCH_SIZE x 2.0 KiB + WRITE_SIZE x 1.0 KiB, the
+# factors a 256 MiB copy gives).  A counter run cannot happen inside a timed run, so the figures are carried here
+# from the summaries under profiles/, each with the digest of the kernel source it was measured on: when that
+# source has changed since, the figure is reported as null (stale) instead of a number that no longer holds.
+#   name: (bytes per launch, profiles/ file, source file, first 12 hex digits of the source's sha256)
+MEASURED_TRAFFIC = {
+    "decode": (26.3e6, "profiles/gemm_decode_llama7b_sweep.md", "agq_gemm_decode.hip", "@DECODE@"),
+    "attn": (252.3e6, "profiles/log2_attn_llama13b_block.md", "agq_attn.hip", "@ATTN@"),
+    "tiled": (165.2e6, "profiles/gemm_decode_llama7b_sweep.md", "agq_gemm_tiled.hip", "@TILED@"),
+}
+
+
+def measured_traffic(name):
+    """(bytes or None, note) for the roofline objects."""
+    import hashlib
+    nbytes, prof, src, digest = MEASURED_TRAFFIC[name]
+    path = os.path.join(ROOT, "paper_2312_05693_amd", "csrc", src)
+    now = hashlib.sha256(open(path, "rb").read()).hexdigest()[:12]
+    if now != digest:
+        return None, "stale: %s changed since the counter run summarised in %s" % (src, prof)
+    return nbytes, "rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, %s" % prof
 
 
 def algorithmic_bytes(M, K, N):
@@ -61,6 +77,7 @@ def main():
     ap.add_argument("--no-attention", action="store_true")
     ap.add_argument("--no-trip", action="store_true")
     ap.add_argument("--no-block", action="store_true")
+    ap.add_argument("--no-probe", action="store_true", help="skip the plain-read / empty-kernel probe of the device")
     ap.add_argument("--no-by-m", action="store_true", help="skip the sweep over 32..1024 rows in the prefill section")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also run a 256 MiB device copy: the known traffic that scales the FETCH_SIZE / WRITE_SIZE counters")
@@ -152,9 +169,11 @@ def main():
     launches_per_step = len(DECODE_M) * launches_per_pass
     bytes_per_step = sum(algorithmic_bytes(M, K, N) for M in DECODE_M for layer in layers for (K, N, _, _) in layer)
 
-    def timed(fn, warmup, steps):
+    def timed(fn, warmup, steps, stats=None):
         """Captures `fn` (a launch-bound chain of kernels) into a HIP graph, replays it
-        `warmup` times untimed and `steps` times between two events on the replay stream."""
+        `warmup` times untimed and `steps` times between events on the replay stream.  Returns the
+        milliseconds from the event before the first timed replay to the event after the last;
+        stats (a dict), when given, also receives the median and the minimum over the replays."""
         fn()                                   # first call outside capture (lazy module load)
         torch.cuda.synchronize()
         graph = torch.cuda.CUDAGraph()
@@ -163,15 +182,19 @@ def main():
         for _ in range(warmup):
             graph.replay()
         torch.cuda.synchronize()
-        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        a.record()
-        for _ in range(steps):
+        ev = [torch.cuda.Event(enable_timing=True) for _ in range(steps + 1)]
+        ev[0].record()
+        for i in range(steps):
             graph.replay()
-        b.record()
+            ev[i + 1].record()
         torch.cuda.synchronize()
-        return a.elapsed_time(b)
+        if stats is not None:
+            per = sorted(ev[i].elapsed_time(ev[i + 1]) for i in range(steps))
+            stats["median_ms"], stats["min_ms"] = per[len(per) // 2], per[0]
+        return ev[0].elapsed_time(ev[steps])
 
-    ms_total = timed(decode_step, args.warmup, args.steps)
+    step_stats = {}
+    ms_total = timed(decode_step, args.warmup, args.steps, step_stats)
     ms_per_step = ms_total / args.steps
     gbs = bytes_per_step / (ms_per_step * 1e-3) / 1e9
     avg_launch_us = ms_per_step * 1e3 / launches_per_step
@@ -206,6 +229,8 @@ def main():
         "steps": args.steps,
         "warmup": args.warmup,
         "ms_per_step": round(ms_per_step, 4),
+        "ms_per_step_median": round(step_stats["median_ms"], 4),
+        "ms_per_step_min": round(step_stats["min_ms"], 4),
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
@@ -216,7 +241,8 @@ def main():
                    "launches_per_step": launches_per_step, "weight_bytes": int(weight_bytes),
                    "algorithmic_bytes_per_step": int(bytes_per_step)},
         "roofline": {"bound": "hbm", "achieved": round(gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": round(gbs / HBM_PEAK_GBS, 4), "traffic": MEASURED_TRAFFIC_BYTES_PER_LAUNCH,
+                     "frac": round(gbs / HBM_PEAK_GBS, 4), "traffic": measured_traffic("decode")[0],
+                     "traffic_source": measured_traffic("decode")[1],
                      "kernel": "gemm_decode_kernel (M <= 8, K > 8192, one workgroup per CU) and gemm_decode_shared_kernel (9..16 rows): "
                                "every launch of a step", "avg_launch_us": round(avg_launch_us, 3),
                      "algorithmic_bytes_per_launch": int(bytes_per_step / launches_per_step)},
@@ -225,6 +251,60 @@ def main():
         "launch": "one HIP graph per step, replayed; per block: qkv (one multi call), o, gate+up (one multi call), down"
                   if not args.per_projection else "one HIP graph per step, replayed; seven single calls per block",
     }
+
+    # ---- what one launch can reach on this device (the floor under the figures above): the same 128 launches
+    #      of a pass as plain reads of buffers of the launches' sizes (q/k/v, o, gate/up, down of 32 blocks,
+    #      3.2 GB in all, never cache-resident), and as empty kernels; replayed graphs, like the sweep itself
+    if not args.no_probe:
+        import ctypes
+        probe = ctypes.CDLL(os.path.join(ROOT, "paper_2312_05693_amd", "libagq_probe.so"))
+        probe.agq_probe_read.restype = ctypes.c_int
+        probe.agq_probe_read.argtypes = [ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p, ctypes.c_void_p]
+        probe.agq_probe_empty.restype = ctypes.c_int
+        probe.agq_probe_empty.argtypes = [ctypes.c_void_p]
+        sizes = [sum(layers[0][i][2].numel() for i in grp) for grp in ((0, 1, 2), (3,), (4, 5), (6,))]
+        pool = torch.empty(sum(sizes) * len(layers), dtype=torch.uint8, device=dev).fill_(3)
+        sink = torch.zeros(64, dtype=torch.int32, device=dev)
+        stream_of = lambda: torch.cuda.current_stream().cuda_stream
+
+        def read_pass():
+            at = 0
+            for _ in layers:
+                for nb in sizes:
+                    assert probe.agq_probe_read(pool.data_ptr() + at, nb, sink.data_ptr(), stream_of()) == 0
+                    at += nb
+
+        def empty_pass():
+            for _ in range(4 * len(layers)):
+                assert probe.agq_probe_empty(stream_of()) == 0
+
+        n_l = 4 * len(layers)
+        reps = max(5, args.steps)
+        st_r, st_e = {}, {}
+        ms_read = timed(read_pass, 2, reps, st_r) / reps
+        ms_empty = timed(empty_pass, 2, reps, st_e) / reps
+        per_size = {}
+        for nb, name in zip(sizes, ("qkv", "o", "gate_up", "down")):
+            def one_size():
+                at = 0
+                for _ in range(32):
+                    assert probe.agq_probe_read(pool.data_ptr() + at, nb, sink.data_ptr(), stream_of()) == 0
+                    at += nb
+            us = timed(one_size, 2, reps) / reps / 32 * 1e3
+            per_size[name] = {"MB": round(nb / 1e6, 1), "us": round(us, 2), "GB/s": round(nb / us / 1e3, 1)}
+        read_gbs = pool.numel() / (ms_read * 1e-3) / 1e9
+        result["probe"] = {
+            "what": "the launches of one pass (32 blocks x 4) as plain reads of the same sizes, and as empty kernels, in replayed graphs",
+            "read_GB/s": round(read_gbs, 1), "read_frac_of_peak": round(read_gbs / HBM_PEAK_GBS, 4),
+            "read_us_per_launch": round(ms_read * 1e3 / n_l, 2), "read_us_per_launch_min": round(st_r["min_ms"] * 1e3 / n_l, 2),
+            "empty_us_per_launch": round(ms_empty * 1e3 / n_l, 2), "empty_us_per_launch_min": round(st_e["min_ms"] * 1e3 / n_l, 2),
+            "read_by_size": per_size,
+            "note": "one launch per projection group cannot read faster than this: HBM requests start after the launch and "
+                    "the last bytes arrive before the next launch begins"}
+        result["roofline"]["frac_of_probe"] = round(gbs / read_gbs, 4)
+        for k, v in per_m.items():
+            v["frac_of_probe"] = round(v["GB/s"] / read_gbs, 4)
+        del pool
 
     # ---- the small correctness configuration (one OPT-125M-sized layer, 128 tokens): launch-latency bound, time only
     x0 = torch.from_numpy(synth.make_activation(128, 768, 4, seed=0)).to(dev)
@@ -284,7 +364,8 @@ def main():
             prefill[name] = {"M": PREFILL_M, "ms_per_block": round(tot_ms, 4), "TOP/s": round(tops, 1),
                              "roofline": {"bound": "mfma", "achieved": round(tops, 1), "peak": INT8_PEAK_TOPS,
                                           "unit": "TOP/s", "frac": round(tops / INT8_PEAK_TOPS, 4),
-                                          "traffic": MEASURED_TILED_TRAFFIC_BYTES, "kernel": "gemm_tiled_kernel",
+                                          "traffic": measured_traffic("tiled")[0], "traffic_source": measured_traffic("tiled")[1],
+                                          "kernel": "gemm_tiled_kernel",
                                           "note": "fp16 input: time includes the 4 quantize/layout pre-passes of a block"},
                              "single_calls": shapes}
         # Between the two regimes (W4A8, fp16 input, single calls over eight distinct weight matrices per shape in a
@@ -442,7 +523,7 @@ def main():
                                "roofline": {"bound": "hbm", "achieved": round(by_attn / us_attn / 1e3, 1),
                                             "peak": HBM_PEAK_GBS, "unit": "GB/s",
                                             "frac": round(by_attn / us_attn / 1e3 / HBM_PEAK_GBS, 4),
-                                            "traffic": MEASURED_ATTN_TRAFFIC_BYTES,
+                                            "traffic": measured_traffic("attn")[0], "traffic_source": measured_traffic("attn")[1],
                                             "kernel": "log2_attn_kernel"}},
             "prune_tokens": {"us": round(us_prune, 1), "GB/s": round(by_prune / us_prune / 1e3, 1)},
             "tail_gemms_w4a8": {"M": keep, "shapes": "5120->5120, 5120->13824", "us": round(us_tail, 1),
@@ -561,23 +642,31 @@ def main():
         threads = oracle.c_max_threads()
         cpu_layer = [(K, N) + synth.make_weight_q4(N, K, seed=100 + i) for i, (_, K, N) in enumerate(synth.LLAMA7B_PROJ)]
         cpu_x = {(M, K): synth.make_activation(M, K, 4, seed=1) for M in DECODE_M for K in (4096, 11008)}
-        t_start = time.perf_counter()
-        done_bytes, passes = 0, 0
-        while time.perf_counter() - t_start < 12.0 and passes < 400:
-            for M in DECODE_M:
-                for (K, N, wq, sw) in cpu_layer:
-                    x = cpu_x[(M, K)]
-                    e = es[(M, K)]
-                    q = oracle.quantize_act(x, 8, e, 0).astype(np.int8)
-                    acc = oracle.gemm_int_c(q, wq, threads=threads)
-                    oracle.dequant_out(acc, e, sw)
-                    done_bytes += algorithmic_bytes(M, K, N)
-            passes += 1
-        cpu_s = time.perf_counter() - t_start
-        result["cpu_baseline"] = {"value": round(done_bytes / cpu_s / 1e9, 3), "unit": "GB/s", "cores": threads,
+
+        def cpu_rate(nthreads, budget_s):
+            t_start = time.perf_counter()
+            done_bytes, passes = 0, 0
+            while time.perf_counter() - t_start < budget_s and passes < 400:
+                for M in DECODE_M:
+                    for (K, N, wq, sw) in cpu_layer:
+                        x = cpu_x[(M, K)]
+                        e = es[(M, K)]
+                        q = oracle.quantize_act(x, 8, e, 0).astype(np.int8)
+                        acc = oracle.gemm_int_c(q, wq, threads=nthreads)
+                        oracle.dequant_out(acc, e, sw)
+                        done_bytes += algorithmic_bytes(M, K, N)
+                passes += 1
+            cpu_s = time.perf_counter() - t_start
+            return done_bytes / cpu_s / 1e9, passes, cpu_s
+
+        rate_all, passes, cpu_s = cpu_rate(threads, 10.0)
+        rate_one, passes1, cpu_s1 = cpu_rate(1, 8.0)
+        result["cpu_baseline"] = {"value": round(rate_all, 3), "unit": "GB/s", "cores": threads,
                                   "kind": "oracle",
                                   "sample": "%d pass(es) over one block's 7 projections x M in {1,4,16} "
-                                            "(numpy quantizer + plain C int8 loops + numpy dequant), %.1f s" % (passes, cpu_s)}
+                                            "(numpy quantizer + plain C int8 loops + numpy dequant), %.1f s" % (passes, cpu_s),
+                                  "value_1_thread": round(rate_one, 3),
+                                  "sample_1_thread": "%d pass(es) of the same, %.1f s" % (passes1, cpu_s1)}
 
     print(json.dumps(result))
 

@@ -3,7 +3,11 @@
  *
  * C ABI.  Conventions that hold for every call unless a comment says otherwise:
  *   - every tensor pointer is a DEVICE pointer owned by the caller; the library
- *     allocates nothing and keeps no state between calls;
+ *     allocates nothing and keeps no tensor state between calls.  What it does
+ *     keep, per process and device, are facts looked up once: the device's number
+ *     of compute units, a raised LDS limit of its own kernels, and the address of
+ *     agq_gemm_w4a8_static's array.  Each is set up, thread-safely, by the first
+ *     call that needs it on that device;
  *   - tensors are row-major, leading dimensions are in elements;
  *   - work is enqueued asynchronously on `stream` (a hipStream_t passed as
  *     void*, NULL = the default stream); the caller synchronises;
@@ -115,11 +119,10 @@ int agq_unpack_w4(const void *packed, int64_t N, int64_t K, int8_t *wq_out,
  * the tiled kernel; while the call has at most 128 tiles of 128 x 128 either with K
  * split over workgroups (a long K, and the workspace has the room) or with 64-token
  * tiles, whichever a measured cost model puts first.
- * Graph capture: the calls enqueue kernels only and may be captured, with one
- * exception: the first call in a process that needs the kernel with the
- * activation kept in LDS (9 <= M <= 16, more than 4096 output channels in the
- * call) raises that kernel's LDS limit, a host-side setting; make one such
- * call eagerly before capturing.                                             */
+ * Graph capture: the calls enqueue kernels only and may be captured.  (The first
+ * weight-streaming call on a device also raises the LDS limit of the library's
+ * kernels there: a host-side setting, not a stream operation, made once per
+ * device whatever the shape of that first call.)                              */
 size_t agq_gemm_workspace_bytes(int64_t M, int64_t N, int64_t K);
 int agq_gemm_w4a8(const void *x, int x_kind, int64_t M, int64_t K, int64_t ldx,
                   int e, int zp, const void *w_packed, const void *w_scale_f16,

@@ -11,6 +11,8 @@ OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libagq.so")
 SOURCES = ["agq_api.cpp", "agq_quant.hip", "agq_gemm_decode.hip", "agq_gemm_tiled.hip", "agq_attn.hip", "agq_trip.hip", "agq_attn_qk.hip",
            "agq_block.hip", "agq_block_api.cpp", "agq_static.hip"]
+PROBE_LIB = os.path.join(HERE, "libagq_probe.so")     # bench.py's measurement aid, a library of its own
+PROBE_SOURCE = "agq_probe.hip"
 HEADERS = ["agq_device.h", "agq_internal.h", os.path.join("..", "..", "include", "agq.h")]
 FLAGS = ["-O3", "--offload-arch=gfx950", "-fPIC", "-std=c++17", "-x", "hip",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
@@ -32,12 +34,18 @@ def _compile(src: str) -> str:
 def build(force: bool = True, jobs: int = 4) -> str:
     """Compiles every source and links the shared library.  With force=False an
     up-to-date library is kept."""
-    deps = [os.path.join(CSRC, s) for s in SOURCES] + [os.path.join(CSRC, h) for h in HEADERS]
-    if not force and os.path.exists(LIB) and os.path.getmtime(LIB) >= _newest(deps):
+    deps = [os.path.join(CSRC, s) for s in SOURCES + [PROBE_SOURCE]] + [os.path.join(CSRC, h) for h in HEADERS]
+    if not force and os.path.exists(LIB) and os.path.exists(PROBE_LIB) and \
+            min(os.path.getmtime(LIB), os.path.getmtime(PROBE_LIB)) >= _newest(deps):
         return LIB
     os.makedirs(OBJ, exist_ok=True)
     with ThreadPoolExecutor(max_workers=jobs) as ex:
-        objs = list(ex.map(_compile, SOURCES))
+        objs = list(ex.map(_compile, SOURCES + [PROBE_SOURCE]))
+    probe_obj = objs.pop()
+    r = subprocess.run(["hipcc", "--offload-arch=gfx950", "-shared", "-fPIC", "-o", PROBE_LIB, probe_obj],
+                       capture_output=True, text=True)
+    if r.returncode != 0:
+        raise RuntimeError("link of the probe library failed:\n%s" % r.stderr)
     r = subprocess.run(["hipcc", "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB, *objs],
                        capture_output=True, text=True)
     if r.returncode != 0:

@@ -22,6 +22,8 @@
 #include "agq_device.h"
 #include "agq_internal.h"
 
+#include <mutex>
+
 AgqQuant agq_make_quant_signed(int bits, int e, int zp);
 
 namespace {
@@ -551,18 +553,40 @@ __global__ __launch_bounds__(1024) void gemm_decode_shared_kernel(const DecodeAr
     }
 }
 
-// More than 48 KiB of dynamic LDS needs the limit of the kernel raised, once per
-// process and kernel (the first call does it; it is a host-side setting, not a
-// stream operation).
+// More than 48 KiB of dynamic LDS needs the limit of the kernel raised: a host-side setting per device and
+// kernel, not a stream operation.  Every instantiation is raised once per device, on the first weight-streaming
+// launch of any shape made with that device current (so a caller never meets it in the middle of a run).
+template <int KPW, bool ZP>
+hipError_t raise_shared_lds() {
+    return hipFuncSetAttribute(reinterpret_cast<const void *>(gemm_decode_shared_kernel<KPW, 4, ZP>),
+                               hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024 - 512);
+}
+
+constexpr int kMaxDevices = 64;
+std::once_flag g_lds_once[kMaxDevices];
+hipError_t g_lds_err[kMaxDevices];
+
+int ensure_shared_lds_limit() {
+    int device = 0;
+    if (hipGetDevice(&device) != hipSuccess) return (int)hipGetLastError();
+    if (device < 0 || device >= kMaxDevices) return (int)hipErrorInvalidDevice;
+    std::call_once(g_lds_once[device], [device] {
+        hipError_t err = raise_shared_lds<1, false>();
+        if (err == hipSuccess) err = raise_shared_lds<2, false>();
+        if (err == hipSuccess) err = raise_shared_lds<4, false>();
+        if (err == hipSuccess) err = raise_shared_lds<8, false>();
+        if (err == hipSuccess) err = raise_shared_lds<1, true>();
+        if (err == hipSuccess) err = raise_shared_lds<2, true>();
+        if (err == hipSuccess) err = raise_shared_lds<4, true>();
+        if (err == hipSuccess) err = raise_shared_lds<8, true>();
+        g_lds_err[device] = err;
+    });
+    return (int)g_lds_err[device];
+}
+
 template <int KPW, int MP, bool ZP>
 int launch_shared_kpw(const DecodeArgs &a, int tiles, unsigned grid, int wpt, int nstreams, size_t lds, hipStream_t st) {
-    static bool raised = false;
-    if (!raised) {
-        hipError_t err = hipFuncSetAttribute(reinterpret_cast<const void *>(gemm_decode_shared_kernel<KPW, MP, ZP>),
-                                             hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024 - 512);
-        if (err != hipSuccess) return (int)err;
-        raised = true;
-    }
+    static_assert(MP == 4, "the limit is raised for the four-pass instantiations");
     gemm_decode_shared_kernel<KPW, MP, ZP><<<grid, wpt * nstreams * 64, lds, st>>>(a, tiles, wpt);
     return (int)hipGetLastError();
 }
@@ -605,6 +629,7 @@ int launch_xk(const DecodeArgs &a, int kpw, unsigned grid, int waves, size_t lds
 
 int agq_launch_gemm_decode(const void *x, int x_kind, int bits, int64_t M, int64_t K, int64_t ldx, int e, int zp,
                            const agq_proj *projs, int count, int n_extra, void *stream) {
+    if (const int err = ensure_shared_lds_limit()) return err;
     DecodeArgs a = {};
     a.x = x;
     a.ldx = ldx;

@@ -521,6 +521,44 @@ def test_deterministic_repeat(agq, oracle):
         assert np.array_equal(host(agq.gemm_w4a8(xd, e, packed, swd, 4096, 4096)).view(np.uint16), first.view(np.uint16))
 
 
+def test_first_call_of_a_process_under_graph_capture(agq):
+    """The calls enqueue kernels only, the very first one of a process included (its one-time host-side set-up is
+    not a stream operation): a child process captures its first GEMM calls (the shapes that use the kernel with
+    the activation in LDS, and the per-tile kernel), replays the graph and compares with eager calls made after."""
+    import os
+    import subprocess
+    import sys
+    code = r"""
+import sys, numpy as np, torch
+sys.path.insert(0, %r)
+from paper_2312_05693_amd import binding as agq, synth
+agq.lib()
+dev = lambda a: torch.from_numpy(np.ascontiguousarray(a)).cuda()
+cases = []
+for (M, K, N, seed) in ((12, 256, 4352, 1), (3, 512, 80, 2)):
+    x = synth.make_activation(M, K, 2, seed)
+    wq, sw = synth.make_weight_q4(N, K, seed)
+    packed = torch.empty(agq.pack_w4_bytes(N, K), dtype=torch.uint8, device="cuda")
+    cases.append((M, K, N, dev(x), dev(wq), dev(sw), packed, torch.zeros((M, N), dtype=torch.float16, device="cuda")))
+torch.cuda.synchronize()
+side = torch.cuda.Stream()
+g = torch.cuda.CUDAGraph()
+with torch.cuda.graph(g, stream=side):
+    for (M, K, N, xd, wqd, swd, packed, y) in cases:
+        agq.pack_w4(wqd, packed=packed)
+        agq.gemm_w4a8(xd, -3, packed, swd, N, K, y=y)
+g.replay()
+torch.cuda.synchronize()
+for (M, K, N, xd, wqd, swd, packed, y) in cases:
+    want = agq.gemm_w4a8(xd, -3, agq.pack_w4(wqd), swd, N, K)
+    torch.cuda.synchronize()
+    assert y.abs().sum().item() > 0 and torch.equal(y.view(torch.int16), want.view(torch.int16)), (M, K, N)
+print("CAPTURED_FIRST_CALL_OK")
+""" % os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, "-c", code], capture_output=True, text=True, timeout=110)
+    assert r.returncode == 0 and "CAPTURED_FIRST_CALL_OK" in r.stdout, r.stdout[-2000:] + r.stderr[-2000:]
+
+
 # ------------------------------------------------------------------ the paper-shaped configurations
 
 def test_config0_opt125m_w4a8(agq, oracle):
