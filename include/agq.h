@@ -32,7 +32,9 @@ enum agq_status {
     AGQ_OK = 0,
     AGQ_EINVAL = -1, /* bad argument (null pointer, size, granularity, range) */
     AGQ_ESIZE = -2,  /* workspace too small                                    */
-    AGQ_EHIP = -3    /* the HIP runtime refused a launch                       */
+    AGQ_EHIP = -3,   /* the HIP runtime refused a launch                       */
+    AGQ_ETIMEOUT = -4 /* agq_gemm_chain_status: a wait inside a chain launch ran
+                         out of time (see there)                                */
 };
 
 /* what `x` of the GEMM calls holds */
@@ -180,6 +182,58 @@ int agq_gemm_w4a8_multi(const void *x, int x_kind, int64_t M, int64_t K, int64_t
 int agq_gemm_w4a4_multi(const void *x, int x_kind, int64_t M, int64_t K, int64_t ldx,
                         int e, int zp, const agq_proj *projs, int count,
                         void *workspace, size_t workspace_bytes, void *stream);
+
+/* A chain of linear layers for a few tokens in ONE kernel launch: the decode
+ * regime, where a step of the model is a sequence of layers that each read
+ * 8-45 MB of 4-bit weights once (Section 3.3: the matrix products are the
+ * workload; Section 4.4: layer-wise activation parameters, so every stage has its
+ * own static exponent).  Stage s computes what agq_gemm_w4a8_multi /
+ * agq_gemm_w4a4_multi computes (zp = 0, fp16 input, Eq.2 inside, per-channel
+ * dequantization, fp16 outputs written to the caller's tensors), on
+ *   - a caller tensor x_f16 [M,K] (ldx % 8 == 0, 16-byte aligned), or
+ *   - x_f16 == NULL: the fp16 output of projection `src_proj` of stage s-1, whose
+ *     width must equal this stage's K (never allowed for stage 0).
+ * Results are those of the single calls, bit for bit.  One persistent workgroup
+ * per compute unit walks through the stages; the weights of the next stage are
+ * requested while the outputs of the current one travel between the compute
+ * units (through records in the workspace that carry their own epoch), which a
+ * launch per layer cannot do.
+ *
+ * M: 1..AGQ_CHAIN_MAX_M.  Per stage: K % 128 == 0, 128 <= K <= 16384; bits 8 or 4;
+ * 1 <= count <= AGQ_MAX_PROJ; every N % 16 == 0, ldy even; pointers as for
+ * agq_gemm_w4a8 (acc_out, if given, 8-byte aligned).  n_stages <=
+ * AGQ_CHAIN_MAX_STAGES.  stages is a HOST array.
+ *
+ * agq_gemm_chain_prepare: checks everything on the host, then writes the stage
+ * table and zeroes the records in `workspace` (agq_gemm_chain_workspace_bytes,
+ * 0 = invalid arguments; 256-byte aligned) and WAITS for `stream`: set-up work,
+ * not capturable.  The pointers inside the stages are baked into the workspace.
+ * agq_gemm_chain_run: enqueues the one kernel on a prepared workspace; allocates
+ * nothing and may be captured and replayed any number of times.  Runs of one
+ * workspace must not overlap in time, and the device must not be busy with other
+ * kernels of comparable length while a chain runs: the workgroups wait for each
+ * other, so all of them have to be resident at once (one per compute unit).
+ * Every wait inside the kernel is bounded (20 ms): if one runs out, all workgroups
+ * leave, outputs are incomplete, and the workspace is marked; later runs on it
+ * return at once.  agq_gemm_chain_status waits for `stream` and returns AGQ_OK or
+ * AGQ_ETIMEOUT for the runs so far; after a time-out prepare the workspace again. */
+#define AGQ_CHAIN_MAX_M 4
+#define AGQ_CHAIN_MAX_STAGES 1024
+typedef struct agq_chain_stage {
+    const void *x_f16;          /* caller input, or NULL: output of the stage before */
+    int64_t ldx;                /* elements; ignored when x_f16 == NULL               */
+    int src_proj;               /* which projection of stage s-1 (x_f16 == NULL)      */
+    int bits;                   /* activation grid: 8 or 4                            */
+    int e;                      /* activation scale 2^e of this stage                 */
+    int64_t K;
+    int count;
+    agq_proj projs[AGQ_MAX_PROJ];
+} agq_chain_stage;
+size_t agq_gemm_chain_workspace_bytes(const agq_chain_stage *stages, int n_stages, int64_t M);
+int agq_gemm_chain_prepare(const agq_chain_stage *stages, int n_stages, int64_t M,
+                           void *workspace, size_t workspace_bytes, void *stream);
+int agq_gemm_chain_run(void *workspace, void *stream);
+int agq_gemm_chain_status(const void *workspace, void *stream);
 
 /* TRIP: per-channel power-of-two factors on top of the layer-wise step
  * (Section 4.3, Eq.5-8) and the matrix product that carries them on the weight

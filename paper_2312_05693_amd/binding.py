@@ -13,7 +13,7 @@ import torch
 HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(HERE, "libagq.so")
 
-AGQ_OK, AGQ_EINVAL, AGQ_ESIZE, AGQ_EHIP = 0, -1, -2, -3
+AGQ_OK, AGQ_EINVAL, AGQ_ESIZE, AGQ_EHIP, AGQ_ETIMEOUT = 0, -1, -2, -3, -4
 AGQ_X_F16, AGQ_X_Q = 0, 1
 
 _i64, _int, _vp, _sz = ctypes.c_int64, ctypes.c_int, ctypes.c_void_p, ctypes.c_size_t
@@ -33,6 +33,10 @@ SIGNATURES = {
     "agq_gemm_w4a8_static": (_int, _GEMM_ARGS[:13] + [_vp]),
     "agq_gemm_w4a8_multi": (_int, [_vp, _int, _i64, _i64, _i64, _int, _int, _vp, _int, _vp, _sz, _vp]),
     "agq_gemm_w4a4_multi": (_int, [_vp, _int, _i64, _i64, _i64, _int, _int, _vp, _int, _vp, _sz, _vp]),
+    "agq_gemm_chain_workspace_bytes": (_sz, [_vp, _int, _i64]),
+    "agq_gemm_chain_prepare": (_int, [_vp, _int, _i64, _vp, _sz, _vp]),
+    "agq_gemm_chain_run": (_int, [_vp, _vp]),
+    "agq_gemm_chain_status": (_int, [_vp, _vp]),
     "agq_trip_search": (_int, [_vp, _i64, _i64, _i64, _int, _int, _int, _int, _vp, _vp]),
     "agq_trip_extra_chunks": (_int, [_vp, _i64]),
     "agq_pack_w4_trip_bytes": (_sz, [_i64, _i64, _int]),
@@ -66,6 +70,15 @@ class AgqProj(ctypes.Structure):
     """struct agq_proj of include/agq.h"""
     _fields_ = [("w_packed", _vp), ("w_scale_f16", _vp), ("N", _i64), ("y_f16", _vp), ("ldy", _i64),
                 ("acc_out", _vp)]
+
+
+AGQ_CHAIN_MAX_M = 4
+
+
+class AgqChainStage(ctypes.Structure):
+    """struct agq_chain_stage of include/agq.h"""
+    _fields_ = [("x_f16", _vp), ("ldx", _i64), ("src_proj", _int), ("bits", _int), ("e", _int), ("K", _i64),
+                ("count", _int), ("projs", AgqProj * AGQ_MAX_PROJ)]
 
 
 BLOCK_PROJ = ("q", "k", "v", "o", "gate", "up", "down")
@@ -232,6 +245,62 @@ def gemm_w4a4_multi(x, e, projs, K, x_kind=AGQ_X_F16, workspace=None, zp=0):
     M = x.shape[0]
     ldx = (x.stride(0) if M else K) * (2 if x_kind == AGQ_X_Q else 1)
     return _gemm_multi("agq_gemm_w4a4_multi", x, x_kind, M, K, ldx, e, zp, projs, workspace)
+
+
+class ChainPlan:
+    """A prepared chain: the stage array, its workspace, and the tensors the baked pointers refer to."""
+
+    def __init__(self, arr, n, M, workspace, keepalive, ys):
+        self.arr, self.n, self.M, self.workspace, self.keepalive, self.ys = arr, n, M, workspace, keepalive, ys
+
+
+def gemm_chain_stages(stages, M):
+    """stages: list of dicts with x (fp16 [M,K] tensor, or None: the output of projection `src_proj` of the stage
+    before), bits, e, K and projs = [(w_packed, w_scale, N, y|None, acc_out|None), ...].  Returns the ctypes array,
+    the per-stage lists of outputs and everything that must stay alive."""
+    arr = (AgqChainStage * len(stages))()
+    keep, ys = [], []
+    for i, st in enumerate(stages):
+        x = st.get("x")
+        c = arr[i]
+        c.x_f16, c.ldx = _ptr(x), (x.stride(0) if x is not None else 0)
+        c.src_proj, c.bits, c.e, c.K, c.count = int(st.get("src_proj", 0)), int(st["bits"]), int(st["e"]), int(st["K"]), len(st["projs"])
+        outs = []
+        for p, (packed, scale, N, y, acc) in enumerate(st["projs"]):
+            if y is None:
+                y = torch.zeros((M, N), dtype=torch.float16, device=packed.device)
+            outs.append(y)
+            c.projs[p] = AgqProj(_ptr(packed), _ptr(scale), N, _ptr(y), y.stride(0), _ptr(acc))
+            keep += [packed, scale, y, acc]
+        keep.append(x)
+        ys.append(outs)
+    return arr, ys, keep
+
+
+def gemm_chain_prepare(stages, M, workspace=None) -> ChainPlan:
+    """agq_gemm_chain_prepare: checks the chain, writes its table into a workspace (allocated here unless given) and
+    waits for the current stream."""
+    arr, ys, keep = gemm_chain_stages(stages, M)
+    n = len(stages)
+    need = lib().agq_gemm_chain_workspace_bytes(ctypes.cast(arr, _vp), n, M)
+    if need == 0:
+        raise AgqError(AGQ_EINVAL, "agq_gemm_chain_workspace_bytes")
+    if workspace is None:
+        workspace = torch.empty(need, dtype=torch.uint8, device=keep[0].device)
+    _ok(lib().agq_gemm_chain_prepare(ctypes.cast(arr, _vp), n, M, _ptr(workspace), workspace.numel(), _stream()),
+        "agq_gemm_chain_prepare")
+    return ChainPlan(arr, n, M, workspace, keep, ys)
+
+
+def gemm_chain_run(plan: ChainPlan):
+    """agq_gemm_chain_run: one kernel launch on the current stream; returns the per-stage lists of outputs."""
+    _ok(lib().agq_gemm_chain_run(_ptr(plan.workspace), _stream()), "agq_gemm_chain_run")
+    return plan.ys
+
+
+def gemm_chain_status(plan: ChainPlan) -> int:
+    """agq_gemm_chain_status: waits for the current stream; AGQ_OK or AGQ_ETIMEOUT."""
+    return lib().agq_gemm_chain_status(_ptr(plan.workspace), _stream())
 
 
 def trip_search(x: torch.Tensor, bits: int, e: int, kmax: int, zp: int = 0, alpha: torch.Tensor | None = None):

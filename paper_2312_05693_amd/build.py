@@ -10,7 +10,7 @@ CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libagq.so")
 SOURCES = ["agq_api.cpp", "agq_quant.hip", "agq_gemm_decode.hip", "agq_gemm_tiled.hip", "agq_attn.hip", "agq_trip.hip", "agq_attn_qk.hip",
-           "agq_block.hip", "agq_block_api.cpp", "agq_static.hip"]
+           "agq_block.hip", "agq_block_api.cpp", "agq_static.hip", "agq_gemm_chain.hip"]
 PROBE_LIB = os.path.join(HERE, "libagq_probe.so")     # bench.py's measurement aid, a library of its own
 PROBE_SOURCE = "agq_probe.hip"
 HEADERS = ["agq_device.h", "agq_internal.h", os.path.join("..", "..", "include", "agq.h")]

@@ -152,6 +152,7 @@ const char *agq_status_string(int status) {
         case AGQ_EINVAL: return "invalid argument";
         case AGQ_ESIZE: return "workspace too small";
         case AGQ_EHIP: return "HIP launch failed";
+        case AGQ_ETIMEOUT: return "a wait inside the kernel timed out";
         default: return "unknown status";
     }
 }

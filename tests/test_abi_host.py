@@ -296,3 +296,53 @@ def test_cascade_keep_matches_the_oracle(lib, oracle):
     assert lib.agq_cascade_keep(100, 0.5, 0, ctypes.cast(out, ctypes.c_void_p)) == -1
     assert lib.agq_cascade_keep(100, float("nan"), 2, ctypes.cast(out, ctypes.c_void_p)) == -1
     assert lib.agq_cascade_keep(100, 0.5, 2, None) == -1
+
+
+def test_chain_argument_errors_need_no_gpu(lib):
+    """agq_gemm_chain_*: every argument error is found on the host (the stage array is host memory)."""
+    from paper_2312_05693_amd.binding import AgqChainStage, AgqProj
+    EINVAL, ESIZE = -1, -2
+    p = 4096
+
+    def chain(*stages):
+        arr = (AgqChainStage * len(stages))()
+        for i, (x, ldx, src, bits, e, K, projs) in enumerate(stages):
+            arr[i].x_f16, arr[i].ldx, arr[i].src_proj, arr[i].bits, arr[i].e, arr[i].K, arr[i].count = x, ldx, src, bits, e, K, len(projs)
+            for j, (N, ldy) in enumerate(projs):
+                arr[i].projs[j] = AgqProj(p, p, N, p, ldy, None)
+        return arr, len(stages)
+
+    def size(arr_n, M=2):
+        return lib.agq_gemm_chain_workspace_bytes(ctypes.cast(arr_n[0], ctypes.c_void_p), arr_n[1], M)
+
+    def prep(arr_n, M=2, ws=256 * 4096, nbytes=1 << 40):
+        return lib.agq_gemm_chain_prepare(ctypes.cast(arr_n[0], ctypes.c_void_p), arr_n[1], M, ws, nbytes, None)
+
+    good = chain((p, 256, 0, 8, 0, 256, [(128, 128), (64, 64)]), (None, 0, 0, 8, -1, 128, [(32, 32)]))
+    need = size(good)
+    assert need > 0 and need % 8 == 0
+    # the records: two parities x M rows x half the widest stage x 8 bytes, behind header, progress words and table
+    assert size(good, 4) - size(good, 2) == 2 * 2 * (192 // 2) * 8
+    assert prep(good, ws=None) == EINVAL and prep(good, ws=4100) == EINVAL        # workspace missing / misaligned
+    assert prep(good, nbytes=need - 1) == ESIZE
+    for M in (0, 5, -1):
+        assert size(good, M) == 0 and prep(good, M) == EINVAL
+    bad = [
+        chain((None, 0, 0, 8, 0, 256, [(128, 128)])),                                  # first stage without input
+        chain((p, 256, 0, 8, 0, 256, [(128, 128)]), (None, 0, 0, 8, 0, 256, [(32, 32)])),   # K != width of the source
+        chain((p, 256, 0, 8, 0, 256, [(128, 128)]), (None, 0, 1, 8, 0, 128, [(32, 32)])),   # no such projection
+        chain((p, 256, 0, 8, 0, 200, [(128, 128)])),                                   # K % 128
+        chain((p, 256, 0, 8, 0, 16512, [(128, 128)])),                                 # K beyond the limit
+        chain((p, 128, 0, 8, 0, 256, [(128, 128)])),                                   # ldx < K
+        chain((p + 4, 256, 0, 8, 0, 256, [(128, 128)])),                               # misaligned input
+        chain((p, 256, 0, 5, 0, 256, [(128, 128)])),                                   # bits
+        chain((p, 256, 0, 8, 41, 256, [(128, 128)])),                                  # exponent
+        chain((p, 256, 0, 8, 0, 256, [(120, 120)])),                                   # N % 16
+        chain((p, 256, 0, 8, 0, 256, [(128, 64)])),                                    # ldy < N
+        chain((p, 256, 0, 8, 0, 256, [])),                                             # no projection
+    ]
+    for c in bad:
+        assert size(c) == 0 and prep(c) == EINVAL
+    assert lib.agq_gemm_chain_run(None, None) == EINVAL and lib.agq_gemm_chain_run(4100, None) == EINVAL
+    assert lib.agq_gemm_chain_status(None, None) == EINVAL
+    assert lib.agq_status_string(-4) == b"a wait inside the kernel timed out"
