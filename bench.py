@@ -77,6 +77,7 @@ def main():
     ap.add_argument("--no-attention", action="store_true")
     ap.add_argument("--no-trip", action="store_true")
     ap.add_argument("--no-block", action="store_true")
+    ap.add_argument("--no-chain", action="store_true", help="skip the one-launch chain of the decode pass")
     ap.add_argument("--no-probe", action="store_true", help="skip the plain-read / empty-kernel probe of the device")
     ap.add_argument("--no-by-m", action="store_true", help="skip the sweep over 32..1024 rows in the prefill section")
     ap.add_argument("--copy-probe", action="store_true",
@@ -251,6 +252,45 @@ def main():
         "launch": "one HIP graph per step, replayed; per block: qkv (one multi call), o, gate+up (one multi call), down"
                   if not args.per_projection else "one HIP graph per step, replayed; seven single calls per block",
     }
+
+    # ---- the same pass as ONE launch (agq_gemm_chain_*, M <= 4): every projection group is a stage of a persistent
+    #      kernel; o reads the output of q (the attention output has that shape), gate/up the output of o, down the
+    #      output of gate, the next block's q/k/v the output of down: a true dependency chain, as in a decode step.
+    #      Exponents come from a calibration pass with single calls; scales are divided so that activations keep
+    #      unit size along the 128 stages.  Reported beside the launch-per-group figures, not instead of them.
+    if not args.no_chain:
+        chain = {}
+        unit_sw = [[(sw.float() / (0.02 * K ** 0.5)).to(torch.float16) for (K, N, _, sw) in layer] for layer in layers]
+        for M in (1, 4):
+            x0 = xs[(M, 4096)]
+            stages, x = [], x0
+            for li, L in enumerate(layers):
+                def group(xin, idxs):
+                    K = L[idxs[0]][0]
+                    e = int(agq.calibrate_act_exp(xin, 8).item())
+                    outs = agq.gemm_w4a8_multi(xin, e, [(L[i][2], unit_sw[li][i], L[i][1], None, None) for i in idxs], K)
+                    st = dict(x=x0 if (li == 0 and idxs[0] == 0) else None, src_proj=0, bits=8, e=e, K=K,
+                              projs=[(L[i][2], unit_sw[li][i], L[i][1], None, None) for i in idxs])
+                    return st, outs
+                st1, (q, _, _) = group(x, (0, 1, 2))
+                st2, (o,) = group(q, (3,))
+                st3, (g, _) = group(o, (4, 5))
+                st4, (x,) = group(g, (6,))
+                stages += [st1, st2, st3, st4]
+            plan = agq.gemm_chain_prepare(stages, M)
+            agq.gemm_chain_run(plan)
+            torch.cuda.synchronize()
+            same = bool(torch.equal(plan.ys[-1][0].view(torch.int16), x.view(torch.int16)))
+            reps = max(5, args.steps)
+            stc = {}
+            ms = timed(lambda: agq.gemm_chain_run(plan), 2, reps, stc) / reps
+            by = sum(algorithmic_bytes(M, K, N) for layer in layers for (K, N, _, _) in layer)
+            chain["M%d" % M] = {"ms_per_pass": round(ms, 4), "ms_min": round(stc["min_ms"], 4), "us_per_stage": round(ms * 1e3 / len(stages), 2),
+                                "GB/s": round(by / ms / 1e6, 1), "frac_hbm": round(by / ms / 1e6 / HBM_PEAK_GBS, 4),
+                                "stages": len(stages), "status": agq.gemm_chain_status(plan),
+                                "last_output_equals_single_calls": same}
+            del plan, stages
+        result["decode_chain"] = chain
 
     # ---- what one launch can reach on this device (the floor under the figures above): the same 128 launches
     #      of a pass as plain reads of buffers of the launches' sizes (q/k/v, o, gate/up, down of 32 blocks,
