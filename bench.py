@@ -222,6 +222,43 @@ def main():
         per_m_a4["M%d" % M] = {"ms_per_sweep": round(ms, 4), "GB/s": round(by / (ms * 1e-3) / 1e9, 1),
                                "frac_hbm": round(by / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
 
+    # the same sweep when the activation arrives as int8 codes (AGQ_X_Q: Eq.2 already applied once per tensor by
+    # whatever produced it, outside the timed region): no quantizer, no LDS staging inside the GEMM
+    per_m_xq = {}
+    xq_codes = {key: agq.quantize_act(x, 8, es[key]) for key, x in xs.items()}
+
+    def decode_pass_xq(M):
+        for layer in layers:
+            for idxs in ((0, 1, 2), (3,), (4, 5), (6,)):
+                K = layer[idxs[0]][0]
+                projs = [(layer[i][2], layer[i][3], layer[i][1], ys[(M, NAMES[i])], None) for i in idxs]
+                agq.gemm_w4a8_multi(xq_codes[(M, K)], es[(M, K)], projs, K, x_kind=agq.AGQ_X_Q)
+
+    for M in DECODE_M:
+        reps = max(3, args.steps // 3)
+        ms = timed(lambda: decode_pass_xq(M), 1, reps) / reps
+        by = sum(algorithmic_bytes(M, K, N) - M * K for layer in layers for (K, N, _, _) in layer)   # int8 activation
+        per_m_xq["M%d" % M] = {"ms_per_sweep": round(ms, 4), "GB/s": round(by / (ms * 1e-3) / 1e9, 1),
+                               "frac_hbm": round(by / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
+
+    # one token row on the vector ALU (AGQ_X_F16_DOT: no LDS staging, no matrix core) against the library's own choice
+    def decode_pass_dot(bits):
+        fn = agq.gemm_w4a8_multi if bits == 8 else agq.gemm_w4a4_multi
+        for layer in layers:
+            for idxs in ((0, 1, 2), (3,), (4, 5), (6,)):
+                K = layer[idxs[0]][0]
+                projs = [(layer[i][2], layer[i][3], layer[i][1], ys[(1, NAMES[i])], None) for i in idxs]
+                fn(xs[(1, K)], es[(1, K)] + (8 - bits), projs, K, x_kind=agq.AGQ_X_F16_DOT)
+
+    dot_m1 = {}
+    for bits in (8, 4):
+        reps = max(3, args.steps // 3)
+        ms = timed(lambda: decode_pass_dot(bits), 1, reps) / reps
+        by = sum(algorithmic_bytes(1, K, N) for layer in layers for (K, N, _, _) in layer)
+        dot_m1["w4a%d" % bits] = {"ms_per_sweep": round(ms, 4), "GB/s": round(by / (ms * 1e-3) / 1e9, 1),
+                                  "frac_hbm": round(by / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+                                  "matrix_core_form_ms": (per_m if bits == 8 else per_m_a4)["M1"]["ms_per_sweep"]}
+
     result = {
         "metric": "W4A8 GEMM HBM GB/s, LLaMA-7B decode sweep (224 projections x M in {1,4,16})",
         "value": round(gbs, 1),
@@ -249,6 +286,8 @@ def main():
                      "algorithmic_bytes_per_launch": int(bytes_per_step / launches_per_step)},
         "decode_by_M": per_m,
         "decode_w4a4_by_M": per_m_a4,
+        "decode_codes_in_by_M": per_m_xq,
+        "decode_M1_vector_alu": dot_m1,
         "launch": "one HIP graph per step, replayed; per block: qkv (one multi call), o, gate+up (one multi call), down"
                   if not args.per_projection else "one HIP graph per step, replayed; seven single calls per block",
     }

@@ -40,8 +40,16 @@ enum agq_status {
 /* what `x` of the GEMM calls holds */
 enum agq_x_kind {
     AGQ_X_F16 = 0, /* fp16 [M,K]; Eq.2 is applied inside the call            */
-    AGQ_X_Q = 1    /* codes written by agq_quantize_act with the same
+    AGQ_X_Q = 1,   /* codes written by agq_quantize_act with the same
                       bits / e / zp: int8 [M,K] (8 bit) or nibbles [M,K/2]   */
+    AGQ_X_F16_DOT = 2 /* as AGQ_X_F16, for M == 1 and zp == 0 only: the product runs
+                      on the vector ALU (v_dot4_i32_i8 / v_dot8_i32_i4, the
+                      chip's counterpart of the paper's 4-bit multiplier,
+                      Section 4.4 and the appendix) with Eq.2 applied in
+                      registers, no LDS staging and no matrix core.  Same
+                      results bit for bit; which form is faster is a
+                      measurement (the library itself never picks this one).
+                      Not accepted by the _trip and chain calls.             */
 };
 
 /* range of the activation exponent e (scale s = 2^e) accepted everywhere */

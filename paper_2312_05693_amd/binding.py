@@ -14,7 +14,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(HERE, "libagq.so")
 
 AGQ_OK, AGQ_EINVAL, AGQ_ESIZE, AGQ_EHIP, AGQ_ETIMEOUT = 0, -1, -2, -3, -4
-AGQ_X_F16, AGQ_X_Q = 0, 1
+AGQ_X_F16, AGQ_X_Q, AGQ_X_F16_DOT = 0, 1, 2
 
 _i64, _int, _vp, _sz = ctypes.c_int64, ctypes.c_int, ctypes.c_void_p, ctypes.c_size_t
 _GEMM_ARGS = [_vp, _int, _i64, _i64, _i64, _int, _int, _vp, _vp, _i64, _vp, _i64, _vp, _vp, _sz, _vp]

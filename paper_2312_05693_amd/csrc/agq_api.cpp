@@ -24,9 +24,10 @@ int agq_gemm_w4_run(int bits, const void *x, int x_kind, int64_t M, int64_t K, i
                     const agq_proj *projs, int count, void *workspace, size_t workspace_bytes, void *stream,
                     bool check_only) {
     if (M < 0 || M > kMaxDim || K < 128 || K > 65536 || (K % 128) != 0) return AGQ_EINVAL;
-    if (x_kind != AGQ_X_F16 && x_kind != AGQ_X_Q) return AGQ_EINVAL;
+    if (x_kind != AGQ_X_F16 && x_kind != AGQ_X_Q && x_kind != AGQ_X_F16_DOT) return AGQ_EINVAL;
+    if (x_kind == AGQ_X_F16_DOT && (M > 1 || zp != 0)) return AGQ_EINVAL;   // the vector-ALU form: one row, signed grid
     if (!e_ok(e) || zp < 0 || zp > (1 << bits) - 1 || ldx < K) return AGQ_EINVAL;
-    if (x_kind == AGQ_X_F16 && (ldx % 8) != 0) return AGQ_EINVAL;
+    if (x_kind != AGQ_X_Q && (ldx % 8) != 0) return AGQ_EINVAL;
     if (x_kind == AGQ_X_Q && (ldx % (bits == 8 ? 16 : 32)) != 0) return AGQ_EINVAL;
     if (!projs || count < 1 || count > AGQ_MAX_PROJ) return AGQ_EINVAL;
     int64_t tiles = 0, n_sum = 0;

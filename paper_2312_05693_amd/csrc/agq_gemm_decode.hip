@@ -553,6 +553,91 @@ __global__ __launch_bounds__(1024) void gemm_decode_shared_kernel(const DecodeAr
     }
 }
 
+// One token row, fp16 input on the signed grid, no matrix core and no LDS staging: the vector-ALU form of the
+// product (what the 4-bit multiplier of the paper's appendix stands for on this chip).  A lane owns the 32 weights
+// of one output channel that its 16 bytes of a chunk hold, loads the 32 activation values they meet (the sixteen
+// lanes of a k group read the same addresses, which the memory pipeline merges), applies Eq.2 to them in registers
+// and multiplies with v_dot4_i32_i8 (8-bit activations: the nibbles widened to 16 w as in the other kernels) or
+// v_dot8_i32_i4 (4-bit activations: code nibbles paired up in the weights' own order, no widening at all).  The four
+// k groups of a channel are joined by two lane shuffles, the wavefronts by one small LDS reduction.
+template <int BITS, int KPW>
+__global__ __launch_bounds__(1024) void gemm_decode_dot_kernel(const DecodeArgs a) {
+    __shared__ int red[16 * 16];   // [wavefront][channel]
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int nwaves = a.waves;
+    const int KT = a.KT;
+    int nt;
+    const int pj = find_proj(a, blockIdx.x, nt);
+    const DecodeProj pr = load_proj(a, pj);
+    const agq_u4 *wptr = reinterpret_cast<const agq_u4 *>(pr.blob) + (int64_t)nt * KT * 64 + lane;
+    const int g = lane >> 4;
+    const __half *xg = reinterpret_cast<const __half *>(a.x) + 16 * g;
+    int acc = 0;
+    for (int kb = wave * KPW; kb < KT; kb += nwaves * KPW) {
+        agq_u4 w[KPW];
+#pragma unroll
+        for (int i = 0; i < KPW; ++i) w[i] = wptr[(int64_t)min(kb + i, KT - 1) * 64];
+        constexpr int XB = KPW < 2 ? KPW : 2;          // chunks of activation in registers at a time
+#pragma unroll
+        for (int i0 = 0; i0 < KPW; i0 += XB) {
+            agq_u4 xv[XB][4];
+#pragma unroll
+            for (int i = 0; i < XB; ++i) {
+                const __half *xh = xg + (int64_t)min(kb + i0 + i, KT - 1) * 128;
+                xv[i][0] = *reinterpret_cast<const agq_u4 *>(xh);        // k = 16 g + 0..7 of the chunk
+                xv[i][1] = *reinterpret_cast<const agq_u4 *>(xh + 8);    //     16 g + 8..15
+                xv[i][2] = *reinterpret_cast<const agq_u4 *>(xh + 64);   //     64 + 16 g + 0..7
+                xv[i][3] = *reinterpret_cast<const agq_u4 *>(xh + 72);   //     64 + 16 g + 8..15
+            }
+#pragma unroll
+            for (int i = 0; i < XB; ++i) {
+                const bool valid = kb + i0 + i < KT;                      // wave-uniform
+                const agq_u2 c0 = quant8v<false>(xv[i][0], a.q), c1 = quant8v<false>(xv[i][1], a.q);
+                const agq_u2 c2 = quant8v<false>(xv[i][2], a.q), c3 = quant8v<false>(xv[i][3], a.q);
+                const uint32_t lo[4] = {c0.x, c0.y, c1.x, c1.y}, hi[4] = {c2.x, c2.y, c3.x, c3.y};
+                const agq_u4 wv = valid ? w[i0 + i] : agq_u4{0u, 0u, 0u, 0u};
+#pragma unroll
+                for (int d = 0; d < 4; ++d) {
+                    if (BITS == 8) {
+                        acc = __builtin_amdgcn_sdot4((int)lo[d], (int)((wv[d] << 4) & 0xF0F0F0F0u), acc, false);
+                        acc = __builtin_amdgcn_sdot4((int)hi[d], (int)(wv[d] & 0xF0F0F0F0u), acc, false);
+                    } else {
+                        // byte j of the weight word: low nibble k = 4 d + j, high nibble k = 64 + 4 d + j
+                        const uint32_t pair = (lo[d] & 0x0F0F0F0Fu) | ((hi[d] << 4) & 0xF0F0F0F0u);
+                        acc = __builtin_amdgcn_sdot8((int)pair, (int)wv[d], acc, false);
+                    }
+                }
+            }
+        }
+    }
+    acc += __shfl_xor(acc, 16);
+    acc += __shfl_xor(acc, 32);
+    if (lane < 16) red[wave * 16 + lane] = acc;
+    __syncthreads();
+    if (threadIdx.x < 16) {
+        const int n = nt * 16 + lane;
+        if (n < pr.N) {
+            int sum = 0;
+            for (int wv = 0; wv < nwaves; ++wv) sum += red[wv * 16 + lane];
+            const int v = BITS == 8 ? sum >> AGQ_W_SHIFT : sum;   // exact: the widened weights carry the factor
+            if (pr.acc_out) pr.acc_out[n] = v;
+            pr.y[n] = agq_dequant(v, a.scale_e * __half2float(pr.sw[n]));
+        }
+    }
+}
+
+template <int BITS>
+int launch_dot(const DecodeArgs &a, int kpw, unsigned grid, int waves, hipStream_t st) {
+    switch (kpw) {
+        case 1: gemm_decode_dot_kernel<BITS, 1><<<grid, waves * 64, 0, st>>>(a); break;
+        case 2: gemm_decode_dot_kernel<BITS, 2><<<grid, waves * 64, 0, st>>>(a); break;
+        case 4: gemm_decode_dot_kernel<BITS, 4><<<grid, waves * 64, 0, st>>>(a); break;
+        default: gemm_decode_dot_kernel<BITS, 8><<<grid, waves * 64, 0, st>>>(a); break;
+    }
+    return (int)hipGetLastError();
+}
+
 // More than 48 KiB of dynamic LDS needs the limit of the kernel raised: a host-side setting per device and
 // kernel, not a stream operation.  Every instantiation is raised once per device, on the first weight-streaming
 // launch of any shape made with that device current (so a caller never meets it in the middle of a run).
@@ -701,6 +786,8 @@ int agq_launch_gemm_decode(const void *x, int x_kind, int bits, int64_t M, int64
     if (per_wave < 1024) per_wave = 1024;
     const size_t lds = (size_t)waves * per_wave;
     hipStream_t st = (hipStream_t)stream;
+    if (x_kind == AGQ_X_F16_DOT)   // the caller's choice (checked there: one row, signed grid, plain blobs)
+        return bits == 8 ? launch_dot<8>(a, kpw, grid, waves, st) : launch_dot<4>(a, kpw, grid, waves, st);
     // Quantizing the activation once per workgroup pays when a CU serves several
     // channel tiles and the activation is large (measured at K = 4096: from nine
     // rows on and more than one tile per CU; below that the per-tile prologue,

@@ -147,6 +147,8 @@ def run_linear(agq, oracle, x, wq, sw, bits, x_kind="f16", e=None, check_y=True,
     fn = agq.gemm_w4a8 if bits == 8 else agq.gemm_w4a4
     if x_kind == "f16":
         xin, kind = dev(x), agq.AGQ_X_F16
+    elif x_kind == "dot":
+        xin, kind = dev(x), agq.AGQ_X_F16_DOT
     else:
         xin, kind = agq.quantize_act(dev(x), bits, e, zp), agq.AGQ_X_Q
     y = fn(xin, e, packed, dev(sw), N, K, x_kind=kind, acc_out=acc, zp=zp)
@@ -168,6 +170,38 @@ def test_decode_small(agq, oracle, M, K, N):
 def test_decode_variants(agq, oracle, bits, x_kind, M, K, N):
     x, wq, sw = make_case(M, K, N, seed=7 * M + K + N + bits)
     run_linear(agq, oracle, x, wq, sw, bits, x_kind)
+
+
+@pytest.mark.parametrize("bits", [8, 4])
+@pytest.mark.parametrize("K,N", [(128, 16), (256, 40), (1408, 272), (4096, 4096), (4096, 11008), (11008, 4096), (16384, 48)])
+def test_decode_vector_alu_form(agq, oracle, K, N, bits):
+    """One token row on the vector ALU (AGQ_X_F16_DOT: Eq.2 in registers, v_dot4_i32_i8 / v_dot8_i32_i4, no matrix
+    core): the accumulators against the oracle bit for bit, and the fp16 output identical to the matrix-core form's."""
+    x, wq, sw = make_case(1, K, N, seed=900 + K + N + bits)
+    e = run_linear(agq, oracle, x, wq, sw, bits, "dot")
+    packed, xd, swd = agq.pack_w4(dev(wq)), dev(x), dev(sw)
+    fn = agq.gemm_w4a8 if bits == 8 else agq.gemm_w4a4
+    y_dot = fn(xd, e, packed, swd, N, K, x_kind=agq.AGQ_X_F16_DOT)
+    y_mfma = fn(xd, e, packed, swd, N, K)
+    assert np.array_equal(host(y_dot).view(np.uint16), host(y_mfma).view(np.uint16))
+    # clipping codes (a too small exponent) saturate the same way
+    run_linear(agq, oracle, x, wq, sw, bits, "dot", e=e - 3)
+    # several projections of the row in one launch
+    wq2, sw2 = synth.make_weight_q4(N + 16, K, seed=77)
+    mfn = agq.gemm_w4a8_multi if bits == 8 else agq.gemm_w4a4_multi
+    accs = [torch.zeros((1, n), dtype=torch.int32, device="cuda") for n in (N, N + 16)]
+    mfn(xd, e, [(packed, swd, N, None, accs[0]), (agq.pack_w4(dev(wq2)), dev(sw2), N + 16, None, accs[1])], K,
+        x_kind=agq.AGQ_X_F16_DOT)
+    assert np.array_equal(host(accs[0]).astype(np.int64), oracle.linear_w4(x, bits, e, 0, wq, sw)[0])
+    assert np.array_equal(host(accs[1]).astype(np.int64), oracle.linear_w4(x, bits, e, 0, wq2, sw2)[0])
+    # only for one row on the signed grid
+    L = agq.lib()
+    two = torch.zeros((2, K), dtype=torch.float16, device="cuda")
+    y2 = torch.zeros((2, N), dtype=torch.float16, device="cuda")
+    assert L.agq_gemm_w4a8(two.data_ptr(), agq.AGQ_X_F16_DOT, 2, K, K, 0, 0, packed.data_ptr(), swd.data_ptr(), N,
+                           y2.data_ptr(), N, None, None, 0, None) == agq.AGQ_EINVAL
+    assert L.agq_gemm_w4a8(xd.data_ptr(), agq.AGQ_X_F16_DOT, 1, K, K, 0, 128, packed.data_ptr(), swd.data_ptr(), N,
+                           y2.data_ptr(), N, None, None, 0, None) == agq.AGQ_EINVAL
 
 
 @pytest.mark.parametrize("M", [17, 64, 128, 129, 200, 257, 300, 333, 400])
@@ -223,6 +257,8 @@ def test_tiled_split_k(agq, oracle, M, K, N, bits, zp, x_kind):
     fn = agq.gemm_w4a8 if bits == 8 else agq.gemm_w4a4
     if x_kind == "f16":
         xin, kind = dev(x), agq.AGQ_X_F16
+    elif x_kind == "dot":
+        xin, kind = dev(x), agq.AGQ_X_F16_DOT
     else:
         xin, kind = agq.quantize_act(dev(x), bits, e, zp), agq.AGQ_X_Q
     packed, swd = agq.pack_w4(dev(wq)), dev(sw)
@@ -253,6 +289,8 @@ def test_tiled_64_token_tiles(agq, oracle, M, K, N, bits, zp, x_kind):
     fn = agq.gemm_w4a8 if bits == 8 else agq.gemm_w4a4
     if x_kind == "f16":
         xin, kind = dev(x), agq.AGQ_X_F16
+    elif x_kind == "dot":
+        xin, kind = dev(x), agq.AGQ_X_F16_DOT
     else:
         xin, kind = agq.quantize_act(dev(x), bits, e, zp), agq.AGQ_X_Q
     acc = torch.full((M, N), -3, dtype=torch.int32, device="cuda")
