@@ -19,7 +19,7 @@ struct AgqQuant {
     float lo;     // MAGIC + lower grid bound - zp
     float hi;     // MAGIC + upper grid bound - zp
     int zp;
-    // the same in packed fp16 pairs: 2^-e, lower and upper bound (minus zp);
+    // the same in packed fp16 pairs: 2^-e, 1536 + lower and 1536 + upper bound (minus zp);
     // h_scale2 == 0 when 2^-e is not a normal fp16 number.  h_zp2: the low byte
     // of zp in both halves, added to the bit patterns after rounding.
     uint32_t h_scale2, h_lo2, h_hi2, h_zp2;
@@ -40,19 +40,22 @@ __device__ __forceinline__ uint32_t agq_pack4(uint32_t b0, uint32_t b1, uint32_t
 }
 
 // Eq.2 on the signed grid in packed fp16, eight values (four words) -> eight codes
-// in two words, k ascending.  x * 2^-e is exact in fp16 unless it underflows, and
-// then it rounds to code 0 either way; clamping to the (integer) grid bounds
-// before rounding gives the same code as clamping after; adding 1536 = 1.5 * 2^10
-// rounds half-to-even to an integer k and leaves k's two's complement in the low
-// byte of the bit pattern 0x6600 + k.  Requires q.h_scale2 != 0.  Built by
-// agq_make_quant_signed: codes on the signed grid, zero point q.zp (may be negative).
+// in two words, k ascending.  One fused multiply-add per pair, x * 2^-e + 1536 (1536 =
+// 1.5 * 2^10; the product is exact, so this is a single rounding of the exact sum),
+// rounds half-to-even to an integer k wherever the sum lands in [1024, 2048), i.e.
+// for every k the grid can hold, and leaves k's two's complement in the low byte of
+// the bit pattern 0x6600 + k; outside that interval the sum is rounded more coarsely
+// or more finely, but monotonically, so the clamp to 1536 + (grid bounds) that follows
+// gives the same code as clamping before the rounding would.  Three instructions per
+// pair.  Requires q.h_scale2 != 0.  Built by agq_make_quant_signed: codes on the
+// signed grid, zero point q.zp (may be negative).
 typedef _Float16 agq_h2v __attribute__((ext_vector_type(2)));
 template <bool ZP>
 __device__ __forceinline__ uint32_t agq_quant2h(uint32_t two, const AgqQuant &q) {
-    agq_h2v v = __builtin_bit_cast(agq_h2v, two) * __builtin_bit_cast(agq_h2v, q.h_scale2);
+    agq_h2v v = __builtin_elementwise_fma(__builtin_bit_cast(agq_h2v, two), __builtin_bit_cast(agq_h2v, q.h_scale2),
+                                          agq_h2v{(_Float16)1536.0f, (_Float16)1536.0f});
     v = __builtin_elementwise_min(__builtin_elementwise_max(v, __builtin_bit_cast(agq_h2v, q.h_lo2)),
                                   __builtin_bit_cast(agq_h2v, q.h_hi2));
-    v = v + agq_h2v{(_Float16)1536.0f, (_Float16)1536.0f};
     // the zero point is added after the rounding (Eq.2 as printed); 0x66xx + zp stays
     // inside its half, so one 32-bit add serves both
     return ZP ? __builtin_bit_cast(uint32_t, v) + q.h_zp2 : __builtin_bit_cast(uint32_t, v);

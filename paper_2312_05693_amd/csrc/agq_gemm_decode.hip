@@ -412,6 +412,10 @@ __global__ __launch_bounds__(1024) void gemm_decode_kernel(const DecodeArgs a) {
     }
 }
 
+// Workgroup barrier that orders LDS traffic only.  __syncthreads() also waits for every outstanding global load
+// of the wavefront, i.e. for weight chunks that were requested ahead on purpose.
+__device__ __forceinline__ void lds_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
+
 // Variant for 9..16 token rows of fp16 input.  With that many rows the activation
 // is no longer small: every workgroup that covers the whole K reads all of it
 // from L2 (M x K x 2 bytes, times the number of workgroups: several times the
@@ -494,7 +498,7 @@ __global__ __launch_bounds__(1024) void gemm_decode_shared_kernel(const DecodeAr
 #pragma unroll
         for (int i = 0; i < KPW; ++i) w[i] = wptr[(int64_t)min(kb + i, KT - 1) * 64];
     }
-    __syncthreads();
+    lds_barrier();
 
     // every stream runs the same number of rounds (the barriers are workgroup-wide);
     // a round past the end of the tiles is computed on the last tile and not stored
@@ -528,7 +532,7 @@ __global__ __launch_bounds__(1024) void gemm_decode_shared_kernel(const DecodeAr
         const agq_v4i acc = acc0 + acc1;
 #pragma unroll
         for (int r = 0; r < 4; ++r) red[(ws * 4 + r) * 64 + lane] = acc[r];
-        __syncthreads();
+        lds_barrier();
         if (ws < 4 && live) {
             const int r = ws;
             const int m = 4 * (lane >> 4) + r;
@@ -543,7 +547,7 @@ __global__ __launch_bounds__(1024) void gemm_decode_shared_kernel(const DecodeAr
                     agq_dequant(v, a.scale_e * __half2float(__ushort_as_half((unsigned short)sw_bits)));
             }
         }
-        __syncthreads();   // partial sums consumed before the next tile overwrites them
+        lds_barrier();   // partial sums consumed before the next tile overwrites them
         if (round + 1 < rounds) {
 #pragma unroll
             for (int i = 0; i < KPW; ++i) w[i] = wn[i];

@@ -239,12 +239,12 @@ AgqQuant agq_make_quant_signed(int bits, int e, int zp) {
     q.hi = AGQ_MAGIC + (float)(hi - off);
     q.zp = off;
     // fp16 images: 2^-e has exponent field 15 - e, a normal number for 1 <= 15 - e <= 30;
-    // the bounds are integers of magnitude <= 255, exact in fp16
+    // the bounds carry the rounding constant 1536: integers in [1281, 1790], exact in fp16
     auto pair = [](uint32_t h) { return h | (h << 16); };
     const int field = 15 - e;
     q.h_scale2 = (field >= 1 && field <= 30) ? pair((uint32_t)field << 10) : 0u;
-    q.h_lo2 = pair((uint32_t)__half_as_ushort(__float2half((float)(lo - off))));
-    q.h_hi2 = pair((uint32_t)__half_as_ushort(__float2half((float)(hi - off))));
+    q.h_lo2 = pair((uint32_t)__half_as_ushort(__float2half((float)(1536 + lo - off))));
+    q.h_hi2 = pair((uint32_t)__half_as_ushort(__float2half((float)(1536 + hi - off))));
     q.h_zp2 = pair((uint32_t)(off & 0xFF));
     return q;
 }
