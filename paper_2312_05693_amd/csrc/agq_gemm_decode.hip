@@ -151,6 +151,8 @@ __global__ __launch_bounds__(1024) void gemm_decode_kernel(const DecodeArgs a) {
                  "s"(bl1), "s"(bl2), "s"(bl3), "s"(sc0), "s"(sc1), "s"(sc2), "s"(sc3), "s"(n0), "s"(n1), "s"(n2), "s"(n3),
                  "s"(a.q.scale), "s"(a.q.lo), "s"(a.q.hi), "s"(a.q.h_scale2), "s"(a.q.h_lo2), "s"(a.q.h_hi2),
                  "s"(ZP ? a.q.h_zp2 : 0u), "s"(F16 ? 0u : a.flip), "s"(a.corr), "s"(TRIP ? a.n_extra : 0));
+    int corr_keep = 0;
+    if (!(F16 && !ZP)) asm volatile("v_mov_b32 %0, %1" : "=v"(corr_keep) : "s"(a.corr));
     int nt;
     const int pj = find_proj(a, blockIdx.x, nt);   // which projection this workgroup serves (uniform)
     // RG: a workgroup serves two neighbouring channel tiles of its projection with the same quantized rows (the
@@ -382,12 +384,17 @@ __global__ __launch_bounds__(1024) void gemm_decode_kernel(const DecodeArgs a) {
     // join the K-slices of the wavefronts, then dequantize (fused epilogue).
     // Partial sums are stored [wave][register][lane] so that both the write and
     // the read below are conflict-free.
-    __syncthreads();   // every wavefront has left its staging region
-    int *red = reinterpret_cast<int *>(smem);
+    // fp16 input on the signed grid has no correction term: nothing of it is compiled.  Otherwise the factor waits
+    // in a vector register: a scalar register would be given up during the weight stream and the argument fetched
+    // again here, a memory round trip on the tail of the launch.
+    const int corr = (F16 && !ZP) ? 0 : __builtin_amdgcn_readfirstlane(corr_keep);
+    // (behind the staging regions, so that a wavefront need not wait for the others to leave theirs)
+    constexpr int kStageBytes = F16 ? HB * kRegion * 16 : 0;
+    int *red = reinterpret_cast<int *>(smem + nwaves * kStageBytes);
     const agq_v4i acc = acc0 + acc1;
 #pragma unroll
     for (int r = 0; r < 4; ++r) red[(wave * 4 + r) * 64 + lane] = acc[r];
-    if (RG) {   // the second tile's sums behind the first's (a wavefront's staging region holds 2 KiB or more here)
+    if (RG) {   // the second tile's sums behind the first's
         const agq_v4i accb = acc2 + acc3;
 #pragma unroll
         for (int r = 0; r < 4; ++r) red[((nwaves + wave) * 4 + r) * 64 + lane] = accb[r];
@@ -403,7 +410,7 @@ __global__ __launch_bounds__(1024) void gemm_decode_kernel(const DecodeArgs a) {
             int sum = 0;
             for (int w = 0; w < nwaves; ++w) sum += red[((tsel * nwaves + w) * 4 + r) * 64 + l];
             int v = sum >> shift;   // exact: every term carries the factor
-            if (a.corr) v += a.corr * blob_wsum(pblob, pN, KTall)[n];
+            if (corr) v += corr * blob_wsum(pblob, pN, KTall)[n];
             if (pacc) pacc[(int64_t)(row0 + m) * pN + n] = v;
             const bool have = RG ? o == (int)threadIdx.x : nmain >= 4;   // prefetched above
             const uint32_t sb = have ? sw_bits : (uint32_t) reinterpret_cast<const uint16_t *>(psw)[n];
@@ -782,13 +789,12 @@ int agq_launch_gemm_decode(const void *x, int x_kind, int bits, int64_t M, int64
     }
     const unsigned grid = (unsigned)tiles;
     a.waves = waves;
-    // staging: per wavefront HB chunks x (8 x 4 MP) 16-byte pieces (see the kernel);
-    // reused as waves x 1 KiB of partial sums
+    // staging: per wavefront HB chunks x (8 x 4 MP) 16-byte pieces (see the kernel)
     const int mp = M <= 4 ? 1 : (M <= 8 ? 2 : 4);
     const int hb = x_kind != 0 ? kpw : (8 / mp < kpw ? 8 / mp : kpw);
-    size_t per_wave = x_kind != 0 ? 0 : (size_t)hb * 8 * 4 * mp * 16;
-    if (per_wave < 1024) per_wave = 1024;
-    const size_t lds = (size_t)waves * per_wave;
+    const size_t per_wave = x_kind != 0 ? 0 : (size_t)hb * 8 * 4 * mp * 16;
+    // behind the staging regions: one KiB of partial sums per wavefront and channel tile
+    const size_t lds = (size_t)waves * (per_wave + (M > AGQ_DECODE_MAX_M ? 2048 : 1024));
     hipStream_t st = (hipStream_t)stream;
     if (x_kind == AGQ_X_F16_DOT)   // the caller's choice (checked there: one row, signed grid, plain blobs)
         return bits == 8 ? launch_dot<8>(a, kpw, grid, waves, st) : launch_dot<4>(a, kpw, grid, waves, st);
