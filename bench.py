@@ -469,6 +469,24 @@ def main():
             by_m.append(row)
         if by_m:
             prefill["w4a8_by_M"] = by_m
+        # The same GEMM launch (4096 -> 11008 at M = 2048, W4A8, codes handed over: the kernel alone) on random
+        # operands and on all-zero operands: identical instructions and bytes, different switching activity
+        pname, K, N = synth.LLAMA7B_PROJ[4]
+        ent = {}
+        for label in ("random", "zero"):
+            if label == "random":
+                xe, pe = xk[K], layers[0][4][2]
+            else:
+                xe = torch.zeros((PREFILL_M, K), dtype=torch.float16, device=dev)
+                pe = agq.pack_w4(torch.zeros((N, K), dtype=torch.int8, device=dev))
+            e8 = int(agq.calibrate_act_exp(xk[K], 8).item())
+            xq = agq.quantize_act(xe, 8, e8)
+            ye = torch.empty((PREFILL_M, N), dtype=torch.float16, device=dev)
+            wse = torch.empty(agq.gemm_workspace_bytes(PREFILL_M, N, K), dtype=torch.uint8, device=dev)
+            ms = time_it(lambda: agq.gemm_w4a8(xq, e8, pe, layers[0][4][3], N, K, x_kind=agq.AGQ_X_Q, y=ye, workspace=wse), reps=50)
+            ent[label] = {"us": round(ms * 1e3, 2), "TOP/s": round(2.0 * PREFILL_M * N * K / (ms * 1e-3) / 1e12, 1)}
+        ent["note"] = "same launch, same instruction stream and bytes; only the operand values differ"
+        prefill["operand_values_w4a8_4096_to_11008"] = ent
         result["prefill"] = prefill
 
     # ---- TRIP (Section 4.3 / 4.4): the same three shapes with per-channel factors found by Eq.8 on a
