@@ -818,7 +818,9 @@ int agq_launch_gemm_decode(const void *x, int x_kind, int bits, int64_t M, int64
         if (M <= 8) return launch_xk<XK_F16_T, 2>(a, kpw, grid, waves, lds, st);
         return launch_xk<XK_F16_T, 4>(a, kpw, grid, waves, lds, st);
     }
-    if (x_kind == 0 && M > 8 && tiles > 256 && a.KT <= kSharedMaxKT && a.KT >= 4) {
+    // (five to eight rows: only from four tiles per CU on - measured at K = 4096: 13.9 against 15.5 us for
+    // gate/up at eight rows, no difference at three tiles per CU, and slower than the per-tile kernel at four rows)
+    if (x_kind == 0 && ((M > 8 && tiles > 256) || (M > 4 && tiles >= 1024)) && a.KT <= kSharedMaxKT && a.KT >= 4) {
         // one workgroup per CU; its sixteen wavefronts form two tile streams when a
         // CU has four or more tiles to walk (measured: 9 % faster for gate/up, no
         // difference at three tiles; four streams and half the CUs are both slower)

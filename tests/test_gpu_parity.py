@@ -390,12 +390,14 @@ def test_multi_projection_equals_single_calls(agq, oracle, M, bits):
 
 
 @pytest.mark.parametrize("M,K,Ns", [(9, 8192, [4100]), (16, 1024, [4096, 4096, 1000]), (13, 4096, [11008, 11008]),
-                                     (12, 11008, [272]), (6, 16384, [64, 16]), (16, 8320, [48])])
+                                     (12, 11008, [272]), (6, 16384, [64, 16]), (16, 8320, [48]),
+                                     (5, 1024, [8192, 8200]), (8, 512, [16390]), (7, 512, [16370]), (4, 512, [16400])])
 def test_decode_many_tiles_per_workgroup(agq, oracle, M, K, Ns):
-    """9..16 rows with more channel tiles than compute units: the workgroups that
-    keep the quantized activation on chip walk over several tiles, also across
-    the projections of one call and into a ragged last tile; K above 8192 and
-    small tile counts stay on the per-tile kernel."""
+    """9..16 rows with more channel tiles than compute units (5..8 rows: with four
+    tiles or more per compute unit): the workgroups that keep the quantized
+    activation on chip walk over several tiles, also across the projections of
+    one call and into a ragged last tile; K above 8192, small tile counts and
+    fewer rows stay on the per-tile kernel."""
     x = synth.make_activation(M, K, 4, seed=70 + M)
     e = oracle.calibrate_act_exp(x, 8)
     projs, wants = [], []
