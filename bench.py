@@ -412,8 +412,13 @@ def main():
             yk = [torch.empty((PREFILL_M, N), dtype=torch.float16, device=dev) for (_, _, N) in synth.LLAMA7B_PROJ]
             ws = torch.empty(agq.gemm_workspace_bytes(PREFILL_M, 4096, 11008), dtype=torch.uint8, device=dev)
 
+            turn = [0]
+
             def block():
-                # q/k/v share one quantize pre-pass, gate/up another: 4 pre-passes, 7 GEMMs
+                # q/k/v share one quantize pre-pass, gate/up another: 4 pre-passes, 7 GEMMs.  Every call takes the
+                # next block's weights (32 x 101 MB in rotation: nothing is left in a cache from the call before)
+                L = layers[turn[0] % len(layers)]
+                turn[0] += 1
                 mfn(xk[4096], ek[4096], [(L[i][2], L[i][3], L[i][1], yk[i], None) for i in (0, 1, 2)], 4096, workspace=ws)
                 fn(xk[4096], ek[4096], L[3][2], L[3][3], 4096, 4096, y=yk[3], workspace=ws)
                 mfn(xk[4096], ek[4096], [(L[i][2], L[i][3], L[i][1], yk[i], None) for i in (4, 5)], 4096, workspace=ws)
