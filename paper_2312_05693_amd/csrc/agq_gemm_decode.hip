@@ -564,6 +564,180 @@ __global__ __launch_bounds__(1024) void gemm_decode_shared_kernel(const DecodeAr
     }
 }
 
+// Variant for 5..16 token rows of fp16 input when a CU serves two to six channel
+// tiles and K <= 8192: one workgroup of sixteen wavefronts per CU, K split over
+// the wavefronts for EVERY tile of the workgroup.  A wavefront owns KPW chunks
+// of K: it loads and quantizes (Eq.2) only that slice of the activation, once,
+// keeps the MFMA operands of the slice in registers, and multiplies them with
+// its slice of each of the workgroup's TL tiles, whose weight chunks it requests
+// all at the start (the first `kPre` tiles ahead of the quantization, the rest
+// right behind it), so the CU's memory queue holds the whole weight stream of
+// the workgroup from the first microsecond on and nothing in the kernel waits
+// on anything but its own oldest load.  The partial sums of all tiles go to LDS
+// (the wavefront's staging area, reused), the workgroup meets ONCE, and
+// wavefront b finishes tile b.  Against the kernel above: the activation is
+// still quantized once per CU, but without the workgroup-wide meeting before
+// the first tile and the two per tile, and with every load of the launch in
+// flight early.  Everything between the loads and their uses is straight-line
+// code with the same loads on every path (tiles past the end request one line
+// of the last tile), which keeps the compiler's wait counts exact.
+//
+// KPW: chunks of K per wavefront (16 KPW >= KT); MP: passes of four rows (M <= 4 MP);
+// TL: tiles a workgroup can hold (its tiles are blockIdx.x + gridDim.x b, b < TL).
+constexpr int kSliceMaxKT = 64;
+
+template <int KPW, int MP, int TL, bool ZP>
+__global__ __launch_bounds__(1024) void gemm_decode_slice_kernel(const DecodeArgs a, int total_tiles) {
+    extern __shared__ __align__(16) unsigned char smem[];
+    constexpr int kPre = TL >= 4 ? 2 : 1;
+    // a wavefront's own LDS: first the operand staging of its slice (2 KiB per chunk), then its partial sums (1 KiB per tile)
+    constexpr int kWaveInts = (KPW * 2048 > TL * 1024 ? KPW * 2048 : TL * 1024) / 4;
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int KT = a.KT;
+    // every argument in scalar registers up front (one round of scalar loads), picked by comparisons later:
+    // an indexed read of the argument record would be a dependent load in the middle of the kernel
+    const int t1 = a.tile_start[1], t2 = a.tile_start[2], t3 = a.tile_start[3];
+    const uint4 *bl0 = a.blob4[0], *bl1 = a.blob4[1], *bl2 = a.blob4[2], *bl3 = a.blob4[3];
+    const __half *sc0 = a.sw4[0], *sc1 = a.sw4[1], *sc2 = a.sw4[2], *sc3 = a.sw4[3];
+    const int n0 = a.N4[0], n1 = a.N4[1], n2 = a.N4[2], n3 = a.N4[3];
+    __half *const y0 = a.y4[0], *const y1 = a.y4[1], *const y2 = a.y4[2], *const y3 = a.y4[3];
+    int32_t *const ac0 = a.acc4[0], *const ac1 = a.acc4[1], *const ac2 = a.acc4[2], *const ac3 = a.acc4[3];
+    const int ld0 = a.ldy4[0], ld1 = a.ldy4[1], ld2 = a.ldy4[2], ld3 = a.ldy4[3];
+    asm volatile("" ::"s"(a.x), "s"(a.ldx), "s"(a.M), "s"(KT), "s"(t1), "s"(t2), "s"(t3), "s"(a.scale_e), "s"(bl0),
+                 "s"(bl1), "s"(bl2), "s"(bl3), "s"(sc0), "s"(sc1), "s"(sc2), "s"(sc3), "s"(n0), "s"(n1), "s"(n2), "s"(n3),
+                 "s"(a.q.h_scale2), "s"(a.q.h_lo2), "s"(a.q.h_hi2), "s"(ZP ? a.q.h_zp2 : 0u), "s"(ZP ? a.corr : 0));
+    asm volatile("" ::"s"(y0), "s"(y1), "s"(y2), "s"(y3), "s"(ac0), "s"(ac1), "s"(ac2), "s"(ac3), "s"(ld0), "s"(ld1),
+                 "s"(ld2), "s"(ld3));
+    int *const mine = reinterpret_cast<int *>(smem) + wave * kWaveInts;
+    agq_u4 *const stage = reinterpret_cast<agq_u4 *>(mine);
+    const int G = (int)gridDim.x;
+    const int first = (int)blockIdx.x;
+    const int my_tiles = (total_tiles - first + G - 1) / G;   // 1 .. TL (the host sizes the grid)
+    // (macros, not lambdas: a lambda that selects among the captured values makes them addressable,
+    // and the argument record and these locals then live in scratch memory)
+#define AGQ_SLICE_PROJ(tile, pj, nt)                                                                       \
+    const int pj = __builtin_amdgcn_readfirstlane(((tile) >= t1) + ((tile) >= t2) + ((tile) >= t3));       \
+    const int nt = (tile) - (pj == 0 ? 0 : (pj == 1 ? +t1 : (pj == 2 ? +t2 : +t3)))
+#define AGQ_SLICE_PICK(pj, v0, v1, v2, v3) (pj == 0 ? +(v0) : (pj == 1 ? +(v1) : (pj == 2 ? +(v2) : +(v3))))
+    const int kb = wave * KPW;
+    const int c16 = lane & 15, rr = lane >> 4;
+    const int s = c16 >> 3, g = (c16 & 7) >> 1, hf = c16 & 1;
+
+    // the channel scales of the tile this wavefront will finish (tile `wave` of the workgroup): lane l holds
+    // channel l & 15.  Kept as the 16 bits that were loaded: widening it here would wait for it here.
+    const int tile_e = first + G * min(wave, my_tiles - 1);
+    AGQ_SLICE_PROJ(tile_e, pj_e, nt_e);
+    const int pN_e = AGQ_SLICE_PICK(pj_e, n0, n1, n2, n3);
+    const unsigned short sw_u =
+        reinterpret_cast<const uint16_t *>(AGQ_SLICE_PICK(pj_e, sc0, sc1, sc2, sc3))[min(nt_e * 16 + c16, pN_e - 1)];
+
+    // the activation slice: unit = (chunk, pass of four rows), lane = eight consecutive k of one row
+    agq_u4 xv[KPW][MP];
+#pragma unroll
+    for (int i = 0; i < KPW; ++i)
+#pragma unroll
+        for (int it = 0; it < MP; ++it) {
+            const __half *xh = reinterpret_cast<const __half *>(a.x) + (int64_t)min(kb + i, KT - 1) * 128 + c16 * 8;
+            xv[i][it] = *reinterpret_cast<const agq_u4 *>(xh + (int64_t)min(it * 4 + rr, a.M - 1) * a.ldx);
+        }
+    // the weight chunks of tile b; past the workgroup's last tile: the same number of loads, all lanes on one line
+    agq_u4 ring[TL][KPW];
+#define AGQ_SLICE_ISSUE(b)                                                                                            \
+    do {                                                                                                              \
+        const bool real = (b) < my_tiles;                                                                             \
+        const int tile_i = first + G * (real ? (b) : my_tiles - 1);                                                   \
+        AGQ_SLICE_PROJ(tile_i, pj_i, nt_i);                                                                           \
+        const uint4 *const blob_i = AGQ_SLICE_PICK(pj_i, bl0, bl1, bl2, bl3);                                         \
+        const agq_u4 *p_i = reinterpret_cast<const agq_u4 *>(blob_i) + ((int64_t)nt_i * KT) * 64 + (real ? lane : 0); \
+        const int stride_i = real ? 64 : 0;                                                                           \
+        _Pragma("unroll") for (int i = 0; i < KPW; ++i) ring[b][i] = p_i[(int64_t)min(kb + i, KT - 1) * stride_i];    \
+    } while (0)
+#pragma unroll
+    for (int b = 0; b < kPre; ++b) AGQ_SLICE_ISSUE(b);
+
+    // Eq.2 on the slice, into the staging area in MFMA operand order; rows past M repeat the last row (never stored)
+#pragma unroll
+    for (int i = 0; i < KPW; ++i)
+#pragma unroll
+        for (int it = 0; it < MP; ++it) {
+            const agq_u2 codes = quant8v<ZP>(xv[i][it], a.q);
+            reinterpret_cast<agq_u2 *>(stage + i * 128 + s * 64 + g * 16 + it * 4 + rr)[hf] = codes;
+        }
+    // the same wavefront wrote and now reads: LDS keeps program order per wave
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    agq_v4i fa0[KPW], fa1[KPW];
+#pragma unroll
+    for (int i = 0; i < KPW; ++i) {
+        fa0[i] = __builtin_bit_cast(agq_v4i, stage[i * 128 + lane]);
+        fa1[i] = __builtin_bit_cast(agq_v4i, stage[i * 128 + 64 + lane]);
+    }
+    asm volatile("" ::"v"(fa0[0]), "v"(fa1[0]));   // read before the rest of the requests, which can stall at issue
+#pragma unroll
+    for (int b = kPre; b < TL; ++b) AGQ_SLICE_ISSUE(b);
+
+    // (leaving the loop, not skipping a tile: with a skip the compiler would have to assume, at every later
+    // tile, the path on which fewer loads are outstanding, and wait for more than the tile's own chunks)
+#pragma unroll
+    for (int b = 0; b < TL; ++b) {
+        if (b >= my_tiles) goto tiles_done;
+        {
+            agq_v4i acc0 = {0, 0, 0, 0}, acc1 = {0, 0, 0, 0};
+#pragma unroll
+            for (int i = 0; i < KPW; ++i) {
+                const agq_u4 wv = kb + i < KT ? ring[b][i] : agq_u4{0u, 0u, 0u, 0u};
+                const agq_v4i b0 = __builtin_bit_cast(agq_v4i, (wv << 4) & 0xF0F0F0F0u);
+                const agq_v4i b1 = __builtin_bit_cast(agq_v4i, wv & 0xF0F0F0F0u);
+                acc0 = __builtin_amdgcn_mfma_i32_16x16x64_i8(fa0[i], b0, acc0, 0, 0, 0);
+                acc1 = __builtin_amdgcn_mfma_i32_16x16x64_i8(fa1[i], b1, acc1, 0, 0, 0);
+            }
+            const agq_v4i acc = acc0 + acc1;
+#pragma unroll
+            for (int r = 0; r < 4; ++r) mine[b * 256 + r * 64 + lane] = acc[r];   // the operands are in registers by now
+        }
+    }
+tiles_done:
+    lds_barrier();
+    if (wave < my_tiles) {
+        // lane l: the four channels 4 (l & 3) .. + 3 of row l >> 2; in the accumulator layout row m sits in
+        // register m & 3 of the lanes 16 (m >> 2) + channel, so four neighbouring channels are one 16-byte read
+        const int *rb = reinterpret_cast<const int *>(smem) + wave * 256;   // tile `wave`, wavefront 0
+        const int m = lane >> 2, c0 = (lane & 3) * 4;
+        const int lsrc = 16 * (m >> 2) + c0, r = m & 3;
+        agq_v4i sum = {0, 0, 0, 0};
+#pragma unroll
+        for (int w = 0; w < 16; ++w) sum += *reinterpret_cast<const agq_v4i *>(rb + w * kWaveInts + r * 64 + lsrc);
+        const int n = nt_e * 16 + c0;
+        uint32_t h[4];
+        int v4[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            int v = sum[i] >> AGQ_W_SHIFT;   // exact: every term carries the factor
+            if (ZP) v += a.corr * blob_wsum(AGQ_SLICE_PICK(pj_e, bl0, bl1, bl2, bl3), pN_e, KT)[min(n + i, pN_e - 1)];
+            v4[i] = v;
+            const unsigned short sb = (unsigned short)__shfl((int)sw_u, c0 + i);   // channel c0 + i sits in lane c0 + i
+            h[i] = __half_as_ushort(agq_dequant(v, a.scale_e * __half2float(__ushort_as_half(sb))));
+        }
+        int32_t *const pacc = AGQ_SLICE_PICK(pj_e, ac0, ac1, ac2, ac3);
+        __half *const py = AGQ_SLICE_PICK(pj_e, y0, y1, y2, y3);
+        const int pldy = AGQ_SLICE_PICK(pj_e, ld0, ld1, ld2, ld3);
+        if (m < a.M) {
+            if (n + 3 < pN_e && (pldy & 3) == 0 && (reinterpret_cast<uintptr_t>(py) & 7) == 0) {
+                *reinterpret_cast<uint2 *>(py + (int64_t)m * pldy + n) = make_uint2(h[0] | (h[1] << 16), h[2] | (h[3] << 16));
+            } else {
+                for (int i = 0; i < 4 && n + i < pN_e; ++i) py[(int64_t)m * pldy + n + i] = __ushort_as_half((unsigned short)h[i]);
+            }
+            if (pacc)
+                for (int i = 0; i < 4 && n + i < pN_e; ++i) pacc[(int64_t)m * pN_e + n + i] = v4[i];
+        }
+    }
+#undef AGQ_SLICE_ISSUE
+#undef AGQ_SLICE_PROJ
+#undef AGQ_SLICE_PICK
+}
+
 // One token row, fp16 input on the signed grid, no matrix core and no LDS staging: the vector-ALU form of the
 // product (what the 4-bit multiplier of the paper's appendix stands for on this chip).  A lane owns the 32 weights
 // of one output channel that its 16 bytes of a chunk hold, loads the 32 activation values they meet (the sixteen
@@ -658,6 +832,16 @@ hipError_t raise_shared_lds() {
                                hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024 - 512);
 }
 
+template <int KPW, int TL, bool ZP>
+hipError_t raise_slice_lds() {
+    hipError_t err = hipFuncSetAttribute(reinterpret_cast<const void *>(gemm_decode_slice_kernel<KPW, 2, TL, ZP>),
+                                         hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024 - 512);
+    if (err == hipSuccess)
+        err = hipFuncSetAttribute(reinterpret_cast<const void *>(gemm_decode_slice_kernel<KPW, 4, TL, ZP>),
+                                  hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024 - 512);
+    return err;
+}
+
 constexpr int kMaxDevices = 64;
 std::once_flag g_lds_once[kMaxDevices];
 hipError_t g_lds_err[kMaxDevices];
@@ -675,6 +859,14 @@ int ensure_shared_lds_limit() {
         if (err == hipSuccess) err = raise_shared_lds<2, true>();
         if (err == hipSuccess) err = raise_shared_lds<4, true>();
         if (err == hipSuccess) err = raise_shared_lds<8, true>();
+        if (err == hipSuccess) err = raise_slice_lds<1, 6, false>();
+        if (err == hipSuccess) err = raise_slice_lds<2, 6, false>();
+        if (err == hipSuccess) err = raise_slice_lds<3, 6, false>();
+        if (err == hipSuccess) err = raise_slice_lds<4, 3, false>();
+        if (err == hipSuccess) err = raise_slice_lds<1, 6, true>();
+        if (err == hipSuccess) err = raise_slice_lds<2, 6, true>();
+        if (err == hipSuccess) err = raise_slice_lds<3, 6, true>();
+        if (err == hipSuccess) err = raise_slice_lds<4, 3, true>();
         g_lds_err[device] = err;
     });
     return (int)g_lds_err[device];
@@ -694,6 +886,28 @@ int launch_shared(const DecodeArgs &a, int kpw, int tiles, unsigned grid, int wp
         case 2: return launch_shared_kpw<2, MP, ZP>(a, tiles, grid, wpt, nstreams, lds, st);
         case 4: return launch_shared_kpw<4, MP, ZP>(a, tiles, grid, wpt, nstreams, lds, st);
         default: return launch_shared_kpw<8, MP, ZP>(a, tiles, grid, wpt, nstreams, lds, st);
+    }
+}
+
+// chunks of K per wavefront -> tiles a workgroup can hold (registers: TL x KPW weight chunks per lane)
+constexpr int slice_tiles(int kpw) { return kpw <= 3 ? 6 : 3; }
+
+template <int KPW, bool ZP>
+int launch_slice_kpw(const DecodeArgs &a, int tiles, hipStream_t st) {
+    constexpr int TL = slice_tiles(KPW);
+    constexpr size_t lds = 16 * (size_t)(KPW * 2048 > TL * 1024 ? KPW * 2048 : TL * 1024);
+    if (a.M <= 8) gemm_decode_slice_kernel<KPW, 2, TL, ZP><<<256, 1024, lds, st>>>(a, tiles);
+    else gemm_decode_slice_kernel<KPW, 4, TL, ZP><<<256, 1024, lds, st>>>(a, tiles);
+    return (int)hipGetLastError();
+}
+
+template <bool ZP>
+int launch_slice(const DecodeArgs &a, int kpw, int tiles, hipStream_t st) {
+    switch (kpw) {
+        case 1: return launch_slice_kpw<1, ZP>(a, tiles, st);
+        case 2: return launch_slice_kpw<2, ZP>(a, tiles, st);
+        case 3: return launch_slice_kpw<3, ZP>(a, tiles, st);
+        default: return launch_slice_kpw<4, ZP>(a, tiles, st);
     }
 }
 
@@ -817,6 +1031,16 @@ int agq_launch_gemm_decode(const void *x, int x_kind, int bits, int64_t M, int64
         if (M <= 4) return launch_xk<XK_F16_T, 1>(a, kpw, grid, waves, lds, st);
         if (M <= 8) return launch_xk<XK_F16_T, 2>(a, kpw, grid, waves, lds, st);
         return launch_xk<XK_F16_T, 4>(a, kpw, grid, waves, lds, st);
+    }
+    // K split over the wavefronts of one workgroup per CU, all of its tiles in flight at once: from nine rows on
+    // whenever a CU has more than one tile and can hold them (measured at K = 4096, sixteen rows: 9.3 against
+    // 10.2 us for q/k/v, 13.2 against 14.2 us for gate/up; K = 5120, N = 15360: 13.2 against 14.7; K = 8192,
+    // N = 8192: 12.5 against 13.5), at five to eight rows from three tiles per CU on (eight rows, q/k/v: 8.1
+    // against 10.1 us; at two tiles per CU the per-tile kernel is level)
+    if (x_kind == 0 && a.KT <= kSliceMaxKT && M > 4) {
+        const int skpw = (a.KT + 15) / 16;
+        if (tiles > (M > 8 ? 256 : 512) && tiles <= 256 * slice_tiles(skpw))
+            return zp ? launch_slice<true>(a, skpw, tiles, st) : launch_slice<false>(a, skpw, tiles, st);
     }
     // (five to eight rows: only from four tiles per CU on - measured at K = 4096: 13.9 against 15.5 us for
     // gate/up at eight rows, no difference at three tiles per CU, and slower than the per-tile kernel at four rows)

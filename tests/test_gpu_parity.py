@@ -391,12 +391,18 @@ def test_multi_projection_equals_single_calls(agq, oracle, M, bits):
 
 @pytest.mark.parametrize("M,K,Ns", [(9, 8192, [4100]), (16, 1024, [4096, 4096, 1000]), (13, 4096, [11008, 11008]),
                                      (12, 11008, [272]), (6, 16384, [64, 16]), (16, 8320, [48]),
-                                     (5, 1024, [8192, 8200]), (8, 512, [16390]), (7, 512, [16370]), (4, 512, [16400])])
+                                     (5, 1024, [8192, 8200]), (8, 512, [16390]), (7, 512, [16370]), (4, 512, [16400]),
+                                     (11, 5120, [4200]), (16, 6144, [2000, 2200]), (9, 2048, [4099, 4102]),
+                                     (6, 640, [8200]), (8, 384, [8192]), (16, 128, [4112, 16, 4000]),
+                                     (16, 512, [24600]), (6, 512, [24600]), (10, 7168, [12304]), (16, 2048, [24576])])
 def test_decode_many_tiles_per_workgroup(agq, oracle, M, K, Ns):
-    """9..16 rows with more channel tiles than compute units (5..8 rows: with four
-    tiles or more per compute unit): the workgroups that keep the quantized
-    activation on chip walk over several tiles, also across the projections of
-    one call and into a ragged last tile; K above 8192, small tile counts and
+    """5..16 rows with more channel tiles than compute units: one workgroup per
+    compute unit serves several tiles, with K split over its wavefronts and all
+    of its tiles in flight (two to six tiles per compute unit, K up to 8192; one
+    to four chunks of K per wavefront, a K that leaves wavefronts idle, odd
+    widths and pitches, tiles of several projections in one workgroup, the
+    largest tile count it takes) or, beyond that, with the quantized activation
+    in LDS and the tiles one after another; K above 8192, small tile counts and
     fewer rows stay on the per-tile kernel."""
     x = synth.make_activation(M, K, 4, seed=70 + M)
     e = oracle.calibrate_act_exp(x, 8)
@@ -494,7 +500,8 @@ def test_graph_replay_matches_eager(agq, oracle):
 
 @pytest.mark.parametrize("x_kind", ["f16", "q"])
 @pytest.mark.parametrize("bits,zp", [(8, 128), (8, 117), (8, 1), (8, 255), (4, 8), (4, 5), (4, 15)])
-@pytest.mark.parametrize("M,K,N", [(1, 512, 48), (4, 1024, 100), (7, 768, 64), (16, 768, 4200), (150, 512, 300)])
+@pytest.mark.parametrize("M,K,N", [(1, 512, 48), (4, 1024, 100), (7, 768, 64), (16, 768, 4200), (150, 512, 300),
+                                   (6, 384, 8300), (16, 256, 24600)])
 def test_unsigned_grid_with_zero_point(agq, oracle, M, K, N, bits, zp, x_kind):
     """Eq.2's unsigned grid inside the GEMMs: acc = sum_k (q - zp) w with q in
     [0, 2^b - 1], through every kernel variant and both input kinds, including
