@@ -45,7 +45,7 @@ PREFILL_M = 2048
 # source has changed since, the figure is reported as null (stale) instead of a number that no longer holds.
 #   name: (bytes per launch, profiles/ file, source file, first 12 hex digits of the source's sha256)
 MEASURED_TRAFFIC = {
-    "decode": (26.3e6, "profiles/gemm_decode_llama7b_sweep.md", "agq_gemm_decode.hip", "84f5db8c6de5"),
+    "decode": (26.3e6, "profiles/gemm_decode_llama7b_sweep.md", "agq_gemm_decode.hip", "9286598534bb"),
     "attn": (252.3e6, "profiles/log2_attn_llama13b_block.md", "agq_attn.hip", "e6b7cee61965"),
     "tiled": (169.1e6, "profiles/gemm_decode_llama7b_sweep.md", "agq_gemm_tiled.hip", "e4a169ae22c1"),
 }
@@ -281,7 +281,7 @@ def main():
         "roofline": {"bound": "hbm", "achieved": round(gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": round(gbs / HBM_PEAK_GBS, 4), "traffic": measured_traffic("decode")[0],
                      "traffic_source": measured_traffic("decode")[1],
-                     "kernel": "gemm_decode_kernel (M <= 8, K > 8192, one workgroup per CU) and gemm_decode_shared_kernel (9..16 rows): "
+                     "kernel": "gemm_decode_kernel (one workgroup per 16-channel tile) and gemm_decode_slice_kernel (sixteen rows, several tiles per CU): "
                                "every launch of a step", "avg_launch_us": round(avg_launch_us, 3),
                      "algorithmic_bytes_per_launch": int(bytes_per_step / launches_per_step)},
         "decode_by_M": per_m,

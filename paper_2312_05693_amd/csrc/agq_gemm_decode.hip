@@ -423,170 +423,35 @@ __global__ __launch_bounds__(1024) void gemm_decode_kernel(const DecodeArgs a) {
 // of the wavefront, i.e. for weight chunks that were requested ahead on purpose.
 __device__ __forceinline__ void lds_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
 
-// Variant for 9..16 token rows of fp16 input.  With that many rows the activation
-// is no longer small: every workgroup that covers the whole K reads all of it
-// from L2 (M x K x 2 bytes, times the number of workgroups: several times the
-// weight bytes) and quantizes all of it.  So here few, large workgroups each do
-// it ONCE, into LDS (MFMA operand order, 2 KiB per 128-column chunk: K <= 8192),
-// and then walk over many channel tiles: the wavefronts form `nstreams` groups
-// of `wpt`, each group streaming its own sequence of tiles with K split over
-// its wavefronts.  All activation loads are issued up front, ahead of the first
-// tiles' weight chunks; the next tile's chunks are requested before the current
-// tile is multiplied, so the weight stream never drains.
-constexpr int kSharedMaxKT = 64;     // 64 chunks x 2 KiB = 128 KiB of LDS for the activation
-
-template <int KPW, int MP, bool ZP>
-__global__ __launch_bounds__(1024) void gemm_decode_shared_kernel(const DecodeArgs a, int total_tiles, int wpt) {
-    extern __shared__ __align__(16) unsigned char smem[];
-    const int lane = threadIdx.x & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int nwaves = blockDim.x >> 6;
-    const int nstreams = nwaves / wpt;
-    const int stream = wave / wpt, ws = wave - stream * wpt;           // tile stream, wavefront inside it
-    const int KT = a.KT;
-    // all scalar arguments are requested in the first round of loads
-    asm volatile("" ::"s"(a.x), "s"(a.ldx), "s"(a.M), "s"(KT), "s"(a.tile_start[1]), "s"(a.tile_start[2]),
-                 "s"(a.tile_start[3]), "s"(a.q.h_scale2), "s"(a.q.h_lo2), "s"(a.q.h_hi2), "s"(a.scale_e),
-                 "s"(ZP ? a.q.h_zp2 : 0u), "s"(a.corr));
-    agq_u4 *xq = reinterpret_cast<agq_u4 *>(smem);                    // [KT][128] 16-byte operand pieces
-    int *red = reinterpret_cast<int *>(smem + (size_t)KT * 2048) + stream * wpt * 256;   // [wpt][4][64] per stream
-
-    const int kb = ws * KPW;                                           // this wavefront's chunks, every tile
-    auto tile_ptr = [&](int tile, DecodeProj &pr, int &nt) {
-        pr = load_proj(a, find_proj(a, min(tile, total_tiles - 1), nt));
-        return reinterpret_cast<const agq_u4 *>(pr.blob) + ((int64_t)nt * KT) * 64 + lane;
-    };
-
-    // ---- Eq.2 on the whole activation.  Unit = (chunk, pass of four rows): lane =
-    // eight consecutive k of one row.  Units are dealt round-robin to wavefronts.
-    constexpr int XB = KPW == 8 ? 4 : 8;   // activation loads in flight per lane, bounded by the 128 registers
-    const int units = KT * MP;
-    const int c16 = lane & 15, rr = lane >> 4;
-    const int s = c16 >> 3, g = (c16 & 7) >> 1, hf = c16 & 1;
-    // Every workgroup reads the same activation; each starts at a different unit so
-    // that they do not all queue at the same L2 channel at the same time.
-    const int rot = (int)((blockIdx.x * 37u) % (unsigned)units);
-    auto unit_of = [&](int u) {
-        u += rot;
-        return u >= units ? u - units : u;
-    };
-    const int tile_step = (int)gridDim.x * nstreams;
-    int tile = (int)blockIdx.x * nstreams + stream;
-    DecodeProj pr;
-    int nt;
-    const agq_u4 *wptr = tile_ptr(tile, pr, nt);
-    agq_u4 w[KPW];
-    for (int u0 = wave; u0 < units; u0 += nwaves * XB) {
-        agq_u4 xv[XB];
-#pragma unroll
-        for (int i = 0; i < XB; ++i) {
-            const int u = unit_of(min(u0 + i * nwaves, units - 1));
-            const int kc = u / MP, it = u - kc * MP;
-            const __half *xh = reinterpret_cast<const __half *>(a.x) + (int64_t)kc * 128 + c16 * 8;
-            xv[i] = *reinterpret_cast<const agq_u4 *>(xh + (int64_t)min(it * 4 + rr, a.M - 1) * a.ldx);
-        }
-        if (u0 == wave) {
-            asm volatile("" ::: "memory");   // activation requests first: loads return in order
-#pragma unroll
-            for (int i = 0; i < KPW; ++i) w[i] = wptr[(int64_t)min(kb + i, KT - 1) * 64];
-            asm volatile("" ::: "memory");
-        }
-#pragma unroll
-        for (int i = 0; i < XB; ++i) {
-            const int u = unit_of(min(u0 + i * nwaves, units - 1));
-            const int kc = u / MP, it = u - kc * MP;
-            const int m = it * 4 + rr;
-            const agq_u2 codes = quant8v<ZP>(xv[i], a.q);
-            if (u0 + i * nwaves < units && m < a.M)
-                reinterpret_cast<agq_u2 *>(xq + (int64_t)kc * 128 + s * 64 + g * 16 + m)[hf] = codes;
-        }
-    }
-    if (units <= wave) {   // a wavefront without a unit still has to request its first chunks
-#pragma unroll
-        for (int i = 0; i < KPW; ++i) w[i] = wptr[(int64_t)min(kb + i, KT - 1) * 64];
-    }
-    lds_barrier();
-
-    // every stream runs the same number of rounds (the barriers are workgroup-wide);
-    // a round past the end of the tiles is computed on the last tile and not stored
-    const int rounds = (total_tiles + tile_step - 1) / tile_step;
-    for (int round = 0; round < rounds; ++round, tile += tile_step) {
-        const bool live = tile < total_tiles;
-        // request the next tile's chunks and scale before multiplying this one
-        DecodeProj prn = pr;
-        int ntn = nt;
-        agq_u4 wn[KPW];
-        const int pN = pr.N;
-        uint32_t sw_bits = 0;
-        if (ws < 4) sw_bits = reinterpret_cast<const uint16_t *>(pr.sw)[min(nt * 16 + (lane & 15), pN - 1)];
-        if (round + 1 < rounds) {
-            const agq_u4 *wnext = tile_ptr(tile + tile_step, prn, ntn);
-#pragma unroll
-            for (int i = 0; i < KPW; ++i) wn[i] = wnext[(int64_t)min(kb + i, KT - 1) * 64];
-        }
-        agq_v4i acc0 = {0, 0, 0, 0}, acc1 = {0, 0, 0, 0};
-#pragma unroll
-        for (int i = 0; i < KPW; ++i) {
-            const int kc = min(kb + i, KT - 1);
-            const agq_v4i a0 = __builtin_bit_cast(agq_v4i, xq[kc * 128 + lane]);
-            const agq_v4i a1 = __builtin_bit_cast(agq_v4i, xq[kc * 128 + 64 + lane]);
-            const agq_u4 wv = kb + i < KT ? w[i] : agq_u4{0u, 0u, 0u, 0u};
-            const agq_v4i b0 = __builtin_bit_cast(agq_v4i, (wv << 4) & 0xF0F0F0F0u);
-            const agq_v4i b1 = __builtin_bit_cast(agq_v4i, wv & 0xF0F0F0F0u);
-            acc0 = __builtin_amdgcn_mfma_i32_16x16x64_i8(a0, b0, acc0, 0, 0, 0);
-            acc1 = __builtin_amdgcn_mfma_i32_16x16x64_i8(a1, b1, acc1, 0, 0, 0);
-        }
-        const agq_v4i acc = acc0 + acc1;
-#pragma unroll
-        for (int r = 0; r < 4; ++r) red[(ws * 4 + r) * 64 + lane] = acc[r];
-        lds_barrier();
-        if (ws < 4 && live) {
-            const int r = ws;
-            const int m = 4 * (lane >> 4) + r;
-            const int n = nt * 16 + (lane & 15);
-            if (m < a.M && n < pN) {
-                int sum = 0;
-                for (int wv = 0; wv < wpt; ++wv) sum += red[(wv * 4 + r) * 64 + lane];
-                int v = sum >> AGQ_W_SHIFT;   // exact: every term carries the factor
-                if (a.corr) v += a.corr * blob_wsum(pr.blob, pN, KT)[n];
-                if (pr.acc_out) pr.acc_out[(int64_t)m * pN + n] = v;
-                pr.y[(int64_t)m * pr.ldy + n] =
-                    agq_dequant(v, a.scale_e * __half2float(__ushort_as_half((unsigned short)sw_bits)));
-            }
-        }
-        lds_barrier();   // partial sums consumed before the next tile overwrites them
-        if (round + 1 < rounds) {
-#pragma unroll
-            for (int i = 0; i < KPW; ++i) w[i] = wn[i];
-        }
-        pr = prn;
-        nt = ntn;
-    }
-}
-
-// Variant for 5..16 token rows of fp16 input when a CU serves two to six channel
-// tiles and K <= 8192: one workgroup of sixteen wavefronts per CU, K split over
-// the wavefronts for EVERY tile of the workgroup.  A wavefront owns KPW chunks
-// of K: it loads and quantizes (Eq.2) only that slice of the activation, once,
-// keeps the MFMA operands of the slice in registers, and multiplies them with
-// its slice of each of the workgroup's TL tiles, whose weight chunks it requests
-// all at the start (the first `kPre` tiles ahead of the quantization, the rest
-// right behind it), so the CU's memory queue holds the whole weight stream of
-// the workgroup from the first microsecond on and nothing in the kernel waits
-// on anything but its own oldest load.  The partial sums of all tiles go to LDS
-// (the wavefront's staging area, reused), the workgroup meets ONCE, and
-// wavefront b finishes tile b.  Against the kernel above: the activation is
-// still quantized once per CU, but without the workgroup-wide meeting before
-// the first tile and the two per tile, and with every load of the launch in
-// flight early.  Everything between the loads and their uses is straight-line
-// code with the same loads on every path (tiles past the end request one line
-// of the last tile), which keeps the compiler's wait counts exact.
+// Variant for 5..16 token rows of fp16 input when a CU serves two or more channel
+// tiles and K <= 8192.  With that many rows the activation is no longer small:
+// every workgroup that covers the whole K reads all of it from L2 (M x K x 2
+// bytes, times the number of workgroups: several times the weight bytes) and
+// quantizes all of it.  Here one workgroup of sixteen wavefronts per CU does
+// that once, with K split over the wavefronts for EVERY tile of the workgroup.
+// A wavefront owns KPW chunks of K: it loads and quantizes (Eq.2) only that
+// slice of the activation, once, keeps the MFMA operands of the slice in
+// registers, and multiplies them with its slice of each of the workgroup's
+// tiles, TL of them in flight: their weight chunks are requested at the start
+// (the first `kPre` tiles ahead of the quantization, the rest right behind it),
+// so the CU's memory queue holds the weight stream from the first microsecond
+// on and nothing in the kernel waits on anything but its own oldest load.  The
+// partial sums of a round of TL tiles go to LDS (the wavefront's staging area,
+// reused), the workgroup meets, and wavefront b finishes tile b of the round.
+// Everything between the loads and their uses is straight-line code with the
+// same loads on every path (tiles past the end request one line of the last
+// tile), which keeps the compiler's wait counts exact: where two paths with
+// different numbers of outstanding loads meet, it waits for the larger number
+// to drain, which is how a look-ahead written with `if (more tiles)` around its
+// loads ends up waiting for the look-ahead itself.
 //
 // KPW: chunks of K per wavefront (16 KPW >= KT); MP: passes of four rows (M <= 4 MP);
-// TL: tiles a workgroup can hold (its tiles are blockIdx.x + gridDim.x b, b < TL).
+// TL: tiles a workgroup holds at a time (its tiles are blockIdx.x + gridDim.x j, j = 0, 1, ...);
+// MULTI: more than TL tiles per workgroup, in rounds of TL: a slot is requested again, for the next round,
+// as soon as it has been multiplied, and the workgroup meets twice per round (the operands stay in registers).
 constexpr int kSliceMaxKT = 64;
 
-template <int KPW, int MP, int TL, bool ZP>
+template <int KPW, int MP, int TL, bool ZP, bool MULTI>
 __global__ __launch_bounds__(1024) void gemm_decode_slice_kernel(const DecodeArgs a, int total_tiles) {
     extern __shared__ __align__(16) unsigned char smem[];
     constexpr int kPre = TL >= 4 ? 2 : 1;
@@ -613,7 +478,7 @@ __global__ __launch_bounds__(1024) void gemm_decode_slice_kernel(const DecodeArg
     agq_u4 *const stage = reinterpret_cast<agq_u4 *>(mine);
     const int G = (int)gridDim.x;
     const int first = (int)blockIdx.x;
-    const int my_tiles = (total_tiles - first + G - 1) / G;   // 1 .. TL (the host sizes the grid)
+    const int my_tiles = (total_tiles - first + G - 1) / G;   // at least one; at most TL unless MULTI
     // (macros, not lambdas: a lambda that selects among the captured values makes them addressable,
     // and the argument record and these locals then live in scratch memory)
 #define AGQ_SLICE_PROJ(tile, pj, nt)                                                                       \
@@ -624,13 +489,13 @@ __global__ __launch_bounds__(1024) void gemm_decode_slice_kernel(const DecodeArg
     const int c16 = lane & 15, rr = lane >> 4;
     const int s = c16 >> 3, g = (c16 & 7) >> 1, hf = c16 & 1;
 
-    // the channel scales of the tile this wavefront will finish (tile `wave` of the workgroup): lane l holds
-    // channel l & 15.  Kept as the 16 bits that were loaded: widening it here would wait for it here.
-    const int tile_e = first + G * min(wave, my_tiles - 1);
-    AGQ_SLICE_PROJ(tile_e, pj_e, nt_e);
-    const int pN_e = AGQ_SLICE_PICK(pj_e, n0, n1, n2, n3);
+    // the channel scales of the tile this wavefront will finish (tile `wave` of the workgroup's first TL): lane l
+    // holds channel l & 15.  Kept as the 16 bits that were loaded: widening it here would wait for it here.
+    const int tile_f = first + G * min(wave, my_tiles - 1);
+    AGQ_SLICE_PROJ(tile_f, pj_f, nt_f);
+    const int pN_f = AGQ_SLICE_PICK(pj_f, n0, n1, n2, n3);
     const unsigned short sw_u =
-        reinterpret_cast<const uint16_t *>(AGQ_SLICE_PICK(pj_e, sc0, sc1, sc2, sc3))[min(nt_e * 16 + c16, pN_e - 1)];
+        reinterpret_cast<const uint16_t *>(AGQ_SLICE_PICK(pj_f, sc0, sc1, sc2, sc3))[min(nt_f * 16 + c16, pN_f - 1)];
 
     // the activation slice: unit = (chunk, pass of four rows), lane = eight consecutive k of one row
     agq_u4 xv[KPW][MP];
@@ -643,10 +508,10 @@ __global__ __launch_bounds__(1024) void gemm_decode_slice_kernel(const DecodeArg
         }
     // the weight chunks of tile b; past the workgroup's last tile: the same number of loads, all lanes on one line
     agq_u4 ring[TL][KPW];
-#define AGQ_SLICE_ISSUE(b)                                                                                            \
+#define AGQ_SLICE_ISSUE(b, idx)                                                                                       \
     do {                                                                                                              \
-        const bool real = (b) < my_tiles;                                                                             \
-        const int tile_i = first + G * (real ? (b) : my_tiles - 1);                                                   \
+        const bool real = (idx) < my_tiles;                                                                           \
+        const int tile_i = first + G * (real ? (idx) : my_tiles - 1);                                                 \
         AGQ_SLICE_PROJ(tile_i, pj_i, nt_i);                                                                           \
         const uint4 *const blob_i = AGQ_SLICE_PICK(pj_i, bl0, bl1, bl2, bl3);                                         \
         const agq_u4 *p_i = reinterpret_cast<const agq_u4 *>(blob_i) + ((int64_t)nt_i * KT) * 64 + (real ? lane : 0); \
@@ -654,7 +519,7 @@ __global__ __launch_bounds__(1024) void gemm_decode_slice_kernel(const DecodeArg
         _Pragma("unroll") for (int i = 0; i < KPW; ++i) ring[b][i] = p_i[(int64_t)min(kb + i, KT - 1) * stride_i];    \
     } while (0)
 #pragma unroll
-    for (int b = 0; b < kPre; ++b) AGQ_SLICE_ISSUE(b);
+    for (int b = 0; b < kPre; ++b) AGQ_SLICE_ISSUE(b, b);
 
     // Eq.2 on the slice, into the staging area in MFMA operand order; rows past M repeat the last row (never stored)
 #pragma unroll
@@ -676,63 +541,105 @@ __global__ __launch_bounds__(1024) void gemm_decode_slice_kernel(const DecodeArg
     }
     asm volatile("" ::"v"(fa0[0]), "v"(fa1[0]));   // read before the rest of the requests, which can stall at issue
 #pragma unroll
-    for (int b = kPre; b < TL; ++b) AGQ_SLICE_ISSUE(b);
+    for (int b = kPre; b < TL; ++b) AGQ_SLICE_ISSUE(b, b);
 
-    // (leaving the loop, not skipping a tile: with a skip the compiler would have to assume, at every later
-    // tile, the path on which fewer loads are outstanding, and wait for more than the tile's own chunks)
+    // this wavefront's slice of the tile in slot b, times the activation slice, into its partial-sum area
+#define AGQ_SLICE_TILE(b)                                                                                   \
+    do {                                                                                                    \
+        agq_v4i acc0 = {0, 0, 0, 0}, acc1 = {0, 0, 0, 0};                                                   \
+        _Pragma("unroll") for (int i = 0; i < KPW; ++i) {                                                   \
+            const agq_u4 wv = kb + i < KT ? ring[b][i] : agq_u4{0u, 0u, 0u, 0u};                            \
+            const agq_v4i b0 = __builtin_bit_cast(agq_v4i, (wv << 4) & 0xF0F0F0F0u);                        \
+            const agq_v4i b1 = __builtin_bit_cast(agq_v4i, wv & 0xF0F0F0F0u);                               \
+            acc0 = __builtin_amdgcn_mfma_i32_16x16x64_i8(fa0[i], b0, acc0, 0, 0, 0);                        \
+            acc1 = __builtin_amdgcn_mfma_i32_16x16x64_i8(fa1[i], b1, acc1, 0, 0, 0);                        \
+        }                                                                                                   \
+        const agq_v4i acc = acc0 + acc1;                                                                    \
+        _Pragma("unroll") for (int r = 0; r < 4; ++r) mine[(b) * 256 + r * 64 + lane] = acc[r];             \
+    } while (0)
+    // Wavefront w < TL finishes tile base + w of the workgroup (slot w of the round): lane l takes the four
+    // channels 4 (l & 3) .. + 3 of row l >> 2; in the accumulator layout row m sits in register m & 3 of the
+    // lanes 16 (m >> 2) + channel, so four neighbouring channels are one 16-byte read.  MULTI: the next
+    // round's weight chunks are in registers already, so four reads in flight, not sixteen.
+#define AGQ_SLICE_FINISH(base, swv)                                                                                        \
+    do {                                                                                                                   \
+        if (wave < TL && (base) + wave < my_tiles) {                                                                       \
+            const int tile_e = first + G * ((base) + wave);                                                                \
+            AGQ_SLICE_PROJ(tile_e, pj_e, nt_e);                                                                            \
+            const int pN_e = AGQ_SLICE_PICK(pj_e, n0, n1, n2, n3);                                                         \
+            const int *rb = reinterpret_cast<const int *>(smem) + wave * 256;                                              \
+            const int m = lane >> 2, c0 = (lane & 3) * 4;                                                                  \
+            const int lsrc = 16 * (m >> 2) + c0, r = m & 3;                                                                \
+            agq_v4i sum = {0, 0, 0, 0};                                                                                    \
+            _Pragma("unroll") for (int w = 0; w < 16; ++w) {                                                               \
+                sum += *reinterpret_cast<const agq_v4i *>(rb + w * kWaveInts + r * 64 + lsrc);                             \
+                if (MULTI && (w & 3) == 3) asm volatile("" : "+v"(sum)::"memory");                                         \
+            }                                                                                                              \
+            const int n = nt_e * 16 + c0;                                                                                  \
+            uint32_t h[4];                                                                                                 \
+            int v4[4];                                                                                                     \
+            _Pragma("unroll") for (int i = 0; i < 4; ++i) {                                                                \
+                int v = sum[i] >> AGQ_W_SHIFT; /* exact: every term carries the factor */                                  \
+                if (ZP)                                                                                                    \
+                    v += a.corr * blob_wsum(AGQ_SLICE_PICK(pj_e, bl0, bl1, bl2, bl3), pN_e, KT)[min(n + i, pN_e - 1)];     \
+                v4[i] = v;                                                                                                 \
+                const unsigned short sb = (unsigned short)__shfl((int)(swv), c0 + i); /* channel c0 + i: lane c0 + i */    \
+                h[i] = __half_as_ushort(agq_dequant(v, a.scale_e * __half2float(__ushort_as_half(sb))));                   \
+            }                                                                                                              \
+            int32_t *const pacc = AGQ_SLICE_PICK(pj_e, ac0, ac1, ac2, ac3);                                                \
+            __half *const py = AGQ_SLICE_PICK(pj_e, y0, y1, y2, y3);                                                       \
+            const int pldy = AGQ_SLICE_PICK(pj_e, ld0, ld1, ld2, ld3);                                                     \
+            if (m < a.M) {                                                                                                 \
+                if (n + 3 < pN_e && (pldy & 3) == 0 && (reinterpret_cast<uintptr_t>(py) & 7) == 0) {                       \
+                    *reinterpret_cast<uint2 *>(py + (int64_t)m * pldy + n) =                                               \
+                        make_uint2(h[0] | (h[1] << 16), h[2] | (h[3] << 16));                                              \
+                } else {                                                                                                   \
+                    for (int i = 0; i < 4 && n + i < pN_e; ++i)                                                            \
+                        py[(int64_t)m * pldy + n + i] = __ushort_as_half((unsigned short)h[i]);                            \
+                }                                                                                                          \
+                if (pacc)                                                                                                  \
+                    for (int i = 0; i < 4 && n + i < pN_e; ++i) pacc[(int64_t)m * pN_e + n + i] = v4[i];                   \
+            }                                                                                                              \
+        }                                                                                                                  \
+    } while (0)
+
+    int base = 0;
+    unsigned short sw_cur = sw_u;
+    if (MULTI) {
+        // Full rounds, no way out of the middle of one: the same loads on every path, so the waits stay exact
+        // across the loop.  A slot is requested again, for the next round, right behind its product; the scales
+        // for the next round's epilogue a round ahead (by every wavefront: those that finish no tile read the
+        // scales of the workgroup's last tile).
+        for (; base + TL <= my_tiles; base += TL) {
+            const int tile_n = first + G * min(base + TL + wave, my_tiles - 1);
+            AGQ_SLICE_PROJ(tile_n, pj_n, nt_n);
+            const int pN_n = AGQ_SLICE_PICK(pj_n, n0, n1, n2, n3);
+            const unsigned short sw_nxt =
+                reinterpret_cast<const uint16_t *>(AGQ_SLICE_PICK(pj_n, sc0, sc1, sc2, sc3))[min(nt_n * 16 + c16, pN_n - 1)];
+#pragma unroll
+            for (int b = 0; b < TL; ++b) {
+                AGQ_SLICE_TILE(b);
+                AGQ_SLICE_ISSUE(b, base + TL + b);
+            }
+            lds_barrier();
+            AGQ_SLICE_FINISH(base, sw_cur);
+            lds_barrier();   // the partial sums are read before the next round overwrites them
+            sw_cur = sw_nxt;
+        }
+    }
+    // The last round (the only one unless MULTI): up to TL tiles.  The loop is left, not skipped through: with a
+    // skip the compiler would have to assume, at every later tile, the path on which fewer loads are outstanding,
+    // and wait for more than the tile's own chunks.
 #pragma unroll
     for (int b = 0; b < TL; ++b) {
-        if (b >= my_tiles) goto tiles_done;
-        {
-            agq_v4i acc0 = {0, 0, 0, 0}, acc1 = {0, 0, 0, 0};
-#pragma unroll
-            for (int i = 0; i < KPW; ++i) {
-                const agq_u4 wv = kb + i < KT ? ring[b][i] : agq_u4{0u, 0u, 0u, 0u};
-                const agq_v4i b0 = __builtin_bit_cast(agq_v4i, (wv << 4) & 0xF0F0F0F0u);
-                const agq_v4i b1 = __builtin_bit_cast(agq_v4i, wv & 0xF0F0F0F0u);
-                acc0 = __builtin_amdgcn_mfma_i32_16x16x64_i8(fa0[i], b0, acc0, 0, 0, 0);
-                acc1 = __builtin_amdgcn_mfma_i32_16x16x64_i8(fa1[i], b1, acc1, 0, 0, 0);
-            }
-            const agq_v4i acc = acc0 + acc1;
-#pragma unroll
-            for (int r = 0; r < 4; ++r) mine[b * 256 + r * 64 + lane] = acc[r];   // the operands are in registers by now
-        }
+        if (base + b >= my_tiles) goto tiles_done;
+        AGQ_SLICE_TILE(b);
     }
 tiles_done:
     lds_barrier();
-    if (wave < my_tiles) {
-        // lane l: the four channels 4 (l & 3) .. + 3 of row l >> 2; in the accumulator layout row m sits in
-        // register m & 3 of the lanes 16 (m >> 2) + channel, so four neighbouring channels are one 16-byte read
-        const int *rb = reinterpret_cast<const int *>(smem) + wave * 256;   // tile `wave`, wavefront 0
-        const int m = lane >> 2, c0 = (lane & 3) * 4;
-        const int lsrc = 16 * (m >> 2) + c0, r = m & 3;
-        agq_v4i sum = {0, 0, 0, 0};
-#pragma unroll
-        for (int w = 0; w < 16; ++w) sum += *reinterpret_cast<const agq_v4i *>(rb + w * kWaveInts + r * 64 + lsrc);
-        const int n = nt_e * 16 + c0;
-        uint32_t h[4];
-        int v4[4];
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            int v = sum[i] >> AGQ_W_SHIFT;   // exact: every term carries the factor
-            if (ZP) v += a.corr * blob_wsum(AGQ_SLICE_PICK(pj_e, bl0, bl1, bl2, bl3), pN_e, KT)[min(n + i, pN_e - 1)];
-            v4[i] = v;
-            const unsigned short sb = (unsigned short)__shfl((int)sw_u, c0 + i);   // channel c0 + i sits in lane c0 + i
-            h[i] = __half_as_ushort(agq_dequant(v, a.scale_e * __half2float(__ushort_as_half(sb))));
-        }
-        int32_t *const pacc = AGQ_SLICE_PICK(pj_e, ac0, ac1, ac2, ac3);
-        __half *const py = AGQ_SLICE_PICK(pj_e, y0, y1, y2, y3);
-        const int pldy = AGQ_SLICE_PICK(pj_e, ld0, ld1, ld2, ld3);
-        if (m < a.M) {
-            if (n + 3 < pN_e && (pldy & 3) == 0 && (reinterpret_cast<uintptr_t>(py) & 7) == 0) {
-                *reinterpret_cast<uint2 *>(py + (int64_t)m * pldy + n) = make_uint2(h[0] | (h[1] << 16), h[2] | (h[3] << 16));
-            } else {
-                for (int i = 0; i < 4 && n + i < pN_e; ++i) py[(int64_t)m * pldy + n + i] = __ushort_as_half((unsigned short)h[i]);
-            }
-            if (pacc)
-                for (int i = 0; i < 4 && n + i < pN_e; ++i) pacc[(int64_t)m * pN_e + n + i] = v4[i];
-        }
-    }
+    AGQ_SLICE_FINISH(base, sw_cur);
+#undef AGQ_SLICE_TILE
+#undef AGQ_SLICE_FINISH
 #undef AGQ_SLICE_ISSUE
 #undef AGQ_SLICE_PROJ
 #undef AGQ_SLICE_PICK
@@ -826,19 +733,15 @@ int launch_dot(const DecodeArgs &a, int kpw, unsigned grid, int waves, hipStream
 // More than 48 KiB of dynamic LDS needs the limit of the kernel raised: a host-side setting per device and
 // kernel, not a stream operation.  Every instantiation is raised once per device, on the first weight-streaming
 // launch of any shape made with that device current (so a caller never meets it in the middle of a run).
-template <int KPW, bool ZP>
-hipError_t raise_shared_lds() {
-    return hipFuncSetAttribute(reinterpret_cast<const void *>(gemm_decode_shared_kernel<KPW, 4, ZP>),
-                               hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024 - 512);
-}
-
 template <int KPW, int TL, bool ZP>
 hipError_t raise_slice_lds() {
-    hipError_t err = hipFuncSetAttribute(reinterpret_cast<const void *>(gemm_decode_slice_kernel<KPW, 2, TL, ZP>),
-                                         hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024 - 512);
-    if (err == hipSuccess)
-        err = hipFuncSetAttribute(reinterpret_cast<const void *>(gemm_decode_slice_kernel<KPW, 4, TL, ZP>),
-                                  hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024 - 512);
+    hipError_t err = hipSuccess;
+    const void *const kernels[4] = {reinterpret_cast<const void *>(gemm_decode_slice_kernel<KPW, 2, TL, ZP, false>),
+                                    reinterpret_cast<const void *>(gemm_decode_slice_kernel<KPW, 4, TL, ZP, false>),
+                                    reinterpret_cast<const void *>(gemm_decode_slice_kernel<KPW, 2, TL, ZP, true>),
+                                    reinterpret_cast<const void *>(gemm_decode_slice_kernel<KPW, 4, TL, ZP, true>)};
+    for (int i = 0; i < 4 && err == hipSuccess; ++i)
+        err = hipFuncSetAttribute(kernels[i], hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024 - 512);
     return err;
 }
 
@@ -846,20 +749,12 @@ constexpr int kMaxDevices = 64;
 std::once_flag g_lds_once[kMaxDevices];
 hipError_t g_lds_err[kMaxDevices];
 
-int ensure_shared_lds_limit() {
+int ensure_lds_limits() {
     int device = 0;
     if (hipGetDevice(&device) != hipSuccess) return (int)hipGetLastError();
     if (device < 0 || device >= kMaxDevices) return (int)hipErrorInvalidDevice;
     std::call_once(g_lds_once[device], [device] {
-        hipError_t err = raise_shared_lds<1, false>();
-        if (err == hipSuccess) err = raise_shared_lds<2, false>();
-        if (err == hipSuccess) err = raise_shared_lds<4, false>();
-        if (err == hipSuccess) err = raise_shared_lds<8, false>();
-        if (err == hipSuccess) err = raise_shared_lds<1, true>();
-        if (err == hipSuccess) err = raise_shared_lds<2, true>();
-        if (err == hipSuccess) err = raise_shared_lds<4, true>();
-        if (err == hipSuccess) err = raise_shared_lds<8, true>();
-        if (err == hipSuccess) err = raise_slice_lds<1, 6, false>();
+        hipError_t err = raise_slice_lds<1, 6, false>();
         if (err == hipSuccess) err = raise_slice_lds<2, 6, false>();
         if (err == hipSuccess) err = raise_slice_lds<3, 6, false>();
         if (err == hipSuccess) err = raise_slice_lds<4, 3, false>();
@@ -872,23 +767,6 @@ int ensure_shared_lds_limit() {
     return (int)g_lds_err[device];
 }
 
-template <int KPW, int MP, bool ZP>
-int launch_shared_kpw(const DecodeArgs &a, int tiles, unsigned grid, int wpt, int nstreams, size_t lds, hipStream_t st) {
-    static_assert(MP == 4, "the limit is raised for the four-pass instantiations");
-    gemm_decode_shared_kernel<KPW, MP, ZP><<<grid, wpt * nstreams * 64, lds, st>>>(a, tiles, wpt);
-    return (int)hipGetLastError();
-}
-
-template <int MP, bool ZP>
-int launch_shared(const DecodeArgs &a, int kpw, int tiles, unsigned grid, int wpt, int nstreams, size_t lds, hipStream_t st) {
-    switch (kpw) {
-        case 1: return launch_shared_kpw<1, MP, ZP>(a, tiles, grid, wpt, nstreams, lds, st);
-        case 2: return launch_shared_kpw<2, MP, ZP>(a, tiles, grid, wpt, nstreams, lds, st);
-        case 4: return launch_shared_kpw<4, MP, ZP>(a, tiles, grid, wpt, nstreams, lds, st);
-        default: return launch_shared_kpw<8, MP, ZP>(a, tiles, grid, wpt, nstreams, lds, st);
-    }
-}
-
 // chunks of K per wavefront -> tiles a workgroup can hold (registers: TL x KPW weight chunks per lane)
 constexpr int slice_tiles(int kpw) { return kpw <= 3 ? 6 : 3; }
 
@@ -896,8 +774,13 @@ template <int KPW, bool ZP>
 int launch_slice_kpw(const DecodeArgs &a, int tiles, hipStream_t st) {
     constexpr int TL = slice_tiles(KPW);
     constexpr size_t lds = 16 * (size_t)(KPW * 2048 > TL * 1024 ? KPW * 2048 : TL * 1024);
-    if (a.M <= 8) gemm_decode_slice_kernel<KPW, 2, TL, ZP><<<256, 1024, lds, st>>>(a, tiles);
-    else gemm_decode_slice_kernel<KPW, 4, TL, ZP><<<256, 1024, lds, st>>>(a, tiles);
+    if (tiles <= 256 * TL) {
+        if (a.M <= 8) gemm_decode_slice_kernel<KPW, 2, TL, ZP, false><<<256, 1024, lds, st>>>(a, tiles);
+        else gemm_decode_slice_kernel<KPW, 4, TL, ZP, false><<<256, 1024, lds, st>>>(a, tiles);
+    } else {
+        if (a.M <= 8) gemm_decode_slice_kernel<KPW, 2, TL, ZP, true><<<256, 1024, lds, st>>>(a, tiles);
+        else gemm_decode_slice_kernel<KPW, 4, TL, ZP, true><<<256, 1024, lds, st>>>(a, tiles);
+    }
     return (int)hipGetLastError();
 }
 
@@ -939,7 +822,7 @@ int launch_xk(const DecodeArgs &a, int kpw, unsigned grid, int waves, size_t lds
 
 int agq_launch_gemm_decode(const void *x, int x_kind, int bits, int64_t M, int64_t K, int64_t ldx, int e, int zp,
                            const agq_proj *projs, int count, int n_extra, void *stream) {
-    if (const int err = ensure_shared_lds_limit()) return err;
+    if (const int err = ensure_lds_limits()) return err;
     DecodeArgs a = {};
     a.x = x;
     a.ldx = ldx;
@@ -1012,10 +895,6 @@ int agq_launch_gemm_decode(const void *x, int x_kind, int bits, int64_t M, int64
     hipStream_t st = (hipStream_t)stream;
     if (x_kind == AGQ_X_F16_DOT)   // the caller's choice (checked there: one row, signed grid, plain blobs)
         return bits == 8 ? launch_dot<8>(a, kpw, grid, waves, st) : launch_dot<4>(a, kpw, grid, waves, st);
-    // Quantizing the activation once per workgroup pays when a CU serves several
-    // channel tiles and the activation is large (measured at K = 4096: from nine
-    // rows on and more than one tile per CU; below that the per-tile prologue,
-    // which overlaps better with the weight stream, is faster).
     if (M > AGQ_DECODE_MAX_M) {   // row groups (the caller has checked: fp16 input, plain blobs)
         const unsigned groups = (unsigned)((M + 15) / 16);
         if (zp) return launch_rg<XK_F16_Z>(a, kpw, grid, groups, waves, lds, st);
@@ -1032,31 +911,18 @@ int agq_launch_gemm_decode(const void *x, int x_kind, int bits, int64_t M, int64
         if (M <= 8) return launch_xk<XK_F16_T, 2>(a, kpw, grid, waves, lds, st);
         return launch_xk<XK_F16_T, 4>(a, kpw, grid, waves, lds, st);
     }
-    // K split over the wavefronts of one workgroup per CU, all of its tiles in flight at once: from nine rows on
-    // whenever a CU has more than one tile and can hold them (measured at K = 4096, sixteen rows: 9.3 against
-    // 10.2 us for q/k/v, 13.2 against 14.2 us for gate/up; K = 5120, N = 15360: 13.2 against 14.7; K = 8192,
-    // N = 8192: 12.5 against 13.5), at five to eight rows from three tiles per CU on (eight rows, q/k/v: 8.1
-    // against 10.1 us; at two tiles per CU the per-tile kernel is level)
+    // K split over the wavefronts of one workgroup per CU, up to six of its tiles in flight at once: from nine
+    // rows on whenever a CU has more than one tile, at five to eight rows from three tiles per CU on (eight rows,
+    // K = 4096, q/k/v: 8.1 against 10.1 us for one workgroup per tile; at two tiles per CU the two are level);
+    // in rounds when a CU has more tiles than a workgroup holds.  Measured at sixteen rows against the kernel
+    // this one replaced (the whole quantized activation in LDS, the tiles one after another with two meetings per
+    // tile): K = 4096 q/k/v 10.2 -> 9.3 us, gate/up 14.2 -> 13.2; K = 5120, N = 27648: 21.9 -> 20.0; K = 8192,
+    // N = 28672: 30.4 -> 26.1.  Below five rows the per-tile prologue, which overlaps better with the weight
+    // stream, is faster (four rows, q/k/v: 7.4 against 8.6 us).
     if (x_kind == 0 && a.KT <= kSliceMaxKT && M > 4) {
         const int skpw = (a.KT + 15) / 16;
-        if (tiles > (M > 8 ? 256 : 512) && tiles <= 256 * slice_tiles(skpw))
+        if (tiles > (M > 8 ? 256 : 512))
             return zp ? launch_slice<true>(a, skpw, tiles, st) : launch_slice<false>(a, skpw, tiles, st);
-    }
-    // (five to eight rows: only from four tiles per CU on - measured at K = 4096: 13.9 against 15.5 us for
-    // gate/up at eight rows, no difference at three tiles per CU, and slower than the per-tile kernel at four rows)
-    if (x_kind == 0 && ((M > 8 && tiles > 256) || (M > 4 && tiles >= 1024)) && a.KT <= kSharedMaxKT && a.KT >= 4) {
-        // one workgroup per CU; its sixteen wavefronts form two tile streams when a
-        // CU has four or more tiles to walk (measured: 9 % faster for gate/up, no
-        // difference at three tiles; four streams and half the CUs are both slower)
-        const int nstreams = tiles >= 1024 ? 2 : 1;
-        int skpw = 1;
-        while ((a.KT + skpw - 1) / skpw > 16 / nstreams) skpw *= 2;
-        const int swaves = (a.KT + skpw - 1) / skpw;
-        int g = (tiles + nstreams - 1) / nstreams;
-        if (g > 256) g = 256;
-        const size_t lds_shared = (size_t)a.KT * 2048 + (size_t)swaves * nstreams * 1024;
-        if (zp) return launch_shared<4, true>(a, skpw, tiles, (unsigned)g, swaves, nstreams, lds_shared, st);
-        return launch_shared<4, false>(a, skpw, tiles, (unsigned)g, swaves, nstreams, lds_shared, st);
     }
     if (x_kind == 0) {
         if (zp) {

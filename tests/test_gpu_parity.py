@@ -394,16 +394,18 @@ def test_multi_projection_equals_single_calls(agq, oracle, M, bits):
                                      (5, 1024, [8192, 8200]), (8, 512, [16390]), (7, 512, [16370]), (4, 512, [16400]),
                                      (11, 5120, [4200]), (16, 6144, [2000, 2200]), (9, 2048, [4099, 4102]),
                                      (6, 640, [8200]), (8, 384, [8192]), (16, 128, [4112, 16, 4000]),
-                                     (16, 512, [24600]), (6, 512, [24600]), (10, 7168, [12304]), (16, 2048, [24576])])
+                                     (16, 512, [24600]), (6, 512, [24600]), (10, 7168, [12304]), (16, 2048, [24576]),
+                                     (16, 256, [49200]), (16, 128, [49152]), (9, 384, [30000, 5000, 77]),
+                                     (7, 5120, [6200, 6200])])
 def test_decode_many_tiles_per_workgroup(agq, oracle, M, K, Ns):
     """5..16 rows with more channel tiles than compute units: one workgroup per
-    compute unit serves several tiles, with K split over its wavefronts and all
-    of its tiles in flight (two to six tiles per compute unit, K up to 8192; one
-    to four chunks of K per wavefront, a K that leaves wavefronts idle, odd
-    widths and pitches, tiles of several projections in one workgroup, the
-    largest tile count it takes) or, beyond that, with the quantized activation
-    in LDS and the tiles one after another; K above 8192, small tile counts and
-    fewer rows stay on the per-tile kernel."""
+    compute unit serves several tiles, with K split over its wavefronts and up
+    to six of its tiles in flight (K up to 8192; one to four chunks of K per
+    wavefront, a K that leaves wavefronts idle, odd widths and pitches, tiles of
+    several projections in one workgroup, the largest count it takes in one
+    round) or, beyond that, in rounds (one full round and a last one of none,
+    one or several tiles; two full rounds and nothing left); K above 8192,
+    small tile counts and fewer rows stay on the per-tile kernel."""
     x = synth.make_activation(M, K, 4, seed=70 + M)
     e = oracle.calibrate_act_exp(x, 8)
     projs, wants = [], []
