@@ -47,7 +47,7 @@ PREFILL_M = 2048
 MEASURED_TRAFFIC = {
     "decode": (26.3e6, "profiles/gemm_decode_llama7b_sweep.md", "agq_gemm_decode.hip", "9286598534bb"),
     "attn": (252.3e6, "profiles/log2_attn_llama13b_block.md", "agq_attn.hip", "e6b7cee61965"),
-    "tiled": (169.1e6, "profiles/gemm_decode_llama7b_sweep.md", "agq_gemm_tiled.hip", "e4a169ae22c1"),
+    "tiled": (169.2e6, "profiles/gemm_decode_llama7b_sweep.md", "agq_gemm_tiled.hip", "11177da4338a"),
 }
 
 
@@ -492,6 +492,48 @@ def main():
             ent[label] = {"us": round(ms * 1e3, 2), "TOP/s": round(2.0 * PREFILL_M * N * K / (ms * 1e-3) / 1e12, 1)}
         ent["note"] = "same launch, same instruction stream and bytes; only the operand values differ"
         prefill["operand_values_w4a8_4096_to_11008"] = ent
+        # What the matrix cores sustain on this device for the kernel's instruction (32 x 32 x 32 int8 MFMA, two
+        # wavefronts per SIMD, four independent accumulators, no memory traffic): with all-zero operands, with
+        # operand values taken from the workload (weights as the kernels feed them, 16 w, and the activation's
+        # 8-bit codes) and with uniformly random bytes.  The instruction stream is the same in all three.
+        if not args.no_probe:
+            import ctypes
+            probe = ctypes.CDLL(os.path.join(ROOT, "paper_2312_05693_amd", "libagq_probe.so"))
+            probe.agq_probe_mfma_i8.restype = ctypes.c_int
+            probe.agq_probe_mfma_i8.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int, ctypes.c_int,
+                                                ctypes.c_void_p, ctypes.c_void_p]
+            gen_p = torch.Generator(device=dev)
+            gen_p.manual_seed(11)
+            nb_p = 16384                                  # operand bytes per side: four registers sets per lane
+            w16 = (torch.randint(-8, 8, (nb_p,), generator=gen_p, device=dev, dtype=torch.int8) * 16).contiguous()
+            codes = agq.quantize_act(xk[4096][:4].contiguous(), 8, ek[4096]).reshape(-1)[:nb_p].contiguous()
+            rnd = torch.randint(-128, 128, (2 * nb_p,), generator=gen_p, device=dev, dtype=torch.int8)
+            zero = torch.zeros(nb_p, dtype=torch.int8, device=dev)
+            sink_p = torch.zeros(64, dtype=torch.int32, device=dev)
+            wgs, reps_p = 512, 20000                     # two workgroups of four wavefronts per CU
+            ops = 8.0 * 32 ** 3 * reps_p * wgs * 4
+            mp = {}
+            for label, pa, pb in (("zero_operands", zero, zero), ("workload_operands", w16, codes),
+                                  ("uniform_random_bytes", rnd[:nb_p].contiguous(), rnd[nb_p:].contiguous())):
+                launch = lambda: probe.agq_probe_mfma_i8(pa.data_ptr(), pb.data_ptr(), wgs, reps_p, sink_p.data_ptr(),
+                                                         torch.cuda.current_stream().cuda_stream)
+                assert launch() == 0
+                torch.cuda.synchronize()
+                best = 1e9
+                for _ in range(3):
+                    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                    e0.record()
+                    assert launch() == 0
+                    e1.record()
+                    torch.cuda.synchronize()
+                    best = min(best, e0.elapsed_time(e1))
+                mp[label + "_TOP/s"] = round(ops / (best * 1e-3) / 1e12, 1)
+            mp["what"] = ("the tiled kernel's matrix instruction alone (no loads, no LDS; every MFMA with other operand "
+                          "registers than the one before), 512 workgroups of four wavefronts, ~2 ms each: the rate the "
+                          "matrix cores sustain depends on the operand values")
+            prefill["mfma_probe"] = mp
+            for name in ("w4a8", "w4a4"):
+                prefill[name]["roofline"]["frac_of_probe"] = round(prefill[name]["TOP/s"] / mp["workload_operands_TOP/s"], 4)
         result["prefill"] = prefill
 
     # ---- TRIP (Section 4.3 / 4.4): the same three shapes with per-channel factors found by Eq.8 on a

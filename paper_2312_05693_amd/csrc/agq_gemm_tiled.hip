@@ -94,7 +94,7 @@ struct TiledArgs {
 // slower than no split at all: it has to read them in dependent rounds through device-scope loads,
 // or with cache-wide write-backs and invalidations around them.  A lone workgroup on a CU is not
 // short of copies in flight either: six stages instead of three changed nothing, its sixteen
-// 64-cycle MFMAs per wavefront and step are the step time.)  An int32 sum does not depend on
+// MFMAs per wavefront and step, about 60 cycles apart in this loop, are the step time.)  An int32 sum does not depend on
 // its order, so the result is the unsplit kernel's bit for bit.
 //
 // NI: 32-token MFMA tiles per wavefront.  2: the 128-token workgroup tile described above.  1: a 64-token
