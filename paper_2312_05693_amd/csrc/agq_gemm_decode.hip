@@ -124,8 +124,11 @@ __device__ __forceinline__ agq_u2 quant8v(const agq_u4 &h, const AgqQuant &q) {
 
 // XK: what x holds; KPW: weight chunks per wavefront and pass over K;
 // MP: passes of four token rows the Eq.2 prologue makes (M <= 4 MP).
+// (The second launch bound, wavefronts per SIMD the compiler has to leave room for: the one-row instantiation
+// with four chunks per wavefront otherwise takes 70 registers, i.e. three of its eight-wavefront workgroups per
+// CU instead of four; with 62 the gate/up launch of LLaMA-7B went from 10.4 to 10.1 us, the others stayed.)
 template <int XK, int KPW, int MP, bool RG = false>
-__global__ __launch_bounds__(1024) void gemm_decode_kernel(const DecodeArgs a) {
+__global__ __launch_bounds__(1024, (XK == XK_F16_ONE && KPW == 4 && MP == 1 && !RG) ? 8 : 1) void gemm_decode_kernel(const DecodeArgs a) {
     extern __shared__ __align__(16) unsigned char smem[];
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
