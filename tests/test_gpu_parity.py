@@ -442,18 +442,20 @@ def test_decode_prologue_every_fp16_value(agq, oracle, M, e, bits):
     run_linear(agq, oracle, x, wq, sw, bits, e=e, check_y=False)
 
 
-@pytest.mark.parametrize("M,K,N", [(1, 4096, 272), (4, 1024, 100), (7, 768, 64), (16, 4096, 64), (16, 1024, 4200),
-                                   (150, 512, 300)])
-def test_strided_input_and_output(agq, oracle, M, K, N):
+@pytest.mark.parametrize("M,K,N,pad", [(1, 4096, 272, 40), (4, 1024, 100, 40), (7, 768, 64, 40), (16, 4096, 64, 40),
+                                       (16, 1024, 4200, 40), (150, 512, 300, 40), (16, 1024, 4200, 41),
+                                       (12, 384, 24650, 40), (6, 256, 24650, 43)])
+def test_strided_input_and_output(agq, oracle, M, K, N, pad):
     """Activation rows and output rows with a pitch larger than their width
     (views into wider buffers): every kernel variant must honour ldx and ldy,
-    and must leave the columns beyond N untouched."""
+    and must leave the columns beyond N untouched (also with an output pitch
+    that rules out the wide stores, and in the multi-round kernel)."""
     x, wq, sw = make_case(M, K, N, seed=300 + M + K + N)
     e = oracle.calibrate_act_exp(x, 8)
     acc_want, y_want = oracle.linear_w4(x, 8, e, 0, wq, sw)
     xbuf = torch.full((M, K + 64), 77.0, dtype=torch.float16, device="cuda")
     xbuf[:, :K] = dev(x)
-    ybuf = torch.full((M, N + 40), -5.0, dtype=torch.float16, device="cuda")
+    ybuf = torch.full((M, N + pad), -5.0, dtype=torch.float16, device="cuda")
     acc = torch.full((M, N), -12345, dtype=torch.int32, device="cuda")
     agq.gemm_w4a8(xbuf[:, :K], e, agq.pack_w4(dev(wq)), dev(sw), N, K, y=ybuf[:, :N], acc_out=acc)
     assert np.array_equal(host(acc).astype(np.int64), acc_want)
@@ -468,7 +470,8 @@ def test_graph_replay_matches_eager(agq, oracle):
     eager warm-up, replay several times with eager work in between, and compare
     every replay with the eager result and with the oracle."""
     cases = []
-    for M, K, Ns in ((1, 4096, [272]), (4, 1024, [100, 64]), (16, 4096, [64]), (16, 1024, [4096, 300])):
+    for M, K, Ns in ((1, 4096, [272]), (4, 1024, [100, 64]), (16, 4096, [64]), (16, 1024, [4096, 300]),
+                     (9, 256, [24700])):
         x = synth.make_activation(M, K, 4, seed=400 + M + K)
         e = oracle.calibrate_act_exp(x, 8)
         projs, wants = [], []
